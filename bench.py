@@ -1,0 +1,147 @@
+#!/usr/bin/env python3
+"""Benchmark of the linear-attention forward path on one MI355X.
+
+A step is one linattn_fwd call (state pass, reduction, query pass) over one batch of synthetic
+Wan-14B/720p-shaped tensors (B=1, H=40, n=75600, d=128, bf16) already resident in HBM.
+Prints one JSON line: whole-path tokens/s, the HBM roofline of the dominant kernel measured with
+HIP events between the stages, and the CPU fp64 oracle timed on a bounded sample beside it.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published peak
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command
+# (profiles/), scaled by a copy kernel of known size; None until measured for a workload.
+MEASURED_TRAFFIC = {}
+
+
+def _hip():
+    lib = ctypes.CDLL("libamdhip64.so")
+    lib.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+    lib.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+    lib.hipEventDestroy.argtypes = [ctypes.c_void_p]
+    return lib
+
+
+def cpu_baseline(x, budget_s: float = 12.0):
+    """The oracle as it stands, on a bounded sample: whole heads of the same workload."""
+    from oracle import linattn_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    done = 0
+    t0 = time.perf_counter()
+    for h in range(x.H):
+        O.fwd(O.to_f64(x.q[0, h]), O.to_f64(x.k[0, h]), O.to_f64(x.v[0, h]), O.to_f64(x.wq[h]), O.to_f64(x.wk[h]))
+        done += 1
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    head_tokens_per_s = done * x.n / dt
+    return {"value": head_tokens_per_s / x.H, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{done} of {x.H} heads of batch item 0, all {x.n} tokens, fp64 numpy, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="C3", help="configuration name in paper_2510_08318_amd.synth")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build is single-GPU (one MI355X); --gpus must be 1")
+
+    import torch
+    from paper_2510_08318_amd import binding as L, synth, torch_glue as G
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    x = synth.generate(args.workload)
+    q, k, v, wq, wk = [G.to_device(t) for t in (x.q, x.k, x.v, x.wq, x.wk)]
+    lay = G.Layer(wq, wk, x.B, x.n)
+    out = torch.empty_like(q)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step():
+        L.linattn_fwd(q, k, v, out, x.B, x.H, x.n, x.d, lay.phi_id, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    tokens_per_s = x.B * x.n / (dt / args.steps)
+
+    # per-stage durations: the same K steps again with HIP events between the stages
+    hip = _hip()
+    evs = []
+    for _ in range(args.steps):
+        four = []
+        for _ in range(4):
+            e = ctypes.c_void_p()
+            assert hip.hipEventCreate(ctypes.byref(e)) == 0
+            four.append(e.value)
+        evs.append(four)
+    for four in evs:
+        L.linattn_set_stage_events(four)
+        step()
+    L.linattn_set_stage_events(None)
+    torch.cuda.synchronize()
+    stage_ms = [0.0, 0.0, 0.0]
+    for four in evs:
+        for i in range(3):
+            ms = ctypes.c_float()
+            assert hip.hipEventElapsedTime(ctypes.byref(ms), four[i], four[i + 1]) == 0
+            stage_ms[i] += ms.value / args.steps
+    for four in evs:
+        for e in four:
+            hip.hipEventDestroy(e)
+
+    esz = 2 if x.dtype == "bf16" else 4
+    head_tokens = x.B * x.H * x.n
+    stage_bytes = [2 * x.d * esz * head_tokens, 0, 2 * x.d * esz * head_tokens]   # read K,V | - | read Q, write out
+    names = ["state_partials (phi(K)^T V, split-n)", "state_reduce", "apply (phi(Q) S / phi(Q).z)"]
+    dom = 0 if stage_ms[0] >= stage_ms[2] else 2
+    achieved = stage_bytes[dom] / (stage_ms[dom] * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": names[dom], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": MEASURED_TRAFFIC.get((args.workload, dom)),
+                "stage_ms": [round(t, 4) for t in stage_ms],
+                "path_GBps": round(4 * x.d * esz * head_tokens / (sum(stage_ms) * 1e-3) / 1e9, 1),
+                "path_frac": round(4 * x.d * esz * head_tokens / (sum(stage_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+    res = {
+        "metric": "linear-attn fwd tokens/s (Wan-14B 720p shape)" if args.workload == "C3" else f"linear-attn fwd tokens/s ({args.workload})",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": x.dtype, "data": "synthetic",
+        "config": {"workload": f"{args.workload}: B={x.B} H={x.H} n={x.n} d={x.d} {x.dtype}, Hedgehog phi, non-causal",
+                   "head_tokens_per_s": round(tokens_per_s * x.H, 1)},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(x)
+    lay.close()
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

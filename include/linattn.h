@@ -1,0 +1,122 @@
+/*
+ * linattn.h -- C ABI of the MI355X (gfx950) linear-attention library.
+ *
+ * The operator is the non-causal linear attention that LinVideo puts in place of
+ * softmax attention in a video diffusion transformer (paper Sec. 3):
+ *
+ *   Eq. 3:  o_i = phi(q_i) S / (phi(q_i) . z),   S = sum_j phi(k_j)^T v_j,  z = sum_j phi(k_j)
+ *   Eq. 5:  phi(x) = softmax(x W~) (+) softmax(-x W~),  W~ in R^{d x d/2}, one W~ for q, one for k
+ *
+ * evaluated independently for every (batch, head) pair over all n tokens (no mask, no
+ * scaling of q.k, no epsilon: every entry of phi is positive so the denominator is too).
+ *
+ * Conventions shared by every entry point
+ *   - q, k, v, out, dout, dq, dk, dv: DEVICE pointers, [B, H, n, d] contiguous, d innermost,
+ *     16-byte aligned.  d in {64, 128}, n >= 1 arbitrary, B, H >= 1, 64-bit indexing inside.
+ *   - element type of those tensors and of W~ is the descriptor's dtype (bf16 or fp32).
+ *     All accumulation is fp32.  The fp32 mode never rounds through bf16.
+ *   - all pointers are borrowed: the caller keeps them alive until the stream work is done.
+ *   - calls only enqueue work on `stream` (a hipStream_t passed as void*, NULL = default
+ *     stream).  They never synchronise and never allocate.
+ *   - every argument error is detected on the host before any HIP call and returned as a
+ *     negative status; nothing is enqueued in that case.
+ *   - results are bitwise reproducible run to run (no floating-point atomics).
+ *   - out must not alias q, k or v; dq, dk, dv must not alias any input.
+ *   - calls that share a descriptor share its workspace: do not overlap them on
+ *     different streams.
+ */
+#ifndef LINATTN_H
+#define LINATTN_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* status codes */
+#define LINATTN_OK            0
+#define LINATTN_E_NULL       -1   /* a required pointer is NULL */
+#define LINATTN_E_SHAPE      -2   /* B, H, n <= 0, unsupported d, shape differs from the descriptor, or too large */
+#define LINATTN_E_DTYPE      -3   /* unknown dtype */
+#define LINATTN_E_ALIGN      -4   /* a tensor pointer is not 16-byte aligned */
+#define LINATTN_E_PHI        -5   /* unknown phi_id / unsupported kind / table full */
+#define LINATTN_E_WORKSPACE  -6   /* workspace missing or smaller than linattn_workspace_bytes() */
+#define LINATTN_E_HIP        -7   /* a HIP launch reported an error */
+#define LINATTN_E_STATE      -8   /* linattn_bwd needs the descriptor's state buffer */
+#define LINATTN_E_ALIAS      -9   /* an output aliases an input */
+
+/* feature-map kinds */
+#define LINATTN_PHI_HEDGEHOG  1   /* Eq. 5 */
+
+/* dtypes */
+#define LINATTN_BF16  1
+#define LINATTN_F32   2
+
+/*
+ * Description of a feature map plus the buffers a layer owns.  Eq. 3 takes q, k, v only;
+ * Eq. 5 adds the two learnable matrices, which live here so that linattn_fwd keeps the
+ * paper's argument list.  The struct is copied by linattn_phi_create.
+ */
+typedef struct linattn_phi_desc {
+  int kind;               /* LINATTN_PHI_HEDGEHOG */
+  int dtype;              /* LINATTN_BF16 or LINATTN_F32: type of q,k,v,out,dout,dq,dk,dv,wq,wk */
+  int H, d;               /* wq, wk: device, [H, d, d/2] contiguous, one map per head (Eq. 5) */
+  const void *wq, *wk;
+  void *dwq, *dwk;        /* optional device fp32 [H, d, d/2]: linattn_bwd OVERWRITES them with the
+                             gradient summed over batch and tokens; NULL = not computed */
+  void *state;            /* optional device fp32 [B, H, d+1, d]: rows 0..d-1 = S with rows indexed by
+                             the feature of phi in the order of Eq. 5 (softmax(+) half first),
+                             row d = z.  linattn_fwd writes it when non-NULL; linattn_bwd reads it. */
+  void *workspace;        /* device scratch, 256-byte aligned, >= linattn_workspace_bytes(...) */
+  size_t workspace_bytes;
+} linattn_phi_desc;
+
+/* Register a descriptor; *phi_id_out receives a handle >= 16.  Host-only, no HIP call.
+ * Errors: E_NULL (desc, out, wq, wk), E_PHI (kind, table full), E_DTYPE, E_SHAPE (H, d), E_ALIGN. */
+int linattn_phi_create(const linattn_phi_desc* desc, int* phi_id_out);
+
+/* Forget a handle.  E_PHI if it is not live.  Buffers stay the caller's. */
+int linattn_phi_destroy(int phi_id);
+
+/* Scratch bytes linattn_fwd / linattn_bwd need for this problem (pure function of its
+ * arguments, no HIP call).  Returns 0 for an invalid argument. */
+size_t linattn_workspace_bytes(int B, int H, int n, int d, int kind, int dtype);
+
+/*
+ * Forward, Eq. 3 with phi of Eq. 5.  Three stages on `stream`: phi(K) fused with a split-n
+ * partial state, a fixed-order reduction of the partials, phi(Q) S / (phi(Q) . z) with the
+ * store of out.  Writes out [B,H,n,d] and, if the descriptor has one, state.
+ * Errors: E_PHI, E_NULL, E_SHAPE (also H or d different from the descriptor), E_ALIGN,
+ * E_WORKSPACE, E_ALIAS, E_HIP.
+ */
+int linattn_fwd(const void* q, const void* k, const void* v, void* out,
+                int B, int H, int n, int d, int phi_id, void* stream);
+
+/*
+ * Backward of linattn_fwd for L with dL/dout = dout: writes dq, dk, dv [B,H,n,d] and, if the
+ * descriptor has them, dwq and dwk.  Needs the state a forward call with the same q-independent
+ * inputs (k, v, wk) left in the descriptor's state buffer.
+ * Errors: as linattn_fwd, plus E_STATE.
+ */
+int linattn_bwd(const void* q, const void* k, const void* v, const void* dout,
+                void* dq, void* dk, void* dv,
+                int B, int H, int n, int d, int phi_id, void* stream);
+
+/*
+ * Optional instrumentation for benchmarks (the paper reports end-to-end latency only, Sec. 5.2;
+ * per-stage times are what the roofline accounting of this library needs).  `events` points to
+ * four hipEvent_t (passed as void*) created by the caller; from then on every linattn_fwd records
+ * events[0] before its first stage and events[1..3] after the state pass, the reduction, and the
+ * query pass, on the call's stream.  NULL switches it off (the default).  Process-wide and not
+ * thread-safe; the caller keeps the events alive while they are set.  Always returns LINATTN_OK.
+ */
+int linattn_set_stage_events(void* const* events);
+
+/* Static description of a status code. */
+const char* linattn_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LINATTN_H */

@@ -1,0 +1,215 @@
+// Host side of the C ABI: descriptor table, argument validation, launch plan, dispatch.
+// Every check happens before the first HIP call, so the error paths run on a machine
+// with no GPU.
+#include "../../include/linattn.h"
+#include "kernels.h"
+
+#include <mutex>
+#include <cstring>
+
+namespace linattn {
+
+bool make_plan(int B, int H, int n, int d, int dtype, Plan* p) {
+  if (B <= 0 || H <= 0 || n <= 0) return false;
+  if (d != 64 && d != 128) return false;
+  if (dtype != LINATTN_BF16 && dtype != LINATTN_F32) return false;
+  const long long BH = (long long)B * H;
+  if (BH > 65535) return false;                       // grid.y
+  if ((long long)n > (1LL << 30)) return false;
+  Plan r{};
+  r.B = B; r.H = H; r.n = n; r.d = d; r.BH = (int)BH;
+  const int tiles = (n + kTile - 1) / kTile;
+  int P = kSlots / (int)BH;
+  if (P < 1) P = 1;
+  if (P > tiles) P = tiles;
+  int tiles_per = (tiles + P - 1) / P;
+  r.chunk = tiles_per * kTile;
+  r.P = (n + r.chunk - 1) / r.chunk;
+  r.QP = r.P;
+  r.qchunk = r.chunk;
+  r.state_elems = (size_t)(d + 1) * d;
+  // packed operand image: (d/16 k-steps) x (d/32 channel blocks + 1 normaliser block) x 64 lanes x 8
+  r.sa_elems = (size_t)(d / 16) * (d / 32 + 1) * 64 * 8;
+  auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  size_t off = 0;
+  r.off_partials = off; off = up(off + (size_t)BH * r.P * r.state_elems * sizeof(float));
+  r.off_state = off;    off = up(off + (size_t)BH * r.state_elems * sizeof(float));
+  r.off_sa = off;
+  if (dtype == LINATTN_BF16) off = up(off + (size_t)BH * r.sa_elems * 2);
+  r.total_bytes = off;
+  *p = r;
+  return true;
+}
+
+namespace {
+
+constexpr int kFirstId = 16;
+constexpr int kMaxDesc = 1024;
+
+struct Slot {
+  bool live = false;
+  linattn_phi_desc d{};
+};
+
+Slot g_slots[kMaxDesc];
+std::mutex g_mu;
+hipEvent_t g_stage_events[4];
+bool g_stage_events_on = false;
+
+inline void mark(int i, hipStream_t s) {
+  if (g_stage_events_on) (void)hipEventRecord(g_stage_events[i], s);
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool overlaps(const void* a, const void* b, size_t bytes) {
+  const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+  return x < y + bytes && y < x + bytes;
+}
+
+int fetch(int phi_id, linattn_phi_desc* out) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  const int i = phi_id - kFirstId;
+  if (i < 0 || i >= kMaxDesc || !g_slots[i].live) return LINATTN_E_PHI;
+  *out = g_slots[i].d;
+  return LINATTN_OK;
+}
+
+// Checks common to forward and backward.  Fills desc and plan.
+int check_call(const void* const* tensors, int n_tensors, int B, int H, int n, int d, int phi_id,
+               linattn_phi_desc* desc, Plan* plan) {
+  int st = fetch(phi_id, desc);
+  if (st != LINATTN_OK) return st;
+  for (int i = 0; i < n_tensors; ++i)
+    if (!tensors[i]) return LINATTN_E_NULL;
+  if (H != desc->H || d != desc->d) return LINATTN_E_SHAPE;
+  if (!make_plan(B, H, n, d, desc->dtype, plan)) return LINATTN_E_SHAPE;
+  for (int i = 0; i < n_tensors; ++i)
+    if (!aligned16(tensors[i])) return LINATTN_E_ALIGN;
+  if (!desc->workspace || desc->workspace_bytes < plan->total_bytes) return LINATTN_E_WORKSPACE;
+  return LINATTN_OK;
+}
+
+}  // namespace
+}  // namespace linattn
+
+using namespace linattn;
+
+extern "C" {
+
+const char* linattn_strerror(int status) {
+  switch (status) {
+    case LINATTN_OK: return "ok";
+    case LINATTN_E_NULL: return "a required pointer is NULL";
+    case LINATTN_E_SHAPE: return "unsupported or inconsistent shape (B,H,n >= 1; d in {64,128}; H,d as in the descriptor)";
+    case LINATTN_E_DTYPE: return "unknown dtype";
+    case LINATTN_E_ALIGN: return "tensor pointer is not 16-byte aligned (workspace: 256)";
+    case LINATTN_E_PHI: return "unknown phi_id, unsupported feature-map kind, or descriptor table full";
+    case LINATTN_E_WORKSPACE: return "workspace missing or smaller than linattn_workspace_bytes()";
+    case LINATTN_E_HIP: return "a HIP launch failed";
+    case LINATTN_E_STATE: return "linattn_bwd needs the descriptor's state buffer";
+    case LINATTN_E_ALIAS: return "an output aliases an input";
+    default: return "unknown status";
+  }
+}
+
+int linattn_set_stage_events(void* const* events) {
+  g_stage_events_on = events != nullptr;
+  if (events)
+    for (int i = 0; i < 4; ++i) g_stage_events[i] = static_cast<hipEvent_t>(events[i]);
+  return LINATTN_OK;
+}
+
+size_t linattn_workspace_bytes(int B, int H, int n, int d, int kind, int dtype) {
+  if (kind != LINATTN_PHI_HEDGEHOG) return 0;
+  Plan p;
+  if (!make_plan(B, H, n, d, dtype, &p)) return 0;
+  return p.total_bytes;
+}
+
+int linattn_phi_create(const linattn_phi_desc* desc, int* phi_id_out) {
+  if (!desc || !phi_id_out) return LINATTN_E_NULL;
+  if (desc->kind != LINATTN_PHI_HEDGEHOG) return LINATTN_E_PHI;
+  if (desc->dtype != LINATTN_BF16 && desc->dtype != LINATTN_F32) return LINATTN_E_DTYPE;
+  if (desc->H <= 0 || (desc->d != 64 && desc->d != 128)) return LINATTN_E_SHAPE;
+  if (!desc->wq || !desc->wk) return LINATTN_E_NULL;
+  if (!aligned16(desc->wq) || !aligned16(desc->wk)) return LINATTN_E_ALIGN;
+  if (desc->dwq && !aligned16(desc->dwq)) return LINATTN_E_ALIGN;
+  if (desc->dwk && !aligned16(desc->dwk)) return LINATTN_E_ALIGN;
+  if (desc->state && !aligned16(desc->state)) return LINATTN_E_ALIGN;
+  if (desc->workspace && (reinterpret_cast<uintptr_t>(desc->workspace) & 255u)) return LINATTN_E_ALIGN;
+  std::lock_guard<std::mutex> lk(g_mu);
+  for (int i = 0; i < kMaxDesc; ++i) {
+    if (!g_slots[i].live) {
+      g_slots[i].live = true;
+      g_slots[i].d = *desc;
+      *phi_id_out = kFirstId + i;
+      return LINATTN_OK;
+    }
+  }
+  return LINATTN_E_PHI;
+}
+
+int linattn_phi_destroy(int phi_id) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  const int i = phi_id - kFirstId;
+  if (i < 0 || i >= kMaxDesc || !g_slots[i].live) return LINATTN_E_PHI;
+  g_slots[i].live = false;
+  return LINATTN_OK;
+}
+
+int linattn_fwd(const void* q, const void* k, const void* v, void* out,
+                int B, int H, int n, int d, int phi_id, void* stream) {
+  linattn_phi_desc desc;
+  Plan plan;
+  const void* tensors[4] = {q, k, v, out};
+  int st = check_call(tensors, 4, B, H, n, d, phi_id, &desc, &plan);
+  if (st != LINATTN_OK) return st;
+  const size_t esz = desc.dtype == LINATTN_BF16 ? 2 : 4;
+  const size_t bytes = (size_t)plan.BH * n * d * esz;
+  if (overlaps(out, q, bytes) || overlaps(out, k, bytes) || overlaps(out, v, bytes)) return LINATTN_E_ALIAS;
+
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(desc.workspace);
+  float* partials = reinterpret_cast<float*>(ws + plan.off_partials);
+  float* state = desc.state ? static_cast<float*>(desc.state) : reinterpret_cast<float*>(ws + plan.off_state);
+  hipError_t e;
+  mark(0, s);
+  if (desc.dtype == LINATTN_F32) {
+    e = launch_state_partials_f32((const float*)k, (const float*)v, (const float*)desc.wk, partials, plan, s);
+    if (e != hipSuccess) return LINATTN_E_HIP;
+    mark(1, s);
+    e = launch_state_reduce(partials, state, nullptr, plan, s);
+    if (e != hipSuccess) return LINATTN_E_HIP;
+    mark(2, s);
+    e = launch_apply_f32((const float*)q, (const float*)desc.wq, state, (float*)out, plan, s);
+    if (e != hipSuccess) return LINATTN_E_HIP;
+  } else {
+    void* sa = ws + plan.off_sa;
+    e = launch_state_partials_bf16(k, v, desc.wk, partials, plan, s);
+    if (e != hipSuccess) return LINATTN_E_HIP;
+    mark(1, s);
+    e = launch_state_reduce(partials, state, sa, plan, s);
+    if (e != hipSuccess) return LINATTN_E_HIP;
+    mark(2, s);
+    e = launch_apply_bf16(q, desc.wq, sa, out, plan, s);
+    if (e != hipSuccess) return LINATTN_E_HIP;
+  }
+  mark(3, s);
+  return LINATTN_OK;
+}
+
+int linattn_bwd(const void* q, const void* k, const void* v, const void* dout,
+                void* dq, void* dk, void* dv,
+                int B, int H, int n, int d, int phi_id, void* stream) {
+  linattn_phi_desc desc;
+  Plan plan;
+  const void* tensors[7] = {q, k, v, dout, dq, dk, dv};
+  int st = check_call(tensors, 7, B, H, n, d, phi_id, &desc, &plan);
+  if (st != LINATTN_OK) return st;
+  if (!desc.state) return LINATTN_E_STATE;
+  (void)stream;
+  return LINATTN_E_PHI;  // backward kernels are not built yet
+}
+
+}  // extern "C"

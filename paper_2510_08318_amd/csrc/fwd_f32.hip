@@ -1,0 +1,215 @@
+// fp32 forward path (no bf16 anywhere): plain-FMA, LDS-tiled kernels.
+// This mode exists for the 1e-5 accuracy contract on fp32 tensors; the bandwidth-tuned
+// path is the bf16 one in fwd_bf16.hip.
+#include "kernels.h"
+
+namespace linattn {
+namespace {
+
+constexpr int TT = 32;        // tokens per tile
+constexpr int NT = 256;       // threads per workgroup
+
+__device__ __forceinline__ float wave_max(float x) {
+  for (int m = 32; m >= 1; m >>= 1) x = fmaxf(x, __shfl_xor(x, m, 64));
+  return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+  for (int m = 32; m >= 1; m >>= 1) x += __shfl_xor(x, m, 64);
+  return x;
+}
+
+// Eq. 5 on a tile: sX [TT][D+1] holds the tokens, sW [D][D/2] the map; on return
+// sPhi [TT][D] holds softmax(u) then softmax(-u) per token, rows >= n_valid are zero.
+// Contains __syncthreads(); every thread of the workgroup must call it.
+template <int D>
+__device__ __forceinline__ void phi_tile(const float* sX, const float* sW, float* sPhi, int tid, int n_valid) {
+  constexpr int HALF = D / 2;
+  {
+    const int tt = tid % TT, fb = tid / TT;      // fb in 0..7
+    float u[HALF / 8];
+#pragma unroll
+    for (int j = 0; j < HALF / 8; ++j) u[j] = 0.f;
+    for (int c = 0; c < D; ++c) {
+      const float x = sX[tt * (D + 1) + c];
+#pragma unroll
+      for (int j = 0; j < HALF / 8; ++j) u[j] = fmaf(x, sW[c * HALF + fb + 8 * j], u[j]);
+    }
+#pragma unroll
+    for (int j = 0; j < HALF / 8; ++j) sPhi[tt * D + fb + 8 * j] = u[j];
+  }
+  __syncthreads();
+  {
+    const int w = tid / 64, lane = tid % 64;
+    for (int i = 0; i < TT / 4; ++i) {
+      const int tt = w * (TT / 4) + i;
+      const float x = sPhi[tt * D + (lane % HALF)];
+      const float mx = wave_max(x);
+      const float mn = -wave_max(-x);
+      const float ep = expf(x - mx);
+      const float em = expf(mn - x);
+      float sp = wave_sum(ep), sm = wave_sum(em);
+      if (HALF == 32) { sp *= 0.5f; sm *= 0.5f; }   // both half-waves hold the same 32 features
+      const bool valid = tt < n_valid;
+      if (lane < HALF) {
+        sPhi[tt * D + lane] = valid ? ep / sp : 0.f;
+        sPhi[tt * D + HALF + lane] = valid ? em / sm : 0.f;
+      }
+    }
+  }
+  __syncthreads();
+}
+
+template <int D>
+__global__ __launch_bounds__(NT) void state_partials_f32_kernel(const float* __restrict__ k, const float* __restrict__ v,
+                                                                const float* __restrict__ wk, float* __restrict__ partials,
+                                                                int H, int n, int P, int chunk) {
+  constexpr int HALF = D / 2;
+  constexpr int BLK = D / 16;
+  extern __shared__ float smem[];
+  float* sW = smem;
+  float* sX = sW + D * HALF;
+  float* sV = sX + TT * (D + 1);
+  float* sPhi = sV + TT * D;
+
+  const int tid = threadIdx.x;
+  const int bh = blockIdx.y, p = blockIdx.x, h = bh % H;
+  const int t_begin = p * chunk;
+  const int t_end = min(n, t_begin + chunk);
+  const float* kb = k + (size_t)bh * n * D;
+  const float* vb = v + (size_t)bh * n * D;
+  const float* wb = wk + (size_t)h * D * HALF;
+  for (int i = tid; i < D * HALF; i += NT) sW[i] = wb[i];
+
+  float acc[BLK][BLK];
+#pragma unroll
+  for (int i = 0; i < BLK; ++i)
+#pragma unroll
+    for (int j = 0; j < BLK; ++j) acc[i][j] = 0.f;
+  float zacc = 0.f;
+  const int f0 = (tid / 16) * BLK, c0 = (tid % 16) * BLK;
+
+  for (int t0 = t_begin; t0 < t_end; t0 += TT) {
+    __syncthreads();
+    for (int i = tid; i < TT * D; i += NT) {
+      const int tt = i / D, c = i % D;
+      const int t = t0 + tt;
+      const bool valid = t < t_end;
+      sX[tt * (D + 1) + c] = valid ? kb[(size_t)t * D + c] : 0.f;
+      sV[tt * D + c] = valid ? vb[(size_t)t * D + c] : 0.f;
+    }
+    __syncthreads();
+    phi_tile<D>(sX, sW, sPhi, tid, t_end - t0);
+    for (int tt = 0; tt < TT; ++tt) {
+      float a[BLK], b[BLK];
+#pragma unroll
+      for (int i = 0; i < BLK; ++i) a[i] = sPhi[tt * D + f0 + i];
+#pragma unroll
+      for (int j = 0; j < BLK; ++j) b[j] = sV[tt * D + c0 + j];
+#pragma unroll
+      for (int i = 0; i < BLK; ++i)
+#pragma unroll
+        for (int j = 0; j < BLK; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    }
+    if (tid < D)
+      for (int tt = 0; tt < TT; ++tt) zacc += sPhi[tt * D + tid];
+  }
+
+  float* dst = partials + ((size_t)bh * P + p) * (size_t)(D + 1) * D;
+#pragma unroll
+  for (int i = 0; i < BLK; ++i)
+#pragma unroll
+    for (int j = 0; j < BLK; ++j) dst[(f0 + i) * D + c0 + j] = acc[i][j];
+  if (tid < D) dst[D * D + tid] = zacc;
+}
+
+template <int D>
+__global__ __launch_bounds__(NT) void apply_f32_kernel(const float* __restrict__ q, const float* __restrict__ wq,
+                                                       const float* __restrict__ state, float* __restrict__ out,
+                                                       int H, int n, int chunk) {
+  constexpr int HALF = D / 2;
+  extern __shared__ float smem[];
+  float* sW = smem;
+  float* sS = sW + D * HALF;            // [(D+1)][D]
+  float* sX = sS + (D + 1) * D;
+  float* sPhi = sX + TT * (D + 1);
+
+  const int tid = threadIdx.x;
+  const int bh = blockIdx.y, p = blockIdx.x, h = bh % H;
+  const int t_begin = p * chunk;
+  const int t_end = min(n, t_begin + chunk);
+  const float* qb = q + (size_t)bh * n * D;
+  float* ob = out + (size_t)bh * n * D;
+  const float* wb = wq + (size_t)h * D * HALF;
+  const float* sb = state + (size_t)bh * (D + 1) * D;
+  for (int i = tid; i < D * HALF; i += NT) sW[i] = wb[i];
+  for (int i = tid; i < (D + 1) * D; i += NT) sS[i] = sb[i];
+
+  const int tt = tid / 8, cb = tid % 8;
+  for (int t0 = t_begin; t0 < t_end; t0 += TT) {
+    __syncthreads();
+    for (int i = tid; i < TT * D; i += NT) {
+      const int r = i / D, c = i % D;
+      const int t = t0 + r;
+      sX[r * (D + 1) + c] = (t < t_end) ? qb[(size_t)t * D + c] : 0.f;
+    }
+    __syncthreads();
+    phi_tile<D>(sX, sW, sPhi, tid, t_end - t0);
+    float acc[D / 8];
+#pragma unroll
+    for (int j = 0; j < D / 8; ++j) acc[j] = 0.f;
+    float den = 0.f;
+    for (int f = 0; f < D; ++f) {
+      const float a = sPhi[tt * D + f];
+      den = fmaf(a, sS[D * D + f], den);
+#pragma unroll
+      for (int j = 0; j < D / 8; ++j) acc[j] = fmaf(a, sS[f * D + cb + 8 * j], acc[j]);
+    }
+    const int t = t0 + tt;
+    if (t < t_end) {
+      const float inv = 1.0f / den;
+#pragma unroll
+      for (int j = 0; j < D / 8; ++j) ob[(size_t)t * D + cb + 8 * j] = acc[j] * inv;
+    }
+  }
+}
+
+template <int D>
+constexpr size_t state_smem() { return sizeof(float) * (D * (D / 2) + TT * (D + 1) + TT * D + TT * D); }
+template <int D>
+constexpr size_t apply_smem() { return sizeof(float) * (D * (D / 2) + (D + 1) * D + TT * (D + 1) + TT * D); }
+
+}  // namespace
+
+hipError_t launch_state_partials_f32(const float* k, const float* v, const float* wk, float* partials,
+                                     const Plan& p, hipStream_t s) {
+  dim3 grid(p.P, p.BH), block(NT);
+  hipError_t e;
+  if (p.d == 128) {
+    e = hipFuncSetAttribute((const void*)state_partials_f32_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)state_smem<128>());
+    if (e != hipSuccess) return e;
+    state_partials_f32_kernel<128><<<grid, block, state_smem<128>(), s>>>(k, v, wk, partials, p.H, p.n, p.P, p.chunk);
+  } else {
+    e = hipFuncSetAttribute((const void*)state_partials_f32_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)state_smem<64>());
+    if (e != hipSuccess) return e;
+    state_partials_f32_kernel<64><<<grid, block, state_smem<64>(), s>>>(k, v, wk, partials, p.H, p.n, p.P, p.chunk);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_apply_f32(const float* q, const float* wq, const float* state, float* out,
+                            const Plan& p, hipStream_t s) {
+  dim3 grid(p.QP, p.BH), block(NT);
+  hipError_t e;
+  if (p.d == 128) {
+    e = hipFuncSetAttribute((const void*)apply_f32_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)apply_smem<128>());
+    if (e != hipSuccess) return e;
+    apply_f32_kernel<128><<<grid, block, apply_smem<128>(), s>>>(q, wq, state, out, p.H, p.n, p.qchunk);
+  } else {
+    e = hipFuncSetAttribute((const void*)apply_f32_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)apply_smem<64>());
+    if (e != hipSuccess) return e;
+    apply_f32_kernel<64><<<grid, block, apply_smem<64>(), s>>>(q, wq, state, out, p.H, p.n, p.qchunk);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace linattn

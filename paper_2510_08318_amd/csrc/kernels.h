@@ -1,0 +1,50 @@
+// Internal interface between the host dispatch (api.cpp) and the gfx950 kernels.
+// Nothing here is exported from the shared library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace linattn {
+
+// Tokens a workgroup of the bf16 kernels consumes per iteration (4 waves x 32 tokens).
+constexpr int kTile = 128;
+// Workgroup slots the split-n plan aims to fill: 256 compute units x 2 resident workgroups.
+constexpr int kSlots = 512;
+
+// How one call is cut into workgroups and where its scratch regions sit in the workspace.
+struct Plan {
+  int B, H, n, d;
+  int BH;
+  int P;            // split-n factor of the state pass (partials per (b,h))
+  int chunk;        // tokens per split, a multiple of kTile
+  int QP;           // splits of the query pass
+  int qchunk;
+  size_t state_elems;     // (d+1)*d
+  size_t sa_elems;        // 16-bit elements of the packed MFMA operand image of one (b,h) state
+  size_t off_partials;    // fp32 [BH][P][(d+1)*d]
+  size_t off_state;       // fp32 [BH][(d+1)*d]   (used when the caller gave no state buffer)
+  size_t off_sa;          // fp16 [BH][sa_elems]  (bf16 mode only)
+  size_t total_bytes;
+};
+
+// Pure host arithmetic; returns false if the shape is unsupported or overflows.
+bool make_plan(int B, int H, int n, int d, int dtype, Plan* p);
+
+// ---- forward launchers (enqueue only) ---------------------------------------------------
+// phi(K) fused with the split-n partial state (Eq. 5 + the two sums of Eq. 3).
+hipError_t launch_state_partials_f32(const float* k, const float* v, const float* wk, float* partials,
+                                     const Plan& p, hipStream_t s);
+hipError_t launch_state_partials_bf16(const void* k, const void* v, const void* wk, float* partials,
+                                      const Plan& p, hipStream_t s);
+// Fixed-order sum of the partials into the exported state layout [BH][d+1][d] fp32,
+// and (bf16 mode) the packed operand image the query pass feeds to MFMA.
+hipError_t launch_state_reduce(const float* partials, float* state, void* sa /*nullable*/,
+                               const Plan& p, hipStream_t s);
+// phi(Q) S / (phi(Q) . z) and the store of out (Eq. 3, right-hand side).
+hipError_t launch_apply_f32(const float* q, const float* wq, const float* state, float* out,
+                            const Plan& p, hipStream_t s);
+hipError_t launch_apply_bf16(const void* q, const void* wq, const void* sa, void* out,
+                             const Plan& p, hipStream_t s);
+
+}  // namespace linattn

@@ -15,6 +15,8 @@ N(0,1) because trained ones are not available.
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field
 from typing import Dict, List, Optional
 
@@ -140,16 +142,29 @@ def generate(name: str, *, n: Optional[int] = None, H: Optional[int] = None,
         n_out = int(np.ceil(cfg.outlier_frac * n_)) if cfg.outlier_frac > 0 else 0
         rows = np.sort(g_out.choice(n_, size=n_out, replace=False)) if n_out else np.zeros(0, np.int64)
         outlier_rows.append(rows)
+        # one child stream per (tensor, head): heads can be drawn in parallel and a head's
+        # values do not depend on how many heads are generated
+        jobs = []
         for ti, (gen, dst) in enumerate(((g_q, q), (g_k, k), (g_v, v))):
-            for h in range(H_):
-                x = gen.standard_normal((n_, d_), dtype=np.float32)
-                x *= inv_sqrt_d * scales[ti, h]
-                if n_out:
-                    x[rows] *= np.float32(20.0)
-                dst[b, h] = _pack(x, dt)
+            for h, child in enumerate(gen.spawn(H_)):
+                jobs.append((child, dst, h, inv_sqrt_d * scales[ti, h], True))
         if want_dout:
-            for h in range(H_):
-                g = g_do.standard_normal((n_, d_), dtype=np.float32) * np.float32(0.1)
-                dout[b, h] = _pack(g, dt)
+            for h, child in enumerate(g_do.spawn(H_)):
+                jobs.append((child, dout, h, np.float32(0.1), False))
+
+        def draw(job, b=b, rows=rows, n_out=n_out):
+            child, dst, h, mul, outliers = job
+            x = child.standard_normal((n_, d_), dtype=np.float32)
+            x *= mul
+            if outliers and n_out:
+                x[rows] *= np.float32(20.0)
+            dst[b, h] = _pack(x, dt)
+
+        if len(jobs) * n_ * d_ > (1 << 22):
+            with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
+                list(ex.map(draw, jobs))
+        else:
+            for j in jobs:
+                draw(j)
 
     return Inputs(cfg, B_, H_, n_, d_, dt, q, k, v, wq, wk, dout, outlier_rows)

@@ -1,0 +1,84 @@
+"""PyTorch as plumbing: device buffers and the current stream for the C-ABI calls.
+
+Nothing of the operator is computed here; `Layer` owns the buffers a converted attention layer
+needs (W~_q, W~_k, state, workspace), registers them as a phi descriptor and forwards to
+linattn_fwd / linattn_bwd.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as B_
+
+
+def to_device(stored: np.ndarray, device="cuda") -> torch.Tensor:
+    """Stored numpy tensor (float32, or uint16 bf16 bit patterns) -> device tensor of that dtype."""
+    if stored.dtype == np.uint16:
+        return torch.from_numpy(stored.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(stored, dtype=np.float32)).to(device)
+
+
+def to_host_f64(t: torch.Tensor) -> np.ndarray:
+    """Device tensor -> fp64 numpy (exact widening)."""
+    return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+class Layer:
+    """Buffers + descriptor of one linear-attention layer (Eq. 3 with the map of Eq. 5)."""
+
+    def __init__(self, wq: torch.Tensor, wk: torch.Tensor, B: int, n: int, *, keep_state: bool = True,
+                 want_wgrads: bool = False):
+        assert wq.is_cuda and wk.is_cuda and wq.dtype == wk.dtype and wq.shape == wk.shape
+        self.H, self.d, half = wq.shape
+        assert half * 2 == self.d
+        self.dtype = B_.BF16 if wq.dtype == torch.bfloat16 else B_.F32
+        assert wq.dtype in (torch.bfloat16, torch.float32)
+        self.wq, self.wk = wq.contiguous(), wk.contiguous()
+        self.B, self.n = B, n
+        dev = wq.device
+        self.state = torch.empty((B, self.H, self.d + 1, self.d), dtype=torch.float32, device=dev) if keep_state else None
+        self.dwq = torch.empty((self.H, self.d, half), dtype=torch.float32, device=dev) if want_wgrads else None
+        self.dwk = torch.empty((self.H, self.d, half), dtype=torch.float32, device=dev) if want_wgrads else None
+        self.workspace_bytes = B_.linattn_workspace_bytes(B, self.H, n, self.d, B_.PHI_HEDGEHOG, self.dtype)
+        if self.workspace_bytes == 0:
+            raise ValueError("unsupported shape")
+        self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=dev)
+        assert self.workspace.data_ptr() % 256 == 0
+        self.phi_id = B_.linattn_phi_create(B_.PHI_HEDGEHOG, self.dtype, self.H, self.d, self.wq, self.wk,
+                                            self.dwq, self.dwk, self.state, self.workspace, self.workspace_bytes)
+
+    def close(self):
+        if self.phi_id is not None:
+            B_.linattn_phi_destroy(self.phi_id)
+            self.phi_id = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _stream(self):
+        return torch.cuda.current_stream().cuda_stream
+
+    def forward(self, q, k, v, out=None):
+        Bq, H, n, d = q.shape
+        assert (Bq, H, n, d) == (self.B, self.H, self.n, self.d)
+        for t in (q, k, v):
+            assert t.is_cuda and t.is_contiguous() and t.dtype == self.wq.dtype and t.shape == q.shape
+        if out is None:
+            out = torch.empty_like(q)
+        B_.linattn_fwd(q, k, v, out, Bq, H, n, d, self.phi_id, self._stream())
+        return out
+
+    def backward(self, q, k, v, dout, dq=None, dk=None, dv=None):
+        Bq, H, n, d = q.shape
+        assert (Bq, H, n, d) == (self.B, self.H, self.n, self.d)
+        for t in (q, k, v, dout):
+            assert t.is_cuda and t.is_contiguous() and t.dtype == self.wq.dtype and t.shape == q.shape
+        dq = torch.empty_like(q) if dq is None else dq
+        dk = torch.empty_like(q) if dk is None else dk
+        dv = torch.empty_like(q) if dv is None else dv
+        B_.linattn_bwd(q, k, v, dout, dq, dk, dv, Bq, H, n, d, self.phi_id, self._stream())
+        return dq, dk, dv

@@ -1,0 +1,126 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports every symbol the
+header declares, and rejects bad arguments before any HIP call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2510_08318_amd import binding as L
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+# A fake, suitably aligned "device address": argument checks never dereference it.
+P = 0x10000000
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "linattn.h")).read()
+    declared = set(re.findall(r"\b(linattn_[a-z_]+)\s*\(", header))
+    assert declared == set(L.EXPORTS)
+    lib = L.lib()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_header_constants_match_binding():
+    header = open(os.path.join(ROOT, "include", "linattn.h")).read()
+    consts = dict((m.group(1), int(m.group(2))) for m in re.finditer(r"#define\s+LINATTN_(\w+)\s+(-?\d+)", header))
+    for name in ("OK", "E_NULL", "E_SHAPE", "E_DTYPE", "E_ALIGN", "E_PHI", "E_WORKSPACE", "E_HIP", "E_STATE",
+                 "E_ALIAS", "PHI_HEDGEHOG", "BF16", "F32"):
+        assert consts[name] == getattr(L, name), name
+    for code in range(0, -10, -1):
+        assert L.linattn_strerror(code) != "unknown status"
+    assert L.linattn_strerror(-99) == "unknown status"
+
+
+def test_workspace_bytes_is_pure_and_monotone():
+    w = L.linattn_workspace_bytes(1, 40, 75600, 128, L.PHI_HEDGEHOG, L.BF16)
+    assert w == L.linattn_workspace_bytes(1, 40, 75600, 128, L.PHI_HEDGEHOG, L.BF16)
+    # partials of at most 512 workgroups + state + operand image: tens of MB, not GB
+    assert 2_000_000 < w < 64_000_000
+    assert L.linattn_workspace_bytes(2, 40, 75600, 128, L.PHI_HEDGEHOG, L.BF16) >= w
+    assert w % 256 == 0
+    for bad in [(0, 1, 8, 64), (1, 0, 8, 64), (1, 1, 0, 64), (1, 1, 8, 32), (1, 1, 8, 96), (1, 1, -5, 128),
+                (70000, 1, 8, 64)]:
+        assert L.linattn_workspace_bytes(*bad, L.PHI_HEDGEHOG, L.BF16) == 0
+    assert L.linattn_workspace_bytes(1, 1, 8, 64, 7, L.BF16) == 0
+    assert L.linattn_workspace_bytes(1, 1, 8, 64, L.PHI_HEDGEHOG, 9) == 0
+
+
+def test_phi_create_rejects_bad_descriptors():
+    mk = lambda **kw: L.linattn_phi_create(**{**dict(kind=L.PHI_HEDGEHOG, dtype=L.BF16, H=2, d=64, wq=P, wk=P + 4096), **kw}, check=False)
+    assert mk(kind=3) == L.E_PHI
+    assert mk(dtype=5) == L.E_DTYPE
+    assert mk(H=0) == L.E_SHAPE
+    assert mk(d=48) == L.E_SHAPE
+    assert mk(wq=None) == L.E_NULL
+    assert mk(wk=None) == L.E_NULL
+    assert mk(wq=P + 2) == L.E_ALIGN
+    assert mk(state=P + 8) == L.E_ALIGN
+    assert mk(workspace=P + 128, workspace_bytes=1 << 20) == L.E_ALIGN
+    out = ctypes.c_int(0)
+    assert L.lib().linattn_phi_create(None, ctypes.byref(out)) == L.E_NULL
+    pid = mk()
+    assert pid >= 16
+    assert L.linattn_phi_destroy(pid, check=False) == L.OK
+    assert L.linattn_phi_destroy(pid, check=False) == L.E_PHI
+    assert L.linattn_phi_destroy(3, check=False) == L.E_PHI
+
+
+def test_fwd_rejects_bad_calls_before_touching_the_gpu():
+    B, H, n, d = 1, 2, 300, 64
+    ws = L.linattn_workspace_bytes(B, H, n, d, L.PHI_HEDGEHOG, L.BF16)
+    pid = L.linattn_phi_create(L.PHI_HEDGEHOG, L.BF16, H, d, P, P + 8192, workspace=P + (1 << 20), workspace_bytes=ws)
+    big = 1 << 24
+    q, k, v, o = P + 2 * big, P + 3 * big, P + 4 * big, P + 5 * big
+    f = lambda *a, **kw: L.linattn_fwd(*a, **kw, check=False)
+    try:
+        assert f(q, k, v, o, B, H, n, d, 5) == L.E_PHI
+        assert f(q, k, v, o, B, H, n, d, pid + 1) == L.E_PHI
+        assert f(None, k, v, o, B, H, n, d, pid) == L.E_NULL
+        assert f(q, k, v, None, B, H, n, d, pid) == L.E_NULL
+        assert f(q, k, v, o, B, H + 1, n, d, pid) == L.E_SHAPE
+        assert f(q, k, v, o, B, H, n, 128, pid) == L.E_SHAPE
+        assert f(q, k, v, o, B, H, 0, d, pid) == L.E_SHAPE
+        assert f(q, k, v, o, 0, H, n, d, pid) == L.E_SHAPE
+        assert f(q + 4, k, v, o, B, H, n, d, pid) == L.E_ALIGN
+        assert f(q, k, v, o + 8, B, H, n, d, pid) == L.E_ALIGN
+        assert f(q, k, v, q, B, H, n, d, pid) == L.E_ALIAS
+        assert f(q, k, v, v + 32, B, H, n, d, pid) == L.E_ALIAS
+        # a problem that needs more scratch than the descriptor has
+        assert f(q, k, v, o, 64, H, 100000, d, pid) == L.E_WORKSPACE
+        with pytest.raises(L.LinattnError) as ei:
+            L.linattn_fwd(q, k, v, o, B, H, n, d, 5)
+        assert ei.value.status == L.E_PHI
+    finally:
+        L.linattn_phi_destroy(pid)
+    pid2 = L.linattn_phi_create(L.PHI_HEDGEHOG, L.BF16, H, d, P, P + 8192)
+    try:
+        assert f(q, k, v, o, B, H, n, d, pid2) == L.E_WORKSPACE
+    finally:
+        L.linattn_phi_destroy(pid2)
+
+
+def test_bwd_rejects_bad_calls():
+    B, H, n, d = 1, 2, 300, 64
+    ws = L.linattn_workspace_bytes(B, H, n, d, L.PHI_HEDGEHOG, L.BF16)
+    pid = L.linattn_phi_create(L.PHI_HEDGEHOG, L.BF16, H, d, P, P + 8192, workspace=P + (1 << 20), workspace_bytes=ws)
+    big = 1 << 24
+    t = [P + (i + 2) * big for i in range(7)]
+    try:
+        assert L.linattn_bwd(*t, B, H, n, d, pid, check=False) == L.E_STATE
+        assert L.linattn_bwd(*t[:3], None, *t[4:], B, H, n, d, pid, check=False) == L.E_NULL
+        assert L.linattn_bwd(*t, B, H, n, d, 2, check=False) == L.E_PHI
+    finally:
+        L.linattn_phi_destroy(pid)
+
+
+def test_descriptor_table_reuses_slots():
+    ids = [L.linattn_phi_create(L.PHI_HEDGEHOG, L.F32, 1, 64, P, P) for _ in range(8)]
+    assert len(set(ids)) == 8
+    for i in ids:
+        L.linattn_phi_destroy(i)
+    again = L.linattn_phi_create(L.PHI_HEDGEHOG, L.F32, 1, 64, P, P)
+    assert again in ids
+    L.linattn_phi_destroy(again)
