@@ -27,6 +27,14 @@ bool make_plan(int B, int H, int n, int d, int dtype, Plan* p) {
   r.P = (n + r.chunk - 1) / r.chunk;
   r.QP = r.P;
   r.qchunk = r.chunk;
+  if (dtype == LINATTN_BF16) {
+    // query pass: 8-wavefront workgroups, one per compute unit, 32-token blocks dealt round-robin
+    const int nblk = (n + 31) / 32;
+    int QP = kCUs / (int)BH;
+    if (QP < 1) QP = 1;
+    if (QP > (nblk + 7) / 8) QP = (nblk + 7) / 8;
+    r.QP = QP;
+  }
   r.state_elems = (size_t)(d + 1) * d;
   // packed operand image: (d/16 k-steps) x (d/32 channel blocks + 1 normaliser block) x 64 lanes x 8
   r.sa_elems = (size_t)(d / 16) * (d / 32 + 1) * 64 * 8;

@@ -36,10 +36,28 @@ struct Cfg {
 
 // XOR swizzle of the 16-byte chunk index inside a tile row: makes the transposing 8-byte reads
 // (4 consecutive rows x 32 bytes per 16 lanes) and the 16-byte row writes hit distinct banks.
+// Depends on r % 16 only, so it is the same for every 16-row k-step of a tile.
 template <int D>
 __device__ __forceinline__ int swz(int r) {
   if (D == 128) return ((r & 3) << 2) | ((r >> 2) & 3);
-  return (((r & 3) << 1) ^ (r >> 2)) & 7;
+  return (((r & 3) << 1) ^ ((r >> 2) & 3)) & 7;
+}
+
+// A zero the optimiser cannot see through: added to an LDS index it keeps loop-invariant
+// operand reads inside the loop (hoisted, they would not fit the register file and spill).
+__device__ __forceinline__ int opaque_zero() {
+  int z = 0;
+  asm volatile("" : "+v"(z));
+  return z;
+}
+
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+// Streaming (non-temporal) 16-byte global load / store: every tensor byte is touched once.
+__device__ __forceinline__ uint4 ld_nt(const uint4* p) {
+  return __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p)));
+}
+__device__ __forceinline__ void st_nt(uint4* p, uint4 v) {
+  __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), reinterpret_cast<u32x4*>(p));
 }
 
 // Exchange with lane^32: returns (value of the low-half lane, value of the high-half lane),
@@ -53,10 +71,10 @@ __device__ __forceinline__ void pair32(float x, float& lo, float& hi) {
 
 // W~ [D][D/2] bf16 (one head) -> LDS image of the A operands of U^T = W~^T X^T:
 // entry (ks, mb, lane=(m,g)) holds W~[16ks + 8g + e][owned_row<HALF>(mb, m)], e = 0..7.
-template <int D>
+template <int D, int NTHREADS>
 __device__ __forceinline__ void build_w_image(const uint16_t* __restrict__ w, uint4* sWA, int tid) {
   using C = Cfg<D>;
-  for (int idx = tid; idx < C::W_IMG; idx += NT) {
+  for (int idx = tid; idx < C::W_IMG; idx += NTHREADS) {
     const int lane = idx % 64, mb = (idx / 64) % C::UM, ks = idx / (64 * C::UM);
     const int m = lane % 32, g = lane / 32;
     const int uf = owned_row<C::HALF>(mb, m);
@@ -84,12 +102,13 @@ __device__ __forceinline__ void phi_block(const uint4 (&xb)[Cfg<D>::UK], const u
   for (int mb = 0; mb < C::UM; ++mb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) u[mb][r] = 0.f;
+  const uint4* wa = sWA + lane + opaque_zero();
 #pragma unroll
   for (int ks = 0; ks < C::UK; ++ks) {
     const bf16x8 b = as_bf16x8(xb[ks]);
 #pragma unroll
     for (int mb = 0; mb < C::UM; ++mb) {
-      const bf16x8 a = as_bf16x8(sWA[(ks * C::UM + mb) * 64 + lane]);
+      const bf16x8 a = as_bf16x8(wa[(ks * C::UM + mb) * 64]);
       u[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, u[mb], 0, 0, 0);
     }
   }
@@ -101,65 +120,86 @@ __device__ __forceinline__ void phi_block(const uint4 (&xb)[Cfg<D>::UK], const u
   float lo, hi;
   pair32(mx, lo, hi); mx = fmaxf(lo, hi);
   pair32(mn, lo, hi); mn = fminf(lo, hi);
-  const float cpos = -mx * kLog2e, cneg = mn * kLog2e;
-  float ep[C::LOC], em[C::LOC];
-  float sp = 0.f, sm = 0.f;
+  // one softmax half at a time keeps only LOC exponentials live
 #pragma unroll
-  for (int mb = 0; mb < C::UM; ++mb)
+  for (int half = 0; half < 2; ++half) {
+    const float sl = half ? -kLog2e : kLog2e;
+    const float c0 = half ? mn * kLog2e : -mx * kLog2e;
+    float e[C::LOC];
+    float s = 0.f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const float x = u[mb][r];
-      const float a = __builtin_amdgcn_exp2f(fmaf(x, kLog2e, cpos));
-      const float b = __builtin_amdgcn_exp2f(fmaf(x, -kLog2e, cneg));
-      ep[16 * mb + r] = a; em[16 * mb + r] = b;
-      sp += a; sm += b;
-    }
-  pair32(sp, lo, hi); sp = lo + hi;
-  pair32(sm, lo, hi); sm = lo + hi;
-  const float ip = valid ? __builtin_amdgcn_rcpf(sp) : 0.f;
-  const float im = valid ? __builtin_amdgcn_rcpf(sm) : 0.f;
+    for (int mb = 0; mb < C::UM; ++mb)
 #pragma unroll
-  for (int j = 0; j < C::LOC / 2; ++j) {
-    pk[j] = pack_f16x2(ep[2 * j] * ip, ep[2 * j + 1] * ip);
-    pk[C::LOC / 2 + j] = pack_f16x2(em[2 * j] * im, em[2 * j + 1] * im);
+      for (int r = 0; r < 16; ++r) {
+        const float a = __builtin_amdgcn_exp2f(fmaf(u[mb][r], sl, c0));
+        e[16 * mb + r] = a;
+        s += a;
+      }
+    pair32(s, lo, hi); s = lo + hi;
+    const float inv = valid ? __builtin_amdgcn_rcpf(s) : 0.f;
+#pragma unroll
+    for (int j = 0; j < C::LOC / 2; ++j) pk[half * (C::LOC / 2) + j] = pack_f16x2(e[2 * j] * inv, e[2 * j + 1] * inv);
   }
 }
 
 // ------------------------------------------------------------------------------------------
+// Query pass.  A wavefront owns 32-token blocks b = p*NW + w, stepping by (gridDim.x * NW), so
+// the workgroups of a head sweep its tokens together.  Per block: load Q rows straight into the
+// B operand, phi, out^T = S^T phi^T (+ the z row block for the normaliser), scale, bf16, then a
+// wavefront-private LDS transpose so that every store instruction writes whole 256-byte rows.
+constexpr int NT3 = 512;         // 8 wavefronts, one workgroup per compute unit
+
 template <int D>
-__global__ __launch_bounds__(NT, 2) void apply_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ wq,
-                                                           const uint4* __restrict__ sa, uint16_t* __restrict__ out,
-                                                           int H, int n, int chunk) {
+__device__ __forceinline__ int swz_out(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
+
+template <int D>
+__global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ wq,
+                                                         const uint4* __restrict__ sa, uint16_t* __restrict__ out,
+                                                         int H, int n) {
   using C = Cfg<D>;
   using L = ApplyLayout<D>;
+  constexpr int NW = NT3 / 64;
   constexpr int SA_IMG = L::KS * L::MBZ * 64;
+  constexpr int RS = D * 2;                 // bytes per output row
+  constexpr int RPI = 64 / C::CH;           // rows one store instruction covers
   extern __shared__ uint4 smem[];
   uint4* sWA = smem;
   uint4* sSA = sWA + C::W_IMG;
+  char* sOut = reinterpret_cast<char*>(sSA + SA_IMG);   // [NW][32 rows][RS], swizzled chunks
 
   const int tid = threadIdx.x, lane = tid % 64, w = tid / 64;
   const int g = lane / 32;
-  const int bh = blockIdx.y, p = blockIdx.x, h = bh % H;
-  const int t_begin = p * chunk;
-  const int t_end = min(n, t_begin + chunk);
+  const int bh = blockIdx.y, h = bh % H;
   const uint16_t* qb = q + (size_t)bh * n * D;
   uint16_t* ob = out + (size_t)bh * n * D;
 
-  build_w_image<D>(wq + (size_t)h * D * C::HALF, sWA, tid);
+  build_w_image<D, NT3>(wq + (size_t)h * D * C::HALF, sWA, tid);
   const uint4* sab = sa + (size_t)bh * SA_IMG;
-  for (int i = tid; i < SA_IMG; i += NT) sSA[i] = sab[i];
+  for (int i = tid; i < SA_IMG; i += NT3) sSA[i] = sab[i];
   __syncthreads();
 
-  for (int t0 = t_begin + 32 * w; t0 < t_end; t0 += 32 * (NT / 64)) {
-    const int t = t0 + (lane % 32);
-    const bool valid = t < t_end;
-    const int tc = valid ? t : (t_end - 1);
+  const int nblk = (n + 31) / 32;
+  const int stride = gridDim.x * NW;
+  char* stage = sOut + w * (32 * RS);
+
+  uint4 xb[C::UK];
+  auto load_block = [&](int b) {
+    const int t = b * 32 + (lane % 32);
+    const int tc = t < n ? t : (n - 1);
     const uint4* row = reinterpret_cast<const uint4*>(qb + (size_t)tc * D);
-    uint4 xb[C::UK];
 #pragma unroll
-    for (int ks = 0; ks < C::UK; ++ks) xb[ks] = row[2 * ks + g];
+    for (int ks = 0; ks < C::UK; ++ks) xb[ks] = ld_nt(row + 2 * ks + g);
+  };
+
+  int b = blockIdx.x * NW + w;
+  if (b < nblk) load_block(b);
+  while (b < nblk) {
+    const int t = b * 32 + (lane % 32);
+    const bool valid = t < n;
     uint32_t pk[C::NPK];
     phi_block<D>(xb, sWA, lane, valid, pk);
+    const int bn = b + stride;
+    if (bn < nblk) load_block(bn);           // in flight during the contraction below
 
     f32x16 o[L::MB], dn;
 #pragma unroll
@@ -168,32 +208,51 @@ __global__ __launch_bounds__(NT, 2) void apply_bf16_kernel(const uint16_t* __res
 #pragma unroll
       for (int mb = 0; mb < L::MB; ++mb) o[mb][r] = 0.f;
     }
+    const uint4* ssa = sSA + lane + opaque_zero();
 #pragma unroll
     for (int ks = 0; ks < L::KS; ++ks) {
       uint4 bq; bq.x = pk[4 * ks]; bq.y = pk[4 * ks + 1]; bq.z = pk[4 * ks + 2]; bq.w = pk[4 * ks + 3];
-      const f16x8 b = as_f16x8(bq);
+      const f16x8 bop = as_f16x8(bq);
 #pragma unroll
       for (int mb = 0; mb < L::MB; ++mb) {
-        const f16x8 a = as_f16x8(sSA[(ks * L::MBZ + mb) * 64 + lane]);
-        o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, o[mb], 0, 0, 0);
+        const f16x8 a = as_f16x8(ssa[(ks * L::MBZ + mb) * 64]);
+        o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bop, o[mb], 0, 0, 0);
       }
-      const f16x8 az = as_f16x8(sSA[(ks * L::MBZ + L::MB) * 64 + lane]);
-      dn = __builtin_amdgcn_mfma_f32_32x32x16_f16(az, b, dn, 0, 0, 0);
+      const f16x8 az = as_f16x8(ssa[(ks * L::MBZ + L::MB) * 64]);
+      dn = __builtin_amdgcn_mfma_f32_32x32x16_f16(az, bop, dn, 0, 0, 0);
     }
-    if (valid) {
-      const float inv = 1.0f / dn[0];
-      uint4* orow = reinterpret_cast<uint4*>(ob + (size_t)t * D + g * (D / 2));
+    // lane (t, g) owns channels g*D/2 .. g*D/2 + D/2 - 1 of its token: 16-byte chunks g*CH/2 + 2mb, +1
+    const float inv = valid ? __builtin_amdgcn_rcpf(dn[0]) : 0.f;
+    {
+      const int row = lane % 32;
+      char* rowp = stage + row * RS;
+      const int sw = swz_out<D>(row);
 #pragma unroll
       for (int mb = 0; mb < L::MB; ++mb) {
-        uint4 a, b;
+        uint4 a, c;
         a.x = pack_bf16x2(o[mb][0] * inv, o[mb][1] * inv);   a.y = pack_bf16x2(o[mb][2] * inv, o[mb][3] * inv);
         a.z = pack_bf16x2(o[mb][4] * inv, o[mb][5] * inv);   a.w = pack_bf16x2(o[mb][6] * inv, o[mb][7] * inv);
-        b.x = pack_bf16x2(o[mb][8] * inv, o[mb][9] * inv);   b.y = pack_bf16x2(o[mb][10] * inv, o[mb][11] * inv);
-        b.z = pack_bf16x2(o[mb][12] * inv, o[mb][13] * inv); b.w = pack_bf16x2(o[mb][14] * inv, o[mb][15] * inv);
-        orow[2 * mb] = a;
-        orow[2 * mb + 1] = b;
+        c.x = pack_bf16x2(o[mb][8] * inv, o[mb][9] * inv);   c.y = pack_bf16x2(o[mb][10] * inv, o[mb][11] * inv);
+        c.z = pack_bf16x2(o[mb][12] * inv, o[mb][13] * inv); c.w = pack_bf16x2(o[mb][14] * inv, o[mb][15] * inv);
+        *reinterpret_cast<uint4*>(rowp + (((g * (C::CH / 2) + 2 * mb) ^ sw) * 16)) = a;
+        *reinterpret_cast<uint4*>(rowp + (((g * (C::CH / 2) + 2 * mb + 1) ^ sw) * 16)) = c;
       }
     }
+    __builtin_amdgcn_wave_barrier();
+    {
+      // read back row-major: instruction i covers rows i*RPI .. i*RPI + RPI-1 completely
+      const int rl = lane / C::CH, pc = lane % C::CH;
+#pragma unroll
+      for (int i = 0; i < 32 / RPI; ++i) {
+        const int row = i * RPI + rl;
+        const uint4 v = *reinterpret_cast<const uint4*>(stage + row * RS + pc * 16);
+        const int tt = b * 32 + row;
+        const int lc = pc ^ swz_out<D>(row);
+        if (tt < n) st_nt(reinterpret_cast<uint4*>(ob + (size_t)tt * D) + lc, v);
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+    b = bn;
   }
 }
 
@@ -202,29 +261,31 @@ __global__ __launch_bounds__(NT, 2) void apply_bf16_kernel(const uint16_t* __res
 // tile[row0 + 8*(l/32) + 0..7][col0 + l%32] -- an MFMA A or B operand whose contraction index
 // is the tile row.  Two ds_read_b64_tr_b16: within each group of 16 lanes, lane s supplies the
 // address of row s/4, columns 4*(s%4)..+3, and receives column s of the four rows.
+// tr_offset() is the lane's byte offset for row0 = 0 and the first (j = 0) or second (j = 1)
+// group of four rows; row0 = 16*ks adds 16*ks*RS bytes (the swizzle repeats every 16 rows).
 template <int D>
-__device__ __forceinline__ f16x8 read_tr(const char* tile, int row0, int col0, int lane) {
-  constexpr int RS = D * 2;   // row stride in bytes
-  const int r = row0 + 8 * (lane / 32) + ((lane % 16) / 4);
+__device__ __forceinline__ int tr_offset(int col0, int lane, int j) {
+  constexpr int RS = D * 2;
+  const int r = 8 * (lane / 32) + ((lane % 16) / 4) + 4 * j;
   const int col = col0 + 16 * ((lane / 16) % 2) + 4 * (lane % 4);    // element column, multiple of 4
-  const int chunk = col / 8, within = (col % 8) * 2;
+  return r * RS + (((col / 8) ^ swz<D>(r)) * 16) + (col % 8) * 2;
+}
+
+__device__ __forceinline__ f16x8 read_tr(const char* tile, int off0, int off1) {
   struct { s16x4 lo, hi; } v;
-  {
-    const char* p = tile + r * RS + ((chunk ^ swz<D>(r)) * 16) + within;
-    v.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p));
-  }
-  {
-    const int r2 = r + 4;
-    const char* p = tile + r2 * RS + ((chunk ^ swz<D>(r2)) * 16) + within;
-    v.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p));
-  }
+  v.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(tile + off0));
+  v.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(tile + off1));
   return __builtin_bit_cast(f16x8, v);
 }
 
+// State pass.  A workgroup (4 wavefronts) owns 128-token tiles p, p + P, p + 2P, ... of its head.
+// Per tile each wavefront turns 32 K rows into phi (fp16) and parks it in LDS next to the V tile
+// (widened to fp16); then every wavefront accumulates its quadrant of S = phi^T V over the 128
+// tokens with transposing LDS reads, and one row block of z = phi^T 1.
 template <int D>
 __global__ __launch_bounds__(NT, 2) void state_partials_bf16_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                                                                     const uint16_t* __restrict__ wk, float* __restrict__ partials,
-                                                                    int H, int n, int P, int chunk) {
+                                                                    int H, int n, int P) {
   using C = Cfg<D>;
   constexpr int RS = D * 2;            // tile row stride, bytes
   constexpr int WMN = D / 64;          // 32x32 blocks per wavefront along each side of S
@@ -234,16 +295,16 @@ __global__ __launch_bounds__(NT, 2) void state_partials_bf16_kernel(const uint16
   char* sPhi = reinterpret_cast<char*>(sWA + C::W_IMG);   // [kTile][D] fp16, swizzled chunks
   char* sV = sPhi + kTile * RS;                           // [kTile][D] fp16, swizzled chunks
 
-  const int tid = threadIdx.x, lane = tid % 64, w = tid / 64;
+  const int tid = threadIdx.x, lane = tid % 64;
+  const int w = __builtin_amdgcn_readfirstlane(tid / 64);   // wave-uniform, lives in an SGPR
   const int g = lane / 32;
   const int mi = w / 2, ni = w % 2;
   const int bh = blockIdx.y, p = blockIdx.x, h = bh % H;
-  const int t_begin = p * chunk;
-  const int t_end = min(n, t_begin + chunk);
   const uint16_t* kb = k + (size_t)bh * n * D;
   const uint16_t* vb = v + (size_t)bh * n * D;
+  const int ntile = (n + kTile - 1) / kTile;
 
-  build_w_image<D>(wk + (size_t)h * D * C::HALF, sWA, tid);
+  build_w_image<D, NT>(wk + (size_t)h * D * C::HALF, sWA, tid);
 
   f32x16 s[WMN][WMN], zacc;
 #pragma unroll
@@ -259,33 +320,46 @@ __global__ __launch_bounds__(NT, 2) void state_partials_bf16_kernel(const uint16
   uint4 ones;
   ones.x = ones.y = ones.z = ones.w = 0x3C003C00u;      // fp16 1.0 pairs
 
+  // lane-constant LDS offsets of the transposing reads (A: phi columns, B: V columns)
+  int offA[WMN][2], offB[WMN][2];
+#pragma unroll
+  for (int i = 0; i < WMN; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      offA[i][j] = tr_offset<D>(32 * (mi * WMN + i), lane, j);
+      offB[i][j] = tr_offset<D>(32 * (ni * WMN + i), lane, j);
+    }
+  // lane-constant LDS offsets of the tile writes
+  const int prow = 32 * w + (lane % 32);
+  const int psw = swz<D>(prow);
+
   uint4 xb[C::UK], vreg[VPT];
-  auto load_tile = [&](int t0) {
+  auto load_tile = [&](int tile) {
+    const int t0 = tile * kTile;
     const int t = t0 + 32 * w + (lane % 32);
-    const int tc = t < t_end ? t : (t_end - 1);
+    const int tc = t < n ? t : (n - 1);
     const uint4* row = reinterpret_cast<const uint4*>(kb + (size_t)tc * D);
 #pragma unroll
-    for (int ks = 0; ks < C::UK; ++ks) xb[ks] = row[2 * ks + g];
+    for (int ks = 0; ks < C::UK; ++ks) xb[ks] = ld_nt(row + 2 * ks + g);
 #pragma unroll
     for (int i = 0; i < VPT; ++i) {
       const int idx = tid + NT * i;
       const int r = idx / C::CH, c = idx % C::CH;
-      const int tv = (t0 + r) < t_end ? (t0 + r) : (t_end - 1);
-      vreg[i] = reinterpret_cast<const uint4*>(vb + (size_t)tv * D)[c];
+      const int tv = (t0 + r) < n ? (t0 + r) : (n - 1);
+      vreg[i] = ld_nt(reinterpret_cast<const uint4*>(vb + (size_t)tv * D) + c);
     }
   };
 
-  load_tile(t_begin);
+  int tile = p;
+  if (tile < ntile) load_tile(tile);
   __syncthreads();                               // W image complete
-  for (int t0 = t_begin; t0 < t_end; t0 += kTile) {
-    const bool valid = (t0 + 32 * w + (lane % 32)) < t_end;
+  for (; tile < ntile; tile += P) {
+    const bool valid = (tile * kTile + 32 * w + (lane % 32)) < n;
     uint32_t pk[C::NPK];
     phi_block<D>(xb, sWA, lane, valid, pk);
     __syncthreads();                             // previous tile's operand reads are done
     {
-      const int r = 32 * w + (lane % 32);
-      char* rowp = sPhi + r * RS;
-      const int sw = swz<D>(r);
+      char* rowp = sPhi + prow * RS;
       constexpr int CPH = C::LOC / 8;            // 16-byte chunks per softmax half a lane owns
 #pragma unroll
       for (int c = 0; c < CPH; ++c) {
@@ -293,36 +367,40 @@ __global__ __launch_bounds__(NT, 2) void state_partials_bf16_kernel(const uint16
         a.x = pk[4 * c]; a.y = pk[4 * c + 1]; a.z = pk[4 * c + 2]; a.w = pk[4 * c + 3];
         b.x = pk[C::LOC / 2 + 4 * c]; b.y = pk[C::LOC / 2 + 4 * c + 1];
         b.z = pk[C::LOC / 2 + 4 * c + 2]; b.w = pk[C::LOC / 2 + 4 * c + 3];
-        *reinterpret_cast<uint4*>(rowp + (((g * CPH + c) ^ sw) * 16)) = a;                 // softmax(+u) half
-        *reinterpret_cast<uint4*>(rowp + (((C::CH / 2 + g * CPH + c) ^ sw) * 16)) = b;     // softmax(-u) half
+        *reinterpret_cast<uint4*>(rowp + (((g * CPH + c) ^ psw) * 16)) = a;                 // softmax(+u) half
+        *reinterpret_cast<uint4*>(rowp + (((C::CH / 2 + g * CPH + c) ^ psw) * 16)) = b;     // softmax(-u) half
       }
 #pragma unroll
       for (int i = 0; i < VPT; ++i) {
         const int idx = tid + NT * i;
         const int rv = idx / C::CH, c = idx % C::CH;
-        uint4 h;
-        h.x = bf16x2_to_f16x2(vreg[i].x); h.y = bf16x2_to_f16x2(vreg[i].y);
-        h.z = bf16x2_to_f16x2(vreg[i].z); h.w = bf16x2_to_f16x2(vreg[i].w);
-        *reinterpret_cast<uint4*>(sV + rv * RS + ((c ^ swz<D>(rv)) * 16)) = h;
+        uint4 hv;
+        hv.x = bf16x2_to_f16x2(vreg[i].x); hv.y = bf16x2_to_f16x2(vreg[i].y);
+        hv.z = bf16x2_to_f16x2(vreg[i].z); hv.w = bf16x2_to_f16x2(vreg[i].w);
+        *reinterpret_cast<uint4*>(sV + rv * RS + ((c ^ swz<D>(rv)) * 16)) = hv;
       }
     }
     __syncthreads();
-    if (t0 + kTile < t_end) load_tile(t0 + kTile);   // in flight during the MFMA phase below
+    if (tile + P < ntile) load_tile(tile + P);   // in flight during the MFMA phase below
 
 #pragma unroll
     for (int ks = 0; ks < kTile / 16; ++ks) {
       f16x8 a[WMN], b[WMN];
 #pragma unroll
-      for (int i = 0; i < WMN; ++i) a[i] = read_tr<D>(sPhi, 16 * ks, 32 * (mi * WMN + i), lane);
+      for (int i = 0; i < WMN; ++i) a[i] = read_tr(sPhi + ks * 16 * RS, offA[i][0], offA[i][1]);
 #pragma unroll
-      for (int j = 0; j < WMN; ++j) b[j] = read_tr<D>(sV, 16 * ks, 32 * (ni * WMN + j), lane);
+      for (int j = 0; j < WMN; ++j) b[j] = read_tr(sV + ks * 16 * RS, offB[j][0], offB[j][1]);
 #pragma unroll
       for (int i = 0; i < WMN; ++i)
 #pragma unroll
         for (int j = 0; j < WMN; ++j) s[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], s[i][j], 0, 0, 0);
-      if (do_z) {
-        const f16x8 az = (WMN == 2) ? a[ni] : a[0];
-        zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(az, as_f16x8(ones), zacc, 0, 0, 0);
+      // z row block: wave-uniform choice, written as branches (indexing a[] with a run-time
+      // value would turn into per-element selects)
+      if (WMN == 2) {
+        if (ni == 0) zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], as_f16x8(ones), zacc, 0, 0, 0);
+        else zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[WMN - 1], as_f16x8(ones), zacc, 0, 0, 0);
+      } else if (do_z) {
+        zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], as_f16x8(ones), zacc, 0, 0, 0);
       }
     }
   }
@@ -348,7 +426,9 @@ __global__ __launch_bounds__(NT, 2) void state_partials_bf16_kernel(const uint16
 template <int D>
 constexpr size_t state_smem() { return sizeof(uint4) * Cfg<D>::W_IMG + 2 * (size_t)kTile * D * 2; }
 template <int D>
-constexpr size_t apply_smem() { return sizeof(uint4) * (Cfg<D>::W_IMG + ApplyLayout<D>::KS * ApplyLayout<D>::MBZ * 64); }
+constexpr size_t apply_smem() {
+  return sizeof(uint4) * (Cfg<D>::W_IMG + ApplyLayout<D>::KS * ApplyLayout<D>::MBZ * 64) + (size_t)(NT3 / 64) * 32 * D * 2;
+}
 
 template <typename K>
 hipError_t set_smem(K kernel, size_t bytes) {
@@ -364,27 +444,27 @@ hipError_t launch_state_partials_bf16(const void* k, const void* v, const void* 
   if (p.d == 128) {
     if ((e = set_smem(state_partials_bf16_kernel<128>, state_smem<128>())) != hipSuccess) return e;
     state_partials_bf16_kernel<128><<<grid, block, state_smem<128>(), s>>>(
-        (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)wk, partials, p.H, p.n, p.P, p.chunk);
+        (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)wk, partials, p.H, p.n, p.P);
   } else {
     if ((e = set_smem(state_partials_bf16_kernel<64>, state_smem<64>())) != hipSuccess) return e;
     state_partials_bf16_kernel<64><<<grid, block, state_smem<64>(), s>>>(
-        (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)wk, partials, p.H, p.n, p.P, p.chunk);
+        (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)wk, partials, p.H, p.n, p.P);
   }
   return hipGetLastError();
 }
 
 hipError_t launch_apply_bf16(const void* q, const void* wq, const void* sa, void* out,
                              const Plan& p, hipStream_t s) {
-  dim3 grid(p.QP, p.BH), block(NT);
+  dim3 grid(p.QP, p.BH), block(NT3);
   hipError_t e;
   if (p.d == 128) {
     if ((e = set_smem(apply_bf16_kernel<128>, apply_smem<128>())) != hipSuccess) return e;
     apply_bf16_kernel<128><<<grid, block, apply_smem<128>(), s>>>(
-        (const uint16_t*)q, (const uint16_t*)wq, (const uint4*)sa, (uint16_t*)out, p.H, p.n, p.qchunk);
+        (const uint16_t*)q, (const uint16_t*)wq, (const uint4*)sa, (uint16_t*)out, p.H, p.n);
   } else {
     if ((e = set_smem(apply_bf16_kernel<64>, apply_smem<64>())) != hipSuccess) return e;
     apply_bf16_kernel<64><<<grid, block, apply_smem<64>(), s>>>(
-        (const uint16_t*)q, (const uint16_t*)wq, (const uint4*)sa, (uint16_t*)out, p.H, p.n, p.qchunk);
+        (const uint16_t*)q, (const uint16_t*)wq, (const uint4*)sa, (uint16_t*)out, p.H, p.n);
   }
   return hipGetLastError();
 }

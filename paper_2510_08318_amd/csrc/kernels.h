@@ -11,15 +11,17 @@ namespace linattn {
 constexpr int kTile = 128;
 // Workgroup slots the split-n plan aims to fill: 256 compute units x 2 resident workgroups.
 constexpr int kSlots = 512;
+// Compute units of the gfx950 parts this library targets (MI355X / MI350X).
+constexpr int kCUs = 256;
 
 // How one call is cut into workgroups and where its scratch regions sit in the workspace.
 struct Plan {
   int B, H, n, d;
   int BH;
   int P;            // split-n factor of the state pass (partials per (b,h))
-  int chunk;        // tokens per split, a multiple of kTile
-  int QP;           // splits of the query pass
-  int qchunk;
+  int chunk;        // tokens per split, a multiple of kTile (fp32 kernels; the bf16 ones deal tiles round-robin)
+  int QP;           // workgroups per (b,h) of the query pass
+  int qchunk;       // tokens per workgroup of the fp32 query pass
   size_t state_elems;     // (d+1)*d
   size_t sa_elems;        // 16-bit elements of the packed MFMA operand image of one (b,h) state
   size_t off_partials;    // fp32 [BH][P][(d+1)*d]
