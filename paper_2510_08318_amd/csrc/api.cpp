@@ -28,22 +28,18 @@ bool make_plan(int B, int H, int n, int d, int dtype, Plan* p) {
   r.QP = r.P;
   r.qchunk = r.chunk;
   if (dtype == LINATTN_BF16) {
-    // query pass: 8-wavefront workgroups, one per compute unit, 32-token blocks dealt round-robin
+    // query pass: 12-wavefront workgroups, one per compute unit, 32-token blocks dealt round-robin
     const int nblk = (n + 31) / 32;
     int QP = kCUs / (int)BH;
     if (QP < 1) QP = 1;
-    if (QP > (nblk + 7) / 8) QP = (nblk + 7) / 8;
+    if (QP > (nblk + 11) / 12) QP = (nblk + 11) / 12;
     r.QP = QP;
   }
   r.state_elems = (size_t)(d + 1) * d;
-  // packed operand image: (d/16 k-steps) x (d/32 channel blocks + 1 normaliser block) x 64 lanes x 8
-  r.sa_elems = (size_t)(d / 16) * (d / 32 + 1) * 64 * 8;
   auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
   size_t off = 0;
   r.off_partials = off; off = up(off + (size_t)BH * r.P * r.state_elems * sizeof(float));
   r.off_state = off;    off = up(off + (size_t)BH * r.state_elems * sizeof(float));
-  r.off_sa = off;
-  if (dtype == LINATTN_BF16) off = up(off + (size_t)BH * r.sa_elems * 2);
   r.total_bytes = off;
   *p = r;
   return true;
@@ -187,20 +183,19 @@ int linattn_fwd(const void* q, const void* k, const void* v, void* out,
     e = launch_state_partials_f32((const float*)k, (const float*)v, (const float*)desc.wk, partials, plan, s);
     if (e != hipSuccess) return LINATTN_E_HIP;
     mark(1, s);
-    e = launch_state_reduce(partials, state, nullptr, plan, s);
+    e = launch_state_reduce(partials, state, plan, s);
     if (e != hipSuccess) return LINATTN_E_HIP;
     mark(2, s);
     e = launch_apply_f32((const float*)q, (const float*)desc.wq, state, (float*)out, plan, s);
     if (e != hipSuccess) return LINATTN_E_HIP;
   } else {
-    void* sa = ws + plan.off_sa;
     e = launch_state_partials_bf16(k, v, desc.wk, partials, plan, s);
     if (e != hipSuccess) return LINATTN_E_HIP;
     mark(1, s);
-    e = launch_state_reduce(partials, state, sa, plan, s);
+    e = launch_state_reduce(partials, state, plan, s);
     if (e != hipSuccess) return LINATTN_E_HIP;
     mark(2, s);
-    e = launch_apply_bf16(q, desc.wq, sa, out, plan, s);
+    e = launch_apply_bf16(q, desc.wq, state, out, plan, s);
     if (e != hipSuccess) return LINATTN_E_HIP;
   }
   mark(3, s);

@@ -52,7 +52,9 @@ __device__ __forceinline__ int opaque_zero() {
 }
 
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-// Streaming (non-temporal) 16-byte global load / store: every tensor byte is touched once.
+// Streaming (non-temporal) 16-byte global load / store, for fully coalesced accesses only: with
+// the operand-layout loads (two 16-byte pieces of a row per instruction, four instructions per
+// 128-byte line) the hint makes the line be fetched again and costs 20 % of the bandwidth.
 __device__ __forceinline__ uint4 ld_nt(const uint4* p) {
   return __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p)));
 }
@@ -88,16 +90,14 @@ __device__ __forceinline__ void build_w_image(const uint16_t* __restrict__ w, ui
   }
 }
 
-// Eq. 5 for the 32 tokens of one wavefront.  xb[ks] is this lane's B operand (8 channels of its
-// token per k-step).  On return pk[] holds the lane's d/2 values of phi as fp16 pairs:
-// first LOC values softmax(+u) for features g*LOC .. g*LOC+LOC-1, then LOC values softmax(-u)
-// for the same features.  valid == false zeroes the token (tail masking happens after phi:
-// phi(0) is the uniform vector, not zero).
+// First half of Eq. 5 for the 32 tokens of one wavefront: U^T = W~^T X^T on bf16 MFMA.
+// xb[ks] is this lane's B operand (8 channels of its token per k-step).  On return the lane holds
+// u[mb][r] = pre-softmax feature g*LOC + 16*mb + r of its token.  xb is dead afterwards, so the
+// caller can refill it with the next block while the softmax runs.
 template <int D>
-__device__ __forceinline__ void phi_block(const uint4 (&xb)[Cfg<D>::UK], const uint4* sWA, int lane, bool valid,
-                                          uint32_t (&pk)[Cfg<D>::NPK]) {
+__device__ __forceinline__ void project(const uint4 (&xb)[Cfg<D>::UK], const uint4* sWA, int lane,
+                                        f32x16 (&u)[Cfg<D>::UM]) {
   using C = Cfg<D>;
-  f32x16 u[C::UM];
 #pragma unroll
   for (int mb = 0; mb < C::UM; ++mb)
 #pragma unroll
@@ -112,6 +112,16 @@ __device__ __forceinline__ void phi_block(const uint4 (&xb)[Cfg<D>::UK], const u
       u[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, u[mb], 0, 0, 0);
     }
   }
+}
+
+// Second half of Eq. 5: the two softmaxes over the d/2 features (in-lane, plus one exchange with
+// lane^32).  pk[] receives the lane's d/2 values of phi as fp16 pairs: first LOC values
+// softmax(+u) for features g*LOC .. g*LOC+LOC-1, then LOC values softmax(-u) for the same
+// features.  valid == false zeroes the token (tail masking happens after phi: phi(0) is the
+// uniform vector, not zero).
+template <int D>
+__device__ __forceinline__ void softmax_pair(const f32x16 (&u)[Cfg<D>::UM], bool valid, uint32_t (&pk)[Cfg<D>::NPK]) {
+  using C = Cfg<D>;
   float mx = u[0][0], mn = u[0][0];
 #pragma unroll
   for (int mb = 0; mb < C::UM; ++mb)
@@ -142,19 +152,112 @@ __device__ __forceinline__ void phi_block(const uint4 (&xb)[Cfg<D>::UK], const u
   }
 }
 
+// Eq. 5 up to a per-token positive factor, for the query side only: the output of Eq. 3 is a ratio
+// that is linear in phi(q_i) above and below, so phi(q_i) may be scaled by any positive number.
+// Scaling by the softmax(+u) denominator s+ leaves exp(u - max u) as the first half and
+// (s+/s-) exp(min u - u) as the second: one multiply per token-half saved, values stay in (0, 64].
+template <int D>
+__device__ __forceinline__ void softmax_pair_ratio(const f32x16 (&u)[Cfg<D>::UM], uint32_t (&pk)[Cfg<D>::NPK]) {
+  using C = Cfg<D>;
+  float mx = u[0][0], mn = u[0][0];
+#pragma unroll
+  for (int mb = 0; mb < C::UM; ++mb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { mx = fmaxf(mx, u[mb][r]); mn = fminf(mn, u[mb][r]); }
+  float lo, hi;
+  pair32(mx, lo, hi); mx = fmaxf(lo, hi);
+  pair32(mn, lo, hi); mn = fminf(lo, hi);
+  float sp = 0.f;
+  {
+    const float c0 = -mx * kLog2e;
+    float e[C::LOC];
+#pragma unroll
+    for (int mb = 0; mb < C::UM; ++mb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float a = __builtin_amdgcn_exp2f(fmaf(u[mb][r], kLog2e, c0));
+        e[16 * mb + r] = a;
+        sp += a;
+      }
+#pragma unroll
+    for (int j = 0; j < C::LOC / 2; ++j) pk[j] = pack_f16x2(e[2 * j], e[2 * j + 1]);
+    pair32(sp, lo, hi); sp = lo + hi;
+  }
+  {
+    const float c0 = mn * kLog2e;
+    float e[C::LOC];
+    float sm = 0.f;
+#pragma unroll
+    for (int mb = 0; mb < C::UM; ++mb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float a = __builtin_amdgcn_exp2f(fmaf(u[mb][r], -kLog2e, c0));
+        e[16 * mb + r] = a;
+        sm += a;
+      }
+    pair32(sm, lo, hi); sm = lo + hi;
+    const float ratio = sp * __builtin_amdgcn_rcpf(sm);
+#pragma unroll
+    for (int j = 0; j < C::LOC / 2; ++j) pk[C::LOC / 2 + j] = pack_f16x2(e[2 * j] * ratio, e[2 * j + 1] * ratio);
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // Query pass.  A wavefront owns 32-token blocks b = p*NW + w, stepping by (gridDim.x * NW), so
 // the workgroups of a head sweep its tokens together.  Per block: load Q rows straight into the
 // B operand, phi, out^T = S^T phi^T (+ the z row block for the normaliser), scale, bf16, then a
 // wavefront-private LDS transpose so that every store instruction writes whole 256-byte rows.
-constexpr int NT3 = 512;         // 8 wavefronts, one workgroup per compute unit
+// fp32 state [D+1][D] of one (b,h) -> LDS image of the fp16 A operands of out^T = S^T phi(q)^T:
+// entry (ks, mb, lane=(m,g)) holds S[feature(ks,g,e)][channel(mb,m)], e = 0..7, and the extra row
+// block mb = MB holds z[feature] in rows 0 and 4 (one per lane group) and zeros elsewhere.
+// S and z are scaled by a common power of two that brings their largest magnitude into
+// [2^13, 2^14): the output is a ratio, so the scale cancels, and fp16 cannot overflow.
+// red: >= NTHREADS/64 floats of LDS scratch.  Contains __syncthreads().
+template <int D, int NTHREADS>
+__device__ __forceinline__ void build_state_image(const float* __restrict__ S, uint4* sSA, float* red, int tid) {
+  using L = ApplyLayout<D>;
+  constexpr int N = (D + 1) * D;
+  float amax = 0.f;
+  for (int i0 = tid; i0 < N; i0 += 8 * NTHREADS) {
+    float t[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { const int i = i0 + j * NTHREADS; t[j] = i < N ? fabsf(S[i]) : 0.f; }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) amax = fmaxf(amax, t[j]);
+  }
+  for (int m = 32; m >= 1; m >>= 1) amax = fmaxf(amax, __shfl_xor(amax, m, 64));
+  if (tid % 64 == 0) red[tid / 64] = amax;
+  __syncthreads();
+  amax = red[0];
+#pragma unroll
+  for (int i = 1; i < NTHREADS / 64; ++i) amax = fmaxf(amax, red[i]);
+  const float scale = (amax > 0.f && amax < 3.0e38f) ? ldexpf(1.0f, 13 - ilogbf(amax)) : 1.0f;
+  __syncthreads();                       // red is reused by the caller
+  for (int idx = tid; idx < L::KS * L::MBZ * 64; idx += NTHREADS) {
+    const int lane = idx % 64, mb = (idx / 64) % L::MBZ, ks = idx / (64 * L::MBZ);
+    const int m = lane % 32, g = lane / 32;
+    float x[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int f = L::feature(ks, g, e);
+      if (mb < L::MB) x[e] = scale * S[f * D + L::channel(mb, m)];
+      else x[e] = (m == 0 || m == 4) ? scale * S[D * D + f] : 0.f;
+    }
+    uint4 r;
+    r.x = pack_f16x2(x[0], x[1]); r.y = pack_f16x2(x[2], x[3]);
+    r.z = pack_f16x2(x[4], x[5]); r.w = pack_f16x2(x[6], x[7]);
+    sSA[idx] = r;
+  }
+}
+
+constexpr int NT3 = 768;         // 12 wavefronts, one workgroup per compute unit
 
 template <int D>
 __device__ __forceinline__ int swz_out(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
 
 template <int D>
 __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ wq,
-                                                         const uint4* __restrict__ sa, uint16_t* __restrict__ out,
+                                                         const float* __restrict__ state, uint16_t* __restrict__ out,
                                                          int H, int n) {
   using C = Cfg<D>;
   using L = ApplyLayout<D>;
@@ -162,80 +265,92 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
   constexpr int SA_IMG = L::KS * L::MBZ * 64;
   constexpr int RS = D * 2;                 // bytes per output row
   constexpr int RPI = 64 / C::CH;           // rows one store instruction covers
+  constexpr int HB = (L::MB + 1) / 2;       // channel row blocks per accumulation pass (two passes)
   extern __shared__ uint4 smem[];
   uint4* sWA = smem;
   uint4* sSA = sWA + C::W_IMG;
   char* sOut = reinterpret_cast<char*>(sSA + SA_IMG);   // [NW][32 rows][RS], swizzled chunks
 
-  const int tid = threadIdx.x, lane = tid % 64, w = tid / 64;
+  const int tid = threadIdx.x, lane = tid % 64;
+  const int w = __builtin_amdgcn_readfirstlane(tid / 64);
   const int g = lane / 32;
   const int bh = blockIdx.y, h = bh % H;
   const uint16_t* qb = q + (size_t)bh * n * D;
   uint16_t* ob = out + (size_t)bh * n * D;
 
   build_w_image<D, NT3>(wq + (size_t)h * D * C::HALF, sWA, tid);
-  const uint4* sab = sa + (size_t)bh * SA_IMG;
-  for (int i = tid; i < SA_IMG; i += NT3) sSA[i] = sab[i];
+  build_state_image<D, NT3>(state + (size_t)bh * (D + 1) * D, sSA, reinterpret_cast<float*>(sOut), tid);
   __syncthreads();
 
   const int nblk = (n + 31) / 32;
   const int stride = gridDim.x * NW;
   char* stage = sOut + w * (32 * RS);
+  const int srow = lane % 32;
+  char* srowp = stage + srow * RS;
+  const int ssw = swz_out<D>(srow);
 
-  uint4 xb[C::UK];
+  uint4 x[C::UK];
   auto load_block = [&](int b) {
     const int t = b * 32 + (lane % 32);
     const int tc = t < n ? t : (n - 1);
     const uint4* row = reinterpret_cast<const uint4*>(qb + (size_t)tc * D);
 #pragma unroll
-    for (int ks = 0; ks < C::UK; ++ks) xb[ks] = ld_nt(row + 2 * ks + g);
+    for (int ks = 0; ks < C::UK; ++ks) x[ks] = row[2 * ks + g];
   };
 
   int b = blockIdx.x * NW + w;
   if (b < nblk) load_block(b);
-  while (b < nblk) {
-    const int t = b * 32 + (lane % 32);
-    const bool valid = t < n;
+  for (; b < nblk; b += stride) {
+    f32x16 u[C::UM];
+    project<D>(x, sWA, lane, u);
+    if (b + stride < nblk) load_block(b + stride);   // next block's rows fly during the rest of this one
     uint32_t pk[C::NPK];
-    phi_block<D>(xb, sWA, lane, valid, pk);
-    const int bn = b + stride;
-    if (bn < nblk) load_block(bn);           // in flight during the contraction below
+    softmax_pair_ratio<D>(u, pk);
 
-    f32x16 o[L::MB], dn;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      dn[r] = 0.f;
-#pragma unroll
-      for (int mb = 0; mb < L::MB; ++mb) o[mb][r] = 0.f;
-    }
+    // out^T = S^T phi^T in two passes over the channel row blocks: the first also carries the
+    // normaliser block, so 1/den is known before anything is scaled
     const uint4* ssa = sSA + lane + opaque_zero();
+    float inv = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < L::KS; ++ks) {
-      uint4 bq; bq.x = pk[4 * ks]; bq.y = pk[4 * ks + 1]; bq.z = pk[4 * ks + 2]; bq.w = pk[4 * ks + 3];
-      const f16x8 bop = as_f16x8(bq);
+    for (int pass = 0; pass < 2; ++pass) {
+      f32x16 o[HB], dn;
 #pragma unroll
-      for (int mb = 0; mb < L::MB; ++mb) {
-        const f16x8 a = as_f16x8(ssa[(ks * L::MBZ + mb) * 64]);
-        o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bop, o[mb], 0, 0, 0);
+      for (int r = 0; r < 16; ++r) {
+        dn[r] = 0.f;
+#pragma unroll
+        for (int i = 0; i < HB; ++i) o[i][r] = 0.f;
       }
-      const f16x8 az = as_f16x8(ssa[(ks * L::MBZ + L::MB) * 64]);
-      dn = __builtin_amdgcn_mfma_f32_32x32x16_f16(az, bop, dn, 0, 0, 0);
-    }
-    // lane (t, g) owns channels g*D/2 .. g*D/2 + D/2 - 1 of its token: 16-byte chunks g*CH/2 + 2mb, +1
-    const float inv = valid ? __builtin_amdgcn_rcpf(dn[0]) : 0.f;
-    {
-      const int row = lane % 32;
-      char* rowp = stage + row * RS;
-      const int sw = swz_out<D>(row);
 #pragma unroll
-      for (int mb = 0; mb < L::MB; ++mb) {
-        uint4 a, c;
-        a.x = pack_bf16x2(o[mb][0] * inv, o[mb][1] * inv);   a.y = pack_bf16x2(o[mb][2] * inv, o[mb][3] * inv);
-        a.z = pack_bf16x2(o[mb][4] * inv, o[mb][5] * inv);   a.w = pack_bf16x2(o[mb][6] * inv, o[mb][7] * inv);
-        c.x = pack_bf16x2(o[mb][8] * inv, o[mb][9] * inv);   c.y = pack_bf16x2(o[mb][10] * inv, o[mb][11] * inv);
-        c.z = pack_bf16x2(o[mb][12] * inv, o[mb][13] * inv); c.w = pack_bf16x2(o[mb][14] * inv, o[mb][15] * inv);
-        *reinterpret_cast<uint4*>(rowp + (((g * (C::CH / 2) + 2 * mb) ^ sw) * 16)) = a;
-        *reinterpret_cast<uint4*>(rowp + (((g * (C::CH / 2) + 2 * mb + 1) ^ sw) * 16)) = c;
+      for (int ks = 0; ks < L::KS; ++ks) {
+        uint4 bq; bq.x = pk[4 * ks]; bq.y = pk[4 * ks + 1]; bq.z = pk[4 * ks + 2]; bq.w = pk[4 * ks + 3];
+        const f16x8 bop = as_f16x8(bq);
+#pragma unroll
+        for (int i = 0; i < HB; ++i) {
+          const int mb = pass * HB + i;
+          if (mb < L::MB) {
+            const f16x8 a = as_f16x8(ssa[(ks * L::MBZ + mb) * 64]);
+            o[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bop, o[i], 0, 0, 0);
+          }
+        }
+        if (pass == 0) {
+          const f16x8 az = as_f16x8(ssa[(ks * L::MBZ + L::MB) * 64]);
+          dn = __builtin_amdgcn_mfma_f32_32x32x16_f16(az, bop, dn, 0, 0, 0);
+        }
+      }
+      if (pass == 0) inv = __builtin_amdgcn_rcpf(dn[0]);
+      // lane (t, g) owns channels g*D/2 + 16*mb + r of its token: 16-byte chunks g*CH/2 + 2*mb, +1
+#pragma unroll
+      for (int i = 0; i < HB; ++i) {
+        const int mb = pass * HB + i;
+        if (mb < L::MB) {
+          uint4 a, c;
+          a.x = pack_bf16x2(o[i][0] * inv, o[i][1] * inv);   a.y = pack_bf16x2(o[i][2] * inv, o[i][3] * inv);
+          a.z = pack_bf16x2(o[i][4] * inv, o[i][5] * inv);   a.w = pack_bf16x2(o[i][6] * inv, o[i][7] * inv);
+          c.x = pack_bf16x2(o[i][8] * inv, o[i][9] * inv);   c.y = pack_bf16x2(o[i][10] * inv, o[i][11] * inv);
+          c.z = pack_bf16x2(o[i][12] * inv, o[i][13] * inv); c.w = pack_bf16x2(o[i][14] * inv, o[i][15] * inv);
+          *reinterpret_cast<uint4*>(srowp + (((g * (C::CH / 2) + 2 * mb) ^ ssw) * 16)) = a;
+          *reinterpret_cast<uint4*>(srowp + (((g * (C::CH / 2) + 2 * mb + 1) ^ ssw) * 16)) = c;
+        }
       }
     }
     __builtin_amdgcn_wave_barrier();
@@ -248,11 +363,10 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
         const uint4 v = *reinterpret_cast<const uint4*>(stage + row * RS + pc * 16);
         const int tt = b * 32 + row;
         const int lc = pc ^ swz_out<D>(row);
-        if (tt < n) st_nt(reinterpret_cast<uint4*>(ob + (size_t)tt * D) + lc, v);
+        if (tt < n) reinterpret_cast<uint4*>(ob + (size_t)tt * D)[lc] = v;
       }
     }
     __builtin_amdgcn_wave_barrier();
-    b = bn;
   }
 }
 
@@ -334,13 +448,15 @@ __global__ __launch_bounds__(NT, 2) void state_partials_bf16_kernel(const uint16
   const int psw = swz<D>(prow);
 
   uint4 xb[C::UK], vreg[VPT];
-  auto load_tile = [&](int tile) {
-    const int t0 = tile * kTile;
-    const int t = t0 + 32 * w + (lane % 32);
+  auto load_k = [&](int tile) {
+    const int t = tile * kTile + 32 * w + (lane % 32);
     const int tc = t < n ? t : (n - 1);
     const uint4* row = reinterpret_cast<const uint4*>(kb + (size_t)tc * D);
 #pragma unroll
-    for (int ks = 0; ks < C::UK; ++ks) xb[ks] = ld_nt(row + 2 * ks + g);
+    for (int ks = 0; ks < C::UK; ++ks) xb[ks] = row[2 * ks + g];
+  };
+  auto load_v = [&](int tile) {
+    const int t0 = tile * kTile;
 #pragma unroll
     for (int i = 0; i < VPT; ++i) {
       const int idx = tid + NT * i;
@@ -351,12 +467,15 @@ __global__ __launch_bounds__(NT, 2) void state_partials_bf16_kernel(const uint16
   };
 
   int tile = p;
-  if (tile < ntile) load_tile(tile);
+  if (tile < ntile) { load_k(tile); load_v(tile); }
   __syncthreads();                               // W image complete
   for (; tile < ntile; tile += P) {
     const bool valid = (tile * kTile + 32 * w + (lane % 32)) < n;
+    f32x16 u[C::UM];
+    project<D>(xb, sWA, lane, u);
+    if (tile + P < ntile) load_k(tile + P);      // next K rows fly during the rest of this tile
     uint32_t pk[C::NPK];
-    phi_block<D>(xb, sWA, lane, valid, pk);
+    softmax_pair<D>(u, valid, pk);
     __syncthreads();                             // previous tile's operand reads are done
     {
       char* rowp = sPhi + prow * RS;
@@ -381,7 +500,7 @@ __global__ __launch_bounds__(NT, 2) void state_partials_bf16_kernel(const uint16
       }
     }
     __syncthreads();
-    if (tile + P < ntile) load_tile(tile + P);   // in flight during the MFMA phase below
+    if (tile + P < ntile) load_v(tile + P);      // next V tile flies during the MFMA phase and the next phi
 
 #pragma unroll
     for (int ks = 0; ks < kTile / 16; ++ks) {
@@ -453,18 +572,18 @@ hipError_t launch_state_partials_bf16(const void* k, const void* v, const void* 
   return hipGetLastError();
 }
 
-hipError_t launch_apply_bf16(const void* q, const void* wq, const void* sa, void* out,
+hipError_t launch_apply_bf16(const void* q, const void* wq, const float* state, void* out,
                              const Plan& p, hipStream_t s) {
   dim3 grid(p.QP, p.BH), block(NT3);
   hipError_t e;
   if (p.d == 128) {
     if ((e = set_smem(apply_bf16_kernel<128>, apply_smem<128>())) != hipSuccess) return e;
     apply_bf16_kernel<128><<<grid, block, apply_smem<128>(), s>>>(
-        (const uint16_t*)q, (const uint16_t*)wq, (const uint4*)sa, (uint16_t*)out, p.H, p.n);
+        (const uint16_t*)q, (const uint16_t*)wq, state, (uint16_t*)out, p.H, p.n);
   } else {
     if ((e = set_smem(apply_bf16_kernel<64>, apply_smem<64>())) != hipSuccess) return e;
     apply_bf16_kernel<64><<<grid, block, apply_smem<64>(), s>>>(
-        (const uint16_t*)q, (const uint16_t*)wq, (const uint4*)sa, (uint16_t*)out, p.H, p.n);
+        (const uint16_t*)q, (const uint16_t*)wq, state, (uint16_t*)out, p.H, p.n);
   }
   return hipGetLastError();
 }

@@ -23,10 +23,8 @@ struct Plan {
   int QP;           // workgroups per (b,h) of the query pass
   int qchunk;       // tokens per workgroup of the fp32 query pass
   size_t state_elems;     // (d+1)*d
-  size_t sa_elems;        // 16-bit elements of the packed MFMA operand image of one (b,h) state
   size_t off_partials;    // fp32 [BH][P][(d+1)*d]
   size_t off_state;       // fp32 [BH][(d+1)*d]   (used when the caller gave no state buffer)
-  size_t off_sa;          // fp16 [BH][sa_elems]  (bf16 mode only)
   size_t total_bytes;
 };
 
@@ -39,14 +37,12 @@ hipError_t launch_state_partials_f32(const float* k, const float* v, const float
                                      const Plan& p, hipStream_t s);
 hipError_t launch_state_partials_bf16(const void* k, const void* v, const void* wk, float* partials,
                                       const Plan& p, hipStream_t s);
-// Fixed-order sum of the partials into the exported state layout [BH][d+1][d] fp32,
-// and (bf16 mode) the packed operand image the query pass feeds to MFMA.
-hipError_t launch_state_reduce(const float* partials, float* state, void* sa /*nullable*/,
-                               const Plan& p, hipStream_t s);
+// Fixed-order sum of the partials into the exported state layout [BH][d+1][d] fp32.
+hipError_t launch_state_reduce(const float* partials, float* state, const Plan& p, hipStream_t s);
 // phi(Q) S / (phi(Q) . z) and the store of out (Eq. 3, right-hand side).
 hipError_t launch_apply_f32(const float* q, const float* wq, const float* state, float* out,
                             const Plan& p, hipStream_t s);
-hipError_t launch_apply_bf16(const void* q, const void* wq, const void* sa, void* out,
+hipError_t launch_apply_bf16(const void* q, const void* wq, const float* state, void* out,
                              const Plan& p, hipStream_t s);
 
 }  // namespace linattn
