@@ -20,9 +20,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published peak
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command
-# (profiles/), scaled by a copy kernel of known size; None until measured for a workload.
-MEASURED_TRAFFIC = {}
+# HBM bytes per launch (read + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# command with --calib-copy, scaled by the readings of the 1 GiB copy kernel (FETCH x2 KiB,
+# WRITE x1 KiB); keyed by (workload, stage).  The committed summary with the commands is
+# profiles/fwd_wan14b_720p_pmc.md.  None for workloads that have not been measured.
+MEASURED_TRAFFIC = {("C3", 0): 1_553_756_000 + 31_703_000, ("C3", 2): 794_132_000 + 774_144_000}
 
 
 def _hip():
@@ -61,6 +63,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C3", help="configuration name in paper_2510_08318_amd.synth")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device copy kernel (reference reading for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU (one MI355X); --gpus must be 1")
@@ -137,6 +141,13 @@ def main():
                    "head_tokens_per_s": round(tokens_per_s * x.H, 1)},
         "roofline": roofline,
     }
+    if args.calib_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                      # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(x)
     lay.close()
