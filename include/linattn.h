@@ -79,9 +79,14 @@ int linattn_phi_create(const linattn_phi_desc* desc, int* phi_id_out);
 /* Forget a handle.  E_PHI if it is not live.  Buffers stay the caller's. */
 int linattn_phi_destroy(int phi_id);
 
-/* Scratch bytes linattn_fwd / linattn_bwd need for this problem (pure function of its
- * arguments, no HIP call).  Returns 0 for an invalid argument. */
+/* Scratch bytes linattn_fwd, and linattn_bwd without weight gradients (dwq == dwk == NULL), need
+ * for this problem (pure function of its arguments, no HIP call).  Returns 0 for an invalid
+ * argument. */
 size_t linattn_workspace_bytes(int B, int H, int n, int d, int kind, int dtype);
+
+/* Scratch bytes linattn_bwd needs when the descriptor asks for dwq or dwk (W~ is learnable, Eq. 5):
+ * the above plus two fp32 [B,H,n,d/2] buffers for dL/du and the partial sums of dW~. */
+size_t linattn_workspace_bytes_wgrads(int B, int H, int n, int d, int kind, int dtype);
 
 /*
  * Forward, Eq. 3 with phi of Eq. 5.  Three stages on `stream`: phi(K) fused with a split-n

@@ -17,7 +17,7 @@ E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_PHI, E_WORKSPACE, E_HIP, E_STATE, E_ALIAS =
 PHI_HEDGEHOG = 1
 BF16, F32 = 1, 2
 
-EXPORTS = ("linattn_phi_create", "linattn_phi_destroy", "linattn_workspace_bytes",
+EXPORTS = ("linattn_phi_create", "linattn_phi_destroy", "linattn_workspace_bytes", "linattn_workspace_bytes_wgrads",
            "linattn_fwd", "linattn_bwd", "linattn_strerror", "linattn_set_stage_events")
 
 
@@ -54,6 +54,8 @@ def lib() -> ctypes.CDLL:
         L.linattn_phi_destroy.restype = ci
         L.linattn_workspace_bytes.argtypes = [ci] * 6
         L.linattn_workspace_bytes.restype = ctypes.c_size_t
+        L.linattn_workspace_bytes_wgrads.argtypes = [ci] * 6
+        L.linattn_workspace_bytes_wgrads.restype = ctypes.c_size_t
         L.linattn_fwd.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, vp]
         L.linattn_fwd.restype = ci
         L.linattn_bwd.argtypes = [vp] * 7 + [ci] * 5 + [vp]
@@ -81,6 +83,10 @@ def linattn_strerror(status: int) -> str:
 
 def linattn_workspace_bytes(B: int, H: int, n: int, d: int, kind: int = PHI_HEDGEHOG, dtype: int = BF16) -> int:
     return int(lib().linattn_workspace_bytes(B, H, n, d, kind, dtype))
+
+
+def linattn_workspace_bytes_wgrads(B: int, H: int, n: int, d: int, kind: int = PHI_HEDGEHOG, dtype: int = BF16) -> int:
+    return int(lib().linattn_workspace_bytes_wgrads(B, H, n, d, kind, dtype))
 
 
 def linattn_phi_create(kind, dtype, H, d, wq, wk, dwq=None, dwk=None, state=None,

@@ -40,6 +40,19 @@ bool make_plan(int B, int H, int n, int d, int dtype, Plan* p) {
   size_t off = 0;
   r.off_partials = off; off = up(off + (size_t)BH * r.P * r.state_elems * sizeof(float));
   r.off_state = off;    off = up(off + (size_t)BH * r.state_elems * sizeof(float));
+  {
+    const int nblk = (n + 31) / 32;
+    int KP = kCUs / (int)BH;
+    if (KP < 1) KP = 1;
+    if (KP > (nblk + 3) / 4) KP = (nblk + 3) / 4;
+    r.KP = KP;
+  }
+  r.off_dstate = off;   off = up(off + (size_t)BH * r.state_elems * sizeof(float));
+  r.off_gimg = off;     off = up(off + (size_t)BH * d * d * 2);
+  r.bytes_no_wgrads = off;
+  r.off_dwpart = off;   off = up(off + (size_t)BH * r.P * d * (d / 2) * sizeof(float));
+  r.off_du_q = off;     off = up(off + (size_t)BH * n * (d / 2) * sizeof(float));
+  r.off_du_k = off;     off = up(off + (size_t)BH * n * (d / 2) * sizeof(float));
   r.total_bytes = off;
   *p = r;
   return true;
@@ -81,7 +94,7 @@ int fetch(int phi_id, linattn_phi_desc* out) {
 
 // Checks common to forward and backward.  Fills desc and plan.
 int check_call(const void* const* tensors, int n_tensors, int B, int H, int n, int d, int phi_id,
-               linattn_phi_desc* desc, Plan* plan) {
+               bool want_wgrads, linattn_phi_desc* desc, Plan* plan) {
   int st = fetch(phi_id, desc);
   if (st != LINATTN_OK) return st;
   for (int i = 0; i < n_tensors; ++i)
@@ -90,7 +103,8 @@ int check_call(const void* const* tensors, int n_tensors, int B, int H, int n, i
   if (!make_plan(B, H, n, d, desc->dtype, plan)) return LINATTN_E_SHAPE;
   for (int i = 0; i < n_tensors; ++i)
     if (!aligned16(tensors[i])) return LINATTN_E_ALIGN;
-  if (!desc->workspace || desc->workspace_bytes < plan->total_bytes) return LINATTN_E_WORKSPACE;
+  const size_t need = (want_wgrads && (desc->dwq || desc->dwk)) ? plan->total_bytes : plan->bytes_no_wgrads;
+  if (!desc->workspace || desc->workspace_bytes < need) return LINATTN_E_WORKSPACE;
   return LINATTN_OK;
 }
 
@@ -125,6 +139,13 @@ int linattn_set_stage_events(void* const* events) {
 }
 
 size_t linattn_workspace_bytes(int B, int H, int n, int d, int kind, int dtype) {
+  if (kind != LINATTN_PHI_HEDGEHOG) return 0;
+  Plan p;
+  if (!make_plan(B, H, n, d, dtype, &p)) return 0;
+  return p.bytes_no_wgrads;
+}
+
+size_t linattn_workspace_bytes_wgrads(int B, int H, int n, int d, int kind, int dtype) {
   if (kind != LINATTN_PHI_HEDGEHOG) return 0;
   Plan p;
   if (!make_plan(B, H, n, d, dtype, &p)) return 0;
@@ -167,7 +188,7 @@ int linattn_fwd(const void* q, const void* k, const void* v, void* out,
   linattn_phi_desc desc;
   Plan plan;
   const void* tensors[4] = {q, k, v, out};
-  int st = check_call(tensors, 4, B, H, n, d, phi_id, &desc, &plan);
+  int st = check_call(tensors, 4, B, H, n, d, phi_id, false, &desc, &plan);
   if (st != LINATTN_OK) return st;
   const size_t esz = desc.dtype == LINATTN_BF16 ? 2 : 4;
   const size_t bytes = (size_t)plan.BH * n * d * esz;
@@ -208,11 +229,35 @@ int linattn_bwd(const void* q, const void* k, const void* v, const void* dout,
   linattn_phi_desc desc;
   Plan plan;
   const void* tensors[7] = {q, k, v, dout, dq, dk, dv};
-  int st = check_call(tensors, 7, B, H, n, d, phi_id, &desc, &plan);
+  int st = check_call(tensors, 7, B, H, n, d, phi_id, true, &desc, &plan);
   if (st != LINATTN_OK) return st;
   if (!desc.state) return LINATTN_E_STATE;
-  (void)stream;
-  return LINATTN_E_PHI;  // backward kernels are not built yet
+  const size_t esz = desc.dtype == LINATTN_BF16 ? 2 : 4;
+  const size_t bytes = (size_t)plan.BH * n * d * esz;
+  const void* ins[4] = {q, k, v, dout};
+  void* outs[3] = {dq, dk, dv};
+  for (int i = 0; i < 3; ++i) {
+    for (int j = 0; j < 4; ++j)
+      if (overlaps(outs[i], ins[j], bytes)) return LINATTN_E_ALIAS;
+    for (int j = i + 1; j < 3; ++j)
+      if (overlaps(outs[i], outs[j], bytes)) return LINATTN_E_ALIAS;
+  }
+  char* ws = static_cast<char*>(desc.workspace);
+  BwdArgs a{};
+  a.q = q; a.k = k; a.v = v; a.dout = dout; a.wq = desc.wq; a.wk = desc.wk;
+  a.dq = dq; a.dk = dk; a.dv = dv;
+  a.state = static_cast<const float*>(desc.state);
+  a.dwq = static_cast<float*>(desc.dwq);
+  a.dwk = static_cast<float*>(desc.dwk);
+  a.partials = reinterpret_cast<float*>(ws + plan.off_partials);
+  a.dstate = reinterpret_cast<float*>(ws + plan.off_dstate);
+  a.gimg = ws + plan.off_gimg;
+  a.dw_part = reinterpret_cast<float*>(ws + plan.off_dwpart);
+  a.du_q = reinterpret_cast<float*>(ws + plan.off_du_q);
+  a.du_k = reinterpret_cast<float*>(ws + plan.off_du_k);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const hipError_t e = desc.dtype == LINATTN_BF16 ? launch_bwd_bf16(a, plan, s) : launch_bwd_f32(a, plan, s);
+  return e == hipSuccess ? LINATTN_OK : LINATTN_E_HIP;
 }
 
 }  // extern "C"

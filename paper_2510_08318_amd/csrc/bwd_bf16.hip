@@ -1,0 +1,536 @@
+// bf16-I/O backward path on gfx950 MFMA.  The paper trains through the converted layers
+// (Sec. 5.1) but prints no gradient formula; these kernels apply the chain rule to Eq. 3 and Eq. 5.
+// With S, z from the forward, den_i = phi(q_i).z, o_i = phi(q_i) S / den_i, delta_i = dO_i.o_i:
+//
+//   query side   g_i  = dL/dphi(q_i) = (dO_i S^T - delta_i z) / den_i
+//                dS   = sum_i phi(q_i)^T dO_i / den_i          dz = -sum_i phi(q_i) delta_i / den_i
+//   key side     g_j  = dL/dphi(k_j) = v_j dS^T + dz           dv_j = phi(k_j) dS
+//   through phi  du = p+ (g+ - <g+,p+>) - p- (g- - <g-,p->),   dx = du W~^T,   dW~ = sum x^T du
+//
+// bwd_prep_kernel : fp16 operand image of S for g (rows = features, contraction over channels)
+// bwd_q_kernel    : per 128-token tile: phi(Q), o, delta, g, du, dq; dS, dz partials (split-n)
+// bwd_k_kernel    : per 32-token block: phi(K), g, du, dk, dv
+// (state_reduce.hip) dW~ = sum over tokens and batch of x^T du (fp32, fixed order)
+//
+// Precision: every 16-bit MFMA operand except the stored bf16 q, k (projection) is fp16.
+// Operands that belong to one token only (dO_i for g_i, du_i for dx_i) are scaled by a per-token
+// power of two taken from their largest magnitude, so any gradient scale is safe.  Operands of
+// the sums over tokens (dO_i/den_i, delta_i/den_i) are scaled by one power of two per workgroup,
+// taken from its first tile so that the tile's largest magnitude lands in [16, 32); later tiles
+// may exceed that by 2^11 before fp16 overflows, and values down to 2^-18 of it keep full
+// precision.  Accumulation is fp32 everywhere; partial sums are combined in a fixed order.
+#include "kernels.h"
+#include "mfma_common.h"
+
+namespace linattn {
+namespace {
+
+// power of two p with p * m in [1, 2) (m > 0), 1 for m == 0 or non-finite
+__device__ __forceinline__ float pow2_normaliser(float m) {
+  return (m > 0.f && m < 3.0e38f) ? ldexpf(1.0f, -ilogbf(m)) : 1.0f;
+}
+
+__device__ __forceinline__ void unpack_bf16x8(uint4 v, float* f) {
+  f[0] = __builtin_bit_cast(float, v.x << 16); f[1] = __builtin_bit_cast(float, v.x & 0xffff0000u);
+  f[2] = __builtin_bit_cast(float, v.y << 16); f[3] = __builtin_bit_cast(float, v.y & 0xffff0000u);
+  f[4] = __builtin_bit_cast(float, v.z << 16); f[5] = __builtin_bit_cast(float, v.z & 0xffff0000u);
+  f[6] = __builtin_bit_cast(float, v.w << 16); f[7] = __builtin_bit_cast(float, v.w & 0xffff0000u);
+}
+
+// ---- operand image of S for g ------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void bwd_prep_kernel(const float* __restrict__ state, uint4* __restrict__ gimg) {
+  using G = GradLayout<D>;
+  __shared__ float red[4];
+  const int bh = blockIdx.x, tid = threadIdx.x;
+  const float* S = state + (size_t)bh * (D + 1) * D;
+  const float scale = head_scale<D, 256>(S, red, tid);
+  for (int idx = tid; idx < G::IMG; idx += 256) gimg[(size_t)bh * G::IMG + idx] = grad_image_entry<D>(S, scale, idx);
+}
+
+// Softmax Jacobian of Eq. 5 for one token spread over a lane pair: gacc holds g in the GradLayout
+// row order (first GM/2 blocks the softmax(+u) half, then the softmax(-u) half), already scaled.
+template <int D>
+__device__ __forceinline__ void phi_jacobian(const float (&gp)[Cfg<D>::LOC], const float (&gm)[Cfg<D>::LOC],
+                                             const float (&pp)[Cfg<D>::LOC], const float (&pm)[Cfg<D>::LOC],
+                                             float (&du)[Cfg<D>::LOC]) {
+  using C = Cfg<D>;
+  float cp = 0.f, cm = 0.f;
+#pragma unroll
+  for (int j = 0; j < C::LOC; ++j) { cp = fmaf(gp[j], pp[j], cp); cm = fmaf(gm[j], pm[j], cm); }
+  float lo, hi;
+  pair32(cp, lo, hi); cp = lo + hi;
+  pair32(cm, lo, hi); cm = lo + hi;
+#pragma unroll
+  for (int j = 0; j < C::LOC; ++j) du[j] = pp[j] * (gp[j] - cp) - pm[j] * (gm[j] - cm);
+}
+
+// dx^T = W~ du^T for one token block: du is scaled per token to [1,2), cast to fp16, contracted
+// with the W~ image, unscaled, rounded to bf16 and packed: xo[mb*8 .. mb*8+7] are the 16 channels
+// g*D/2 + 16*mb + r of the lane's token.
+template <int D>
+__device__ __forceinline__ void du_to_dx(const float (&du)[Cfg<D>::LOC], const uint4* sWB, int lane,
+                                         uint32_t (&xo)[D / 4]) {
+  using C = Cfg<D>;
+  using L = ApplyLayout<D>;
+  constexpr int DK = C::LOC / 8;
+  float m = 0.f;
+#pragma unroll
+  for (int j = 0; j < C::LOC; ++j) m = fmaxf(m, fabsf(du[j]));
+  float lo, hi;
+  pair32(m, lo, hi); m = fmaxf(lo, hi);
+  const float ts = pow2_normaliser(m);
+  uint32_t dub[C::LOC / 2];
+#pragma unroll
+  for (int j = 0; j < C::LOC / 2; ++j) dub[j] = pack_f16x2(du[2 * j] * ts, du[2 * j + 1] * ts);
+  f32x16 acc[L::MB];
+#pragma unroll
+  for (int mb = 0; mb < L::MB; ++mb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[mb][r] = 0.f;
+  const uint4* wb = sWB + lane + opaque_zero();
+#pragma unroll
+  for (int ks = 0; ks < DK; ++ks) {
+    uint4 bq; bq.x = dub[4 * ks]; bq.y = dub[4 * ks + 1]; bq.z = dub[4 * ks + 2]; bq.w = dub[4 * ks + 3];
+    const f16x8 bop = as_f16x8(bq);
+#pragma unroll
+    for (int mb = 0; mb < L::MB; ++mb)
+      acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(wb[(ks * L::MB + mb) * 64]), bop, acc[mb], 0, 0, 0);
+  }
+  const float its = __builtin_amdgcn_rcpf(ts);     // exact: ts is a power of two
+#pragma unroll
+  for (int mb = 0; mb < L::MB; ++mb)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) xo[mb * 8 + j] = pack_bf16x2(acc[mb][2 * j] * its, acc[mb][2 * j + 1] * its);
+}
+
+// The lane's half row (channels g*D/2 .. +D/2-1 of token t) as packed bf16: D/16 stores of 16 bytes.
+template <int D>
+__device__ __forceinline__ void store_half_row(uint16_t* base, size_t t, int g, const uint32_t (&xo)[D / 4]) {
+  uint4* row = reinterpret_cast<uint4*>(base + t * D + g * (D / 2));
+#pragma unroll
+  for (int i = 0; i < D / 16; ++i) {
+    uint4 v; v.x = xo[4 * i]; v.y = xo[4 * i + 1]; v.z = xo[4 * i + 2]; v.w = xo[4 * i + 3];
+    row[i] = v;
+  }
+}
+
+// ---- query side --------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ dout,
+                                                   const uint16_t* __restrict__ wq, const float* __restrict__ state,
+                                                   const uint4* __restrict__ gimg, uint16_t* __restrict__ dq,
+                                                   float* __restrict__ partials, float* __restrict__ du_ws,
+                                                   int H, int n, int P) {
+  using C = Cfg<D>;
+  using L = ApplyLayout<D>;
+  using G = GradLayout<D>;
+  constexpr int RS = D * 2;
+  constexpr int WMN = D / 64;
+  constexpr int SA_IMG = L::KS * L::MBZ * 64;
+  constexpr int WB_IMG = (C::LOC / 8) * L::MB * 64;
+  extern __shared__ uint4 smem[];
+  uint4* sWA = smem;
+  uint4* sSA = sWA + C::W_IMG;
+  uint4* sWB = sSA + SA_IMG;
+  char* sPhi = reinterpret_cast<char*>(sWB + WB_IMG);      // [kTile][D] fp16: phi(q)
+  char* sDO = sPhi + kTile * RS;                           // [kTile][D] fp16: gamma * dO / den
+  uint16_t* sW16 = reinterpret_cast<uint16_t*>(sDO + kTile * RS);   // [kTile] fp16: -gamma * delta / den
+  float* sZ = reinterpret_cast<float*>(sW16 + kTile);      // [D] z, unscaled
+  float* sRed = sZ + D;                                    // [8]
+
+  const int tid = threadIdx.x, lane = tid % 64;
+  const int w = __builtin_amdgcn_readfirstlane(tid / 64);
+  const int g = lane / 32;
+  const int mi = w / 2, ni = w % 2;
+  const int bh = blockIdx.y, p = blockIdx.x, h = bh % H;
+  const uint16_t* qb = q + (size_t)bh * n * D;
+  const uint16_t* dob = dout + (size_t)bh * n * D;
+  uint16_t* dqb = dq + (size_t)bh * n * D;
+  const float* sb = state + (size_t)bh * (D + 1) * D;
+  const uint4* gim = gimg + (size_t)bh * G::IMG;
+  const int ntile = (n + kTile - 1) / kTile;
+
+  build_w_image<D, NT>(wq + (size_t)h * D * C::HALF, sWA, tid);
+  build_w_image_t<D, NT>(wq + (size_t)h * D * C::HALF, sWB, tid);
+  const float scale = head_scale<D, NT>(sb, sRed, tid);
+  build_state_image<D, NT>(sb, sSA, scale, tid);
+  for (int i = tid; i < D; i += NT) sZ[i] = sb[D * D + i];
+  __syncthreads();
+
+  f32x16 s[WMN][WMN], zacc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    zacc[r] = 0.f;
+#pragma unroll
+    for (int i = 0; i < WMN; ++i)
+#pragma unroll
+      for (int j = 0; j < WMN; ++j) s[i][j][r] = 0.f;
+  }
+  const int zmb = (WMN == 2) ? (2 * mi + ni) : mi;
+  const bool do_z = (WMN == 2) || (ni == 0);
+  int offA[WMN][2], offB[WMN][2];
+#pragma unroll
+  for (int i = 0; i < WMN; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      offA[i][j] = tr_offset<D>(32 * (mi * WMN + i), lane, j);
+      offB[i][j] = tr_offset<D>(32 * (ni * WMN + i), lane, j);
+    }
+  const int prow = 32 * w + (lane % 32);
+  const int psw = swz<D>(prow);
+  float gamma = 1.f;
+
+  for (int tile = p; tile < ntile; tile += P) {
+    const int t = tile * kTile + prow;
+    const bool valid = t < n;
+    const int tc = valid ? t : (n - 1);
+    uint4 xq[C::UK], dor[D / 16];
+    {
+      const uint4* row = reinterpret_cast<const uint4*>(qb + (size_t)tc * D);
+#pragma unroll
+      for (int ks = 0; ks < C::UK; ++ks) xq[ks] = row[2 * ks + g];
+      const uint4* drow = reinterpret_cast<const uint4*>(dob + (size_t)tc * D + g * (D / 2));
+#pragma unroll
+      for (int i = 0; i < D / 16; ++i) dor[i] = drow[i];
+    }
+    f32x16 u[C::UM];
+    project<D>(xq, sWA, lane, u);
+    float pp[C::LOC], pm[C::LOC];
+    uint32_t pk[C::NPK];
+    softmax_full<D>(u, pp, pm, pk);
+
+    // o = phi(q) S / den on the lane's channels g*D/2 + 16*mb + r
+    float o[D / 2];
+    float den_s;                                   // scale * den
+    {
+      f32x16 oa[L::MB], dn;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        dn[r] = 0.f;
+#pragma unroll
+        for (int mb = 0; mb < L::MB; ++mb) oa[mb][r] = 0.f;
+      }
+      const uint4* ssa = sSA + lane + opaque_zero();
+#pragma unroll
+      for (int ks = 0; ks < L::KS; ++ks) {
+        uint4 bq; bq.x = pk[4 * ks]; bq.y = pk[4 * ks + 1]; bq.z = pk[4 * ks + 2]; bq.w = pk[4 * ks + 3];
+        const f16x8 bop = as_f16x8(bq);
+#pragma unroll
+        for (int mb = 0; mb < L::MB; ++mb)
+          oa[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(ssa[(ks * L::MBZ + mb) * 64]), bop, oa[mb], 0, 0, 0);
+        dn = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(ssa[(ks * L::MBZ + L::MB) * 64]), bop, dn, 0, 0, 0);
+      }
+      den_s = dn[0];
+      const float inv = __builtin_amdgcn_rcpf(den_s);
+#pragma unroll
+      for (int mb = 0; mb < L::MB; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[16 * mb + r] = oa[mb][r] * inv;
+    }
+    const float inv_den = scale * __builtin_amdgcn_rcpf(den_s);     // 1 / den
+
+    // dO on the same channels, delta = dO . o
+    float dof[D / 2];
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) unpack_bf16x8(dor[i], dof + 8 * i);
+    float delta = 0.f, dmax = 0.f;
+#pragma unroll
+    for (int c = 0; c < D / 2; ++c) { delta = fmaf(dof[c], o[c], delta); dmax = fmaxf(dmax, fabsf(dof[c])); }
+    float lo, hi;
+    pair32(delta, lo, hi); delta = lo + hi;
+    pair32(dmax, lo, hi); dmax = fmaxf(lo, hi);
+    const float stok = pow2_normaliser(dmax);
+
+    // g = (dO S^T - delta z) / den, rows laid out like phi
+    float gp[C::LOC], gm[C::LOC];
+    {
+      f32x16 ga[G::GM];
+#pragma unroll
+      for (int mb = 0; mb < G::GM; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) ga[mb][r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < G::KS; ++ks) {
+        uint4 bq;
+        bq.x = pack_f16x2(dof[8 * ks] * stok, dof[8 * ks + 1] * stok);     bq.y = pack_f16x2(dof[8 * ks + 2] * stok, dof[8 * ks + 3] * stok);
+        bq.z = pack_f16x2(dof[8 * ks + 4] * stok, dof[8 * ks + 5] * stok); bq.w = pack_f16x2(dof[8 * ks + 6] * stok, dof[8 * ks + 7] * stok);
+        const f16x8 bop = as_f16x8(bq);
+#pragma unroll
+        for (int mb = 0; mb < G::GM; ++mb)
+          ga[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(gim[(ks * G::GM + mb) * 64 + lane]), bop, ga[mb], 0, 0, 0);
+      }
+      const float r1 = __builtin_amdgcn_rcpf(den_s * stok);          // 1 / (scale * stok * den)
+      const float r2 = delta * inv_den;
+#pragma unroll
+      for (int mb = 0; mb < G::GM; ++mb) {
+        const int f0 = (mb < G::GM / 2 ? 0 : C::HALF) + g * C::LOC + 16 * (mb % (G::GM / 2));
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float val = ga[mb][r] * r1 - r2 * sZ[f0 + r];
+          if (mb < G::GM / 2) gp[16 * mb + r] = val; else gm[16 * (mb - G::GM / 2) + r] = val;
+        }
+      }
+    }
+    float du[C::LOC];
+    phi_jacobian<D>(gp, gm, pp, pm, du);
+
+    uint32_t xo[D / 4];
+    du_to_dx<D>(du, sWB, lane, xo);
+    if (valid) {
+      store_half_row<D>(dqb, (size_t)t, g, xo);
+      if (du_ws) {
+        float4* drow = reinterpret_cast<float4*>(du_ws + ((size_t)bh * n + t) * C::HALF + g * C::LOC);
+#pragma unroll
+        for (int i = 0; i < C::LOC / 4; ++i) drow[i] = make_float4(du[4 * i], du[4 * i + 1], du[4 * i + 2], du[4 * i + 3]);
+      }
+    }
+
+    // operands of the sums over tokens
+    if (tile == p) {
+      float m = valid ? dmax * inv_den : 0.f;
+      for (int k = 32; k >= 1; k >>= 1) m = fmaxf(m, __shfl_xor(m, k, 64));
+      if (lane == 0) sRed[w] = m;
+      __syncthreads();
+      m = fmaxf(fmaxf(sRed[0], sRed[1]), fmaxf(sRed[2], sRed[3]));
+      gamma = 16.f * pow2_normaliser(m);
+    }
+    __syncthreads();                             // previous tile's operand reads are done
+    {
+      char* rowp = sPhi + prow * RS;
+      constexpr int CPH = C::LOC / 8;
+#pragma unroll
+      for (int c = 0; c < CPH; ++c) {
+        uint4 a, b;
+        a.x = pk[4 * c]; a.y = pk[4 * c + 1]; a.z = pk[4 * c + 2]; a.w = pk[4 * c + 3];
+        b.x = pk[C::LOC / 2 + 4 * c]; b.y = pk[C::LOC / 2 + 4 * c + 1];
+        b.z = pk[C::LOC / 2 + 4 * c + 2]; b.w = pk[C::LOC / 2 + 4 * c + 3];
+        if (!valid) { a = make_uint4(0, 0, 0, 0); b = a; }
+        *reinterpret_cast<uint4*>(rowp + (((g * CPH + c) ^ psw) * 16)) = a;
+        *reinterpret_cast<uint4*>(rowp + (((C::CH / 2 + g * CPH + c) ^ psw) * 16)) = b;
+      }
+      const float sc = valid ? inv_den * gamma : 0.f;
+      char* drowp = sDO + prow * RS;
+#pragma unroll
+      for (int c = 0; c < D / 16; ++c) {
+        uint4 a;
+        a.x = pack_f16x2(dof[8 * c] * sc, dof[8 * c + 1] * sc);     a.y = pack_f16x2(dof[8 * c + 2] * sc, dof[8 * c + 3] * sc);
+        a.z = pack_f16x2(dof[8 * c + 4] * sc, dof[8 * c + 5] * sc); a.w = pack_f16x2(dof[8 * c + 6] * sc, dof[8 * c + 7] * sc);
+        *reinterpret_cast<uint4*>(drowp + (((g * (C::CH / 2) + c) ^ psw) * 16)) = a;
+      }
+      if (g == 0) sW16[prow] = (uint16_t)(pack_f16x2(valid ? -delta * sc : 0.f, 0.f) & 0xffffu);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < kTile / 16; ++ks) {
+      f16x8 a[WMN], b[WMN];
+#pragma unroll
+      for (int i = 0; i < WMN; ++i) a[i] = read_tr(sPhi + ks * 16 * RS, offA[i][0], offA[i][1]);
+#pragma unroll
+      for (int j = 0; j < WMN; ++j) b[j] = read_tr(sDO + ks * 16 * RS, offB[j][0], offB[j][1]);
+#pragma unroll
+      for (int i = 0; i < WMN; ++i)
+#pragma unroll
+        for (int j = 0; j < WMN; ++j) s[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], s[i][j], 0, 0, 0);
+      // dz row block: B operand = the 8 tokens' weights, the same in every column
+      const f16x8 wop = as_f16x8(*reinterpret_cast<const uint4*>(sW16 + 16 * ks + 8 * g));
+      if (WMN == 2) {
+        if (ni == 0) zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], wop, zacc, 0, 0, 0);
+        else zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[WMN - 1], wop, zacc, 0, 0, 0);
+      } else if (do_z) {
+        zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], wop, zacc, 0, 0, 0);
+      }
+    }
+  }
+
+  const float ig = __builtin_amdgcn_rcpf(gamma);    // exact: gamma is a power of two
+  float* dst = partials + ((size_t)bh * P + p) * (size_t)(D + 1) * D;
+  const int c = lane % 32;
+#pragma unroll
+  for (int i = 0; i < WMN; ++i)
+#pragma unroll
+    for (int j = 0; j < WMN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int f = 32 * (mi * WMN + i) + 8 * (r / 4) + 4 * g + (r % 4);
+        dst[f * D + 32 * (ni * WMN + j) + c] = s[i][j][r] * ig;
+      }
+  if (do_z && c == 0) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dst[D * D + 32 * zmb + 8 * (r / 4) + 4 * g + (r % 4)] = zacc[r] * ig;
+  }
+}
+
+// ---- key side ----------------------------------------------------------------------------
+constexpr int NTK = 256;
+
+template <int D>
+__global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+                                                    const uint16_t* __restrict__ wk, const float* __restrict__ dstate,
+                                                    uint16_t* __restrict__ dk, uint16_t* __restrict__ dv,
+                                                    float* __restrict__ du_ws, int H, int n) {
+  using C = Cfg<D>;
+  using L = ApplyLayout<D>;
+  using G = GradLayout<D>;
+  constexpr int NW = NTK / 64;
+  constexpr int SA_IMG = L::KS * L::MBZ * 64;
+  constexpr int WB_IMG = (C::LOC / 8) * L::MB * 64;
+  extern __shared__ uint4 smem[];
+  uint4* sWA = smem;
+  uint4* sVA = sWA + C::W_IMG;             // image of dS^T for dv (contraction over features)
+  uint4* sGA = sVA + SA_IMG;               // image of dS for g (contraction over channels)
+  uint4* sWB = sGA + G::IMG;
+  float* sZ = reinterpret_cast<float*>(sWB + WB_IMG);   // [D] dz, unscaled
+  float* sRed = sZ + D;
+
+  const int tid = threadIdx.x, lane = tid % 64;
+  const int w = __builtin_amdgcn_readfirstlane(tid / 64);
+  const int g = lane / 32;
+  const int bh = blockIdx.y, h = bh % H;
+  const uint16_t* kb = k + (size_t)bh * n * D;
+  const uint16_t* vb = v + (size_t)bh * n * D;
+  uint16_t* dkb = dk + (size_t)bh * n * D;
+  uint16_t* dvb = dv + (size_t)bh * n * D;
+  const float* ds = dstate + (size_t)bh * (D + 1) * D;
+
+  build_w_image<D, NTK>(wk + (size_t)h * D * C::HALF, sWA, tid);
+  build_w_image_t<D, NTK>(wk + (size_t)h * D * C::HALF, sWB, tid);
+  const float scale = head_scale<D, NTK>(ds, sRed, tid);
+  build_state_image<D, NTK>(ds, sVA, scale, tid);
+  for (int idx = tid; idx < G::IMG; idx += NTK) sGA[idx] = grad_image_entry<D>(ds, scale, idx);
+  for (int i = tid; i < D; i += NTK) sZ[i] = ds[D * D + i];
+  __syncthreads();
+  const float inv_scale = __builtin_amdgcn_rcpf(scale);    // exact: power of two
+
+  const int nblk = (n + 31) / 32;
+  const int stride = gridDim.x * NW;
+  for (int b = blockIdx.x * NW + w; b < nblk; b += stride) {
+    const int t = b * 32 + (lane % 32);
+    const bool valid = t < n;
+    const int tc = valid ? t : (n - 1);
+    uint4 xk[C::UK], vr[D / 16];
+    {
+      const uint4* row = reinterpret_cast<const uint4*>(kb + (size_t)tc * D);
+#pragma unroll
+      for (int ks = 0; ks < C::UK; ++ks) xk[ks] = row[2 * ks + g];
+      const uint4* vrow = reinterpret_cast<const uint4*>(vb + (size_t)tc * D + g * (D / 2));
+#pragma unroll
+      for (int i = 0; i < D / 16; ++i) vr[i] = vrow[i];
+    }
+    f32x16 u[C::UM];
+    project<D>(xk, sWA, lane, u);
+    float pp[C::LOC], pm[C::LOC];
+    uint32_t pk[C::NPK];
+    softmax_full<D>(u, pp, pm, pk);
+
+    // dv = phi(k) dS on the lane's channels
+    {
+      f32x16 va[L::MB];
+#pragma unroll
+      for (int mb = 0; mb < L::MB; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) va[mb][r] = 0.f;
+      const uint4* sva = sVA + lane + opaque_zero();
+#pragma unroll
+      for (int ks = 0; ks < L::KS; ++ks) {
+        uint4 bq; bq.x = pk[4 * ks]; bq.y = pk[4 * ks + 1]; bq.z = pk[4 * ks + 2]; bq.w = pk[4 * ks + 3];
+        const f16x8 bop = as_f16x8(bq);
+#pragma unroll
+        for (int mb = 0; mb < L::MB; ++mb)
+          va[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(sva[(ks * L::MBZ + mb) * 64]), bop, va[mb], 0, 0, 0);
+      }
+      uint32_t xo[D / 4];
+#pragma unroll
+      for (int mb = 0; mb < L::MB; ++mb)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) xo[mb * 8 + j] = pack_bf16x2(va[mb][2 * j] * inv_scale, va[mb][2 * j + 1] * inv_scale);
+      if (valid) store_half_row<D>(dvb, (size_t)t, g, xo);
+    }
+
+    // g = v dS^T + dz, rows laid out like phi
+    float gp[C::LOC], gm[C::LOC];
+    {
+      f32x16 ga[G::GM];
+#pragma unroll
+      for (int mb = 0; mb < G::GM; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) ga[mb][r] = 0.f;
+      const uint4* sga = sGA + lane + opaque_zero();
+#pragma unroll
+      for (int ks = 0; ks < G::KS; ++ks) {
+        uint4 bq;
+        bq.x = bf16x2_to_f16x2(vr[ks].x); bq.y = bf16x2_to_f16x2(vr[ks].y);
+        bq.z = bf16x2_to_f16x2(vr[ks].z); bq.w = bf16x2_to_f16x2(vr[ks].w);
+        const f16x8 bop = as_f16x8(bq);
+#pragma unroll
+        for (int mb = 0; mb < G::GM; ++mb)
+          ga[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(sga[(ks * G::GM + mb) * 64]), bop, ga[mb], 0, 0, 0);
+      }
+#pragma unroll
+      for (int mb = 0; mb < G::GM; ++mb) {
+        const int f0 = (mb < G::GM / 2 ? 0 : C::HALF) + g * C::LOC + 16 * (mb % (G::GM / 2));
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float val = fmaf(ga[mb][r], inv_scale, sZ[f0 + r]);
+          if (mb < G::GM / 2) gp[16 * mb + r] = val; else gm[16 * (mb - G::GM / 2) + r] = val;
+        }
+      }
+    }
+    float du[C::LOC];
+    phi_jacobian<D>(gp, gm, pp, pm, du);
+    uint32_t xo[D / 4];
+    du_to_dx<D>(du, sWB, lane, xo);
+    if (valid) {
+      store_half_row<D>(dkb, (size_t)t, g, xo);
+      if (du_ws) {
+        float4* drow = reinterpret_cast<float4*>(du_ws + ((size_t)bh * n + t) * C::HALF + g * C::LOC);
+#pragma unroll
+        for (int i = 0; i < C::LOC / 4; ++i) drow[i] = make_float4(du[4 * i], du[4 * i + 1], du[4 * i + 2], du[4 * i + 3]);
+      }
+    }
+  }
+}
+
+template <int D>
+constexpr size_t q_smem() {
+  return sizeof(uint4) * (Cfg<D>::W_IMG + ApplyLayout<D>::KS * ApplyLayout<D>::MBZ * 64 + (Cfg<D>::LOC / 8) * ApplyLayout<D>::MB * 64)
+       + 2 * (size_t)kTile * D * 2 + kTile * 2 + (D + 8) * sizeof(float);
+}
+template <int D>
+constexpr size_t k_smem() {
+  return sizeof(uint4) * (Cfg<D>::W_IMG + ApplyLayout<D>::KS * ApplyLayout<D>::MBZ * 64 + GradLayout<D>::IMG
+                          + (Cfg<D>::LOC / 8) * ApplyLayout<D>::MB * 64) + (D + 8) * sizeof(float);
+}
+template <typename K>
+hipError_t set_smem(K kernel, size_t bytes) {
+  return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+template <int D>
+hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
+  hipError_t e;
+  bwd_prep_kernel<D><<<p.BH, 256, 0, s>>>(a.state, (uint4*)a.gimg);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if ((e = set_smem(bwd_q_kernel<D>, q_smem<D>())) != hipSuccess) return e;
+  bwd_q_kernel<D><<<dim3(p.P, p.BH), NT, q_smem<D>(), s>>>(
+      (const uint16_t*)a.q, (const uint16_t*)a.dout, (const uint16_t*)a.wq, a.state, (const uint4*)a.gimg,
+      (uint16_t*)a.dq, a.partials, a.dwq ? a.du_q : nullptr, p.H, p.n, p.P);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if ((e = launch_state_reduce(a.partials, a.dstate, p, s)) != hipSuccess) return e;
+  if ((e = set_smem(bwd_k_kernel<D>, k_smem<D>())) != hipSuccess) return e;
+  bwd_k_kernel<D><<<dim3(p.KP, p.BH), NTK, k_smem<D>(), s>>>(
+      (const uint16_t*)a.k, (const uint16_t*)a.v, (const uint16_t*)a.wk, a.dstate,
+      (uint16_t*)a.dk, (uint16_t*)a.dv, a.dwk ? a.du_k : nullptr, p.H, p.n);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (a.dwq && (e = launch_dw(a.q, true, a.du_q, a.dw_part, a.dwq, p, s)) != hipSuccess) return e;
+  if (a.dwk && (e = launch_dw(a.k, true, a.du_k, a.dw_part, a.dwk, p, s)) != hipSuccess) return e;
+  return hipSuccess;
+}
+
+}  // namespace
+
+hipError_t launch_bwd_bf16(const BwdArgs& a, const Plan& p, hipStream_t s) {
+  return p.d == 128 ? run_bwd<128>(a, p, s) : run_bwd<64>(a, p, s);
+}
+
+}  // namespace linattn

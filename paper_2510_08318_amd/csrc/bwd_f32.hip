@@ -1,0 +1,263 @@
+// fp32 backward path (no bf16/fp16 anywhere): plain FMA on LDS tiles of 16 tokens.
+// Same mathematics as bwd_bf16.hip (chain rule through Eq. 3 and Eq. 5); this mode exists for the
+// 1e-5 accuracy contract on fp32 tensors, not for bandwidth.
+#include "kernels.h"
+#include "f32_common.h"
+
+namespace linattn {
+namespace {
+
+using namespace f32;
+constexpr int TB = 16;        // tokens per tile
+constexpr int TPT = NT / TB;  // threads per token (16)
+
+// du for a tile: sG [TB][D] = dL/dphi, sPhi [TB][D] = phi; writes sDU [TB][D/2].
+// Contains __syncthreads(); sC: [TB][2] scratch.
+template <int D>
+__device__ __forceinline__ void jacobian_tile(const float* sG, const float* sPhi, float* sDU, float* sC, int tid) {
+  constexpr int HALF = D / 2;
+  if (tid < 2 * TB) {
+    const int tt = tid / 2, half = tid % 2;
+    float c = 0.f;
+    for (int a = 0; a < HALF; ++a) c = fmaf(sG[tt * D + half * HALF + a], sPhi[tt * D + half * HALF + a], c);
+    sC[tt * 2 + half] = c;
+  }
+  __syncthreads();
+  for (int i = tid; i < TB * HALF; i += NT) {
+    const int tt = i / HALF, a = i % HALF;
+    sDU[tt * HALF + a] = sPhi[tt * D + a] * (sG[tt * D + a] - sC[tt * 2])
+                       - sPhi[tt * D + HALF + a] * (sG[tt * D + HALF + a] - sC[tt * 2 + 1]);
+  }
+  __syncthreads();
+}
+
+// dx[tt][c] = sum_a du[tt][a] W[c][a], stored for valid tokens; optional copy of du to the workspace.
+template <int D>
+__device__ __forceinline__ void dx_tile(const float* sDU, const float* sW, float* xout, float* du_ws,
+                                        int t0, int n_valid, int tid) {
+  constexpr int HALF = D / 2;
+  const int tt = tid / TPT, cb = tid % TPT;
+  if (tt < n_valid) {
+#pragma unroll 1
+    for (int j = 0; j < D / TPT; ++j) {
+      const int c = cb + TPT * j;
+      float acc = 0.f;
+      for (int a = 0; a < HALF; ++a) acc = fmaf(sDU[tt * HALF + a], sW[c * HALF + a], acc);
+      xout[(size_t)(t0 + tt) * D + c] = acc;
+    }
+    if (du_ws)
+      for (int a = cb; a < HALF; a += TPT) du_ws[(size_t)(t0 + tt) * HALF + a] = sDU[tt * HALF + a];
+  }
+}
+
+template <int D>
+__global__ __launch_bounds__(NT) void bwd_q_f32_kernel(const float* __restrict__ q, const float* __restrict__ dout,
+                                                       const float* __restrict__ wq, const float* __restrict__ state,
+                                                       float* __restrict__ dq, float* __restrict__ partials,
+                                                       float* __restrict__ du_ws, int H, int n, int P, int chunk) {
+  constexpr int HALF = D / 2;
+  constexpr int BLK = D / 16;
+  constexpr int SS = D + 1;                 // row stride of the state copy (bank spread)
+  extern __shared__ float smem[];
+  float* sW = smem;                         // [D][HALF]
+  float* sS = sW + D * HALF;                // [D+1][SS]
+  float* sX = sS + (D + 1) * SS;            // [TB][D+1]
+  float* sPhi = sX + TB * (D + 1);          // [TB][D]
+  float* sDO = sPhi + TB * D;               // [TB][D]   dO, later dO / den
+  float* sG = sDO + TB * D;                 // [TB][D]   o, then g
+  float* sDU = sG + TB * D;                 // [TB][HALF]
+  float* sDen = sDU + TB * HALF;            // [TB]
+  float* sDel = sDen + TB;                  // [TB]
+  float* sC = sDel + TB;                    // [TB][2]
+
+  const int tid = threadIdx.x;
+  const int bh = blockIdx.y, p = blockIdx.x, h = bh % H;
+  const int t_begin = p * chunk, t_end = min(n, t_begin + chunk);
+  const float* qb = q + (size_t)bh * n * D;
+  const float* dob = dout + (size_t)bh * n * D;
+  float* dqb = dq + (size_t)bh * n * D;
+  const float* wb = wq + (size_t)h * D * HALF;
+  const float* sb = state + (size_t)bh * (D + 1) * D;
+  for (int i = tid; i < D * HALF; i += NT) sW[i] = wb[i];
+  for (int i = tid; i < (D + 1) * D; i += NT) sS[(i / D) * SS + (i % D)] = sb[i];
+
+  float acc[BLK][BLK];
+#pragma unroll
+  for (int i = 0; i < BLK; ++i)
+#pragma unroll
+    for (int j = 0; j < BLK; ++j) acc[i][j] = 0.f;
+  float zacc = 0.f;
+  const int f0 = (tid / 16) * BLK, c0 = (tid % 16) * BLK;
+  const int tt = tid / TPT, cb = tid % TPT;
+
+  for (int t0 = t_begin; t0 < t_end; t0 += TB) {
+    const int n_valid = min(TB, t_end - t0);
+    __syncthreads();
+    for (int i = tid; i < TB * D; i += NT) {
+      const int r = i / D, c = i % D;
+      const bool valid = r < n_valid;
+      sX[r * (D + 1) + c] = valid ? qb[(size_t)(t0 + r) * D + c] : 0.f;
+      sDO[r * D + c] = valid ? dob[(size_t)(t0 + r) * D + c] : 0.f;
+    }
+    __syncthreads();
+    phi_tile<D, TB>(sX, sW, sPhi, tid, n_valid);     // rows >= n_valid are zero
+    // o = phi S / den  -> sG, den -> sDen
+    {
+      float den = 0.f;
+      for (int f = 0; f < D; ++f) den = fmaf(sPhi[tt * D + f], sS[D * SS + f], den);
+      const float inv = tt < n_valid ? 1.0f / den : 0.f;
+#pragma unroll 1
+      for (int j = 0; j < D / TPT; ++j) {
+        const int c = cb + TPT * j;
+        float a = 0.f;
+        for (int f = 0; f < D; ++f) a = fmaf(sPhi[tt * D + f], sS[f * SS + c], a);
+        sG[tt * D + c] = a * inv;
+      }
+      if (cb == 0) sDen[tt] = tt < n_valid ? den : 1.f;
+    }
+    __syncthreads();
+    if (tid < TB) {
+      float dl = 0.f;
+      for (int c = 0; c < D; ++c) dl = fmaf(sDO[tid * D + c], sG[tid * D + c], dl);
+      sDel[tid] = dl;
+    }
+    __syncthreads();
+    // g = (dO S^T - delta z) / den  -> sG (o is dead)
+    {
+      const float inv = 1.0f / sDen[tt];
+      const float dl = sDel[tt];
+      float gv[D / TPT];
+#pragma unroll 1
+      for (int j = 0; j < D / TPT; ++j) {
+        const int f = cb + TPT * j;
+        float a = 0.f;
+        for (int c = 0; c < D; ++c) a = fmaf(sDO[tt * D + c], sS[f * SS + c], a);
+        gv[j] = (a - dl * sS[D * SS + f]) * inv;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < D / TPT; ++j) sG[tt * D + cb + TPT * j] = gv[j];
+      // dO / den in place (operand of dS); delta / den
+#pragma unroll 1
+      for (int j = 0; j < D / TPT; ++j) sDO[tt * D + cb + TPT * j] *= inv;
+      if (cb == 0) sDel[tt] = dl * inv;
+    }
+    __syncthreads();
+    jacobian_tile<D>(sG, sPhi, sDU, sC, tid);
+    dx_tile<D>(sDU, sW, dqb, du_ws ? du_ws + (size_t)bh * n * HALF : nullptr, t0, n_valid, tid);
+    // dS += phi^T (dO / den), dz -= phi * (delta / den)
+    for (int r = 0; r < TB; ++r) {
+      float a[BLK], b[BLK];
+#pragma unroll
+      for (int i = 0; i < BLK; ++i) a[i] = sPhi[r * D + f0 + i];
+#pragma unroll
+      for (int j = 0; j < BLK; ++j) b[j] = sDO[r * D + c0 + j];
+#pragma unroll
+      for (int i = 0; i < BLK; ++i)
+#pragma unroll
+        for (int j = 0; j < BLK; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    }
+    if (tid < D)
+      for (int r = 0; r < TB; ++r) zacc = fmaf(-sPhi[r * D + tid], sDel[r], zacc);
+  }
+
+  float* dst = partials + ((size_t)bh * P + p) * (size_t)(D + 1) * D;
+#pragma unroll
+  for (int i = 0; i < BLK; ++i)
+#pragma unroll
+    for (int j = 0; j < BLK; ++j) dst[(f0 + i) * D + c0 + j] = acc[i][j];
+  if (tid < D) dst[D * D + tid] = zacc;
+}
+
+template <int D>
+__global__ __launch_bounds__(NT) void bwd_k_f32_kernel(const float* __restrict__ k, const float* __restrict__ v,
+                                                       const float* __restrict__ wk, const float* __restrict__ dstate,
+                                                       float* __restrict__ dk, float* __restrict__ dv,
+                                                       float* __restrict__ du_ws, int H, int n, int chunk) {
+  constexpr int HALF = D / 2;
+  constexpr int SS = D + 1;
+  extern __shared__ float smem[];
+  float* sW = smem;
+  float* sS = sW + D * HALF;                // dS, dz  [D+1][SS]
+  float* sX = sS + (D + 1) * SS;            // [TB][D+1]
+  float* sPhi = sX + TB * (D + 1);
+  float* sV = sPhi + TB * D;
+  float* sG = sV + TB * D;
+  float* sDU = sG + TB * D;
+  float* sC = sDU + TB * HALF;
+
+  const int tid = threadIdx.x;
+  const int bh = blockIdx.y, p = blockIdx.x, h = bh % H;
+  const int t_begin = p * chunk, t_end = min(n, t_begin + chunk);
+  const float* kb = k + (size_t)bh * n * D;
+  const float* vb = v + (size_t)bh * n * D;
+  float* dkb = dk + (size_t)bh * n * D;
+  float* dvb = dv + (size_t)bh * n * D;
+  const float* wb = wk + (size_t)h * D * HALF;
+  const float* sb = dstate + (size_t)bh * (D + 1) * D;
+  for (int i = tid; i < D * HALF; i += NT) sW[i] = wb[i];
+  for (int i = tid; i < (D + 1) * D; i += NT) sS[(i / D) * SS + (i % D)] = sb[i];
+  const int tt = tid / TPT, cb = tid % TPT;
+
+  for (int t0 = t_begin; t0 < t_end; t0 += TB) {
+    const int n_valid = min(TB, t_end - t0);
+    __syncthreads();
+    for (int i = tid; i < TB * D; i += NT) {
+      const int r = i / D, c = i % D;
+      const bool valid = r < n_valid;
+      sX[r * (D + 1) + c] = valid ? kb[(size_t)(t0 + r) * D + c] : 0.f;
+      sV[r * D + c] = valid ? vb[(size_t)(t0 + r) * D + c] : 0.f;
+    }
+    __syncthreads();
+    phi_tile<D, TB>(sX, sW, sPhi, tid, n_valid);
+    // dv = phi dS ; g = v dS^T + dz
+#pragma unroll 1
+    for (int j = 0; j < D / TPT; ++j) {
+      const int c = cb + TPT * j;
+      float a = 0.f, gsum = 0.f;
+      for (int f = 0; f < D; ++f) a = fmaf(sPhi[tt * D + f], sS[f * SS + c], a);
+      if (tt < n_valid) dvb[(size_t)(t0 + tt) * D + c] = a;
+      const int f = c;
+      for (int cc = 0; cc < D; ++cc) gsum = fmaf(sV[tt * D + cc], sS[f * SS + cc], gsum);
+      sG[tt * D + f] = gsum + sS[D * SS + f];
+    }
+    __syncthreads();
+    jacobian_tile<D>(sG, sPhi, sDU, sC, tid);
+    dx_tile<D>(sDU, sW, dkb, du_ws ? du_ws + (size_t)bh * n * HALF : nullptr, t0, n_valid, tid);
+  }
+}
+
+template <int D>
+constexpr size_t q_smem() {
+  return sizeof(float) * (D * (D / 2) + (D + 1) * (D + 1) + TB * (D + 1) + 3 * TB * D + TB * (D / 2) + 4 * TB);
+}
+template <int D>
+constexpr size_t k_smem() {
+  return sizeof(float) * (D * (D / 2) + (D + 1) * (D + 1) + TB * (D + 1) + 3 * TB * D + TB * (D / 2) + 2 * TB);
+}
+
+template <int D>
+hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
+  hipError_t e;
+  const dim3 grid(p.P, p.BH);
+  if ((e = hipFuncSetAttribute((const void*)bwd_q_f32_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)q_smem<D>())) != hipSuccess) return e;
+  bwd_q_f32_kernel<D><<<grid, NT, q_smem<D>(), s>>>((const float*)a.q, (const float*)a.dout, (const float*)a.wq, a.state,
+                                                    (float*)a.dq, a.partials, a.dwq ? a.du_q : nullptr, p.H, p.n, p.P, p.chunk);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if ((e = launch_state_reduce(a.partials, a.dstate, p, s)) != hipSuccess) return e;
+  if ((e = hipFuncSetAttribute((const void*)bwd_k_f32_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)k_smem<D>())) != hipSuccess) return e;
+  bwd_k_f32_kernel<D><<<grid, NT, k_smem<D>(), s>>>((const float*)a.k, (const float*)a.v, (const float*)a.wk, a.dstate,
+                                                    (float*)a.dk, (float*)a.dv, a.dwk ? a.du_k : nullptr, p.H, p.n, p.chunk);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (a.dwq && (e = launch_dw(a.q, false, a.du_q, a.dw_part, a.dwq, p, s)) != hipSuccess) return e;
+  if (a.dwk && (e = launch_dw(a.k, false, a.du_k, a.dw_part, a.dwk, p, s)) != hipSuccess) return e;
+  return hipSuccess;
+}
+
+}  // namespace
+
+hipError_t launch_bwd_f32(const BwdArgs& a, const Plan& p, hipStream_t s) {
+  return p.d == 128 ? run_bwd<128>(a, p, s) : run_bwd<64>(a, p, s);
+}
+
+}  // namespace linattn

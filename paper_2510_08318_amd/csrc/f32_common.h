@@ -1,0 +1,62 @@
+// Building blocks of the fp32 (no bf16/fp16 anywhere) kernels: plain FMA on LDS tiles.
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace linattn {
+namespace f32 {
+
+constexpr int NT = 256;       // threads per workgroup
+
+__device__ __forceinline__ float wave_max(float x) {
+  for (int m = 32; m >= 1; m >>= 1) x = fmaxf(x, __shfl_xor(x, m, 64));
+  return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+  for (int m = 32; m >= 1; m >>= 1) x += __shfl_xor(x, m, 64);
+  return x;
+}
+
+// Eq. 5 on a tile of TT tokens (TT = 16 or 32): sX [TT][D+1] holds the tokens, sW [D][D/2] the map; on return
+// sPhi [TT][D] holds softmax(u) then softmax(-u) per token, rows >= n_valid are zero.
+// Contains __syncthreads(); every thread of the workgroup must call it.
+template <int D, int TT>
+__device__ __forceinline__ void phi_tile(const float* sX, const float* sW, float* sPhi, int tid, int n_valid) {
+  constexpr int HALF = D / 2;
+  {
+    constexpr int FB = NT / TT;                  // feature groups
+    const int tt = tid % TT, fb = tid / TT;
+    float u[HALF / FB];
+#pragma unroll
+    for (int j = 0; j < HALF / FB; ++j) u[j] = 0.f;
+    for (int c = 0; c < D; ++c) {
+      const float x = sX[tt * (D + 1) + c];
+#pragma unroll
+      for (int j = 0; j < HALF / FB; ++j) u[j] = fmaf(x, sW[c * HALF + fb + FB * j], u[j]);
+    }
+#pragma unroll
+    for (int j = 0; j < HALF / FB; ++j) sPhi[tt * D + fb + FB * j] = u[j];
+  }
+  __syncthreads();
+  {
+    const int w = tid / 64, lane = tid % 64;
+    for (int i = 0; i < TT / 4; ++i) {
+      const int tt = w * (TT / 4) + i;
+      const float x = sPhi[tt * D + (lane % HALF)];
+      const float mx = wave_max(x);
+      const float mn = -wave_max(-x);
+      const float ep = expf(x - mx);
+      const float em = expf(mn - x);
+      float sp = wave_sum(ep), sm = wave_sum(em);
+      if (HALF == 32) { sp *= 0.5f; sm *= 0.5f; }   // both half-waves hold the same 32 features
+      const bool valid = tt < n_valid;
+      if (lane < HALF) {
+        sPhi[tt * D + lane] = valid ? ep / sp : 0.f;
+        sPhi[tt * D + HALF + lane] = valid ? em / sm : 0.f;
+      }
+    }
+  }
+  __syncthreads();
+}
+
+}  // namespace f32
+}  // namespace linattn

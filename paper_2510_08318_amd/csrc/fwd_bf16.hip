@@ -15,245 +15,17 @@
 // (16 bytes per lane), so a lane owns one token and d/4 of its d/2 pre-softmax features; the
 // softmax reductions are in-lane plus one exchange with lane^32.
 #include "kernels.h"
-#include "mfma_layout.h"
+#include "mfma_common.h"
 
 namespace linattn {
 namespace {
-
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr int NT = 256;          // 4 wavefronts
-
-template <int D>
-struct Cfg {
-  static constexpr int HALF = D / 2;     // pre-softmax features u = x W~
-  static constexpr int UM = HALF / 32;   // row blocks of U^T
-  static constexpr int UK = D / 16;      // k-steps over the d input channels
-  static constexpr int LOC = HALF / 2;   // pre-softmax features a lane owns
-  static constexpr int NPK = D / 4;      // packed fp16 pairs of phi a lane owns (d/2 values)
-  static constexpr int CH = D / 8;       // 16-byte chunks per tile row
-  static constexpr int W_IMG = UK * UM * 64;   // uint4 entries of the W~^T operand image
-};
-
-// XOR swizzle of the 16-byte chunk index inside a tile row: makes the transposing 8-byte reads
-// (4 consecutive rows x 32 bytes per 16 lanes) and the 16-byte row writes hit distinct banks.
-// Depends on r % 16 only, so it is the same for every 16-row k-step of a tile.
-template <int D>
-__device__ __forceinline__ int swz(int r) {
-  if (D == 128) return ((r & 3) << 2) | ((r >> 2) & 3);
-  return (((r & 3) << 1) ^ ((r >> 2) & 3)) & 7;
-}
-
-// A zero the optimiser cannot see through: added to an LDS index it keeps loop-invariant
-// operand reads inside the loop (hoisted, they would not fit the register file and spill).
-__device__ __forceinline__ int opaque_zero() {
-  int z = 0;
-  asm volatile("" : "+v"(z));
-  return z;
-}
-
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-// Streaming (non-temporal) 16-byte global load / store, for fully coalesced accesses only: with
-// the operand-layout loads (two 16-byte pieces of a row per instruction, four instructions per
-// 128-byte line) the hint makes the line be fetched again and costs 20 % of the bandwidth.
-__device__ __forceinline__ uint4 ld_nt(const uint4* p) {
-  return __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p)));
-}
-__device__ __forceinline__ void st_nt(uint4* p, uint4 v) {
-  __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), reinterpret_cast<u32x4*>(p));
-}
-
-// Exchange with lane^32: returns (value of the low-half lane, value of the high-half lane),
-// identical in both lanes of a pair.
-__device__ __forceinline__ void pair32(float x, float& lo, float& hi) {
-  const uint32_t u = __builtin_bit_cast(uint32_t, x);
-  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  lo = __builtin_bit_cast(float, (uint32_t)r[0]);
-  hi = __builtin_bit_cast(float, (uint32_t)r[1]);
-}
-
-// W~ [D][D/2] bf16 (one head) -> LDS image of the A operands of U^T = W~^T X^T:
-// entry (ks, mb, lane=(m,g)) holds W~[16ks + 8g + e][owned_row<HALF>(mb, m)], e = 0..7.
-template <int D, int NTHREADS>
-__device__ __forceinline__ void build_w_image(const uint16_t* __restrict__ w, uint4* sWA, int tid) {
-  using C = Cfg<D>;
-  for (int idx = tid; idx < C::W_IMG; idx += NTHREADS) {
-    const int lane = idx % 64, mb = (idx / 64) % C::UM, ks = idx / (64 * C::UM);
-    const int m = lane % 32, g = lane / 32;
-    const int uf = owned_row<C::HALF>(mb, m);
-    uint32_t x[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) x[e] = w[(16 * ks + 8 * g + e) * C::HALF + uf];
-    uint4 r;
-    r.x = x[0] | (x[1] << 16); r.y = x[2] | (x[3] << 16);
-    r.z = x[4] | (x[5] << 16); r.w = x[6] | (x[7] << 16);
-    sWA[idx] = r;
-  }
-}
-
-// First half of Eq. 5 for the 32 tokens of one wavefront: U^T = W~^T X^T on bf16 MFMA.
-// xb[ks] is this lane's B operand (8 channels of its token per k-step).  On return the lane holds
-// u[mb][r] = pre-softmax feature g*LOC + 16*mb + r of its token.  xb is dead afterwards, so the
-// caller can refill it with the next block while the softmax runs.
-template <int D>
-__device__ __forceinline__ void project(const uint4 (&xb)[Cfg<D>::UK], const uint4* sWA, int lane,
-                                        f32x16 (&u)[Cfg<D>::UM]) {
-  using C = Cfg<D>;
-#pragma unroll
-  for (int mb = 0; mb < C::UM; ++mb)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) u[mb][r] = 0.f;
-  const uint4* wa = sWA + lane + opaque_zero();
-#pragma unroll
-  for (int ks = 0; ks < C::UK; ++ks) {
-    const bf16x8 b = as_bf16x8(xb[ks]);
-#pragma unroll
-    for (int mb = 0; mb < C::UM; ++mb) {
-      const bf16x8 a = as_bf16x8(wa[(ks * C::UM + mb) * 64]);
-      u[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, u[mb], 0, 0, 0);
-    }
-  }
-}
-
-// Second half of Eq. 5: the two softmaxes over the d/2 features (in-lane, plus one exchange with
-// lane^32).  pk[] receives the lane's d/2 values of phi as fp16 pairs: first LOC values
-// softmax(+u) for features g*LOC .. g*LOC+LOC-1, then LOC values softmax(-u) for the same
-// features.  valid == false zeroes the token (tail masking happens after phi: phi(0) is the
-// uniform vector, not zero).
-template <int D>
-__device__ __forceinline__ void softmax_pair(const f32x16 (&u)[Cfg<D>::UM], bool valid, uint32_t (&pk)[Cfg<D>::NPK]) {
-  using C = Cfg<D>;
-  float mx = u[0][0], mn = u[0][0];
-#pragma unroll
-  for (int mb = 0; mb < C::UM; ++mb)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) { mx = fmaxf(mx, u[mb][r]); mn = fminf(mn, u[mb][r]); }
-  float lo, hi;
-  pair32(mx, lo, hi); mx = fmaxf(lo, hi);
-  pair32(mn, lo, hi); mn = fminf(lo, hi);
-  // one softmax half at a time keeps only LOC exponentials live
-#pragma unroll
-  for (int half = 0; half < 2; ++half) {
-    const float sl = half ? -kLog2e : kLog2e;
-    const float c0 = half ? mn * kLog2e : -mx * kLog2e;
-    float e[C::LOC];
-    float s = 0.f;
-#pragma unroll
-    for (int mb = 0; mb < C::UM; ++mb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float a = __builtin_amdgcn_exp2f(fmaf(u[mb][r], sl, c0));
-        e[16 * mb + r] = a;
-        s += a;
-      }
-    pair32(s, lo, hi); s = lo + hi;
-    const float inv = valid ? __builtin_amdgcn_rcpf(s) : 0.f;
-#pragma unroll
-    for (int j = 0; j < C::LOC / 2; ++j) pk[half * (C::LOC / 2) + j] = pack_f16x2(e[2 * j] * inv, e[2 * j + 1] * inv);
-  }
-}
-
-// Eq. 5 up to a per-token positive factor, for the query side only: the output of Eq. 3 is a ratio
-// that is linear in phi(q_i) above and below, so phi(q_i) may be scaled by any positive number.
-// Scaling by the softmax(+u) denominator s+ leaves exp(u - max u) as the first half and
-// (s+/s-) exp(min u - u) as the second: one multiply per token-half saved, values stay in (0, 64].
-template <int D>
-__device__ __forceinline__ void softmax_pair_ratio(const f32x16 (&u)[Cfg<D>::UM], uint32_t (&pk)[Cfg<D>::NPK]) {
-  using C = Cfg<D>;
-  float mx = u[0][0], mn = u[0][0];
-#pragma unroll
-  for (int mb = 0; mb < C::UM; ++mb)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) { mx = fmaxf(mx, u[mb][r]); mn = fminf(mn, u[mb][r]); }
-  float lo, hi;
-  pair32(mx, lo, hi); mx = fmaxf(lo, hi);
-  pair32(mn, lo, hi); mn = fminf(lo, hi);
-  float sp = 0.f;
-  {
-    const float c0 = -mx * kLog2e;
-    float e[C::LOC];
-#pragma unroll
-    for (int mb = 0; mb < C::UM; ++mb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float a = __builtin_amdgcn_exp2f(fmaf(u[mb][r], kLog2e, c0));
-        e[16 * mb + r] = a;
-        sp += a;
-      }
-#pragma unroll
-    for (int j = 0; j < C::LOC / 2; ++j) pk[j] = pack_f16x2(e[2 * j], e[2 * j + 1]);
-    pair32(sp, lo, hi); sp = lo + hi;
-  }
-  {
-    const float c0 = mn * kLog2e;
-    float e[C::LOC];
-    float sm = 0.f;
-#pragma unroll
-    for (int mb = 0; mb < C::UM; ++mb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float a = __builtin_amdgcn_exp2f(fmaf(u[mb][r], -kLog2e, c0));
-        e[16 * mb + r] = a;
-        sm += a;
-      }
-    pair32(sm, lo, hi); sm = lo + hi;
-    const float ratio = sp * __builtin_amdgcn_rcpf(sm);
-#pragma unroll
-    for (int j = 0; j < C::LOC / 2; ++j) pk[C::LOC / 2 + j] = pack_f16x2(e[2 * j] * ratio, e[2 * j + 1] * ratio);
-  }
-}
 
 // ------------------------------------------------------------------------------------------
 // Query pass.  A wavefront owns 32-token blocks b = p*NW + w, stepping by (gridDim.x * NW), so
 // the workgroups of a head sweep its tokens together.  Per block: load Q rows straight into the
 // B operand, phi, out^T = S^T phi^T (+ the z row block for the normaliser), scale, bf16, then a
 // wavefront-private LDS transpose so that every store instruction writes whole 256-byte rows.
-// fp32 state [D+1][D] of one (b,h) -> LDS image of the fp16 A operands of out^T = S^T phi(q)^T:
-// entry (ks, mb, lane=(m,g)) holds S[feature(ks,g,e)][channel(mb,m)], e = 0..7, and the extra row
-// block mb = MB holds z[feature] in rows 0 and 4 (one per lane group) and zeros elsewhere.
-// S and z are scaled by a common power of two that brings their largest magnitude into
-// [2^13, 2^14): the output is a ratio, so the scale cancels, and fp16 cannot overflow.
-// red: >= NTHREADS/64 floats of LDS scratch.  Contains __syncthreads().
-template <int D, int NTHREADS>
-__device__ __forceinline__ void build_state_image(const float* __restrict__ S, uint4* sSA, float* red, int tid) {
-  using L = ApplyLayout<D>;
-  constexpr int N = (D + 1) * D;
-  float amax = 0.f;
-  for (int i0 = tid; i0 < N; i0 += 8 * NTHREADS) {
-    float t[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) { const int i = i0 + j * NTHREADS; t[j] = i < N ? fabsf(S[i]) : 0.f; }
-#pragma unroll
-    for (int j = 0; j < 8; ++j) amax = fmaxf(amax, t[j]);
-  }
-  for (int m = 32; m >= 1; m >>= 1) amax = fmaxf(amax, __shfl_xor(amax, m, 64));
-  if (tid % 64 == 0) red[tid / 64] = amax;
-  __syncthreads();
-  amax = red[0];
-#pragma unroll
-  for (int i = 1; i < NTHREADS / 64; ++i) amax = fmaxf(amax, red[i]);
-  const float scale = (amax > 0.f && amax < 3.0e38f) ? ldexpf(1.0f, 13 - ilogbf(amax)) : 1.0f;
-  __syncthreads();                       // red is reused by the caller
-  for (int idx = tid; idx < L::KS * L::MBZ * 64; idx += NTHREADS) {
-    const int lane = idx % 64, mb = (idx / 64) % L::MBZ, ks = idx / (64 * L::MBZ);
-    const int m = lane % 32, g = lane / 32;
-    float x[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int f = L::feature(ks, g, e);
-      if (mb < L::MB) x[e] = scale * S[f * D + L::channel(mb, m)];
-      else x[e] = (m == 0 || m == 4) ? scale * S[D * D + f] : 0.f;
-    }
-    uint4 r;
-    r.x = pack_f16x2(x[0], x[1]); r.y = pack_f16x2(x[2], x[3]);
-    r.z = pack_f16x2(x[4], x[5]); r.w = pack_f16x2(x[6], x[7]);
-    sSA[idx] = r;
-  }
-}
-
 constexpr int NT3 = 768;         // 12 wavefronts, one workgroup per compute unit
-
-template <int D>
-__device__ __forceinline__ int swz_out(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
 
 template <int D>
 __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ wq,
@@ -279,7 +51,11 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
   uint16_t* ob = out + (size_t)bh * n * D;
 
   build_w_image<D, NT3>(wq + (size_t)h * D * C::HALF, sWA, tid);
-  build_state_image<D, NT3>(state + (size_t)bh * (D + 1) * D, sSA, reinterpret_cast<float*>(sOut), tid);
+  {
+    const float* sb = state + (size_t)bh * (D + 1) * D;
+    const float scale = head_scale<D, NT3>(sb, reinterpret_cast<float*>(sOut), tid);
+    build_state_image<D, NT3>(sb, sSA, scale, tid);
+  }
   __syncthreads();
 
   const int nblk = (n + 31) / 32;
@@ -368,28 +144,6 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
     }
     __builtin_amdgcn_wave_barrier();
   }
-}
-
-// ------------------------------------------------------------------------------------------
-// Transposing LDS read: from a [row][column] fp16 tile, lane l of a wavefront receives
-// tile[row0 + 8*(l/32) + 0..7][col0 + l%32] -- an MFMA A or B operand whose contraction index
-// is the tile row.  Two ds_read_b64_tr_b16: within each group of 16 lanes, lane s supplies the
-// address of row s/4, columns 4*(s%4)..+3, and receives column s of the four rows.
-// tr_offset() is the lane's byte offset for row0 = 0 and the first (j = 0) or second (j = 1)
-// group of four rows; row0 = 16*ks adds 16*ks*RS bytes (the swizzle repeats every 16 rows).
-template <int D>
-__device__ __forceinline__ int tr_offset(int col0, int lane, int j) {
-  constexpr int RS = D * 2;
-  const int r = 8 * (lane / 32) + ((lane % 16) / 4) + 4 * j;
-  const int col = col0 + 16 * ((lane / 16) % 2) + 4 * (lane % 4);    // element column, multiple of 4
-  return r * RS + (((col / 8) ^ swz<D>(r)) * 16) + (col % 8) * 2;
-}
-
-__device__ __forceinline__ f16x8 read_tr(const char* tile, int off0, int off1) {
-  struct { s16x4 lo, hi; } v;
-  v.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(tile + off0));
-  v.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(tile + off1));
-  return __builtin_bit_cast(f16x8, v);
 }
 
 // State pass.  A workgroup (4 wavefronts) owns 128-token tiles p, p + P, p + 2P, ... of its head.

@@ -2,62 +2,13 @@
 // This mode exists for the 1e-5 accuracy contract on fp32 tensors; the bandwidth-tuned
 // path is the bf16 one in fwd_bf16.hip.
 #include "kernels.h"
+#include "f32_common.h"
 
 namespace linattn {
 namespace {
 
+using namespace f32;
 constexpr int TT = 32;        // tokens per tile
-constexpr int NT = 256;       // threads per workgroup
-
-__device__ __forceinline__ float wave_max(float x) {
-  for (int m = 32; m >= 1; m >>= 1) x = fmaxf(x, __shfl_xor(x, m, 64));
-  return x;
-}
-__device__ __forceinline__ float wave_sum(float x) {
-  for (int m = 32; m >= 1; m >>= 1) x += __shfl_xor(x, m, 64);
-  return x;
-}
-
-// Eq. 5 on a tile: sX [TT][D+1] holds the tokens, sW [D][D/2] the map; on return
-// sPhi [TT][D] holds softmax(u) then softmax(-u) per token, rows >= n_valid are zero.
-// Contains __syncthreads(); every thread of the workgroup must call it.
-template <int D>
-__device__ __forceinline__ void phi_tile(const float* sX, const float* sW, float* sPhi, int tid, int n_valid) {
-  constexpr int HALF = D / 2;
-  {
-    const int tt = tid % TT, fb = tid / TT;      // fb in 0..7
-    float u[HALF / 8];
-#pragma unroll
-    for (int j = 0; j < HALF / 8; ++j) u[j] = 0.f;
-    for (int c = 0; c < D; ++c) {
-      const float x = sX[tt * (D + 1) + c];
-#pragma unroll
-      for (int j = 0; j < HALF / 8; ++j) u[j] = fmaf(x, sW[c * HALF + fb + 8 * j], u[j]);
-    }
-#pragma unroll
-    for (int j = 0; j < HALF / 8; ++j) sPhi[tt * D + fb + 8 * j] = u[j];
-  }
-  __syncthreads();
-  {
-    const int w = tid / 64, lane = tid % 64;
-    for (int i = 0; i < TT / 4; ++i) {
-      const int tt = w * (TT / 4) + i;
-      const float x = sPhi[tt * D + (lane % HALF)];
-      const float mx = wave_max(x);
-      const float mn = -wave_max(-x);
-      const float ep = expf(x - mx);
-      const float em = expf(mn - x);
-      float sp = wave_sum(ep), sm = wave_sum(em);
-      if (HALF == 32) { sp *= 0.5f; sm *= 0.5f; }   // both half-waves hold the same 32 features
-      const bool valid = tt < n_valid;
-      if (lane < HALF) {
-        sPhi[tt * D + lane] = valid ? ep / sp : 0.f;
-        sPhi[tt * D + HALF + lane] = valid ? em / sm : 0.f;
-      }
-    }
-  }
-  __syncthreads();
-}
 
 template <int D>
 __global__ __launch_bounds__(NT) void state_partials_f32_kernel(const float* __restrict__ k, const float* __restrict__ v,
@@ -98,7 +49,7 @@ __global__ __launch_bounds__(NT) void state_partials_f32_kernel(const float* __r
       sV[tt * D + c] = valid ? vb[(size_t)t * D + c] : 0.f;
     }
     __syncthreads();
-    phi_tile<D>(sX, sW, sPhi, tid, t_end - t0);
+    phi_tile<D, TT>(sX, sW, sPhi, tid, t_end - t0);
     for (int tt = 0; tt < TT; ++tt) {
       float a[BLK], b[BLK];
 #pragma unroll
@@ -153,7 +104,7 @@ __global__ __launch_bounds__(NT) void apply_f32_kernel(const float* __restrict__
       sX[r * (D + 1) + c] = (t < t_end) ? qb[(size_t)t * D + c] : 0.f;
     }
     __syncthreads();
-    phi_tile<D>(sX, sW, sPhi, tid, t_end - t0);
+    phi_tile<D, TT>(sX, sW, sPhi, tid, t_end - t0);
     float acc[D / 8];
 #pragma unroll
     for (int j = 0; j < D / 8; ++j) acc[j] = 0.f;

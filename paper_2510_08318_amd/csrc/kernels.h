@@ -25,11 +25,30 @@ struct Plan {
   size_t state_elems;     // (d+1)*d
   size_t off_partials;    // fp32 [BH][P][(d+1)*d]
   size_t off_state;       // fp32 [BH][(d+1)*d]   (used when the caller gave no state buffer)
+  // backward only
+  int KP;                 // workgroups per (b,h) of the key-side backward pass
+  size_t off_dstate;      // fp32 [BH][(d+1)*d]   dS, dz
+  size_t off_gimg;        // fp16 [BH][d*d]       operand image of S for dL/dphi(q) (bf16 mode)
+  size_t off_dwpart;      // fp32 [BH][P][d*d/2]  partial dW~           (weight gradients only)
+  size_t off_du_q;        // fp32 [BH][n][d/2]    dL/du of the query side (weight gradients only)
+  size_t off_du_k;        // fp32 [BH][n][d/2]    dL/du of the key side   (weight gradients only)
+  size_t bytes_no_wgrads; // workspace needed by forward and by backward without dW~
   size_t total_bytes;
 };
 
 // Pure host arithmetic; returns false if the shape is unsupported or overflows.
+// total_bytes includes the weight-gradient regions, bytes_no_wgrads does not.
 bool make_plan(int B, int H, int n, int d, int dtype, Plan* p);
+
+// Everything one backward call touches (device pointers; workspace regions already resolved).
+struct BwdArgs {
+  const void *q, *k, *v, *dout, *wq, *wk;
+  void *dq, *dk, *dv;
+  const float* state;     // [BH][d+1][d] from the forward
+  float *dwq, *dwk;       // nullable
+  float *partials, *dstate, *dw_part, *du_q, *du_k;
+  void* gimg;
+};
 
 // ---- forward launchers (enqueue only) ---------------------------------------------------
 // phi(K) fused with the split-n partial state (Eq. 5 + the two sums of Eq. 3).
@@ -44,5 +63,11 @@ hipError_t launch_apply_f32(const float* q, const float* wq, const float* state,
                             const Plan& p, hipStream_t s);
 hipError_t launch_apply_bf16(const void* q, const void* wq, const float* state, void* out,
                              const Plan& p, hipStream_t s);
+
+// ---- backward launchers (enqueue only) --------------------------------------------------
+// dw[H][d][d/2] = sum over batch and tokens of x^T du; x is [B,H,n,d] bf16 or fp32, du fp32 [B,H,n,d/2].
+hipError_t launch_dw(const void* x, bool x_is_bf16, const float* du, float* part, float* dw, const Plan& p, hipStream_t s);
+hipError_t launch_bwd_bf16(const BwdArgs& a, const Plan& p, hipStream_t s);
+hipError_t launch_bwd_f32(const BwdArgs& a, const Plan& p, hipStream_t s);
 
 }  // namespace linattn

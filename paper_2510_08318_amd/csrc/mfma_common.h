@@ -1,0 +1,353 @@
+// Device-side building blocks shared by the bf16-I/O forward and backward kernels (gfx950 MFMA,
+// tokens along the N dimension): operand images in LDS, the two halves of Eq. 5, transposing
+// LDS reads.  Header-only; include after kernels.h.
+#pragma once
+#include "mfma_layout.h"
+
+namespace linattn {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr int NT = 256;          // 4 wavefronts (tile-synchronised kernels)
+
+template <int D>
+struct Cfg {
+  static constexpr int HALF = D / 2;     // pre-softmax features u = x W~
+  static constexpr int UM = HALF / 32;   // row blocks of U^T
+  static constexpr int UK = D / 16;      // k-steps over the d input channels
+  static constexpr int LOC = HALF / 2;   // pre-softmax features a lane owns
+  static constexpr int NPK = D / 4;      // packed fp16 pairs of phi a lane owns (d/2 values)
+  static constexpr int CH = D / 8;       // 16-byte chunks per tile row
+  static constexpr int W_IMG = UK * UM * 64;   // uint4 entries of the W~^T operand image
+};
+
+// XOR swizzle of the 16-byte chunk index inside a tile row: makes the transposing 8-byte reads
+// (4 consecutive rows x 32 bytes per 16 lanes) and the 16-byte row writes hit distinct banks.
+// Depends on r % 16 only, so it is the same for every 16-row k-step of a tile.
+template <int D>
+__device__ __forceinline__ int swz(int r) {
+  if (D == 128) return ((r & 3) << 2) | ((r >> 2) & 3);
+  return (((r & 3) << 1) ^ ((r >> 2) & 3)) & 7;
+}
+
+// A zero the optimiser cannot see through: added to an LDS index it keeps loop-invariant
+// operand reads inside the loop (hoisted, they would not fit the register file and spill).
+__device__ __forceinline__ int opaque_zero() {
+  int z = 0;
+  asm volatile("" : "+v"(z));
+  return z;
+}
+
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+// Streaming (non-temporal) 16-byte global load / store, for fully coalesced accesses only: with
+// the operand-layout loads (two 16-byte pieces of a row per instruction, four instructions per
+// 128-byte line) the hint makes the line be fetched again and costs 20 % of the bandwidth.
+__device__ __forceinline__ uint4 ld_nt(const uint4* p) {
+  return __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p)));
+}
+__device__ __forceinline__ void st_nt(uint4* p, uint4 v) {
+  __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), reinterpret_cast<u32x4*>(p));
+}
+
+// Exchange with lane^32: returns (value of the low-half lane, value of the high-half lane),
+// identical in both lanes of a pair.
+__device__ __forceinline__ void pair32(float x, float& lo, float& hi) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  lo = __builtin_bit_cast(float, (uint32_t)r[0]);
+  hi = __builtin_bit_cast(float, (uint32_t)r[1]);
+}
+
+// W~ [D][D/2] bf16 (one head) -> LDS image of the A operands of U^T = W~^T X^T:
+// entry (ks, mb, lane=(m,g)) holds W~[16ks + 8g + e][owned_row<HALF>(mb, m)], e = 0..7.
+template <int D, int NTHREADS>
+__device__ __forceinline__ void build_w_image(const uint16_t* __restrict__ w, uint4* sWA, int tid) {
+  using C = Cfg<D>;
+  for (int idx = tid; idx < C::W_IMG; idx += NTHREADS) {
+    const int lane = idx % 64, mb = (idx / 64) % C::UM, ks = idx / (64 * C::UM);
+    const int m = lane % 32, g = lane / 32;
+    const int uf = owned_row<C::HALF>(mb, m);
+    uint32_t x[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = w[(16 * ks + 8 * g + e) * C::HALF + uf];
+    uint4 r;
+    r.x = x[0] | (x[1] << 16); r.y = x[2] | (x[3] << 16);
+    r.z = x[4] | (x[5] << 16); r.w = x[6] | (x[7] << 16);
+    sWA[idx] = r;
+  }
+}
+
+// First half of Eq. 5 for the 32 tokens of one wavefront: U^T = W~^T X^T on bf16 MFMA.
+// xb[ks] is this lane's B operand (8 channels of its token per k-step).  On return the lane holds
+// u[mb][r] = pre-softmax feature g*LOC + 16*mb + r of its token.  xb is dead afterwards, so the
+// caller can refill it with the next block while the softmax runs.
+template <int D>
+__device__ __forceinline__ void project(const uint4 (&xb)[Cfg<D>::UK], const uint4* sWA, int lane,
+                                        f32x16 (&u)[Cfg<D>::UM]) {
+  using C = Cfg<D>;
+#pragma unroll
+  for (int mb = 0; mb < C::UM; ++mb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) u[mb][r] = 0.f;
+  const uint4* wa = sWA + lane + opaque_zero();
+#pragma unroll
+  for (int ks = 0; ks < C::UK; ++ks) {
+    const bf16x8 b = as_bf16x8(xb[ks]);
+#pragma unroll
+    for (int mb = 0; mb < C::UM; ++mb) {
+      const bf16x8 a = as_bf16x8(wa[(ks * C::UM + mb) * 64]);
+      u[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, u[mb], 0, 0, 0);
+    }
+  }
+}
+
+// Second half of Eq. 5: the two softmaxes over the d/2 features (in-lane, plus one exchange with
+// lane^32).  pk[] receives the lane's d/2 values of phi as fp16 pairs: first LOC values
+// softmax(+u) for features g*LOC .. g*LOC+LOC-1, then LOC values softmax(-u) for the same
+// features.  valid == false zeroes the token (tail masking happens after phi: phi(0) is the
+// uniform vector, not zero).
+template <int D>
+__device__ __forceinline__ void softmax_pair(const f32x16 (&u)[Cfg<D>::UM], bool valid, uint32_t (&pk)[Cfg<D>::NPK]) {
+  using C = Cfg<D>;
+  float mx = u[0][0], mn = u[0][0];
+#pragma unroll
+  for (int mb = 0; mb < C::UM; ++mb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { mx = fmaxf(mx, u[mb][r]); mn = fminf(mn, u[mb][r]); }
+  float lo, hi;
+  pair32(mx, lo, hi); mx = fmaxf(lo, hi);
+  pair32(mn, lo, hi); mn = fminf(lo, hi);
+  // one softmax half at a time keeps only LOC exponentials live
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    const float sl = half ? -kLog2e : kLog2e;
+    const float c0 = half ? mn * kLog2e : -mx * kLog2e;
+    float e[C::LOC];
+    float s = 0.f;
+#pragma unroll
+    for (int mb = 0; mb < C::UM; ++mb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float a = __builtin_amdgcn_exp2f(fmaf(u[mb][r], sl, c0));
+        e[16 * mb + r] = a;
+        s += a;
+      }
+    pair32(s, lo, hi); s = lo + hi;
+    const float inv = valid ? __builtin_amdgcn_rcpf(s) : 0.f;
+#pragma unroll
+    for (int j = 0; j < C::LOC / 2; ++j) pk[half * (C::LOC / 2) + j] = pack_f16x2(e[2 * j] * inv, e[2 * j + 1] * inv);
+  }
+}
+
+// Eq. 5 with the normalised values kept in fp32 as well (the backward needs them for the softmax
+// Jacobian): pp[j], pm[j] = softmax(+u), softmax(-u) of feature g*LOC + j; pk as in softmax_pair.
+template <int D>
+__device__ __forceinline__ void softmax_full(const f32x16 (&u)[Cfg<D>::UM], float (&pp)[Cfg<D>::LOC],
+                                             float (&pm)[Cfg<D>::LOC], uint32_t (&pk)[Cfg<D>::NPK]) {
+  using C = Cfg<D>;
+  float mx = u[0][0], mn = u[0][0];
+#pragma unroll
+  for (int mb = 0; mb < C::UM; ++mb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { mx = fmaxf(mx, u[mb][r]); mn = fminf(mn, u[mb][r]); }
+  float lo, hi;
+  pair32(mx, lo, hi); mx = fmaxf(lo, hi);
+  pair32(mn, lo, hi); mn = fminf(lo, hi);
+  float sp = 0.f, sm = 0.f;
+#pragma unroll
+  for (int mb = 0; mb < C::UM; ++mb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float a = __builtin_amdgcn_exp2f(fmaf(u[mb][r], kLog2e, -mx * kLog2e));
+      const float b = __builtin_amdgcn_exp2f(fmaf(u[mb][r], -kLog2e, mn * kLog2e));
+      pp[16 * mb + r] = a; pm[16 * mb + r] = b;
+      sp += a; sm += b;
+    }
+  pair32(sp, lo, hi); sp = lo + hi;
+  pair32(sm, lo, hi); sm = lo + hi;
+  const float ip = __builtin_amdgcn_rcpf(sp), im = __builtin_amdgcn_rcpf(sm);
+#pragma unroll
+  for (int j = 0; j < C::LOC; ++j) { pp[j] *= ip; pm[j] *= im; }
+#pragma unroll
+  for (int j = 0; j < C::LOC / 2; ++j) {
+    pk[j] = pack_f16x2(pp[2 * j], pp[2 * j + 1]);
+    pk[C::LOC / 2 + j] = pack_f16x2(pm[2 * j], pm[2 * j + 1]);
+  }
+}
+
+// Eq. 5 up to a per-token positive factor, for the query side only: the output of Eq. 3 is a ratio
+// that is linear in phi(q_i) above and below, so phi(q_i) may be scaled by any positive number.
+// Scaling by the softmax(+u) denominator s+ leaves exp(u - max u) as the first half and
+// (s+/s-) exp(min u - u) as the second: one multiply per token-half saved, values stay in (0, 64].
+template <int D>
+__device__ __forceinline__ void softmax_pair_ratio(const f32x16 (&u)[Cfg<D>::UM], uint32_t (&pk)[Cfg<D>::NPK]) {
+  using C = Cfg<D>;
+  float mx = u[0][0], mn = u[0][0];
+#pragma unroll
+  for (int mb = 0; mb < C::UM; ++mb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { mx = fmaxf(mx, u[mb][r]); mn = fminf(mn, u[mb][r]); }
+  float lo, hi;
+  pair32(mx, lo, hi); mx = fmaxf(lo, hi);
+  pair32(mn, lo, hi); mn = fminf(lo, hi);
+  float sp = 0.f;
+  {
+    const float c0 = -mx * kLog2e;
+    float e[C::LOC];
+#pragma unroll
+    for (int mb = 0; mb < C::UM; ++mb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float a = __builtin_amdgcn_exp2f(fmaf(u[mb][r], kLog2e, c0));
+        e[16 * mb + r] = a;
+        sp += a;
+      }
+#pragma unroll
+    for (int j = 0; j < C::LOC / 2; ++j) pk[j] = pack_f16x2(e[2 * j], e[2 * j + 1]);
+    pair32(sp, lo, hi); sp = lo + hi;
+  }
+  {
+    const float c0 = mn * kLog2e;
+    float e[C::LOC];
+    float sm = 0.f;
+#pragma unroll
+    for (int mb = 0; mb < C::UM; ++mb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float a = __builtin_amdgcn_exp2f(fmaf(u[mb][r], -kLog2e, c0));
+        e[16 * mb + r] = a;
+        sm += a;
+      }
+    pair32(sm, lo, hi); sm = lo + hi;
+    const float ratio = sp * __builtin_amdgcn_rcpf(sm);
+#pragma unroll
+    for (int j = 0; j < C::LOC / 2; ++j) pk[C::LOC / 2 + j] = pack_f16x2(e[2 * j] * ratio, e[2 * j + 1] * ratio);
+  }
+}
+
+// Power of two that brings the largest magnitude of a (b,h) state [D+1][D] (S rows, then z) into
+// [2^13, 2^14): fp16 operand images of the state are scaled by it.  Every consumer forms a ratio
+// or divides the scale out again.  red: >= NTHREADS/64 floats of LDS.  Contains __syncthreads().
+template <int D, int NTHREADS>
+__device__ __forceinline__ float head_scale(const float* __restrict__ S, float* red, int tid) {
+  constexpr int N = (D + 1) * D;
+  float amax = 0.f;
+  for (int i0 = tid; i0 < N; i0 += 8 * NTHREADS) {
+    float t[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { const int i = i0 + j * NTHREADS; t[j] = i < N ? fabsf(S[i]) : 0.f; }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) amax = fmaxf(amax, t[j]);
+  }
+  for (int m = 32; m >= 1; m >>= 1) amax = fmaxf(amax, __shfl_xor(amax, m, 64));
+  if (tid % 64 == 0) red[tid / 64] = amax;
+  __syncthreads();
+  amax = red[0];
+#pragma unroll
+  for (int i = 1; i < NTHREADS / 64; ++i) amax = fmaxf(amax, red[i]);
+  __syncthreads();                       // red may be reused by the caller
+  return (amax > 0.f && amax < 3.0e38f) ? ldexpf(1.0f, 13 - ilogbf(amax)) : 1.0f;
+}
+
+// fp32 state [D+1][D] of one (b,h) -> LDS image of the fp16 A operands of Y^T = S^T phi^T
+// (contraction over the features of phi): entry (ks, mb, lane=(m,g)) holds
+// scale * S[feature(ks,g,e)][channel(mb,m)], e = 0..7; the extra row block mb = MB holds
+// scale * z[feature] in rows 0 and 4 (one per lane group) and zeros elsewhere.
+template <int D, int NTHREADS>
+__device__ __forceinline__ void build_state_image(const float* __restrict__ S, uint4* sSA, float scale, int tid) {
+  using L = ApplyLayout<D>;
+  for (int idx = tid; idx < L::KS * L::MBZ * 64; idx += NTHREADS) {
+    const int lane = idx % 64, mb = (idx / 64) % L::MBZ, ks = idx / (64 * L::MBZ);
+    const int m = lane % 32, g = lane / 32;
+    float x[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int f = L::feature(ks, g, e);
+      if (mb < L::MB) x[e] = scale * S[f * D + L::channel(mb, m)];
+      else x[e] = (m == 0 || m == 4) ? scale * S[D * D + f] : 0.f;
+    }
+    uint4 r;
+    r.x = pack_f16x2(x[0], x[1]); r.y = pack_f16x2(x[2], x[3]);
+    r.z = pack_f16x2(x[4], x[5]); r.w = pack_f16x2(x[6], x[7]);
+    sSA[idx] = r;
+  }
+}
+
+// Index maps of G^T = S Y^T (contraction over the d channels; rows = features of phi), used by the
+// backward kernels.  The B operand is a token's half row: lane (t, g) feeds channels
+// g*D/2 + 8*ks + e in k-step ks.  The accumulator rows are laid out like phi itself: lane (t, g),
+// row block mb, register r holds the softmax(+u) feature g*LOC + 16*mb + r for mb < GM/2 and
+// the softmax(-u) feature HALF + g*LOC + 16*(mb - GM/2) + r otherwise.
+template <int D>
+struct GradLayout {
+  static constexpr int HALF = D / 2;
+  static constexpr int LOC = D / 4;
+  static constexpr int KS = D / 16;       // k-steps over the channels
+  static constexpr int GM = D / 32;       // row blocks over the D features
+  static constexpr int IMG = KS * GM * 64;
+  __device__ static constexpr int channel(int ks, int g, int e) { return g * (D / 2) + 8 * ks + e; }
+  __device__ static constexpr int feature(int mb, int m) {
+    const int gg = (m / 4) % 2, r = 4 * (m / 8) + (m % 4);
+    return (mb < GM / 2 ? 0 : HALF) + gg * LOC + 16 * (mb % (GM / 2)) + r;
+  }
+};
+
+// One A-operand entry (ks, mb, lane) of the image of G^T = S Y^T: scale * S[feature][channel .. +7].
+template <int D>
+__device__ __forceinline__ uint4 grad_image_entry(const float* __restrict__ S, float scale, int idx) {
+  using G = GradLayout<D>;
+  const int lane = idx % 64, mb = (idx / 64) % G::GM, ks = idx / (64 * G::GM);
+  const int m = lane % 32, g = lane / 32;
+  const float* row = S + G::feature(mb, m) * D + G::channel(ks, g, 0);
+  uint4 r;
+  r.x = pack_f16x2(scale * row[0], scale * row[1]); r.y = pack_f16x2(scale * row[2], scale * row[3]);
+  r.z = pack_f16x2(scale * row[4], scale * row[5]); r.w = pack_f16x2(scale * row[6], scale * row[7]);
+  return r;
+}
+
+// W~ [D][D/2] bf16 (one head) -> LDS image (fp16, exact) of the A operands of dX^T = W~ dU^T
+// (contraction over the d/2 pre-softmax features): entry (ks, mb, lane=(m,g)) holds
+// W~[channel(mb,m)][g*LOC + 8ks + e], e = 0..7; ks < LOC/8, mb < D/32.
+template <int D, int NTHREADS>
+__device__ __forceinline__ void build_w_image_t(const uint16_t* __restrict__ w, uint4* sWB, int tid) {
+  using C = Cfg<D>;
+  using L = ApplyLayout<D>;
+  constexpr int DK = C::LOC / 8;
+  for (int idx = tid; idx < DK * L::MB * 64; idx += NTHREADS) {
+    const int lane = idx % 64, mb = (idx / 64) % L::MB, ks = idx / (64 * L::MB);
+    const int m = lane % 32, g = lane / 32;
+    const uint16_t* row = w + L::channel(mb, m) * C::HALF + g * C::LOC + 8 * ks;
+    float x[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = __builtin_bit_cast(float, (uint32_t)row[e] << 16);
+    uint4 r;
+    r.x = pack_f16x2(x[0], x[1]); r.y = pack_f16x2(x[2], x[3]);
+    r.z = pack_f16x2(x[4], x[5]); r.w = pack_f16x2(x[6], x[7]);
+    sWB[idx] = r;
+  }
+}
+
+template <int D>
+__device__ __forceinline__ int swz_out(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
+
+// Transposing LDS read: from a [row][column] fp16 tile, lane l of a wavefront receives
+// tile[row0 + 8*(l/32) + 0..7][col0 + l%32] -- an MFMA A or B operand whose contraction index
+// is the tile row.  Two ds_read_b64_tr_b16: within each group of 16 lanes, lane s supplies the
+// address of row s/4, columns 4*(s%4)..+3, and receives column s of the four rows.
+// tr_offset() is the lane's byte offset for row0 = 0 and the first (j = 0) or second (j = 1)
+// group of four rows; row0 = 16*ks adds 16*ks*RS bytes (the swizzle repeats every 16 rows).
+template <int D>
+__device__ __forceinline__ int tr_offset(int col0, int lane, int j) {
+  constexpr int RS = D * 2;
+  const int r = 8 * (lane / 32) + ((lane % 16) / 4) + 4 * j;
+  const int col = col0 + 16 * ((lane / 16) % 2) + 4 * (lane % 4);    // element column, multiple of 4
+  return r * RS + (((col / 8) ^ swz<D>(r)) * 16) + (col % 8) * 2;
+}
+
+__device__ __forceinline__ f16x8 read_tr(const char* tile, int off0, int off1) {
+  struct { s16x4 lo, hi; } v;
+  v.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(tile + off0));
+  v.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(tile + off1));
+  return __builtin_bit_cast(f16x8, v);
+}
+
+}  // namespace linattn

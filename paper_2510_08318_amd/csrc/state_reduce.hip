@@ -1,5 +1,5 @@
-// Cross-workgroup reduction of the split-n partial states, in a fixed order (no atomics, so
-// the result is bitwise reproducible).
+// Cross-workgroup reductions in a fixed order (no atomics, so the results are bitwise
+// reproducible): the split-n partial states, and the weight gradient dW~ = sum x^T du.
 #include "kernels.h"
 
 namespace linattn {
@@ -26,11 +26,96 @@ __global__ __launch_bounds__(256) void state_reduce_kernel(const float* __restri
   state[(size_t)bh * elems + e] = acc;
 }
 
+// ---- dW~ = sum_{b, i} x_i^T du_i ------------------------------------------------------------
+// Partial sums per (b,h) and token split (fp32 FMA, LDS tiles), then a fixed-order reduction over
+// splits and batch items.
+template <int D, typename XT>
+__global__ __launch_bounds__(256) void dw_partial_kernel(const XT* __restrict__ x, const float* __restrict__ du,
+                                                         float* __restrict__ part, int n, int P, int chunk) {
+  constexpr int HALF = D / 2;
+  constexpr int TT = 32;
+  __shared__ float sX[TT][D + 1];
+  __shared__ float sU[TT][HALF];
+  const int tid = threadIdx.x, bh = blockIdx.y, p = blockIdx.x;
+  const int t_begin = p * chunk, t_end = min(n, t_begin + chunk);
+  const XT* xb = x + (size_t)bh * n * D;
+  const float* ub = du + (size_t)bh * n * HALF;
+  constexpr int BC = D / 16, BF = HALF / 16;        // each thread owns BC x BF entries
+  const int c0 = (tid / 16) * BC, f0 = (tid % 16) * BF;
+  float acc[BC][BF];
+#pragma unroll
+  for (int i = 0; i < BC; ++i)
+#pragma unroll
+    for (int j = 0; j < BF; ++j) acc[i][j] = 0.f;
+  for (int t0 = t_begin; t0 < t_end; t0 += TT) {
+    __syncthreads();
+    for (int i = tid; i < TT * D; i += 256) {
+      const int r = i / D, c = i % D, t = t0 + r;
+      float val = 0.f;
+      if (t < t_end) {
+        if constexpr (sizeof(XT) == 2) val = __builtin_bit_cast(float, (uint32_t)xb[(size_t)t * D + c] << 16);
+        else val = xb[(size_t)t * D + c];
+      }
+      sX[r][c] = val;
+    }
+    for (int i = tid; i < TT * HALF; i += 256) {
+      const int r = i / HALF, f = i % HALF, t = t0 + r;
+      sU[r][f] = t < t_end ? ub[(size_t)t * HALF + f] : 0.f;
+    }
+    __syncthreads();
+    for (int r = 0; r < TT; ++r) {
+      float a[BC], b[BF];
+#pragma unroll
+      for (int i = 0; i < BC; ++i) a[i] = sX[r][c0 + i];
+#pragma unroll
+      for (int j = 0; j < BF; ++j) b[j] = sU[r][f0 + j];
+#pragma unroll
+      for (int i = 0; i < BC; ++i)
+#pragma unroll
+        for (int j = 0; j < BF; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    }
+  }
+  float* dst = part + ((size_t)bh * P + p) * (size_t)D * HALF;
+#pragma unroll
+  for (int i = 0; i < BC; ++i)
+#pragma unroll
+    for (int j = 0; j < BF; ++j) dst[(c0 + i) * HALF + f0 + j] = acc[i][j];
+}
+
+// dw[h][e] = sum_b sum_p part[(b*H + h)][p][e], b then p ascending.
+__global__ __launch_bounds__(256) void dw_reduce_kernel(const float* __restrict__ part, float* __restrict__ dw,
+                                                        int B, int H, int P, int elems) {
+  const int e = blockIdx.x * 256 + threadIdx.x, h = blockIdx.y;
+  if (e >= elems) return;
+  float acc = 0.f;
+  for (int b = 0; b < B; ++b) {
+    const float* src = part + ((size_t)(b * H + h) * P) * elems + e;
+    for (int p = 0; p < P; ++p) acc += src[(size_t)p * elems];
+  }
+  dw[(size_t)h * elems + e] = acc;
+}
+
 }  // namespace
 
 hipError_t launch_state_reduce(const float* partials, float* state, const Plan& p, hipStream_t s) {
   const int elems = (int)p.state_elems;
   state_reduce_kernel<<<dim3((elems + 255) / 256, p.BH), 256, 0, s>>>(partials, state, p.P, elems);
+  return hipGetLastError();
+}
+
+hipError_t launch_dw(const void* x, bool x_is_bf16, const float* du, float* part, float* dw, const Plan& p, hipStream_t s) {
+  const int elems = p.d * (p.d / 2);
+  const dim3 grid(p.P, p.BH);
+  if (p.d == 128) {
+    if (x_is_bf16) dw_partial_kernel<128, uint16_t><<<grid, 256, 0, s>>>((const uint16_t*)x, du, part, p.n, p.P, p.chunk);
+    else dw_partial_kernel<128, float><<<grid, 256, 0, s>>>((const float*)x, du, part, p.n, p.P, p.chunk);
+  } else {
+    if (x_is_bf16) dw_partial_kernel<64, uint16_t><<<grid, 256, 0, s>>>((const uint16_t*)x, du, part, p.n, p.P, p.chunk);
+    else dw_partial_kernel<64, float><<<grid, 256, 0, s>>>((const float*)x, du, part, p.n, p.P, p.chunk);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  dw_reduce_kernel<<<dim3((elems + 255) / 256, p.H), 256, 0, s>>>(part, dw, p.B, p.H, p.P, elems);
   return hipGetLastError();
 }
 

@@ -40,7 +40,8 @@ class Layer:
         self.state = torch.empty((B, self.H, self.d + 1, self.d), dtype=torch.float32, device=dev) if keep_state else None
         self.dwq = torch.empty((self.H, self.d, half), dtype=torch.float32, device=dev) if want_wgrads else None
         self.dwk = torch.empty((self.H, self.d, half), dtype=torch.float32, device=dev) if want_wgrads else None
-        self.workspace_bytes = B_.linattn_workspace_bytes(B, self.H, n, self.d, B_.PHI_HEDGEHOG, self.dtype)
+        size_fn = B_.linattn_workspace_bytes_wgrads if want_wgrads else B_.linattn_workspace_bytes
+        self.workspace_bytes = size_fn(B, self.H, n, self.d, B_.PHI_HEDGEHOG, self.dtype)
         if self.workspace_bytes == 0:
             raise ValueError("unsupported shape")
         self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=dev)
