@@ -79,7 +79,7 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
   for (; b < nblk; b += stride) {
     f32x16 u[C::UM];
     project<D>(x, sWA, lane, u);
-    if (b + stride < nblk) load_block(b + stride);   // next block's rows fly during the rest of this one
+    load_block(b + stride < nblk ? b + stride : b);  // next block's rows fly during the rest of this one
     uint32_t pk[C::NPK];
     softmax_pair_ratio<D>(u, pk);
 
@@ -183,8 +183,11 @@ __global__ __launch_bounds__(NT, 2) void state_partials_bf16_kernel(const uint16
 #pragma unroll
       for (int j = 0; j < WMN; ++j) s[i][j][r] = 0.f;
   }
-  const int zmb = (WMN == 2) ? (2 * mi + ni) : mi;      // row block of z this wavefront sums
+  // Row blocks of S this wavefront owns, ordered so that the first one is also the row block of z
+  // it sums (every wavefront sums a different one when WMN == 2): fblk(i) = mi*WMN + (i ^ ni).
+  const int zmb = (WMN == 2) ? (2 * mi + ni) : mi;
   const bool do_z = (WMN == 2) || (ni == 0);
+  auto fblk = [&](int i) { return mi * WMN + ((WMN == 2) ? (i ^ ni) : i); };
   uint4 ones;
   ones.x = ones.y = ones.z = ones.w = 0x3C003C00u;      // fp16 1.0 pairs
 
@@ -194,7 +197,7 @@ __global__ __launch_bounds__(NT, 2) void state_partials_bf16_kernel(const uint16
   for (int i = 0; i < WMN; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      offA[i][j] = tr_offset<D>(32 * (mi * WMN + i), lane, j);
+      offA[i][j] = tr_offset<D>(32 * fblk(i), lane, j);
       offB[i][j] = tr_offset<D>(32 * (ni * WMN + i), lane, j);
     }
   // lane-constant LDS offsets of the tile writes
@@ -227,7 +230,10 @@ __global__ __launch_bounds__(NT, 2) void state_partials_bf16_kernel(const uint16
     const bool valid = (tile * kTile + 32 * w + (lane % 32)) < n;
     f32x16 u[C::UM];
     project<D>(xb, sWA, lane, u);
-    if (tile + P < ntile) load_k(tile + P);      // next K rows fly during the rest of this tile
+    // Prefetches are unconditional (the last iteration re-reads its own, cached, tile): a load
+    // behind a branch makes the compiler wait for everything outstanding at the next use.
+    const int next = (tile + P < ntile) ? tile + P : tile;
+    load_k(next);                                // next K rows fly during the rest of this tile
     uint32_t pk[C::NPK];
     softmax_pair<D>(u, valid, pk);
     __syncthreads();                             // previous tile's operand reads are done
@@ -254,7 +260,7 @@ __global__ __launch_bounds__(NT, 2) void state_partials_bf16_kernel(const uint16
       }
     }
     __syncthreads();
-    if (tile + P < ntile) load_v(tile + P);      // next V tile flies during the MFMA phase and the next phi
+    load_v(next);                                // next V tile flies during the MFMA phase and the next phi
 
 #pragma unroll
     for (int ks = 0; ks < kTile / 16; ++ks) {
@@ -267,14 +273,9 @@ __global__ __launch_bounds__(NT, 2) void state_partials_bf16_kernel(const uint16
       for (int i = 0; i < WMN; ++i)
 #pragma unroll
         for (int j = 0; j < WMN; ++j) s[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], s[i][j], 0, 0, 0);
-      // z row block: wave-uniform choice, written as branches (indexing a[] with a run-time
-      // value would turn into per-element selects)
-      if (WMN == 2) {
-        if (ni == 0) zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], as_f16x8(ones), zacc, 0, 0, 0);
-        else zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[WMN - 1], as_f16x8(ones), zacc, 0, 0, 0);
-      } else if (do_z) {
-        zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], as_f16x8(ones), zacc, 0, 0, 0);
-      }
+      // z row block = the first owned row block (no branch inside the MFMA phase; for WMN == 1
+      // the odd wavefronts compute a copy that is not written)
+      zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], as_f16x8(ones), zacc, 0, 0, 0);
     }
   }
 
@@ -287,7 +288,7 @@ __global__ __launch_bounds__(NT, 2) void state_partials_bf16_kernel(const uint16
     for (int j = 0; j < WMN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int f = 32 * (mi * WMN + i) + 8 * (r / 4) + 4 * g + (r % 4);
+        const int f = 32 * fblk(i) + 8 * (r / 4) + 4 * g + (r % 4);
         dst[f * D + 32 * (ni * WMN + j) + c] = s[i][j][r];
       }
   if (do_z && c == 0) {
@@ -295,6 +296,192 @@ __global__ __launch_bounds__(NT, 2) void state_partials_bf16_kernel(const uint16
     for (int r = 0; r < 16; ++r) dst[D * D + 32 * zmb + 8 * (r / 4) + 4 * g + (r % 4)] = zacc[r];
   }
 }
+
+// State pass, wavefront-specialised: 8 wavefronts, one workgroup per compute unit.  Wavefronts
+// 0-3 ("phi") turn the K rows of tile i+1 into phi and park it in one of two LDS buffers;
+// wavefronts 4-7 ("acc") park the V tile there and meanwhile accumulate S = phi^T V, z = phi^T 1
+// from the other buffer (tile i).  Each SIMD hosts one wavefront of each kind, so the softmax
+// arithmetic of one tile overlaps the MFMA phase of the previous one; a single barrier per tile
+// swaps the buffers.
+constexpr int NT1 = 512;
+
+template <int D>
+__global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+                                                                const uint16_t* __restrict__ wk, float* __restrict__ partials,
+                                                                int H, int n, int P) {
+  using C = Cfg<D>;
+  constexpr int RS = D * 2;
+  constexpr int WMN = D / 64;
+  constexpr int VPT = (kTile * C::CH) / 256;     // 16-byte chunks of the V tile per acc thread
+  constexpr int BUF = 2 * kTile * RS;            // one buffer: phi tile, then V tile
+  extern __shared__ uint4 smem[];
+  uint4* sWA = smem;
+  char* sBuf = reinterpret_cast<char*>(sWA + C::W_IMG);
+
+  const int tid = threadIdx.x, lane = tid % 64;
+  const int w = __builtin_amdgcn_readfirstlane(tid / 64);
+  const int role = w / 4, pw = w % 4;            // role 0: phi, role 1: acc
+  const int g = lane / 32;
+  const int bh = blockIdx.y, p = blockIdx.x, h = bh % H;
+  const uint16_t* kb = k + (size_t)bh * n * D;
+  const uint16_t* vb = v + (size_t)bh * n * D;
+  const int ntile = (n + kTile - 1) / kTile;
+  const int nt = (ntile - p + P - 1) / P;        // tiles of this workgroup: p, p+P, ...
+
+  build_w_image<D, NT1>(wk + (size_t)h * D * C::HALF, sWA, tid);
+  __syncthreads();
+
+  if (role == 0) {
+    // ---- phi wavefronts ------------------------------------------------------------------
+    const int prow = 32 * pw + (lane % 32);
+    const int psw = swz<D>(prow);
+    auto load_k = [&](uint4 (&x)[C::UK], int tile) {
+      const int t = tile * kTile + prow;
+      const int tc = t < n ? t : (n - 1);
+      const uint4* row = reinterpret_cast<const uint4*>(kb + (size_t)tc * D);
+#pragma unroll
+      for (int ks = 0; ks < C::UK; ++ks) x[ks] = row[2 * ks + g];
+    };
+    // one tile: x holds its K rows and is refilled with the tile two steps ahead as soon as the
+    // projection has consumed it
+    auto phi_step = [&](uint4 (&x)[C::UK], int it) {
+      if (it < nt) {
+        const int tile = p + it * P;
+        const bool valid = (tile * kTile + prow) < n;
+        f32x16 u[C::UM];
+        project<D>(x, sWA, lane, u);
+        if (it + 2 < nt) load_k(x, tile + 2 * P);
+        uint32_t pk[C::NPK];
+        softmax_pair<D>(u, valid, pk);
+        char* rowp = sBuf + (it & 1) * BUF + prow * RS;
+        constexpr int CPH = C::LOC / 8;
+#pragma unroll
+        for (int c = 0; c < CPH; ++c) {
+          uint4 a, b;
+          a.x = pk[4 * c]; a.y = pk[4 * c + 1]; a.z = pk[4 * c + 2]; a.w = pk[4 * c + 3];
+          b.x = pk[C::LOC / 2 + 4 * c]; b.y = pk[C::LOC / 2 + 4 * c + 1];
+          b.z = pk[C::LOC / 2 + 4 * c + 2]; b.w = pk[C::LOC / 2 + 4 * c + 3];
+          *reinterpret_cast<uint4*>(rowp + (((g * CPH + c) ^ psw) * 16)) = a;
+          *reinterpret_cast<uint4*>(rowp + (((C::CH / 2 + g * CPH + c) ^ psw) * 16)) = b;
+        }
+      }
+      __syncthreads();
+    };
+    uint4 xa[C::UK], xc[C::UK];
+    load_k(xa, p);
+    if (nt > 1) load_k(xc, p + P);
+    for (int it = 0; it <= nt; it += 2) {       // nt + 1 barriers in total, as in the acc branch
+      phi_step(xa, it);
+      if (it + 1 <= nt) phi_step(xc, it + 1);
+    }
+  } else {
+    // ---- acc wavefronts ------------------------------------------------------------------
+    const int mi = pw / 2, ni = pw % 2;
+    const int atid = tid - 256;
+    f32x16 s[WMN][WMN], zacc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      zacc[r] = 0.f;
+#pragma unroll
+      for (int i = 0; i < WMN; ++i)
+#pragma unroll
+        for (int j = 0; j < WMN; ++j) s[i][j][r] = 0.f;
+    }
+    const int zmb = (WMN == 2) ? (2 * mi + ni) : mi;
+    const bool do_z = (WMN == 2) || (ni == 0);
+    auto fblk = [&](int i) { return mi * WMN + ((WMN == 2) ? (i ^ ni) : i); };
+    uint4 ones;
+    ones.x = ones.y = ones.z = ones.w = 0x3C003C00u;
+    int offA[WMN][2], offB[WMN][2];
+#pragma unroll
+    for (int i = 0; i < WMN; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        offA[i][j] = tr_offset<D>(32 * fblk(i), lane, j);
+        offB[i][j] = tr_offset<D>(32 * (ni * WMN + i), lane, j) + kTile * RS;
+      }
+    auto load_v = [&](uint4 (&vr)[VPT], int tile) {
+      const int t0 = tile * kTile;
+#pragma unroll
+      for (int i = 0; i < VPT; ++i) {
+        const int idx = atid + 256 * i;
+        const int r = idx / C::CH, c = idx % C::CH;
+        const int tv = (t0 + r) < n ? (t0 + r) : (n - 1);
+        vr[i] = ld_nt(reinterpret_cast<const uint4*>(vb + (size_t)tv * D) + c);
+      }
+    };
+    // one step: park V tile `it` (held in vr, refilled with the tile two steps ahead), then
+    // accumulate tile it-1 from the other buffer
+    auto acc_step = [&](uint4 (&vr)[VPT], int it) {
+      if (it < nt) {
+        char* sV = sBuf + (it & 1) * BUF + kTile * RS;
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+          const int idx = atid + 256 * i;
+          const int rv = idx / C::CH, c = idx % C::CH;
+          uint4 hv;
+          hv.x = bf16x2_to_f16x2(vr[i].x); hv.y = bf16x2_to_f16x2(vr[i].y);
+          hv.z = bf16x2_to_f16x2(vr[i].z); hv.w = bf16x2_to_f16x2(vr[i].w);
+          *reinterpret_cast<uint4*>(sV + rv * RS + ((c ^ swz<D>(rv)) * 16)) = hv;
+        }
+        if (it + 2 < nt) load_v(vr, p + (it + 2) * P);
+      }
+      if (it >= 1) {
+        // operands of k-step ks+1 are requested before the MFMAs of k-step ks are issued
+        const char* buf = sBuf + ((it - 1) & 1) * BUF;
+        f16x8 a[2][WMN], b[2][WMN];
+#pragma unroll
+        for (int i = 0; i < WMN; ++i) a[0][i] = read_tr(buf, offA[i][0], offA[i][1]);
+#pragma unroll
+        for (int j = 0; j < WMN; ++j) b[0][j] = read_tr(buf, offB[j][0], offB[j][1]);
+#pragma unroll
+        for (int ks = 0; ks < kTile / 16; ++ks) {
+          const int cur = ks & 1, nxt = cur ^ 1;
+          if (ks + 1 < kTile / 16) {
+#pragma unroll
+            for (int i = 0; i < WMN; ++i) a[nxt][i] = read_tr(buf + (ks + 1) * 16 * RS, offA[i][0], offA[i][1]);
+#pragma unroll
+            for (int j = 0; j < WMN; ++j) b[nxt][j] = read_tr(buf + (ks + 1) * 16 * RS, offB[j][0], offB[j][1]);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int i = 0; i < WMN; ++i)
+#pragma unroll
+            for (int j = 0; j < WMN; ++j)
+              s[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[cur][i], b[cur][j], s[i][j], 0, 0, 0);
+          zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[cur][0], as_f16x8(ones), zacc, 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      __syncthreads();
+    };
+    uint4 va[VPT], vc[VPT];
+    load_v(va, p);
+    if (nt > 1) load_v(vc, p + P);
+    for (int it = 0; it <= nt; it += 2) {
+      acc_step(va, it);
+      if (it + 1 <= nt) acc_step(vc, it + 1);
+    }
+    float* dst = partials + ((size_t)bh * P + p) * (size_t)(D + 1) * D;
+    const int c = lane % 32;
+#pragma unroll
+    for (int i = 0; i < WMN; ++i)
+#pragma unroll
+      for (int j = 0; j < WMN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int f = 32 * fblk(i) + 8 * (r / 4) + 4 * g + (r % 4);
+          dst[f * D + 32 * (ni * WMN + j) + c] = s[i][j][r];
+        }
+    if (do_z && c == 0) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dst[D * D + 32 * zmb + 8 * (r / 4) + 4 * g + (r % 4)] = zacc[r];
+    }
+  }
+}
+
+template <int D>
+constexpr size_t state_ws_smem() { return sizeof(uint4) * Cfg<D>::W_IMG + 4 * (size_t)kTile * D * 2; }
 
 template <int D>
 constexpr size_t state_smem() { return sizeof(uint4) * Cfg<D>::W_IMG + 2 * (size_t)kTile * D * 2; }
@@ -312,15 +499,15 @@ hipError_t set_smem(K kernel, size_t bytes) {
 
 hipError_t launch_state_partials_bf16(const void* k, const void* v, const void* wk, float* partials,
                                       const Plan& p, hipStream_t s) {
-  dim3 grid(p.P, p.BH), block(NT);
+  dim3 grid(p.P, p.BH), block(NT1);
   hipError_t e;
   if (p.d == 128) {
-    if ((e = set_smem(state_partials_bf16_kernel<128>, state_smem<128>())) != hipSuccess) return e;
-    state_partials_bf16_kernel<128><<<grid, block, state_smem<128>(), s>>>(
+    if ((e = set_smem(state_partials_ws_kernel<128>, state_ws_smem<128>())) != hipSuccess) return e;
+    state_partials_ws_kernel<128><<<grid, block, state_ws_smem<128>(), s>>>(
         (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)wk, partials, p.H, p.n, p.P);
   } else {
-    if ((e = set_smem(state_partials_bf16_kernel<64>, state_smem<64>())) != hipSuccess) return e;
-    state_partials_bf16_kernel<64><<<grid, block, state_smem<64>(), s>>>(
+    if ((e = set_smem(state_partials_ws_kernel<64>, state_ws_smem<64>())) != hipSuccess) return e;
+    state_partials_ws_kernel<64><<<grid, block, state_ws_smem<64>(), s>>>(
         (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)wk, partials, p.H, p.n, p.P);
   }
   return hipGetLastError();

@@ -9,8 +9,8 @@ namespace linattn {
 
 // Tokens a workgroup of the bf16 kernels consumes per iteration (4 waves x 32 tokens).
 constexpr int kTile = 128;
-// Workgroup slots the split-n plan aims to fill: 256 compute units x 2 resident workgroups.
-constexpr int kSlots = 512;
+// Workgroup slots the split-n plan aims to fill: one resident workgroup per compute unit.
+constexpr int kSlots = 256;
 // Compute units of the gfx950 parts this library targets (MI355X / MI350X).
 constexpr int kCUs = 256;
 
