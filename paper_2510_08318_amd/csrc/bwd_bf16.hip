@@ -10,7 +10,7 @@
 // bwd_prep_kernel : fp16 operand image of S for g (rows = features, contraction over channels)
 // bwd_q_kernel    : per 128-token tile: phi(Q), o, delta, g, du, dq; dS, dz partials (split-n)
 // bwd_k_kernel    : per 32-token block: phi(K), g, du, dk, dv
-// (state_reduce.hip) dW~ = sum over tokens and batch of x^T du (fp32, fixed order)
+// dw_mfma_kernel  : dW~ partials = x^T du per token split (reduced in state_reduce.hip)
 //
 // Precision: every 16-bit MFMA operand except the stored bf16 q, k (projection) is fp16.
 // Operands that belong to one token only (dO_i for g_i, du_i for dx_i) are scaled by a per-token
@@ -44,8 +44,9 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(const float* __restrict__
   __shared__ float red[4];
   const int bh = blockIdx.x, tid = threadIdx.x;
   const float* S = state + (size_t)bh * (D + 1) * D;
-  const float scale = head_scale<D, 256>(S, red, tid);
-  for (int idx = tid; idx < G::IMG; idx += 256) gimg[(size_t)bh * G::IMG + idx] = grad_image_entry<D>(S, scale, idx);
+  const float scale = head_scale<D, 256>(S, red, tid);      // every block of a head computes the same value
+  for (int idx = blockIdx.y * 256 + tid; idx < G::IMG; idx += 256 * gridDim.y)
+    gimg[(size_t)bh * G::IMG + idx] = grad_image_entry<D>(S, scale, idx);
 }
 
 // Softmax Jacobian of Eq. 5 for one token spread over a lane pair: gacc holds g in the GradLayout
@@ -491,6 +492,117 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
   }
 }
 
+// ---- dW~ = sum_{b, i} x_i^T du_i on MFMA -----------------------------------------------------
+// x [BH][n][D] bf16, du [BH][n][D/2] fp32 (written by the kernels above).  Per 128-token tile both
+// are parked in LDS as fp16 (du times one power of two per workgroup, taken from its first tile)
+// and contracted over the tokens with transposing reads; wavefront w owns the channel rows
+// 32w .. 32w+31.  Partials per (b,h) and split are reduced in a fixed order afterwards.
+template <int D>
+__global__ __launch_bounds__(NT) void dw_mfma_kernel(const uint16_t* __restrict__ x, const float* __restrict__ du,
+                                                     float* __restrict__ part, int n, int P) {
+  constexpr int HALF = D / 2;
+  constexpr int RSX = D * 2, RSU = HALF * 2;
+  constexpr int NB = HALF / 32;                 // 32-column blocks of du
+  constexpr int XPT = (kTile * (D / 8)) / NT;   // 16-byte chunks of the x tile per thread
+  constexpr int UPT = (kTile * (HALF / 8)) / NT;
+  __shared__ __attribute__((aligned(16))) char sX[kTile * RSX];
+  __shared__ __attribute__((aligned(16))) char sU[kTile * RSU];
+  __shared__ float sRed[4];
+  const int tid = threadIdx.x, lane = tid % 64;
+  const int w = __builtin_amdgcn_readfirstlane(tid / 64);
+  const int g = lane / 32;
+  const int bh = blockIdx.y, p = blockIdx.x;
+  const uint16_t* xb = x + (size_t)bh * n * D;
+  const float* ub = du + (size_t)bh * n * HALF;
+  const int ntile = (n + kTile - 1) / kTile;
+  const bool active = w < D / 32;
+
+  f32x16 acc[NB];
+#pragma unroll
+  for (int j = 0; j < NB; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+  int offA[2], offB[NB][2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    offA[j] = tr_offset<D>(32 * (active ? w : 0), lane, j);
+#pragma unroll
+    for (int b = 0; b < NB; ++b) offB[b][j] = tr_offset<HALF>(32 * b, lane, j);
+  }
+  float gamma = 1.f;
+  for (int tile = p; tile < ntile; tile += P) {
+    const int t0 = tile * kTile;
+    uint4 xr[XPT];
+    float4 ur[UPT][2];
+#pragma unroll
+    for (int i = 0; i < XPT; ++i) {
+      const int idx = tid + NT * i, r = idx / (D / 8), c = idx % (D / 8);
+      const int t = t0 + r;
+      xr[i] = t < n ? ld_nt(reinterpret_cast<const uint4*>(xb + (size_t)t * D) + c) : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < UPT; ++i) {
+      const int idx = tid + NT * i, r = idx / (HALF / 8), c = idx % (HALF / 8);
+      const int t = t0 + r;
+      const float4* src = reinterpret_cast<const float4*>(ub + (size_t)t * HALF) + 2 * c;
+      ur[i][0] = t < n ? src[0] : make_float4(0.f, 0.f, 0.f, 0.f);
+      ur[i][1] = t < n ? src[1] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    if (tile == p) {
+      float m = 0.f;
+#pragma unroll
+      for (int i = 0; i < UPT; ++i)
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2)
+          m = fmaxf(m, fmaxf(fmaxf(fabsf(ur[i][k2].x), fabsf(ur[i][k2].y)), fmaxf(fabsf(ur[i][k2].z), fabsf(ur[i][k2].w))));
+      for (int k2 = 32; k2 >= 1; k2 >>= 1) m = fmaxf(m, __shfl_xor(m, k2, 64));
+      if (lane == 0) sRed[w] = m;
+      __syncthreads();
+      m = fmaxf(fmaxf(sRed[0], sRed[1]), fmaxf(sRed[2], sRed[3]));
+      gamma = 16.f * pow2_normaliser(m);
+    }
+    __syncthreads();                              // previous tile's operand reads are done
+#pragma unroll
+    for (int i = 0; i < XPT; ++i) {
+      const int idx = tid + NT * i, r = idx / (D / 8), c = idx % (D / 8);
+      uint4 hv;
+      hv.x = bf16x2_to_f16x2(xr[i].x); hv.y = bf16x2_to_f16x2(xr[i].y);
+      hv.z = bf16x2_to_f16x2(xr[i].z); hv.w = bf16x2_to_f16x2(xr[i].w);
+      *reinterpret_cast<uint4*>(sX + r * RSX + ((c ^ swz<D>(r)) * 16)) = hv;
+    }
+#pragma unroll
+    for (int i = 0; i < UPT; ++i) {
+      const int idx = tid + NT * i, r = idx / (HALF / 8), c = idx % (HALF / 8);
+      uint4 hv;
+      hv.x = pack_f16x2(ur[i][0].x * gamma, ur[i][0].y * gamma); hv.y = pack_f16x2(ur[i][0].z * gamma, ur[i][0].w * gamma);
+      hv.z = pack_f16x2(ur[i][1].x * gamma, ur[i][1].y * gamma); hv.w = pack_f16x2(ur[i][1].z * gamma, ur[i][1].w * gamma);
+      *reinterpret_cast<uint4*>(sU + r * RSU + ((c ^ swz<HALF>(r)) * 16)) = hv;
+    }
+    __syncthreads();
+    if (active) {
+#pragma unroll
+      for (int ks = 0; ks < kTile / 16; ++ks) {
+        const f16x8 a = read_tr(sX + ks * 16 * RSX, offA[0], offA[1]);
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+          const f16x8 bo = read_tr(sU + ks * 16 * RSU, offB[b][0], offB[b][1]);
+          acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bo, acc[b], 0, 0, 0);
+        }
+      }
+    }
+  }
+  if (active) {
+    const float ig = __builtin_amdgcn_rcpf(gamma);
+    float* dst = part + ((size_t)bh * P + p) * (size_t)D * HALF;
+    const int c = lane % 32;
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        dst[(32 * w + 8 * (r / 4) + 4 * g + (r % 4)) * HALF + 32 * b + c] = acc[b][r] * ig;
+  }
+}
+
 template <int D>
 constexpr size_t q_smem() {
   return sizeof(uint4) * (Cfg<D>::W_IMG + ApplyLayout<D>::KS * ApplyLayout<D>::MBZ * 64 + (Cfg<D>::LOC / 8) * ApplyLayout<D>::MB * 64)
@@ -509,7 +621,7 @@ hipError_t set_smem(K kernel, size_t bytes) {
 template <int D>
 hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   hipError_t e;
-  bwd_prep_kernel<D><<<p.BH, 256, 0, s>>>(a.state, (uint4*)a.gimg);
+  bwd_prep_kernel<D><<<dim3(p.BH, 8), 256, 0, s>>>(a.state, (uint4*)a.gimg);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if ((e = set_smem(bwd_q_kernel<D>, q_smem<D>())) != hipSuccess) return e;
   bwd_q_kernel<D><<<dim3(p.P, p.BH), NT, q_smem<D>(), s>>>(
@@ -522,8 +634,16 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
       (const uint16_t*)a.k, (const uint16_t*)a.v, (const uint16_t*)a.wk, a.dstate,
       (uint16_t*)a.dk, (uint16_t*)a.dv, a.dwk ? a.du_k : nullptr, p.H, p.n);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  if (a.dwq && (e = launch_dw(a.q, true, a.du_q, a.dw_part, a.dwq, p, s)) != hipSuccess) return e;
-  if (a.dwk && (e = launch_dw(a.k, true, a.du_k, a.dw_part, a.dwk, p, s)) != hipSuccess) return e;
+  if (a.dwq) {
+    dw_mfma_kernel<D><<<dim3(p.P, p.BH), NT, 0, s>>>((const uint16_t*)a.q, a.du_q, a.dw_part, p.n, p.P);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if ((e = launch_dw_reduce(a.dw_part, a.dwq, p, s)) != hipSuccess) return e;
+  }
+  if (a.dwk) {
+    dw_mfma_kernel<D><<<dim3(p.P, p.BH), NT, 0, s>>>((const uint16_t*)a.k, a.du_k, a.dw_part, p.n, p.P);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if ((e = launch_dw_reduce(a.dw_part, a.dwk, p, s)) != hipSuccess) return e;
+  }
   return hipSuccess;
 }
 

@@ -66,6 +66,8 @@ hipError_t launch_apply_bf16(const void* q, const void* wq, const float* state, 
 
 // ---- backward launchers (enqueue only) --------------------------------------------------
 // dw[H][d][d/2] = sum over batch and tokens of x^T du; x is [B,H,n,d] bf16 or fp32, du fp32 [B,H,n,d/2].
+// dw[h][e] = sum over b, then over the P splits, of part[(b*H+h)][p][e].
+hipError_t launch_dw_reduce(const float* part, float* dw, const Plan& p, hipStream_t s);
 hipError_t launch_dw(const void* x, bool x_is_bf16, const float* du, float* part, float* dw, const Plan& p, hipStream_t s);
 hipError_t launch_bwd_bf16(const BwdArgs& a, const Plan& p, hipStream_t s);
 hipError_t launch_bwd_f32(const BwdArgs& a, const Plan& p, hipStream_t s);

@@ -26,6 +26,7 @@ struct Cfg {
 template <int D>
 __device__ __forceinline__ int swz(int r) {
   if (D == 128) return ((r & 3) << 2) | ((r >> 2) & 3);
+  if (D == 32) return r & 3;                               // 4 chunks per row
   return (((r & 3) << 1) ^ ((r >> 2) & 3)) & 7;
 }
 

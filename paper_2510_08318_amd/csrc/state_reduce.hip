@@ -115,6 +115,11 @@ hipError_t launch_dw(const void* x, bool x_is_bf16, const float* du, float* part
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  return launch_dw_reduce(part, dw, p, s);
+}
+
+hipError_t launch_dw_reduce(const float* part, float* dw, const Plan& p, hipStream_t s) {
+  const int elems = p.d * (p.d / 2);
   dw_reduce_kernel<<<dim3((elems + 255) / 256, p.H), 256, 0, s>>>(part, dw, p.B, p.H, p.P, elems);
   return hipGetLastError();
 }
