@@ -44,7 +44,7 @@ bool make_plan(int B, int H, int n, int d, int dtype, Plan* p) {
     const int nblk = (n + 31) / 32;
     int KP = kCUs / (int)BH;
     if (KP < 1) KP = 1;
-    if (KP > (nblk + 3) / 4) KP = (nblk + 3) / 4;
+    if (KP > (nblk + 7) / 8) KP = (nblk + 7) / 8;
     r.KP = KP;
   }
   r.off_dstate = off;   off = up(off + (size_t)BH * r.state_elems * sizeof(float));

@@ -363,7 +363,7 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
 }
 
 // ---- key side ----------------------------------------------------------------------------
-constexpr int NTK = 256;
+constexpr int NTK = 512;     // 8 wavefronts, one workgroup per compute unit
 
 template <int D>
 __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
@@ -405,21 +405,31 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
 
   const int nblk = (n + 31) / 32;
   const int stride = gridDim.x * NW;
-  for (int b = blockIdx.x * NW + w; b < nblk; b += stride) {
+  uint4 xk[C::UK], vr[D / 16], vnext[D / 16];
+  auto load_k = [&](int b) {
+    const int t = b * 32 + (lane % 32);
+    const int tc = t < n ? t : (n - 1);
+    const uint4* row = reinterpret_cast<const uint4*>(kb + (size_t)tc * D);
+#pragma unroll
+    for (int ks = 0; ks < C::UK; ++ks) xk[ks] = row[2 * ks + g];
+  };
+  auto load_v = [&](int b) {
+    const int t = b * 32 + (lane % 32);
+    const int tc = t < n ? t : (n - 1);
+    const uint4* vrow = reinterpret_cast<const uint4*>(vb + (size_t)tc * D + g * (D / 2));
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) vnext[i] = vrow[i];
+  };
+  int b = blockIdx.x * NW + w;
+  if (b < nblk) { load_k(b); load_v(b); }
+  for (; b < nblk; b += stride) {
     const int t = b * 32 + (lane % 32);
     const bool valid = t < n;
-    const int tc = valid ? t : (n - 1);
-    uint4 xk[C::UK], vr[D / 16];
-    {
-      const uint4* row = reinterpret_cast<const uint4*>(kb + (size_t)tc * D);
 #pragma unroll
-      for (int ks = 0; ks < C::UK; ++ks) xk[ks] = row[2 * ks + g];
-      const uint4* vrow = reinterpret_cast<const uint4*>(vb + (size_t)tc * D + g * (D / 2));
-#pragma unroll
-      for (int i = 0; i < D / 16; ++i) vr[i] = vrow[i];
-    }
+    for (int i = 0; i < D / 16; ++i) vr[i] = vnext[i];
     f32x16 u[C::UM];
     project<D>(xk, sWA, lane, u);
+    if (b + stride < nblk) { load_k(b + stride); load_v(b + stride); }   // next block flies during this one
     float pp[C::LOC], pm[C::LOC];
     uint32_t pk[C::NPK];
     softmax_full<D>(u, pp, pm, pk);
