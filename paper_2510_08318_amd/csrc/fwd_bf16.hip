@@ -50,11 +50,21 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
   const uint16_t* qb = q + (size_t)bh * n * D;
   uint16_t* ob = out + (size_t)bh * n * D;
 
-  build_w_image<D, NT3>(wq + (size_t)h * D * C::HALF, sWA, tid);
   {
-    const float* sb = state + (size_t)bh * (D + 1) * D;
-    const float scale = head_scale<D, NT3>(sb, reinterpret_cast<float*>(sOut), tid);
-    build_state_image<D, NT3>(sb, sSA, scale, tid);
+    // The state and W~ of this (b,h) are first copied into LDS with coalesced 16-byte loads (the
+    // output staging area is free until the main loop), then turned into the operand images from
+    // there: the scattered reads the images need would cost tens of microseconds from global memory.
+    float* stS = reinterpret_cast<float*>(sOut);
+    uint16_t* stW = reinterpret_cast<uint16_t*>(stS + (D + 1) * D);
+    float* red = reinterpret_cast<float*>(stW + D * C::HALF);
+    const uint4* gS = reinterpret_cast<const uint4*>(state + (size_t)bh * (D + 1) * D);
+    const uint4* gW = reinterpret_cast<const uint4*>(wq + (size_t)h * D * C::HALF);
+    for (int i = tid; i < (D + 1) * D / 4; i += NT3) reinterpret_cast<uint4*>(stS)[i] = gS[i];
+    for (int i = tid; i < D * C::HALF / 8; i += NT3) reinterpret_cast<uint4*>(stW)[i] = gW[i];
+    __syncthreads();
+    const float scale = head_scale<D, NT3>(stS, red, tid);
+    build_w_image<D, NT3>(stW, sWA, tid);
+    build_state_image<D, NT3>(stS, sSA, scale, tid);
   }
   __syncthreads();
 
