@@ -5,6 +5,10 @@ A step is one linattn_fwd call (state pass, reduction, query pass) over one batc
 Wan-14B/720p-shaped tensors (B=1, H=40, n=75600, d=128, bf16) already resident in HBM.
 Prints one JSON line: whole-path tokens/s, the HBM roofline of the dominant kernel measured with
 HIP events between the stages, and the CPU fp64 oracle timed on a bounded sample beside it.
+
+`--pass bwd` times linattn_bwd instead (default workload: the config-5 training shape, with the
+weight gradients unless --no-wgrads); its roofline object covers the whole call against the seven
+compulsory tensor passes.  The headline metric is the forward one.
 """
 from __future__ import annotations
 
@@ -56,12 +60,75 @@ def cpu_baseline(x, budget_s: float = 12.0):
             "sample": f"{done} of {x.H} heads of batch item 0, all {x.n} tokens, fp64 numpy, {dt:.1f} s"}
 
 
+def cpu_baseline_bwd(x, budget_s: float = 12.0):
+    """The oracle's backward (forward recomputed inside it), whole heads of the same workload."""
+    from oracle import linattn_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    done = 0
+    t0 = time.perf_counter()
+    for h in range(x.H):
+        O.bwd(O.to_f64(x.q[0, h]), O.to_f64(x.k[0, h]), O.to_f64(x.v[0, h]), O.to_f64(x.wq[h]), O.to_f64(x.wk[h]),
+              O.to_f64(x.dout[0, h]))
+        done += 1
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    return {"value": done * x.n / dt / x.H, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{done} of {x.H} heads of batch item 0, all {x.n} tokens, fp64 numpy backward, {dt:.1f} s"}
+
+
+def bench_bwd(args):
+    """linattn_bwd on one batch (state from one forward call made before the timed region)."""
+    import torch
+    from paper_2510_08318_amd import synth, torch_glue as G
+    x = synth.generate(args.workload, with_dout=True)
+    q, k, v, wq, wk, dout = [G.to_device(t) for t in (x.q, x.k, x.v, x.wq, x.wk, x.dout)]
+    lay = G.Layer(wq, wk, x.B, x.n, want_wgrads=not args.no_wgrads)
+    lay.forward(q, k, v)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+
+    def step():
+        lay.backward(q, k, v, dout, dq, dk, dv)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    esz = 2 if x.dtype == "bf16" else 4
+    head_tokens = x.B * x.H * x.n
+    algo = 7 * x.d * esz * head_tokens          # read q, k, v, dO; write dq, dk, dv
+    achieved = algo / dt / 1e9
+    res = {
+        "metric": f"linear-attn bwd tokens/s ({args.workload})", "value": round(x.B * x.n / dt, 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": x.dtype, "data": "synthetic",
+        "config": {"workload": f"{args.workload}: B={x.B} H={x.H} n={x.n} d={x.d} {x.dtype}, backward of Eq. 3 + Eq. 5, "
+                               f"state saved by the forward, weight gradients {'off' if args.no_wgrads else 'on'}"},
+        "roofline": {"bound": "hbm", "kernel": "linattn_bwd (all kernels of one call)", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline_bwd(x)
+    lay.close()
+    print(json.dumps(res), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="C3", help="configuration name in paper_2510_08318_amd.synth")
+    ap.add_argument("--workload", default=None, help="configuration name in paper_2510_08318_amd.synth (default C3; C5 for --pass bwd)")
+    ap.add_argument("--pass", dest="which", choices=("fwd", "bwd"), default="fwd")
+    ap.add_argument("--no-wgrads", action="store_true", help="--pass bwd: skip the weight gradients")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy kernel (reference reading for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
@@ -73,6 +140,10 @@ def main():
     from paper_2510_08318_amd import binding as L, synth, torch_glue as G
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.workload is None:
+        args.workload = "C5" if args.which == "bwd" else "C3"
+    if args.which == "bwd":
+        return bench_bwd(args)
 
     x = synth.generate(args.workload)
     q, k, v, wq, wk = [G.to_device(t) for t in (x.q, x.k, x.v, x.wq, x.wk)]
