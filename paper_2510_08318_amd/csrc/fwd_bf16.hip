@@ -7,7 +7,7 @@
 // fp16 operands leave the bf16 rounding of the output as the largest error.  V is widened
 // bf16 -> fp16 on its way into LDS (exact for 2^-14 <= |v| < 65520).
 //
-// state_partials_bf16_kernel : phi(K) (Eq. 5) fused with the split-n partial state
+// state_partials_ws_kernel   : phi(K) (Eq. 5) fused with the split-n partial state
 //                              S_p = sum_j phi(k_j)^T v_j, z_p = sum_j phi(k_j)  (Eq. 3)
 // apply_bf16_kernel          : phi(Q), out = phi(Q) S / (phi(Q) . z), bf16 store (Eq. 3)
 //
@@ -153,157 +153,6 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
       }
     }
     __builtin_amdgcn_wave_barrier();
-  }
-}
-
-// State pass.  A workgroup (4 wavefronts) owns 128-token tiles p, p + P, p + 2P, ... of its head.
-// Per tile each wavefront turns 32 K rows into phi (fp16) and parks it in LDS next to the V tile
-// (widened to fp16); then every wavefront accumulates its quadrant of S = phi^T V over the 128
-// tokens with transposing LDS reads, and one row block of z = phi^T 1.
-template <int D>
-__global__ __launch_bounds__(NT, 2) void state_partials_bf16_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-                                                                    const uint16_t* __restrict__ wk, float* __restrict__ partials,
-                                                                    int H, int n, int P) {
-  using C = Cfg<D>;
-  constexpr int RS = D * 2;            // tile row stride, bytes
-  constexpr int WMN = D / 64;          // 32x32 blocks per wavefront along each side of S
-  constexpr int VPT = (kTile * C::CH) / NT;   // 16-byte chunks of the V tile per thread
-  extern __shared__ uint4 smem[];
-  uint4* sWA = smem;
-  char* sPhi = reinterpret_cast<char*>(sWA + C::W_IMG);   // [kTile][D] fp16, swizzled chunks
-  char* sV = sPhi + kTile * RS;                           // [kTile][D] fp16, swizzled chunks
-
-  const int tid = threadIdx.x, lane = tid % 64;
-  const int w = __builtin_amdgcn_readfirstlane(tid / 64);   // wave-uniform, lives in an SGPR
-  const int g = lane / 32;
-  const int mi = w / 2, ni = w % 2;
-  const int bh = blockIdx.y, p = blockIdx.x, h = bh % H;
-  const uint16_t* kb = k + (size_t)bh * n * D;
-  const uint16_t* vb = v + (size_t)bh * n * D;
-  const int ntile = (n + kTile - 1) / kTile;
-
-  build_w_image<D, NT>(wk + (size_t)h * D * C::HALF, sWA, tid);
-
-  f32x16 s[WMN][WMN], zacc;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    zacc[r] = 0.f;
-#pragma unroll
-    for (int i = 0; i < WMN; ++i)
-#pragma unroll
-      for (int j = 0; j < WMN; ++j) s[i][j][r] = 0.f;
-  }
-  // Row blocks of S this wavefront owns, ordered so that the first one is also the row block of z
-  // it sums (every wavefront sums a different one when WMN == 2): fblk(i) = mi*WMN + (i ^ ni).
-  const int zmb = (WMN == 2) ? (2 * mi + ni) : mi;
-  const bool do_z = (WMN == 2) || (ni == 0);
-  auto fblk = [&](int i) { return mi * WMN + ((WMN == 2) ? (i ^ ni) : i); };
-  uint4 ones;
-  ones.x = ones.y = ones.z = ones.w = 0x3C003C00u;      // fp16 1.0 pairs
-
-  // lane-constant LDS offsets of the transposing reads (A: phi columns, B: V columns)
-  int offA[WMN][2], offB[WMN][2];
-#pragma unroll
-  for (int i = 0; i < WMN; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      offA[i][j] = tr_offset<D>(32 * fblk(i), lane, j);
-      offB[i][j] = tr_offset<D>(32 * (ni * WMN + i), lane, j);
-    }
-  // lane-constant LDS offsets of the tile writes
-  const int prow = 32 * w + (lane % 32);
-  const int psw = swz<D>(prow);
-
-  uint4 xb[C::UK], vreg[VPT];
-  auto load_k = [&](int tile) {
-    const int t = tile * kTile + 32 * w + (lane % 32);
-    const int tc = t < n ? t : (n - 1);
-    const uint4* row = reinterpret_cast<const uint4*>(kb + (size_t)tc * D);
-#pragma unroll
-    for (int ks = 0; ks < C::UK; ++ks) xb[ks] = row[2 * ks + g];
-  };
-  auto load_v = [&](int tile) {
-    const int t0 = tile * kTile;
-#pragma unroll
-    for (int i = 0; i < VPT; ++i) {
-      const int idx = tid + NT * i;
-      const int r = idx / C::CH, c = idx % C::CH;
-      const int tv = (t0 + r) < n ? (t0 + r) : (n - 1);
-      vreg[i] = ld_nt(reinterpret_cast<const uint4*>(vb + (size_t)tv * D) + c);
-    }
-  };
-
-  int tile = p;
-  if (tile < ntile) { load_k(tile); load_v(tile); }
-  __syncthreads();                               // W image complete
-  for (; tile < ntile; tile += P) {
-    const bool valid = (tile * kTile + 32 * w + (lane % 32)) < n;
-    f32x16 u[C::UM];
-    project<D>(xb, sWA, lane, u);
-    // Prefetches are unconditional (the last iteration re-reads its own, cached, tile): a load
-    // behind a branch makes the compiler wait for everything outstanding at the next use.
-    const int next = (tile + P < ntile) ? tile + P : tile;
-    load_k(next);                                // next K rows fly during the rest of this tile
-    uint32_t pk[C::NPK];
-    softmax_pair<D>(u, valid, pk);
-    __syncthreads();                             // previous tile's operand reads are done
-    {
-      char* rowp = sPhi + prow * RS;
-      constexpr int CPH = C::LOC / 8;            // 16-byte chunks per softmax half a lane owns
-#pragma unroll
-      for (int c = 0; c < CPH; ++c) {
-        uint4 a, b;
-        a.x = pk[4 * c]; a.y = pk[4 * c + 1]; a.z = pk[4 * c + 2]; a.w = pk[4 * c + 3];
-        b.x = pk[C::LOC / 2 + 4 * c]; b.y = pk[C::LOC / 2 + 4 * c + 1];
-        b.z = pk[C::LOC / 2 + 4 * c + 2]; b.w = pk[C::LOC / 2 + 4 * c + 3];
-        *reinterpret_cast<uint4*>(rowp + (((g * CPH + c) ^ psw) * 16)) = a;                 // softmax(+u) half
-        *reinterpret_cast<uint4*>(rowp + (((C::CH / 2 + g * CPH + c) ^ psw) * 16)) = b;     // softmax(-u) half
-      }
-#pragma unroll
-      for (int i = 0; i < VPT; ++i) {
-        const int idx = tid + NT * i;
-        const int rv = idx / C::CH, c = idx % C::CH;
-        uint4 hv;
-        hv.x = bf16x2_to_f16x2(vreg[i].x); hv.y = bf16x2_to_f16x2(vreg[i].y);
-        hv.z = bf16x2_to_f16x2(vreg[i].z); hv.w = bf16x2_to_f16x2(vreg[i].w);
-        *reinterpret_cast<uint4*>(sV + rv * RS + ((c ^ swz<D>(rv)) * 16)) = hv;
-      }
-    }
-    __syncthreads();
-    load_v(next);                                // next V tile flies during the MFMA phase and the next phi
-
-#pragma unroll
-    for (int ks = 0; ks < kTile / 16; ++ks) {
-      f16x8 a[WMN], b[WMN];
-#pragma unroll
-      for (int i = 0; i < WMN; ++i) a[i] = read_tr(sPhi + ks * 16 * RS, offA[i][0], offA[i][1]);
-#pragma unroll
-      for (int j = 0; j < WMN; ++j) b[j] = read_tr(sV + ks * 16 * RS, offB[j][0], offB[j][1]);
-#pragma unroll
-      for (int i = 0; i < WMN; ++i)
-#pragma unroll
-        for (int j = 0; j < WMN; ++j) s[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], s[i][j], 0, 0, 0);
-      // z row block = the first owned row block (no branch inside the MFMA phase; for WMN == 1
-      // the odd wavefronts compute a copy that is not written)
-      zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], as_f16x8(ones), zacc, 0, 0, 0);
-    }
-  }
-
-  // partial state in the exported layout: S [D][D] (feature rows in the order of Eq. 5), then z [D]
-  float* dst = partials + ((size_t)bh * P + p) * (size_t)(D + 1) * D;
-  const int c = lane % 32;
-#pragma unroll
-  for (int i = 0; i < WMN; ++i)
-#pragma unroll
-    for (int j = 0; j < WMN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int f = 32 * fblk(i) + 8 * (r / 4) + 4 * g + (r % 4);
-        dst[f * D + 32 * (ni * WMN + j) + c] = s[i][j][r];
-      }
-  if (do_z && c == 0) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) dst[D * D + 32 * zmb + 8 * (r / 4) + 4 * g + (r % 4)] = zacc[r];
   }
 }
 
@@ -493,8 +342,6 @@ __global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* 
 template <int D>
 constexpr size_t state_ws_smem() { return sizeof(uint4) * Cfg<D>::W_IMG + 4 * (size_t)kTile * D * 2; }
 
-template <int D>
-constexpr size_t state_smem() { return sizeof(uint4) * Cfg<D>::W_IMG + 2 * (size_t)kTile * D * 2; }
 template <int D>
 constexpr size_t apply_smem() {
   return sizeof(uint4) * (Cfg<D>::W_IMG + ApplyLayout<D>::KS * ApplyLayout<D>::MBZ * 64) + (size_t)(NT3 / 64) * 32 * D * 2;
