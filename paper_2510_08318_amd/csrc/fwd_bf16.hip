@@ -364,16 +364,24 @@ constexpr int NTI = 256;
 // wait states between the last MFMA of a chain and the first ordinary read of its result are
 // inserted by hand (mfma_settle).  Back-to-back accumulation into the same registers needs none.
 __device__ __forceinline__ void mfma_bf16_v0(f32x16& d, bf16x8 a, bf16x8 b) {
-  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "v"(b));
+  asm("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "v"(b));
 }
 __device__ __forceinline__ void mfma_bf16_v(f32x16& d, bf16x8 a, bf16x8 b) {
   asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "v"(b));
 }
-__device__ __forceinline__ void mfma_f16_v0(f32x16& d, f16x8 a, f16x8 b) {
-  asm("v_mfma_f32_32x32x16_f16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "v"(b));
-}
-__device__ __forceinline__ void mfma_f16_v(f32x16& d, f16x8 a, f16x8 b) {
-  asm("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "v"(b));
+// Turn of two 32-feature blocks at once: t0 = a00 s0 + a01 s1, t1 = a10 s0 + a11 s1, the two chains
+// interleaved so that dependent MFMAs are one MFMA apart.  The leading wait states separate the
+// first MFMA from ordinary instructions that may just have written its operands (gfx950 needs
+// them between a vector ALU write and an MFMA read; the compiler adds them for its own MFMAs).
+__device__ __forceinline__ void turn_pair_v(f32x16& t0, f32x16& t1, f16x8 a00, f16x8 a01, f16x8 a10, f16x8 a11,
+                                            f16x8 s0, f16x8 s1) {
+  asm("s_nop 3\n\t"
+      "v_mfma_f32_32x32x16_f16 %0, %2, %6, 0\n\t"
+      "v_mfma_f32_32x32x16_f16 %1, %4, %6, 0\n\t"
+      "v_mfma_f32_32x32x16_f16 %0, %3, %7, %0\n\t"
+      "v_mfma_f32_32x32x16_f16 %1, %5, %7, %1"
+      : "=&v"(t0), "=&v"(t1)
+      : "v"(a00), "v"(a01), "v"(a10), "v"(a11), "v"(s0), "v"(s1));
 }
 // 20 wait states: covers the longest documented MFMA-result-to-VALU-read distance (19).
 __device__ __forceinline__ void mfma_settle(f32x16& d) { asm volatile("s_nop 15\n\ts_nop 3" : "+v"(d)); }
@@ -535,34 +543,42 @@ __global__ __launch_bounds__(NTI) void state_partials_iw_kernel(const uint16_t* 
 #pragma unroll
       for (int kb2 = 0; kb2 < 2; ++kb2) vop[c][kb2] = read_tr(buf + kb2 * 16 * RS, offV[c][0], offV[c][1]);
 #pragma unroll
-    for (int fb = 0; fb < FB; ++fb) {
-      const int half = fb / (D / 64), b = fb % (D / 64);
-      f32x16 t;
+    for (int fp = 0; fp < FB; fp += 2) {
+      f32x16 t[2];
+      f16x8 ta[2][2];
 #pragma unroll
-      for (int jj = 0; jj < 2; ++jj) {
-        const int base = half * (C::LOC / 2) + 4 * (2 * b + jj);
-        uint4 a; a.x = pk[base]; a.y = pk[base + 1]; a.z = pk[base + 2]; a.w = pk[base + 3];
-        if (jj == 0) mfma_f16_v0(t, as_f16x8(a), sel[jj]);
-        else mfma_f16_v(t, as_f16x8(a), sel[jj]);
+      for (int i = 0; i < 2; ++i) {
+        const int half = (fp + i) / (D / 64), b = (fp + i) % (D / 64);
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+          const int base = half * (C::LOC / 2) + 4 * (2 * b + jj);
+          uint4 a; a.x = pk[base]; a.y = pk[base + 1]; a.z = pk[base + 2]; a.w = pk[base + 3];
+          ta[i][jj] = as_f16x8(a);
+        }
       }
-      mfma_settle(t);
-      float zsum = 0.f;
+      turn_pair_v(t[0], t[1], ta[0][0], ta[0][1], ta[1][0], ta[1][1], sel[0], sel[1]);
+      mfma_settle(t[0], t[1]);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) zsum += t[r];
-      zs[fb] += zsum;
-      f16x8 pt[2];
+      for (int i = 0; i < 2; ++i) {
+        const int fb = fp + i;
+        float zsum = 0.f;
 #pragma unroll
-      for (int kb2 = 0; kb2 < 2; ++kb2) {
-        uint4 a;
-        a.x = pack_f16x2(t[8 * kb2], t[8 * kb2 + 1]);     a.y = pack_f16x2(t[8 * kb2 + 2], t[8 * kb2 + 3]);
-        a.z = pack_f16x2(t[8 * kb2 + 4], t[8 * kb2 + 5]); a.w = pack_f16x2(t[8 * kb2 + 6], t[8 * kb2 + 7]);
-        pt[kb2] = as_f16x8(a);
+        for (int r = 0; r < 16; ++r) zsum += t[i][r];
+        zs[fb] += zsum;
+        f16x8 pt[2];
+#pragma unroll
+        for (int kb2 = 0; kb2 < 2; ++kb2) {
+          uint4 a;
+          a.x = pack_f16x2(t[i][8 * kb2], t[i][8 * kb2 + 1]);     a.y = pack_f16x2(t[i][8 * kb2 + 2], t[i][8 * kb2 + 3]);
+          a.z = pack_f16x2(t[i][8 * kb2 + 4], t[i][8 * kb2 + 5]); a.w = pack_f16x2(t[i][8 * kb2 + 6], t[i][8 * kb2 + 7]);
+          pt[kb2] = as_f16x8(a);
+        }
+#pragma unroll
+        for (int c = 0; c < CB; ++c)
+#pragma unroll
+          for (int kb2 = 0; kb2 < 2; ++kb2)
+            acc[fb][c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(pt[kb2], vop[c][kb2], acc[fb][c], 0, 0, 0);
       }
-#pragma unroll
-      for (int c = 0; c < CB; ++c)
-#pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2)
-          acc[fb][c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(pt[kb2], vop[c][kb2], acc[fb][c], 0, 0, 0);
     }
     __builtin_amdgcn_wave_barrier();
   };
