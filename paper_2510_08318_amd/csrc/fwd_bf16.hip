@@ -339,325 +339,6 @@ __global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* 
   }
 }
 
-// State pass with independent wavefronts: 4 wavefronts per workgroup, one per SIMD with the whole
-// register file (512 registers per lane), no workgroup barrier inside the main loop.  Wavefront w
-// owns tokens 32w .. 32w+31 of every 128-token tile of its workgroup and accumulates a complete
-// S (d x d) and z of its own; the four are summed through LDS at the end in a fixed order.
-//
-// phi never goes through LDS.  The softmax leaves phi with one token per lane (features in
-// registers), while S = phi^T V contracts over tokens and needs tokens in registers.  The turn is
-// an MFMA against a 0/1 selection operand: with phi as the A operand (row = token, contraction over
-// 16 features) and B[k][n] = [n == slot(k)], the accumulator comes back with one feature slot per
-// lane and 16 tokens in its registers -- exactly (after an exact fp32 -> fp16 repack) the A operand
-// of S = phi^T V with the tokens of a 16-token k-step in the order {4g..4g+3, 8+4g..8+4g+3}.
-// The V operand uses the same token order through the row addresses of its transposing reads.
-// z is the in-lane sum of the turned accumulators.
-//
-// Feature slot n (0..31) of row block fb = half*(D/64) + b:  jj = n/16, g' = (n%16)/8, e = n%8
-//   feature = half*D/2 + g'*D/4 + 8*(2b + jj) + e.
-constexpr int NTI = 256;
-
-// MFMA whose accumulator stays in ordinary (architectural) registers.  The S accumulators of this
-// kernel fill the accumulation register file, and the compiler's own MFMA selection would put
-// every MFMA result there, shuffling S blocks out and back to make room for the short-lived
-// projection and turn results.  Nothing tells the compiler that these statements are MFMAs, so the
-// wait states between the last MFMA of a chain and the first ordinary read of its result are
-// inserted by hand (mfma_settle).  Back-to-back accumulation into the same registers needs none.
-__device__ __forceinline__ void mfma_bf16_v0(f32x16& d, bf16x8 a, bf16x8 b) {
-  asm("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "v"(b));
-}
-__device__ __forceinline__ void mfma_bf16_v(f32x16& d, bf16x8 a, bf16x8 b) {
-  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "v"(b));
-}
-// Turn of two 32-feature blocks at once: t0 = a00 s0 + a01 s1, t1 = a10 s0 + a11 s1, the two chains
-// interleaved so that dependent MFMAs are one MFMA apart.  The leading wait states separate the
-// first MFMA from ordinary instructions that may just have written its operands (gfx950 needs
-// them between a vector ALU write and an MFMA read; the compiler adds them for its own MFMAs).
-__device__ __forceinline__ void turn_pair_v(f32x16& t0, f32x16& t1, f16x8 a00, f16x8 a01, f16x8 a10, f16x8 a11,
-                                            f16x8 s0, f16x8 s1) {
-  asm("s_nop 3\n\t"
-      "v_mfma_f32_32x32x16_f16 %0, %2, %6, 0\n\t"
-      "v_mfma_f32_32x32x16_f16 %1, %4, %6, 0\n\t"
-      "v_mfma_f32_32x32x16_f16 %0, %3, %7, %0\n\t"
-      "v_mfma_f32_32x32x16_f16 %1, %5, %7, %1"
-      : "=&v"(t0), "=&v"(t1)
-      : "v"(a00), "v"(a01), "v"(a10), "v"(a11), "v"(s0), "v"(s1));
-}
-// 20 wait states: covers the longest documented MFMA-result-to-VALU-read distance (19).
-__device__ __forceinline__ void mfma_settle(f32x16& d) { asm volatile("s_nop 15\n\ts_nop 3" : "+v"(d)); }
-__device__ __forceinline__ void mfma_settle(f32x16& d0, f32x16& d1) {
-  asm volatile("s_nop 15\n\ts_nop 3" : "+v"(d0), "+v"(d1));
-}
-
-// project() with the accumulators in ordinary registers (see above).  The W~ operands are
-// requested two k-steps ahead in program order (the compiler does not move loads across the
-// MFMA statements).
-template <int D>
-__device__ __forceinline__ void project_v(const uint4 (&xb)[Cfg<D>::UK], const uint4* sWA, int lane,
-                                          f32x16 (&u)[Cfg<D>::UM]) {
-  using C = Cfg<D>;
-  constexpr int AHEAD = 2;
-  const uint4* wa = sWA + lane + opaque_zero();
-  uint4 a[C::UK][C::UM];
-#pragma unroll
-  for (int ks = 0; ks < AHEAD; ++ks)
-#pragma unroll
-    for (int mb = 0; mb < C::UM; ++mb) a[ks][mb] = wa[(ks * C::UM + mb) * 64];
-#pragma unroll
-  for (int ks = 0; ks < C::UK; ++ks) {
-    if (ks + AHEAD < C::UK) {
-#pragma unroll
-      for (int mb = 0; mb < C::UM; ++mb) a[ks + AHEAD][mb] = wa[((ks + AHEAD) * C::UM + mb) * 64];
-    }
-    const bf16x8 b = as_bf16x8(xb[ks]);
-#pragma unroll
-    for (int mb = 0; mb < C::UM; ++mb) {
-      if (ks == 0) mfma_bf16_v0(u[mb], as_bf16x8(a[ks][mb]), b);
-      else mfma_bf16_v(u[mb], as_bf16x8(a[ks][mb]), b);
-    }
-  }
-  if constexpr (C::UM == 2) mfma_settle(u[0], u[1]);
-  else mfma_settle(u[0]);
-}
-
-template <int D>
-__device__ __forceinline__ int iw_feature(int fb, int n) {
-  const int half = fb / (D / 64), b = fb % (D / 64);
-  return half * (D / 2) + ((n % 16) / 8) * (D / 4) + 8 * (2 * b + n / 16) + (n % 8);
-}
-
-// Byte offset of this lane's address for a transposing read of the V operand of k-step 0:
-// j = 0: tile rows 4g .. 4g+3, j = 1: rows 8+4g .. 8+4g+3 (g = lane/32); columns col0 + lane%32.
-template <int D>
-__device__ __forceinline__ int tr_offset_g4(int col0, int lane, int j) {
-  constexpr int RS = D * 2;
-  const int r = 4 * (lane / 32) + ((lane % 16) / 4) + 8 * j;
-  const int col = col0 + 16 * ((lane / 16) % 2) + 4 * (lane % 4);
-  return r * RS + (((col / 8) ^ swz<D>(r)) * 16) + (col % 8) * 2;
-}
-
-template <int D>
-__global__ __launch_bounds__(NTI) void state_partials_iw_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-                                                                const uint16_t* __restrict__ wk, float* __restrict__ partials,
-                                                                int H, int n, int P) {
-  using C = Cfg<D>;
-  constexpr int RS = D * 2;
-  constexpr int FB = D / 32, CB = D / 32;        // 32-row blocks of S over features / channels
-  constexpr int VPT = C::CH / 2;                 // 16-byte chunks of a 32-token V block per lane
-  constexpr int VBUF = 32 * RS;                  // one wavefront's V block in LDS
-  constexpr int DUMP = FB * CB * 16 * 64;        // floats of one wavefront's S accumulators
-  extern __shared__ uint4 smem[];
-  uint4* sWA = smem;
-  char* sV = reinterpret_cast<char*>(sWA + C::W_IMG);
-
-  const int tid = threadIdx.x, lane = tid % 64;
-  const int w = __builtin_amdgcn_readfirstlane(tid / 64);
-  const int g = lane / 32, nl = lane % 32;
-  const int bh = blockIdx.y, p = blockIdx.x, h = bh % H;
-  const uint16_t* kb = k + (size_t)bh * n * D;
-  const uint16_t* vb = v + (size_t)bh * n * D;
-  const int ntile = (n + kTile - 1) / kTile;
-  const int nt = (ntile - p + P - 1) / P;        // tiles of this workgroup: p, p+P, ...
-
-  build_w_image<D, NTI>(wk + (size_t)h * D * C::HALF, sWA, tid);
-  __syncthreads();
-
-  f32x16 acc[FB][CB];
-  float zs[FB];
-#pragma unroll
-  for (int i = 0; i < FB; ++i) {
-    zs[i] = 0.f;
-#pragma unroll
-    for (int j = 0; j < CB; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-  }
-  // selection operands: B[k = 8g+e][n] = 1 iff n == 16*jj + 8g + e
-  f16x8 sel[2];
-#pragma unroll
-  for (int jj = 0; jj < 2; ++jj) {
-    uint4 t;
-    uint32_t q[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int e0 = 16 * jj + 8 * g + 2 * i;
-      q[i] = (nl == e0 ? 0x3C00u : 0u) | (nl == e0 + 1 ? 0x3C000000u : 0u);
-    }
-    t.x = q[0]; t.y = q[1]; t.z = q[2]; t.w = q[3];
-    sel[jj] = as_f16x8(t);
-  }
-  int offV[CB][2];
-#pragma unroll
-  for (int c = 0; c < CB; ++c)
-#pragma unroll
-    for (int j = 0; j < 2; ++j) offV[c][j] = tr_offset_g4<D>(32 * c, lane, j);
-
-  char* sVw = sV + w * (2 * VBUF);
-  const int krow = 32 * w + nl;                  // this lane's token inside a tile
-  auto load_k = [&](uint4 (&x)[C::UK], int tile) {
-    const int t = tile * kTile + krow;
-    const int tc = t < n ? t : (n - 1);
-    const uint4* row = reinterpret_cast<const uint4*>(kb + (size_t)tc * D);
-#pragma unroll
-    for (int ks = 0; ks < C::UK; ++ks) x[ks] = row[2 * ks + g];
-  };
-  auto load_v = [&](uint4 (&vr)[VPT], int tile) {
-    const int t0 = tile * kTile + 32 * w;
-#pragma unroll
-    for (int i = 0; i < VPT; ++i) {
-      const int idx = lane + 64 * i;
-      const int r = idx / C::CH, c = idx % C::CH;
-      const int tv = (t0 + r) < n ? (t0 + r) : (n - 1);
-      vr[i] = ld_nt(reinterpret_cast<const uint4*>(vb + (size_t)tv * D) + c);
-    }
-  };
-
-  uint4 vr[VPT];
-  auto step = [&](uint4 (&x)[C::UK], int it) {
-    const int tile = p + it * P;
-    char* buf = sVw + (it & 1) * VBUF;
-    // V block: bf16 -> fp16 into this wavefront's LDS buffer; the registers take the next block
-#pragma unroll
-    for (int i = 0; i < VPT; ++i) {
-      const int idx = lane + 64 * i;
-      const int rv = idx / C::CH, c = idx % C::CH;
-      uint4 hv;
-      hv.x = bf16x2_to_f16x2(vr[i].x); hv.y = bf16x2_to_f16x2(vr[i].y);
-      hv.z = bf16x2_to_f16x2(vr[i].z); hv.w = bf16x2_to_f16x2(vr[i].w);
-      *reinterpret_cast<uint4*>(buf + rv * RS + ((c ^ swz<D>(rv)) * 16)) = hv;
-    }
-    // the next tile's loads are unconditional (the last step fetches its own tile again) so that
-    // the number of loads in flight at each wait is the same on every path
-    const int tnext = it + 1 < nt ? tile + P : tile;
-    load_v(vr, tnext);
-    const bool valid = (tile * kTile + krow) < n;
-    f32x16 u[C::UM];
-    project_v<D>(x, sWA, lane, u);
-    load_k(x, tnext);
-    uint32_t pk[C::NPK];
-    softmax_pair<D>(u, valid, pk);
-    __builtin_amdgcn_wave_barrier();
-    f16x8 vop[CB][2];
-#pragma unroll
-    for (int c = 0; c < CB; ++c)
-#pragma unroll
-      for (int kb2 = 0; kb2 < 2; ++kb2) vop[c][kb2] = read_tr(buf + kb2 * 16 * RS, offV[c][0], offV[c][1]);
-#pragma unroll
-    for (int fp = 0; fp < FB; fp += 2) {
-      f32x16 t[2];
-      f16x8 ta[2][2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int half = (fp + i) / (D / 64), b = (fp + i) % (D / 64);
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
-          const int base = half * (C::LOC / 2) + 4 * (2 * b + jj);
-          uint4 a; a.x = pk[base]; a.y = pk[base + 1]; a.z = pk[base + 2]; a.w = pk[base + 3];
-          ta[i][jj] = as_f16x8(a);
-        }
-      }
-      turn_pair_v(t[0], t[1], ta[0][0], ta[0][1], ta[1][0], ta[1][1], sel[0], sel[1]);
-      mfma_settle(t[0], t[1]);
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int fb = fp + i;
-        float zsum = 0.f;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) zsum += t[i][r];
-        zs[fb] += zsum;
-        f16x8 pt[2];
-#pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2) {
-          uint4 a;
-          a.x = pack_f16x2(t[i][8 * kb2], t[i][8 * kb2 + 1]);     a.y = pack_f16x2(t[i][8 * kb2 + 2], t[i][8 * kb2 + 3]);
-          a.z = pack_f16x2(t[i][8 * kb2 + 4], t[i][8 * kb2 + 5]); a.w = pack_f16x2(t[i][8 * kb2 + 6], t[i][8 * kb2 + 7]);
-          pt[kb2] = as_f16x8(a);
-        }
-#pragma unroll
-        for (int c = 0; c < CB; ++c)
-#pragma unroll
-          for (int kb2 = 0; kb2 < 2; ++kb2)
-            acc[fb][c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(pt[kb2], vop[c][kb2], acc[fb][c], 0, 0, 0);
-      }
-    }
-    __builtin_amdgcn_wave_barrier();
-  };
-
-  uint4 xa[C::UK];
-  load_k(xa, p);
-  load_v(vr, p);
-  for (int it = 0; it < nt; ++it) step(xa, it);
-
-  // ---- sum the four wavefronts in the fixed order (S0 + S2) + (S1 + S3) ---------------------
-  __syncthreads();                               // the W~ image and the V buffers are dead
-  float* dump = reinterpret_cast<float*>(smem);  // two regions of DUMP floats, then the z area
-  float* zred = dump + 2 * DUMP;                 // [4][D]
-  auto put = [&](float* region) {
-#pragma unroll
-    for (int i = 0; i < FB; ++i)
-#pragma unroll
-      for (int j = 0; j < CB; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          float4 t4 = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-          reinterpret_cast<float4*>(region)[((i * CB + j) * 4 + q) * 64 + lane] = t4;
-        }
-  };
-  auto add = [&](const float* region) {
-#pragma unroll
-    for (int i = 0; i < FB; ++i)
-#pragma unroll
-      for (int j = 0; j < CB; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const float4 t4 = reinterpret_cast<const float4*>(region)[((i * CB + j) * 4 + q) * 64 + lane];
-          acc[i][j][4 * q] += t4.x; acc[i][j][4 * q + 1] += t4.y; acc[i][j][4 * q + 2] += t4.z; acc[i][j][4 * q + 3] += t4.w;
-        }
-  };
-  {
-    // z: both lane groups of a slot, then the wavefronts
-#pragma unroll
-    for (int i = 0; i < FB; ++i) {
-      float lo, hi;
-      pair32(zs[i], lo, hi);
-      if (g == 0) zred[w * D + 32 * i + nl] = lo + hi;
-    }
-  }
-  if (w >= 2) put(dump + (w - 2) * DUMP);
-  __syncthreads();
-  if (w < 2) add(dump + w * DUMP);
-  __syncthreads();
-  if (w == 1) put(dump);
-  __syncthreads();
-  if (w == 0) {
-    add(dump);
-    float* dst = partials + ((size_t)bh * P + p) * (size_t)(D + 1) * D;
-#pragma unroll
-    for (int i = 0; i < FB; ++i)
-#pragma unroll
-      for (int j = 0; j < CB; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int f = iw_feature<D>(i, 8 * (r / 4) + 4 * g + (r % 4));
-          dst[f * D + 32 * j + nl] = acc[i][j][r];
-        }
-    if (g == 0) {
-#pragma unroll
-      for (int i = 0; i < FB; ++i) {
-        const int e = 32 * i + nl;
-        dst[D * D + iw_feature<D>(i, nl)] = (zred[e] + zred[2 * D + e]) + (zred[D + e] + zred[3 * D + e]);
-      }
-    }
-  }
-}
-
-template <int D>
-constexpr size_t state_iw_smem() {
-  const size_t loop = sizeof(uint4) * Cfg<D>::W_IMG + 4 * 2 * (size_t)32 * D * 2;
-  const size_t fin = 2 * (size_t)(D / 32) * (D / 32) * 16 * 64 * sizeof(float) + 4 * D * sizeof(float);
-  return loop > fin ? loop : fin;
-}
-
 template <int D>
 constexpr size_t state_ws_smem() { return sizeof(uint4) * Cfg<D>::W_IMG + 4 * (size_t)kTile * D * 2; }
 
@@ -675,15 +356,15 @@ hipError_t set_smem(K kernel, size_t bytes) {
 
 hipError_t launch_state_partials_bf16(const void* k, const void* v, const void* wk, float* partials,
                                       const Plan& p, hipStream_t s) {
-  dim3 grid(p.P, p.BH), block(NTI);
+  dim3 grid(p.P, p.BH), block(NT1);
   hipError_t e;
   if (p.d == 128) {
-    if ((e = set_smem(state_partials_iw_kernel<128>, state_iw_smem<128>())) != hipSuccess) return e;
-    state_partials_iw_kernel<128><<<grid, block, state_iw_smem<128>(), s>>>(
+    if ((e = set_smem(state_partials_ws_kernel<128>, state_ws_smem<128>())) != hipSuccess) return e;
+    state_partials_ws_kernel<128><<<grid, block, state_ws_smem<128>(), s>>>(
         (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)wk, partials, p.H, p.n, p.P);
   } else {
-    if ((e = set_smem(state_partials_iw_kernel<64>, state_iw_smem<64>())) != hipSuccess) return e;
-    state_partials_iw_kernel<64><<<grid, block, state_iw_smem<64>(), s>>>(
+    if ((e = set_smem(state_partials_ws_kernel<64>, state_ws_smem<64>())) != hipSuccess) return e;
+    state_partials_ws_kernel<64><<<grid, block, state_ws_smem<64>(), s>>>(
         (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)wk, partials, p.H, p.n, p.P);
   }
   return hipGetLastError();
