@@ -164,6 +164,26 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
 // swaps the buffers.
 constexpr int NT1 = 512;
 
+// Feature of phi (order of Eq. 5) behind feature slot n (0..31) of 32-row block fb of the turned
+// phi (see state_partials_ws_kernel): fb = half*(D/64) + b, jj = n/16, g' = (n%16)/8, e = n%8
+//   feature = half*D/2 + g'*D/4 + 8*(2b + jj) + e.
+template <int D>
+__device__ __forceinline__ int turned_feature(int fb, int n) {
+  const int half = fb / (D / 64), b = fb % (D / 64);
+  return half * (D / 2) + ((n % 16) / 8) * (D / 4) + 8 * (2 * b + n / 16) + (n % 8);
+}
+
+// Byte offset of this lane's address for a transposing read of the V operand of k-step 0 in the
+// token order of the turned phi: j = 0: tile rows 4g .. 4g+3, j = 1: rows 8+4g .. 8+4g+3
+// (g = lane/32); columns col0 + lane%32.
+template <int D>
+__device__ __forceinline__ int tr_offset_g4(int col0, int lane, int j) {
+  constexpr int RS = D * 2;
+  const int r = 4 * (lane / 32) + ((lane % 16) / 4) + 8 * j;
+  const int col = col0 + 16 * ((lane / 16) % 2) + 4 * (lane % 4);
+  return r * RS + (((col / 8) ^ swz<D>(r)) * 16) + (col % 8) * 2;
+}
+
 template <int D>
 __global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                                                                 const uint16_t* __restrict__ wk, float* __restrict__ partials,
@@ -172,10 +192,12 @@ __global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* 
   constexpr int RS = D * 2;
   constexpr int WMN = D / 64;
   constexpr int VPT = (kTile * C::CH) / 256;     // 16-byte chunks of the V tile per acc thread
-  constexpr int BUF = 2 * kTile * RS;            // one buffer: phi tile, then V tile
+  constexpr int BUF = 2 * kTile * RS;            // one buffer: turned-phi operand image, then V tile
+  constexpr int FB = D / 32;                     // 32-row blocks of S over the features
   extern __shared__ uint4 smem[];
   uint4* sWA = smem;
   char* sBuf = reinterpret_cast<char*>(sWA + C::W_IMG);
+  float* zred = reinterpret_cast<float*>(sBuf + 2 * BUF);      // [4][D] z of the four phi wavefronts
 
   const int tid = threadIdx.x, lane = tid % 64;
   const int w = __builtin_amdgcn_readfirstlane(tid / 64);
@@ -193,7 +215,22 @@ __global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* 
   if (role == 0) {
     // ---- phi wavefronts ------------------------------------------------------------------
     const int prow = 32 * pw + (lane % 32);
-    const int psw = swz<D>(prow);
+    // selection operands: B[k = 8g+e][n] = 1 iff n == 16*jj + 8g + e
+    f16x8 sel[2];
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj) {
+      uint32_t q[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int e0 = 16 * jj + 8 * g + 2 * i;
+        q[i] = ((lane % 32) == e0 ? 0x3C00u : 0u) | ((lane % 32) == e0 + 1 ? 0x3C000000u : 0u);
+      }
+      uint4 t; t.x = q[0]; t.y = q[1]; t.z = q[2]; t.w = q[3];
+      sel[jj] = as_f16x8(t);
+    }
+    float zs[FB];
+#pragma unroll
+    for (int i = 0; i < FB; ++i) zs[i] = 0.f;
     auto load_k = [&](uint4 (&x)[C::UK], int tile) {
       const int t = tile * kTile + prow;
       const int tc = t < n ? t : (n - 1);
@@ -212,16 +249,34 @@ __global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* 
         if (it + 2 < nt) load_k(x, tile + 2 * P);
         uint32_t pk[C::NPK];
         softmax_pair<D>(u, valid, pk);
-        char* rowp = sBuf + (it & 1) * BUF + prow * RS;
-        constexpr int CPH = C::LOC / 8;
+        // turn phi from "token per lane" to "feature slot per lane" with an MFMA against the 0/1
+        // selection operands: the accumulator is then (after an exact repack to fp16) the A operand
+        // of S = phi^T V with the tokens of a 16-token k-step in the order {4g..4g+3, 8+4g..8+4g+3};
+        // z is the in-lane sum.  The operands go to LDS ready-made: entry (pw, fb, kb, lane).
+        uint4* img = reinterpret_cast<uint4*>(sBuf + (it & 1) * BUF) + (pw * FB * 2) * 64 + lane;
 #pragma unroll
-        for (int c = 0; c < CPH; ++c) {
-          uint4 a, b;
-          a.x = pk[4 * c]; a.y = pk[4 * c + 1]; a.z = pk[4 * c + 2]; a.w = pk[4 * c + 3];
-          b.x = pk[C::LOC / 2 + 4 * c]; b.y = pk[C::LOC / 2 + 4 * c + 1];
-          b.z = pk[C::LOC / 2 + 4 * c + 2]; b.w = pk[C::LOC / 2 + 4 * c + 3];
-          *reinterpret_cast<uint4*>(rowp + (((g * CPH + c) ^ psw) * 16)) = a;
-          *reinterpret_cast<uint4*>(rowp + (((C::CH / 2 + g * CPH + c) ^ psw) * 16)) = b;
+        for (int fb = 0; fb < FB; ++fb) {
+          const int half = fb / (D / 64), b = fb % (D / 64);
+          f32x16 t;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) t[r] = 0.f;
+#pragma unroll
+          for (int jj = 0; jj < 2; ++jj) {
+            const int base = half * (C::LOC / 2) + 4 * (2 * b + jj);
+            uint4 a; a.x = pk[base]; a.y = pk[base + 1]; a.z = pk[base + 2]; a.w = pk[base + 3];
+            t = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a), sel[jj], t, 0, 0, 0);
+          }
+          float zsum = 0.f;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) zsum += t[r];
+          zs[fb] += zsum;
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb) {
+            uint4 a;
+            a.x = pack_f16x2(t[8 * kb], t[8 * kb + 1]);     a.y = pack_f16x2(t[8 * kb + 2], t[8 * kb + 3]);
+            a.z = pack_f16x2(t[8 * kb + 4], t[8 * kb + 5]); a.w = pack_f16x2(t[8 * kb + 6], t[8 * kb + 7]);
+            img[(fb * 2 + kb) * 64] = a;
+          }
         }
       }
       __syncthreads();
@@ -233,32 +288,30 @@ __global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* 
       phi_step(xa, it);
       if (it + 1 <= nt) phi_step(xc, it + 1);
     }
+    // z of this wavefront's tokens: both lane groups of a slot
+#pragma unroll
+    for (int fb = 0; fb < FB; ++fb) {
+      float lo, hi;
+      pair32(zs[fb], lo, hi);
+      if (g == 0) zred[pw * D + 32 * fb + lane] = lo + hi;
+    }
   } else {
     // ---- acc wavefronts ------------------------------------------------------------------
     const int mi = pw / 2, ni = pw % 2;
     const int atid = tid - 256;
-    f32x16 s[WMN][WMN], zacc;
+    f32x16 s[WMN][WMN];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      zacc[r] = 0.f;
+    for (int r = 0; r < 16; ++r)
 #pragma unroll
       for (int i = 0; i < WMN; ++i)
 #pragma unroll
         for (int j = 0; j < WMN; ++j) s[i][j][r] = 0.f;
-    }
-    const int zmb = (WMN == 2) ? (2 * mi + ni) : mi;
-    const bool do_z = (WMN == 2) || (ni == 0);
     auto fblk = [&](int i) { return mi * WMN + ((WMN == 2) ? (i ^ ni) : i); };
-    uint4 ones;
-    ones.x = ones.y = ones.z = ones.w = 0x3C003C00u;
-    int offA[WMN][2], offB[WMN][2];
+    int offB[WMN][2];
 #pragma unroll
     for (int i = 0; i < WMN; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        offA[i][j] = tr_offset<D>(32 * fblk(i), lane, j);
-        offB[i][j] = tr_offset<D>(32 * (ni * WMN + i), lane, j) + kTile * RS;
-      }
+      for (int j = 0; j < 2; ++j) offB[i][j] = tr_offset_g4<D>(32 * (ni * WMN + i), lane, j) + kTile * RS;
     auto load_v = [&](uint4 (&vr)[VPT], int tile) {
       const int t0 = tile * kTile;
 #pragma unroll
@@ -286,21 +339,24 @@ __global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* 
         if (it + 2 < nt) load_v(vr, p + (it + 2) * P);
       }
       if (it >= 1) {
-        // operands of k-step ks+1 are requested before the MFMAs of k-step ks are issued
+        // operands of k-step ks+1 are requested before the MFMAs of k-step ks are issued.
+        // k-step ks = tokens 16ks .. 16ks+15 = phi wavefront ks/2, half kb = ks%2 of its block.
         const char* buf = sBuf + ((it - 1) & 1) * BUF;
+        const uint4* img = reinterpret_cast<const uint4*>(buf) + lane + opaque_zero();
         f16x8 a[2][WMN], b[2][WMN];
 #pragma unroll
-        for (int i = 0; i < WMN; ++i) a[0][i] = read_tr(buf, offA[i][0], offA[i][1]);
+        for (int i = 0; i < WMN; ++i) a[0][i] = as_f16x8(img[(fblk(i) * 2) * 64]);
 #pragma unroll
         for (int j = 0; j < WMN; ++j) b[0][j] = read_tr(buf, offB[j][0], offB[j][1]);
 #pragma unroll
         for (int ks = 0; ks < kTile / 16; ++ks) {
           const int cur = ks & 1, nxt = cur ^ 1;
           if (ks + 1 < kTile / 16) {
+            const int kn = ks + 1;
 #pragma unroll
-            for (int i = 0; i < WMN; ++i) a[nxt][i] = read_tr(buf + (ks + 1) * 16 * RS, offA[i][0], offA[i][1]);
+            for (int i = 0; i < WMN; ++i) a[nxt][i] = as_f16x8(img[(((kn / 2) * FB + fblk(i)) * 2 + (kn % 2)) * 64]);
 #pragma unroll
-            for (int j = 0; j < WMN; ++j) b[nxt][j] = read_tr(buf + (ks + 1) * 16 * RS, offB[j][0], offB[j][1]);
+            for (int j = 0; j < WMN; ++j) b[nxt][j] = read_tr(buf + kn * 16 * RS, offB[j][0], offB[j][1]);
           }
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -308,7 +364,6 @@ __global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* 
 #pragma unroll
             for (int j = 0; j < WMN; ++j)
               s[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[cur][i], b[cur][j], s[i][j], 0, 0, 0);
-          zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[cur][0], as_f16x8(ones), zacc, 0, 0, 0);
           __builtin_amdgcn_sched_barrier(0);
         }
       }
@@ -329,18 +384,20 @@ __global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* 
       for (int j = 0; j < WMN; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int f = 32 * fblk(i) + 8 * (r / 4) + 4 * g + (r % 4);
+          const int f = turned_feature<D>(fblk(i), 8 * (r / 4) + 4 * g + (r % 4));
           dst[f * D + 32 * (ni * WMN + j) + c] = s[i][j][r];
         }
-    if (do_z && c == 0) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) dst[D * D + 32 * zmb + 8 * (r / 4) + 4 * g + (r % 4)] = zacc[r];
-    }
+  }
+  // z: the four phi wavefronts, in a fixed order
+  __syncthreads();
+  if (tid < D) {
+    float* dst = partials + ((size_t)bh * P + p) * (size_t)(D + 1) * D;
+    dst[D * D + turned_feature<D>(tid / 32, tid % 32)] = (zred[tid] + zred[2 * D + tid]) + (zred[D + tid] + zred[3 * D + tid]);
   }
 }
 
 template <int D>
-constexpr size_t state_ws_smem() { return sizeof(uint4) * Cfg<D>::W_IMG + 4 * (size_t)kTile * D * 2; }
+constexpr size_t state_ws_smem() { return sizeof(uint4) * Cfg<D>::W_IMG + 4 * (size_t)kTile * D * 2 + 4 * D * sizeof(float); }
 
 template <int D>
 constexpr size_t apply_smem() {
