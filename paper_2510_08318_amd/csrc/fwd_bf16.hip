@@ -163,6 +163,7 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
 // arithmetic of one tile overlaps the MFMA phase of the previous one; a single barrier per tile
 // swaps the buffers.
 constexpr int NT1 = 512;
+constexpr int OPA = 1;           // k-steps of operand read-ahead in the accumulate phase (1, 2, 3 measured alike)
 
 // Feature of phi (order of Eq. 5) behind feature slot n (0..31) of 32-row block fb of the turned
 // phi (see state_partials_ws_kernel): fb = half*(D/64) + b, jj = n/16, g' = (n%16)/8, e = n%8
@@ -339,31 +340,29 @@ __global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* 
         if (it + 2 < nt) load_v(vr, p + (it + 2) * P);
       }
       if (it >= 1) {
-        // operands of k-step ks+1 are requested before the MFMAs of k-step ks are issued.
+        // operands are requested OPA k-steps before the MFMAs that use them.
         // k-step ks = tokens 16ks .. 16ks+15 = phi wavefront ks/2, half kb = ks%2 of its block.
         const char* buf = sBuf + ((it - 1) & 1) * BUF;
         const uint4* img = reinterpret_cast<const uint4*>(buf) + lane + opaque_zero();
-        f16x8 a[2][WMN], b[2][WMN];
+        constexpr int KSN = kTile / 16;
+        f16x8 a[KSN][WMN], b[KSN][WMN];
+        auto request = [&](int kn) {
 #pragma unroll
-        for (int i = 0; i < WMN; ++i) a[0][i] = as_f16x8(img[(fblk(i) * 2) * 64]);
+          for (int i = 0; i < WMN; ++i) a[kn][i] = as_f16x8(img[(((kn / 2) * FB + fblk(i)) * 2 + (kn % 2)) * 64]);
 #pragma unroll
-        for (int j = 0; j < WMN; ++j) b[0][j] = read_tr(buf, offB[j][0], offB[j][1]);
+          for (int j = 0; j < WMN; ++j) b[kn][j] = read_tr(buf + kn * 16 * RS, offB[j][0], offB[j][1]);
+        };
 #pragma unroll
-        for (int ks = 0; ks < kTile / 16; ++ks) {
-          const int cur = ks & 1, nxt = cur ^ 1;
-          if (ks + 1 < kTile / 16) {
-            const int kn = ks + 1;
+        for (int ks = 0; ks < OPA; ++ks) request(ks);
 #pragma unroll
-            for (int i = 0; i < WMN; ++i) a[nxt][i] = as_f16x8(img[(((kn / 2) * FB + fblk(i)) * 2 + (kn % 2)) * 64]);
-#pragma unroll
-            for (int j = 0; j < WMN; ++j) b[nxt][j] = read_tr(buf + kn * 16 * RS, offB[j][0], offB[j][1]);
-          }
+        for (int ks = 0; ks < KSN; ++ks) {
+          if (ks + OPA < KSN) request(ks + OPA);
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int i = 0; i < WMN; ++i)
 #pragma unroll
             for (int j = 0; j < WMN; ++j)
-              s[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[cur][i], b[cur][j], s[i][j], 0, 0, 0);
+              s[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[ks][i], b[ks][j], s[i][j], 0, 0, 0);
           __builtin_amdgcn_sched_barrier(0);
         }
       }
