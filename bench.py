@@ -124,8 +124,8 @@ def bench_bwd(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default=None, help="configuration name in paper_2510_08318_amd.synth (default C3; C5 for --pass bwd)")
     ap.add_argument("--pass", dest="which", choices=("fwd", "bwd"), default="fwd")
     ap.add_argument("--no-wgrads", action="store_true", help="--pass bwd: skip the weight gradients")
