@@ -11,8 +11,12 @@
  * scaling of q.k, no epsilon: every entry of phi is positive so the denominator is too).
  *
  * Conventions shared by every entry point
- *   - q, k, v, out, dout, dq, dk, dv: DEVICE pointers, [B, H, n, d] contiguous, d innermost,
- *     16-byte aligned.  d in {64, 128}, n >= 1 arbitrary, B, H >= 1, 64-bit indexing inside.
+ *   - q, k, v, out, dout, dq, dk, dv: DEVICE pointers, 16-byte aligned, d innermost and
+ *     contiguous, all eight in the descriptor's layout: [B, H, n, d] (LINATTN_LAYOUT_BHND, the
+ *     default) or [B, n, H, d] (LINATTN_LAYOUT_BNHD: heads interleaved per token, the form in
+ *     which a transformer block's projection q = x W_q (Sec. 3) leaves them, so no transpose
+ *     copy is needed around the operator).  d in {64, 128}, n >= 1 arbitrary, B, H >= 1,
+ *     64-bit indexing inside.
  *   - element type of those tensors and of W~ is the descriptor's dtype (bf16 or fp32).
  *     All accumulation is fp32.  The fp32 mode never rounds through bf16.
  *   - all pointers are borrowed: the caller keeps them alive until the stream work is done.
@@ -53,6 +57,10 @@ extern "C" {
 #define LINATTN_BF16  1
 #define LINATTN_F32   2
 
+/* memory layouts of q, k, v, out, dout, dq, dk, dv */
+#define LINATTN_LAYOUT_BHND  0   /* element (b,h,t,c) at ((b*H + h)*n + t)*d + c */
+#define LINATTN_LAYOUT_BNHD  1   /* element (b,h,t,c) at ((b*n + t)*H + h)*d + c */
+
 /*
  * Description of a feature map plus the buffers a layer owns.  Eq. 3 takes q, k, v only;
  * Eq. 5 adds the two learnable matrices, which live here so that linattn_fwd keeps the
@@ -70,10 +78,13 @@ typedef struct linattn_phi_desc {
                              row d = z.  linattn_fwd writes it when non-NULL; linattn_bwd reads it. */
   void *workspace;        /* device scratch, 256-byte aligned, >= linattn_workspace_bytes(...) */
   size_t workspace_bytes;
+  int layout;             /* LINATTN_LAYOUT_BHND (0) or LINATTN_LAYOUT_BNHD; the state, dW~ and the
+                             workspace do not depend on it */
 } linattn_phi_desc;
 
 /* Register a descriptor; *phi_id_out receives a handle >= 16.  Host-only, no HIP call.
- * Errors: E_NULL (desc, out, wq, wk), E_PHI (kind, table full), E_DTYPE, E_SHAPE (H, d), E_ALIGN. */
+ * Errors: E_NULL (desc, out, wq, wk), E_PHI (kind, table full), E_DTYPE, E_SHAPE (H, d, layout),
+ * E_ALIGN. */
 int linattn_phi_create(const linattn_phi_desc* desc, int* phi_id_out);
 
 /* Forget a handle.  E_PHI if it is not live.  Buffers stay the caller's. */

@@ -16,6 +16,7 @@ OK = 0
 E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_PHI, E_WORKSPACE, E_HIP, E_STATE, E_ALIAS = range(-1, -10, -1)
 PHI_HEDGEHOG = 1
 BF16, F32 = 1, 2
+LAYOUT_BHND, LAYOUT_BNHD = 0, 1
 
 EXPORTS = ("linattn_phi_create", "linattn_phi_destroy", "linattn_workspace_bytes", "linattn_workspace_bytes_wgrads",
            "linattn_fwd", "linattn_bwd", "linattn_strerror", "linattn_set_stage_events")
@@ -28,6 +29,7 @@ class PhiDesc(ctypes.Structure):
         ("dwq", ctypes.c_void_p), ("dwk", ctypes.c_void_p),
         ("state", ctypes.c_void_p),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+        ("layout", ctypes.c_int),
     ]
 
 
@@ -90,9 +92,9 @@ def linattn_workspace_bytes_wgrads(B: int, H: int, n: int, d: int, kind: int = P
 
 
 def linattn_phi_create(kind, dtype, H, d, wq, wk, dwq=None, dwk=None, state=None,
-                       workspace=None, workspace_bytes: int = 0, *, check: bool = True) -> int:
+                       workspace=None, workspace_bytes: int = 0, layout: int = 0, *, check: bool = True) -> int:
     desc = PhiDesc(int(kind), int(dtype), int(H), int(d), _ptr(wq), _ptr(wk), _ptr(dwq), _ptr(dwk),
-                   _ptr(state), _ptr(workspace), int(workspace_bytes))
+                   _ptr(state), _ptr(workspace), int(workspace_bytes), int(layout))
     out = ctypes.c_int(-1)
     st = lib().linattn_phi_create(ctypes.byref(desc), ctypes.byref(out))
     if st != OK:

@@ -9,15 +9,18 @@
 
 namespace linattn {
 
-bool make_plan(int B, int H, int n, int d, int dtype, Plan* p) {
+bool make_plan(int B, int H, int n, int d, int dtype, int layout, Plan* p) {
   if (B <= 0 || H <= 0 || n <= 0) return false;
   if (d != 64 && d != 128) return false;
   if (dtype != LINATTN_BF16 && dtype != LINATTN_F32) return false;
+  if (layout != LINATTN_LAYOUT_BHND && layout != LINATTN_LAYOUT_BNHD) return false;
   const long long BH = (long long)B * H;
   if (BH > 65535) return false;                       // grid.y
   if ((long long)n > (1LL << 30)) return false;
   Plan r{};
   r.B = B; r.H = H; r.n = n; r.d = d; r.BH = (int)BH;
+  if (layout == LINATTN_LAYOUT_BHND) r.rows = Rows{(size_t)H * n * d, (size_t)n * d, (size_t)d};
+  else r.rows = Rows{(size_t)n * H * d, (size_t)d, (size_t)H * d};
   const int tiles = (n + kTile - 1) / kTile;
   int P = kSlots / (int)BH;
   if (P < 1) P = 1;
@@ -100,7 +103,7 @@ int check_call(const void* const* tensors, int n_tensors, int B, int H, int n, i
   for (int i = 0; i < n_tensors; ++i)
     if (!tensors[i]) return LINATTN_E_NULL;
   if (H != desc->H || d != desc->d) return LINATTN_E_SHAPE;
-  if (!make_plan(B, H, n, d, desc->dtype, plan)) return LINATTN_E_SHAPE;
+  if (!make_plan(B, H, n, d, desc->dtype, desc->layout, plan)) return LINATTN_E_SHAPE;
   for (int i = 0; i < n_tensors; ++i)
     if (!aligned16(tensors[i])) return LINATTN_E_ALIGN;
   const size_t need = (want_wgrads && (desc->dwq || desc->dwk)) ? plan->total_bytes : plan->bytes_no_wgrads;
@@ -141,14 +144,14 @@ int linattn_set_stage_events(void* const* events) {
 size_t linattn_workspace_bytes(int B, int H, int n, int d, int kind, int dtype) {
   if (kind != LINATTN_PHI_HEDGEHOG) return 0;
   Plan p;
-  if (!make_plan(B, H, n, d, dtype, &p)) return 0;
+  if (!make_plan(B, H, n, d, dtype, LINATTN_LAYOUT_BHND, &p)) return 0;
   return p.bytes_no_wgrads;
 }
 
 size_t linattn_workspace_bytes_wgrads(int B, int H, int n, int d, int kind, int dtype) {
   if (kind != LINATTN_PHI_HEDGEHOG) return 0;
   Plan p;
-  if (!make_plan(B, H, n, d, dtype, &p)) return 0;
+  if (!make_plan(B, H, n, d, dtype, LINATTN_LAYOUT_BHND, &p)) return 0;
   return p.total_bytes;
 }
 
@@ -157,6 +160,7 @@ int linattn_phi_create(const linattn_phi_desc* desc, int* phi_id_out) {
   if (desc->kind != LINATTN_PHI_HEDGEHOG) return LINATTN_E_PHI;
   if (desc->dtype != LINATTN_BF16 && desc->dtype != LINATTN_F32) return LINATTN_E_DTYPE;
   if (desc->H <= 0 || (desc->d != 64 && desc->d != 128)) return LINATTN_E_SHAPE;
+  if (desc->layout != LINATTN_LAYOUT_BHND && desc->layout != LINATTN_LAYOUT_BNHD) return LINATTN_E_SHAPE;
   if (!desc->wq || !desc->wk) return LINATTN_E_NULL;
   if (!aligned16(desc->wq) || !aligned16(desc->wk)) return LINATTN_E_ALIGN;
   if (desc->dwq && !aligned16(desc->dwq)) return LINATTN_E_ALIGN;

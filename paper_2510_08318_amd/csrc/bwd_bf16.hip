@@ -107,8 +107,8 @@ __device__ __forceinline__ void du_to_dx(const float (&du)[Cfg<D>::LOC], const u
 
 // The lane's half row (channels g*D/2 .. +D/2-1 of token t) as packed bf16: D/16 stores of 16 bytes.
 template <int D>
-__device__ __forceinline__ void store_half_row(uint16_t* base, size_t t, int g, const uint32_t (&xo)[D / 4]) {
-  uint4* row = reinterpret_cast<uint4*>(base + t * D + g * (D / 2));
+__device__ __forceinline__ void store_half_row(uint16_t* base, size_t row_offset, int g, const uint32_t (&xo)[D / 4]) {
+  uint4* row = reinterpret_cast<uint4*>(base + row_offset + g * (D / 2));
 #pragma unroll
   for (int i = 0; i < D / 16; ++i) {
     uint4 v; v.x = xo[4 * i]; v.y = xo[4 * i + 1]; v.z = xo[4 * i + 2]; v.w = xo[4 * i + 3];
@@ -122,7 +122,7 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
                                                    const uint16_t* __restrict__ wq, const float* __restrict__ state,
                                                    const uint4* __restrict__ gimg, uint16_t* __restrict__ dq,
                                                    float* __restrict__ partials, float* __restrict__ du_ws,
-                                                   int H, int n, int P) {
+                                                   int H, int n, int P, Rows rw) {
   using C = Cfg<D>;
   using L = ApplyLayout<D>;
   using G = GradLayout<D>;
@@ -145,9 +145,9 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
   const int g = lane / 32;
   const int mi = w / 2, ni = w % 2;
   const int bh = blockIdx.y, p = blockIdx.x, h = bh % H;
-  const uint16_t* qb = q + (size_t)bh * n * D;
-  const uint16_t* dob = dout + (size_t)bh * n * D;
-  uint16_t* dqb = dq + (size_t)bh * n * D;
+  const uint16_t* qb = q + head_base(rw, bh, H);
+  const uint16_t* dob = dout + head_base(rw, bh, H);
+  uint16_t* dqb = dq + head_base(rw, bh, H);
   const float* sb = state + (size_t)bh * (D + 1) * D;
   const uint4* gim = gimg + (size_t)bh * G::IMG;
   const int ntile = (n + kTile - 1) / kTile;
@@ -188,10 +188,10 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
     const int tc = valid ? t : (n - 1);
     uint4 xq[C::UK], dor[D / 16];
     {
-      const uint4* row = reinterpret_cast<const uint4*>(qb + (size_t)tc * D);
+      const uint4* row = reinterpret_cast<const uint4*>(qb + (size_t)tc * rw.sn);
 #pragma unroll
       for (int ks = 0; ks < C::UK; ++ks) xq[ks] = row[2 * ks + g];
-      const uint4* drow = reinterpret_cast<const uint4*>(dob + (size_t)tc * D + g * (D / 2));
+      const uint4* drow = reinterpret_cast<const uint4*>(dob + (size_t)tc * rw.sn + g * (D / 2));
 #pragma unroll
       for (int i = 0; i < D / 16; ++i) dor[i] = drow[i];
     }
@@ -279,7 +279,7 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
     uint32_t xo[D / 4];
     du_to_dx<D>(du, sWB, lane, xo);
     if (valid) {
-      store_half_row<D>(dqb, (size_t)t, g, xo);
+      store_half_row<D>(dqb, (size_t)t * rw.sn, g, xo);
       if (du_ws) {
         float4* drow = reinterpret_cast<float4*>(du_ws + ((size_t)bh * n + t) * C::HALF + g * C::LOC);
 #pragma unroll
@@ -369,7 +369,7 @@ template <int D>
 __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                                                     const uint16_t* __restrict__ wk, const float* __restrict__ dstate,
                                                     uint16_t* __restrict__ dk, uint16_t* __restrict__ dv,
-                                                    float* __restrict__ du_ws, int H, int n) {
+                                                    float* __restrict__ du_ws, int H, int n, Rows rw) {
   using C = Cfg<D>;
   using L = ApplyLayout<D>;
   using G = GradLayout<D>;
@@ -388,10 +388,10 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
   const int w = __builtin_amdgcn_readfirstlane(tid / 64);
   const int g = lane / 32;
   const int bh = blockIdx.y, h = bh % H;
-  const uint16_t* kb = k + (size_t)bh * n * D;
-  const uint16_t* vb = v + (size_t)bh * n * D;
-  uint16_t* dkb = dk + (size_t)bh * n * D;
-  uint16_t* dvb = dv + (size_t)bh * n * D;
+  const uint16_t* kb = k + head_base(rw, bh, H);
+  const uint16_t* vb = v + head_base(rw, bh, H);
+  uint16_t* dkb = dk + head_base(rw, bh, H);
+  uint16_t* dvb = dv + head_base(rw, bh, H);
   const float* ds = dstate + (size_t)bh * (D + 1) * D;
 
   build_w_image<D, NTK>(wk + (size_t)h * D * C::HALF, sWA, tid);
@@ -409,14 +409,14 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
   auto load_k = [&](int b) {
     const int t = b * 32 + (lane % 32);
     const int tc = t < n ? t : (n - 1);
-    const uint4* row = reinterpret_cast<const uint4*>(kb + (size_t)tc * D);
+    const uint4* row = reinterpret_cast<const uint4*>(kb + (size_t)tc * rw.sn);
 #pragma unroll
     for (int ks = 0; ks < C::UK; ++ks) xk[ks] = row[2 * ks + g];
   };
   auto load_v = [&](int b) {
     const int t = b * 32 + (lane % 32);
     const int tc = t < n ? t : (n - 1);
-    const uint4* vrow = reinterpret_cast<const uint4*>(vb + (size_t)tc * D + g * (D / 2));
+    const uint4* vrow = reinterpret_cast<const uint4*>(vb + (size_t)tc * rw.sn + g * (D / 2));
 #pragma unroll
     for (int i = 0; i < D / 16; ++i) vnext[i] = vrow[i];
   };
@@ -455,7 +455,7 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
       for (int mb = 0; mb < L::MB; ++mb)
 #pragma unroll
         for (int j = 0; j < 8; ++j) xo[mb * 8 + j] = pack_bf16x2(va[mb][2 * j] * inv_scale, va[mb][2 * j + 1] * inv_scale);
-      if (valid) store_half_row<D>(dvb, (size_t)t, g, xo);
+      if (valid) store_half_row<D>(dvb, (size_t)t * rw.sn, g, xo);
     }
 
     // g = v dS^T + dz, rows laid out like phi
@@ -492,7 +492,7 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
     uint32_t xo[D / 4];
     du_to_dx<D>(du, sWB, lane, xo);
     if (valid) {
-      store_half_row<D>(dkb, (size_t)t, g, xo);
+      store_half_row<D>(dkb, (size_t)t * rw.sn, g, xo);
       if (du_ws) {
         float4* drow = reinterpret_cast<float4*>(du_ws + ((size_t)bh * n + t) * C::HALF + g * C::LOC);
 #pragma unroll
@@ -509,7 +509,7 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
 // 32w .. 32w+31.  Partials per (b,h) and split are reduced in a fixed order afterwards.
 template <int D>
 __global__ __launch_bounds__(NT) void dw_mfma_kernel(const uint16_t* __restrict__ x, const float* __restrict__ du,
-                                                     float* __restrict__ part, int n, int P) {
+                                                     float* __restrict__ part, int H, int n, int P, Rows rw) {
   constexpr int HALF = D / 2;
   constexpr int RSX = D * 2, RSU = HALF * 2;
   constexpr int NB = HALF / 32;                 // 32-column blocks of du
@@ -522,7 +522,7 @@ __global__ __launch_bounds__(NT) void dw_mfma_kernel(const uint16_t* __restrict_
   const int w = __builtin_amdgcn_readfirstlane(tid / 64);
   const int g = lane / 32;
   const int bh = blockIdx.y, p = blockIdx.x;
-  const uint16_t* xb = x + (size_t)bh * n * D;
+  const uint16_t* xb = x + head_base(rw, bh, H);
   const float* ub = du + (size_t)bh * n * HALF;
   const int ntile = (n + kTile - 1) / kTile;
   const bool active = w < D / 32;
@@ -548,7 +548,7 @@ __global__ __launch_bounds__(NT) void dw_mfma_kernel(const uint16_t* __restrict_
     for (int i = 0; i < XPT; ++i) {
       const int idx = tid + NT * i, r = idx / (D / 8), c = idx % (D / 8);
       const int t = t0 + r;
-      xr[i] = t < n ? ld_nt(reinterpret_cast<const uint4*>(xb + (size_t)t * D) + c) : make_uint4(0, 0, 0, 0);
+      xr[i] = t < n ? ld_nt(reinterpret_cast<const uint4*>(xb + (size_t)t * rw.sn) + c) : make_uint4(0, 0, 0, 0);
     }
 #pragma unroll
     for (int i = 0; i < UPT; ++i) {
@@ -636,21 +636,21 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   if ((e = set_smem(bwd_q_kernel<D>, q_smem<D>())) != hipSuccess) return e;
   bwd_q_kernel<D><<<dim3(p.P, p.BH), NT, q_smem<D>(), s>>>(
       (const uint16_t*)a.q, (const uint16_t*)a.dout, (const uint16_t*)a.wq, a.state, (const uint4*)a.gimg,
-      (uint16_t*)a.dq, a.partials, a.dwq ? a.du_q : nullptr, p.H, p.n, p.P);
+      (uint16_t*)a.dq, a.partials, a.dwq ? a.du_q : nullptr, p.H, p.n, p.P, p.rows);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if ((e = launch_state_reduce(a.partials, a.dstate, p, s)) != hipSuccess) return e;
   if ((e = set_smem(bwd_k_kernel<D>, k_smem<D>())) != hipSuccess) return e;
   bwd_k_kernel<D><<<dim3(p.KP, p.BH), NTK, k_smem<D>(), s>>>(
       (const uint16_t*)a.k, (const uint16_t*)a.v, (const uint16_t*)a.wk, a.dstate,
-      (uint16_t*)a.dk, (uint16_t*)a.dv, a.dwk ? a.du_k : nullptr, p.H, p.n);
+      (uint16_t*)a.dk, (uint16_t*)a.dv, a.dwk ? a.du_k : nullptr, p.H, p.n, p.rows);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (a.dwq) {
-    dw_mfma_kernel<D><<<dim3(p.P, p.BH), NT, 0, s>>>((const uint16_t*)a.q, a.du_q, a.dw_part, p.n, p.P);
+    dw_mfma_kernel<D><<<dim3(p.P, p.BH), NT, 0, s>>>((const uint16_t*)a.q, a.du_q, a.dw_part, p.H, p.n, p.P, p.rows);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if ((e = launch_dw_reduce(a.dw_part, a.dwq, p, s)) != hipSuccess) return e;
   }
   if (a.dwk) {
-    dw_mfma_kernel<D><<<dim3(p.P, p.BH), NT, 0, s>>>((const uint16_t*)a.k, a.du_k, a.dw_part, p.n, p.P);
+    dw_mfma_kernel<D><<<dim3(p.P, p.BH), NT, 0, s>>>((const uint16_t*)a.k, a.du_k, a.dw_part, p.H, p.n, p.P, p.rows);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if ((e = launch_dw_reduce(a.dw_part, a.dwk, p, s)) != hipSuccess) return e;
   }

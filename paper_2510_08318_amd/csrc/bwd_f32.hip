@@ -33,7 +33,7 @@ __device__ __forceinline__ void jacobian_tile(const float* sG, const float* sPhi
 
 // dx[tt][c] = sum_a du[tt][a] W[c][a], stored for valid tokens; optional copy of du to the workspace.
 template <int D>
-__device__ __forceinline__ void dx_tile(const float* sDU, const float* sW, float* xout, float* du_ws,
+__device__ __forceinline__ void dx_tile(const float* sDU, const float* sW, float* xout, size_t sn, float* du_ws,
                                         int t0, int n_valid, int tid) {
   constexpr int HALF = D / 2;
   const int tt = tid / TPT, cb = tid % TPT;
@@ -43,7 +43,7 @@ __device__ __forceinline__ void dx_tile(const float* sDU, const float* sW, float
       const int c = cb + TPT * j;
       float acc = 0.f;
       for (int a = 0; a < HALF; ++a) acc = fmaf(sDU[tt * HALF + a], sW[c * HALF + a], acc);
-      xout[(size_t)(t0 + tt) * D + c] = acc;
+      xout[(size_t)(t0 + tt) * sn + c] = acc;
     }
     if (du_ws)
       for (int a = cb; a < HALF; a += TPT) du_ws[(size_t)(t0 + tt) * HALF + a] = sDU[tt * HALF + a];
@@ -54,7 +54,7 @@ template <int D>
 __global__ __launch_bounds__(NT) void bwd_q_f32_kernel(const float* __restrict__ q, const float* __restrict__ dout,
                                                        const float* __restrict__ wq, const float* __restrict__ state,
                                                        float* __restrict__ dq, float* __restrict__ partials,
-                                                       float* __restrict__ du_ws, int H, int n, int P, int chunk) {
+                                                       float* __restrict__ du_ws, int H, int n, int P, int chunk, Rows rw) {
   constexpr int HALF = D / 2;
   constexpr int BLK = D / 16;
   constexpr int SS = D + 1;                 // row stride of the state copy (bank spread)
@@ -73,9 +73,9 @@ __global__ __launch_bounds__(NT) void bwd_q_f32_kernel(const float* __restrict__
   const int tid = threadIdx.x;
   const int bh = blockIdx.y, p = blockIdx.x, h = bh % H;
   const int t_begin = p * chunk, t_end = min(n, t_begin + chunk);
-  const float* qb = q + (size_t)bh * n * D;
-  const float* dob = dout + (size_t)bh * n * D;
-  float* dqb = dq + (size_t)bh * n * D;
+  const float* qb = q + head_base(rw, bh, H);
+  const float* dob = dout + head_base(rw, bh, H);
+  float* dqb = dq + head_base(rw, bh, H);
   const float* wb = wq + (size_t)h * D * HALF;
   const float* sb = state + (size_t)bh * (D + 1) * D;
   for (int i = tid; i < D * HALF; i += NT) sW[i] = wb[i];
@@ -96,8 +96,8 @@ __global__ __launch_bounds__(NT) void bwd_q_f32_kernel(const float* __restrict__
     for (int i = tid; i < TB * D; i += NT) {
       const int r = i / D, c = i % D;
       const bool valid = r < n_valid;
-      sX[r * (D + 1) + c] = valid ? qb[(size_t)(t0 + r) * D + c] : 0.f;
-      sDO[r * D + c] = valid ? dob[(size_t)(t0 + r) * D + c] : 0.f;
+      sX[r * (D + 1) + c] = valid ? qb[(size_t)(t0 + r) * rw.sn + c] : 0.f;
+      sDO[r * D + c] = valid ? dob[(size_t)(t0 + r) * rw.sn + c] : 0.f;
     }
     __syncthreads();
     phi_tile<D, TB>(sX, sW, sPhi, tid, n_valid);     // rows >= n_valid are zero
@@ -144,7 +144,7 @@ __global__ __launch_bounds__(NT) void bwd_q_f32_kernel(const float* __restrict__
     }
     __syncthreads();
     jacobian_tile<D>(sG, sPhi, sDU, sC, tid);
-    dx_tile<D>(sDU, sW, dqb, du_ws ? du_ws + (size_t)bh * n * HALF : nullptr, t0, n_valid, tid);
+    dx_tile<D>(sDU, sW, dqb, rw.sn, du_ws ? du_ws + (size_t)bh * n * HALF : nullptr, t0, n_valid, tid);
     // dS += phi^T (dO / den), dz -= phi * (delta / den)
     for (int r = 0; r < TB; ++r) {
       float a[BLK], b[BLK];
@@ -173,7 +173,7 @@ template <int D>
 __global__ __launch_bounds__(NT) void bwd_k_f32_kernel(const float* __restrict__ k, const float* __restrict__ v,
                                                        const float* __restrict__ wk, const float* __restrict__ dstate,
                                                        float* __restrict__ dk, float* __restrict__ dv,
-                                                       float* __restrict__ du_ws, int H, int n, int chunk) {
+                                                       float* __restrict__ du_ws, int H, int n, int chunk, Rows rw) {
   constexpr int HALF = D / 2;
   constexpr int SS = D + 1;
   extern __shared__ float smem[];
@@ -189,10 +189,10 @@ __global__ __launch_bounds__(NT) void bwd_k_f32_kernel(const float* __restrict__
   const int tid = threadIdx.x;
   const int bh = blockIdx.y, p = blockIdx.x, h = bh % H;
   const int t_begin = p * chunk, t_end = min(n, t_begin + chunk);
-  const float* kb = k + (size_t)bh * n * D;
-  const float* vb = v + (size_t)bh * n * D;
-  float* dkb = dk + (size_t)bh * n * D;
-  float* dvb = dv + (size_t)bh * n * D;
+  const float* kb = k + head_base(rw, bh, H);
+  const float* vb = v + head_base(rw, bh, H);
+  float* dkb = dk + head_base(rw, bh, H);
+  float* dvb = dv + head_base(rw, bh, H);
   const float* wb = wk + (size_t)h * D * HALF;
   const float* sb = dstate + (size_t)bh * (D + 1) * D;
   for (int i = tid; i < D * HALF; i += NT) sW[i] = wb[i];
@@ -205,8 +205,8 @@ __global__ __launch_bounds__(NT) void bwd_k_f32_kernel(const float* __restrict__
     for (int i = tid; i < TB * D; i += NT) {
       const int r = i / D, c = i % D;
       const bool valid = r < n_valid;
-      sX[r * (D + 1) + c] = valid ? kb[(size_t)(t0 + r) * D + c] : 0.f;
-      sV[r * D + c] = valid ? vb[(size_t)(t0 + r) * D + c] : 0.f;
+      sX[r * (D + 1) + c] = valid ? kb[(size_t)(t0 + r) * rw.sn + c] : 0.f;
+      sV[r * D + c] = valid ? vb[(size_t)(t0 + r) * rw.sn + c] : 0.f;
     }
     __syncthreads();
     phi_tile<D, TB>(sX, sW, sPhi, tid, n_valid);
@@ -216,14 +216,14 @@ __global__ __launch_bounds__(NT) void bwd_k_f32_kernel(const float* __restrict__
       const int c = cb + TPT * j;
       float a = 0.f, gsum = 0.f;
       for (int f = 0; f < D; ++f) a = fmaf(sPhi[tt * D + f], sS[f * SS + c], a);
-      if (tt < n_valid) dvb[(size_t)(t0 + tt) * D + c] = a;
+      if (tt < n_valid) dvb[(size_t)(t0 + tt) * rw.sn + c] = a;
       const int f = c;
       for (int cc = 0; cc < D; ++cc) gsum = fmaf(sV[tt * D + cc], sS[f * SS + cc], gsum);
       sG[tt * D + f] = gsum + sS[D * SS + f];
     }
     __syncthreads();
     jacobian_tile<D>(sG, sPhi, sDU, sC, tid);
-    dx_tile<D>(sDU, sW, dkb, du_ws ? du_ws + (size_t)bh * n * HALF : nullptr, t0, n_valid, tid);
+    dx_tile<D>(sDU, sW, dkb, rw.sn, du_ws ? du_ws + (size_t)bh * n * HALF : nullptr, t0, n_valid, tid);
   }
 }
 
@@ -242,12 +242,12 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   const dim3 grid(p.P, p.BH);
   if ((e = hipFuncSetAttribute((const void*)bwd_q_f32_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)q_smem<D>())) != hipSuccess) return e;
   bwd_q_f32_kernel<D><<<grid, NT, q_smem<D>(), s>>>((const float*)a.q, (const float*)a.dout, (const float*)a.wq, a.state,
-                                                    (float*)a.dq, a.partials, a.dwq ? a.du_q : nullptr, p.H, p.n, p.P, p.chunk);
+                                                    (float*)a.dq, a.partials, a.dwq ? a.du_q : nullptr, p.H, p.n, p.P, p.chunk, p.rows);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if ((e = launch_state_reduce(a.partials, a.dstate, p, s)) != hipSuccess) return e;
   if ((e = hipFuncSetAttribute((const void*)bwd_k_f32_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)k_smem<D>())) != hipSuccess) return e;
   bwd_k_f32_kernel<D><<<grid, NT, k_smem<D>(), s>>>((const float*)a.k, (const float*)a.v, (const float*)a.wk, a.dstate,
-                                                    (float*)a.dk, (float*)a.dv, a.dwk ? a.du_k : nullptr, p.H, p.n, p.chunk);
+                                                    (float*)a.dk, (float*)a.dv, a.dwk ? a.du_k : nullptr, p.H, p.n, p.chunk, p.rows);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (a.dwq && (e = launch_dw(a.q, false, a.du_q, a.dw_part, a.dwq, p, s)) != hipSuccess) return e;
   if (a.dwk && (e = launch_dw(a.k, false, a.du_k, a.dw_part, a.dwk, p, s)) != hipSuccess) return e;

@@ -30,7 +30,7 @@ constexpr int NT3 = 768;         // 12 wavefronts, one workgroup per compute uni
 template <int D>
 __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ wq,
                                                          const float* __restrict__ state, uint16_t* __restrict__ out,
-                                                         int H, int n) {
+                                                         int H, int n, Rows rw) {
   using C = Cfg<D>;
   using L = ApplyLayout<D>;
   constexpr int NW = NT3 / 64;
@@ -47,8 +47,8 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
   const int w = __builtin_amdgcn_readfirstlane(tid / 64);
   const int g = lane / 32;
   const int bh = blockIdx.y, h = bh % H;
-  const uint16_t* qb = q + (size_t)bh * n * D;
-  uint16_t* ob = out + (size_t)bh * n * D;
+  const uint16_t* qb = q + head_base(rw, bh, H);
+  uint16_t* ob = out + head_base(rw, bh, H);
 
   {
     // The state and W~ of this (b,h) are first copied into LDS with coalesced 16-byte loads (the
@@ -79,7 +79,7 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
   auto load_block = [&](int b) {
     const int t = b * 32 + (lane % 32);
     const int tc = t < n ? t : (n - 1);
-    const uint4* row = reinterpret_cast<const uint4*>(qb + (size_t)tc * D);
+    const uint4* row = reinterpret_cast<const uint4*>(qb + (size_t)tc * rw.sn);
 #pragma unroll
     for (int ks = 0; ks < C::UK; ++ks) x[ks] = row[2 * ks + g];
   };
@@ -149,7 +149,7 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
         const uint4 v = *reinterpret_cast<const uint4*>(stage + row * RS + pc * 16);
         const int tt = b * 32 + row;
         const int lc = pc ^ swz_out<D>(row);
-        if (tt < n) reinterpret_cast<uint4*>(ob + (size_t)tt * D)[lc] = v;
+        if (tt < n) reinterpret_cast<uint4*>(ob + (size_t)tt * rw.sn)[lc] = v;
       }
     }
     __builtin_amdgcn_wave_barrier();
@@ -188,7 +188,7 @@ __device__ __forceinline__ int tr_offset_g4(int col0, int lane, int j) {
 template <int D>
 __global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                                                                 const uint16_t* __restrict__ wk, float* __restrict__ partials,
-                                                                int H, int n, int P) {
+                                                                int H, int n, int P, Rows rw) {
   using C = Cfg<D>;
   constexpr int RS = D * 2;
   constexpr int WMN = D / 64;
@@ -205,8 +205,8 @@ __global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* 
   const int role = w / 4, pw = w % 4;            // role 0: phi, role 1: acc
   const int g = lane / 32;
   const int bh = blockIdx.y, p = blockIdx.x, h = bh % H;
-  const uint16_t* kb = k + (size_t)bh * n * D;
-  const uint16_t* vb = v + (size_t)bh * n * D;
+  const uint16_t* kb = k + head_base(rw, bh, H);
+  const uint16_t* vb = v + head_base(rw, bh, H);
   const int ntile = (n + kTile - 1) / kTile;
   const int nt = (ntile - p + P - 1) / P;        // tiles of this workgroup: p, p+P, ...
 
@@ -235,7 +235,7 @@ __global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* 
     auto load_k = [&](uint4 (&x)[C::UK], int tile) {
       const int t = tile * kTile + prow;
       const int tc = t < n ? t : (n - 1);
-      const uint4* row = reinterpret_cast<const uint4*>(kb + (size_t)tc * D);
+      const uint4* row = reinterpret_cast<const uint4*>(kb + (size_t)tc * rw.sn);
 #pragma unroll
       for (int ks = 0; ks < C::UK; ++ks) x[ks] = row[2 * ks + g];
     };
@@ -320,7 +320,7 @@ __global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* 
         const int idx = atid + 256 * i;
         const int r = idx / C::CH, c = idx % C::CH;
         const int tv = (t0 + r) < n ? (t0 + r) : (n - 1);
-        vr[i] = ld_nt(reinterpret_cast<const uint4*>(vb + (size_t)tv * D) + c);
+        vr[i] = ld_nt(reinterpret_cast<const uint4*>(vb + (size_t)tv * rw.sn) + c);
       }
     };
     // one step: park V tile `it` (held in vr, refilled with the tile two steps ahead), then
@@ -417,11 +417,11 @@ hipError_t launch_state_partials_bf16(const void* k, const void* v, const void* 
   if (p.d == 128) {
     if ((e = set_smem(state_partials_ws_kernel<128>, state_ws_smem<128>())) != hipSuccess) return e;
     state_partials_ws_kernel<128><<<grid, block, state_ws_smem<128>(), s>>>(
-        (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)wk, partials, p.H, p.n, p.P);
+        (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)wk, partials, p.H, p.n, p.P, p.rows);
   } else {
     if ((e = set_smem(state_partials_ws_kernel<64>, state_ws_smem<64>())) != hipSuccess) return e;
     state_partials_ws_kernel<64><<<grid, block, state_ws_smem<64>(), s>>>(
-        (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)wk, partials, p.H, p.n, p.P);
+        (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)wk, partials, p.H, p.n, p.P, p.rows);
   }
   return hipGetLastError();
 }
@@ -433,11 +433,11 @@ hipError_t launch_apply_bf16(const void* q, const void* wq, const float* state, 
   if (p.d == 128) {
     if ((e = set_smem(apply_bf16_kernel<128>, apply_smem<128>())) != hipSuccess) return e;
     apply_bf16_kernel<128><<<grid, block, apply_smem<128>(), s>>>(
-        (const uint16_t*)q, (const uint16_t*)wq, state, (uint16_t*)out, p.H, p.n);
+        (const uint16_t*)q, (const uint16_t*)wq, state, (uint16_t*)out, p.H, p.n, p.rows);
   } else {
     if ((e = set_smem(apply_bf16_kernel<64>, apply_smem<64>())) != hipSuccess) return e;
     apply_bf16_kernel<64><<<grid, block, apply_smem<64>(), s>>>(
-        (const uint16_t*)q, (const uint16_t*)wq, state, (uint16_t*)out, p.H, p.n);
+        (const uint16_t*)q, (const uint16_t*)wq, state, (uint16_t*)out, p.H, p.n, p.rows);
   }
   return hipGetLastError();
 }

@@ -13,7 +13,7 @@ constexpr int TT = 32;        // tokens per tile
 template <int D>
 __global__ __launch_bounds__(NT) void state_partials_f32_kernel(const float* __restrict__ k, const float* __restrict__ v,
                                                                 const float* __restrict__ wk, float* __restrict__ partials,
-                                                                int H, int n, int P, int chunk) {
+                                                                int H, int n, int P, int chunk, Rows rw) {
   constexpr int HALF = D / 2;
   constexpr int BLK = D / 16;
   extern __shared__ float smem[];
@@ -26,8 +26,8 @@ __global__ __launch_bounds__(NT) void state_partials_f32_kernel(const float* __r
   const int bh = blockIdx.y, p = blockIdx.x, h = bh % H;
   const int t_begin = p * chunk;
   const int t_end = min(n, t_begin + chunk);
-  const float* kb = k + (size_t)bh * n * D;
-  const float* vb = v + (size_t)bh * n * D;
+  const float* kb = k + head_base(rw, bh, H);
+  const float* vb = v + head_base(rw, bh, H);
   const float* wb = wk + (size_t)h * D * HALF;
   for (int i = tid; i < D * HALF; i += NT) sW[i] = wb[i];
 
@@ -45,8 +45,8 @@ __global__ __launch_bounds__(NT) void state_partials_f32_kernel(const float* __r
       const int tt = i / D, c = i % D;
       const int t = t0 + tt;
       const bool valid = t < t_end;
-      sX[tt * (D + 1) + c] = valid ? kb[(size_t)t * D + c] : 0.f;
-      sV[tt * D + c] = valid ? vb[(size_t)t * D + c] : 0.f;
+      sX[tt * (D + 1) + c] = valid ? kb[(size_t)t * rw.sn + c] : 0.f;
+      sV[tt * D + c] = valid ? vb[(size_t)t * rw.sn + c] : 0.f;
     }
     __syncthreads();
     phi_tile<D, TT>(sX, sW, sPhi, tid, t_end - t0);
@@ -76,7 +76,7 @@ __global__ __launch_bounds__(NT) void state_partials_f32_kernel(const float* __r
 template <int D>
 __global__ __launch_bounds__(NT) void apply_f32_kernel(const float* __restrict__ q, const float* __restrict__ wq,
                                                        const float* __restrict__ state, float* __restrict__ out,
-                                                       int H, int n, int chunk) {
+                                                       int H, int n, int chunk, Rows rw) {
   constexpr int HALF = D / 2;
   extern __shared__ float smem[];
   float* sW = smem;
@@ -88,8 +88,8 @@ __global__ __launch_bounds__(NT) void apply_f32_kernel(const float* __restrict__
   const int bh = blockIdx.y, p = blockIdx.x, h = bh % H;
   const int t_begin = p * chunk;
   const int t_end = min(n, t_begin + chunk);
-  const float* qb = q + (size_t)bh * n * D;
-  float* ob = out + (size_t)bh * n * D;
+  const float* qb = q + head_base(rw, bh, H);
+  float* ob = out + head_base(rw, bh, H);
   const float* wb = wq + (size_t)h * D * HALF;
   const float* sb = state + (size_t)bh * (D + 1) * D;
   for (int i = tid; i < D * HALF; i += NT) sW[i] = wb[i];
@@ -101,7 +101,7 @@ __global__ __launch_bounds__(NT) void apply_f32_kernel(const float* __restrict__
     for (int i = tid; i < TT * D; i += NT) {
       const int r = i / D, c = i % D;
       const int t = t0 + r;
-      sX[r * (D + 1) + c] = (t < t_end) ? qb[(size_t)t * D + c] : 0.f;
+      sX[r * (D + 1) + c] = (t < t_end) ? qb[(size_t)t * rw.sn + c] : 0.f;
     }
     __syncthreads();
     phi_tile<D, TT>(sX, sW, sPhi, tid, t_end - t0);
@@ -119,7 +119,7 @@ __global__ __launch_bounds__(NT) void apply_f32_kernel(const float* __restrict__
     if (t < t_end) {
       const float inv = 1.0f / den;
 #pragma unroll
-      for (int j = 0; j < D / 8; ++j) ob[(size_t)t * D + cb + 8 * j] = acc[j] * inv;
+      for (int j = 0; j < D / 8; ++j) ob[(size_t)t * rw.sn + cb + 8 * j] = acc[j] * inv;
     }
   }
 }
@@ -138,11 +138,11 @@ hipError_t launch_state_partials_f32(const float* k, const float* v, const float
   if (p.d == 128) {
     e = hipFuncSetAttribute((const void*)state_partials_f32_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)state_smem<128>());
     if (e != hipSuccess) return e;
-    state_partials_f32_kernel<128><<<grid, block, state_smem<128>(), s>>>(k, v, wk, partials, p.H, p.n, p.P, p.chunk);
+    state_partials_f32_kernel<128><<<grid, block, state_smem<128>(), s>>>(k, v, wk, partials, p.H, p.n, p.P, p.chunk, p.rows);
   } else {
     e = hipFuncSetAttribute((const void*)state_partials_f32_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)state_smem<64>());
     if (e != hipSuccess) return e;
-    state_partials_f32_kernel<64><<<grid, block, state_smem<64>(), s>>>(k, v, wk, partials, p.H, p.n, p.P, p.chunk);
+    state_partials_f32_kernel<64><<<grid, block, state_smem<64>(), s>>>(k, v, wk, partials, p.H, p.n, p.P, p.chunk, p.rows);
   }
   return hipGetLastError();
 }
@@ -154,11 +154,11 @@ hipError_t launch_apply_f32(const float* q, const float* wq, const float* state,
   if (p.d == 128) {
     e = hipFuncSetAttribute((const void*)apply_f32_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)apply_smem<128>());
     if (e != hipSuccess) return e;
-    apply_f32_kernel<128><<<grid, block, apply_smem<128>(), s>>>(q, wq, state, out, p.H, p.n, p.qchunk);
+    apply_f32_kernel<128><<<grid, block, apply_smem<128>(), s>>>(q, wq, state, out, p.H, p.n, p.qchunk, p.rows);
   } else {
     e = hipFuncSetAttribute((const void*)apply_f32_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)apply_smem<64>());
     if (e != hipSuccess) return e;
-    apply_f32_kernel<64><<<grid, block, apply_smem<64>(), s>>>(q, wq, state, out, p.H, p.n, p.qchunk);
+    apply_f32_kernel<64><<<grid, block, apply_smem<64>(), s>>>(q, wq, state, out, p.H, p.n, p.qchunk, p.rows);
   }
   return hipGetLastError();
 }

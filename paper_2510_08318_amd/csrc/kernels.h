@@ -14,10 +14,22 @@ constexpr int kSlots = 256;
 // Compute units of the gfx950 parts this library targets (MI355X / MI350X).
 constexpr int kCUs = 256;
 
+// Where the rows of q, k, v, out (and dout, dq, dk, dv) sit in memory, in elements: element
+// (b, h, t, c) is at b*sb + h*sh + t*sn + c.  [B,H,n,d]: sb = H*n*d, sh = n*d, sn = d;
+// [B,n,H,d] (heads interleaved per token, what a transformer block's projection emits):
+// sb = n*H*d, sh = d, sn = H*d.
+struct Rows {
+  size_t sb, sh, sn;
+};
+__host__ __device__ inline size_t head_base(const Rows& r, int bh, int H) {
+  return (size_t)(bh / H) * r.sb + (size_t)(bh % H) * r.sh;
+}
+
 // How one call is cut into workgroups and where its scratch regions sit in the workspace.
 struct Plan {
   int B, H, n, d;
   int BH;
+  Rows rows;        // memory layout of the token tensors
   int P;            // split-n factor of the state pass (partials per (b,h))
   int chunk;        // tokens per split, a multiple of kTile (fp32 kernels; the bf16 ones deal tiles round-robin)
   int QP;           // workgroups per (b,h) of the query pass
@@ -38,7 +50,7 @@ struct Plan {
 
 // Pure host arithmetic; returns false if the shape is unsupported or overflows.
 // total_bytes includes the weight-gradient regions, bytes_no_wgrads does not.
-bool make_plan(int B, int H, int n, int d, int dtype, Plan* p);
+bool make_plan(int B, int H, int n, int d, int dtype, int layout, Plan* p);
 
 // Everything one backward call touches (device pointers; workspace regions already resolved).
 struct BwdArgs {

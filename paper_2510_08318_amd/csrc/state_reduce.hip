@@ -31,14 +31,14 @@ __global__ __launch_bounds__(256) void state_reduce_kernel(const float* __restri
 // splits and batch items.
 template <int D, typename XT>
 __global__ __launch_bounds__(256) void dw_partial_kernel(const XT* __restrict__ x, const float* __restrict__ du,
-                                                         float* __restrict__ part, int n, int P, int chunk) {
+                                                         float* __restrict__ part, int H, int n, int P, int chunk, Rows rw) {
   constexpr int HALF = D / 2;
   constexpr int TT = 32;
   __shared__ float sX[TT][D + 1];
   __shared__ float sU[TT][HALF];
   const int tid = threadIdx.x, bh = blockIdx.y, p = blockIdx.x;
   const int t_begin = p * chunk, t_end = min(n, t_begin + chunk);
-  const XT* xb = x + (size_t)bh * n * D;
+  const XT* xb = x + head_base(rw, bh, H);
   const float* ub = du + (size_t)bh * n * HALF;
   constexpr int BC = D / 16, BF = HALF / 16;        // each thread owns BC x BF entries
   const int c0 = (tid / 16) * BC, f0 = (tid % 16) * BF;
@@ -53,8 +53,8 @@ __global__ __launch_bounds__(256) void dw_partial_kernel(const XT* __restrict__ 
       const int r = i / D, c = i % D, t = t0 + r;
       float val = 0.f;
       if (t < t_end) {
-        if constexpr (sizeof(XT) == 2) val = __builtin_bit_cast(float, (uint32_t)xb[(size_t)t * D + c] << 16);
-        else val = xb[(size_t)t * D + c];
+        if constexpr (sizeof(XT) == 2) val = __builtin_bit_cast(float, (uint32_t)xb[(size_t)t * rw.sn + c] << 16);
+        else val = xb[(size_t)t * rw.sn + c];
       }
       sX[r][c] = val;
     }
@@ -107,11 +107,11 @@ hipError_t launch_dw(const void* x, bool x_is_bf16, const float* du, float* part
   const int elems = p.d * (p.d / 2);
   const dim3 grid(p.P, p.BH);
   if (p.d == 128) {
-    if (x_is_bf16) dw_partial_kernel<128, uint16_t><<<grid, 256, 0, s>>>((const uint16_t*)x, du, part, p.n, p.P, p.chunk);
-    else dw_partial_kernel<128, float><<<grid, 256, 0, s>>>((const float*)x, du, part, p.n, p.P, p.chunk);
+    if (x_is_bf16) dw_partial_kernel<128, uint16_t><<<grid, 256, 0, s>>>((const uint16_t*)x, du, part, p.H, p.n, p.P, p.chunk, p.rows);
+    else dw_partial_kernel<128, float><<<grid, 256, 0, s>>>((const float*)x, du, part, p.H, p.n, p.P, p.chunk, p.rows);
   } else {
-    if (x_is_bf16) dw_partial_kernel<64, uint16_t><<<grid, 256, 0, s>>>((const uint16_t*)x, du, part, p.n, p.P, p.chunk);
-    else dw_partial_kernel<64, float><<<grid, 256, 0, s>>>((const float*)x, du, part, p.n, p.P, p.chunk);
+    if (x_is_bf16) dw_partial_kernel<64, uint16_t><<<grid, 256, 0, s>>>((const uint16_t*)x, du, part, p.H, p.n, p.P, p.chunk, p.rows);
+    else dw_partial_kernel<64, float><<<grid, 256, 0, s>>>((const float*)x, du, part, p.H, p.n, p.P, p.chunk, p.rows);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -28,7 +28,10 @@ class Layer:
     """Buffers + descriptor of one linear-attention layer (Eq. 3 with the map of Eq. 5)."""
 
     def __init__(self, wq: torch.Tensor, wk: torch.Tensor, B: int, n: int, *, keep_state: bool = True,
-                 want_wgrads: bool = False):
+                 want_wgrads: bool = False, layout: str = "bhnd"):
+        """layout "bhnd": q, k, v, out are [B, H, n, d]; "bnhd": [B, n, H, d] (heads interleaved per token)."""
+        assert layout in ("bhnd", "bnhd")
+        self.layout = layout
         assert wq.is_cuda and wk.is_cuda and wq.dtype == wk.dtype and wq.shape == wk.shape
         self.H, self.d, half = wq.shape
         assert half * 2 == self.d
@@ -47,7 +50,8 @@ class Layer:
         self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=dev)
         assert self.workspace.data_ptr() % 256 == 0
         self.phi_id = B_.linattn_phi_create(B_.PHI_HEDGEHOG, self.dtype, self.H, self.d, self.wq, self.wk,
-                                            self.dwq, self.dwk, self.state, self.workspace, self.workspace_bytes)
+                                            self.dwq, self.dwk, self.state, self.workspace, self.workspace_bytes,
+                                            B_.LAYOUT_BNHD if layout == "bnhd" else B_.LAYOUT_BHND)
 
     def close(self):
         if self.phi_id is not None:
@@ -63,9 +67,16 @@ class Layer:
     def _stream(self):
         return torch.cuda.current_stream().cuda_stream
 
-    def forward(self, q, k, v, out=None):
-        Bq, H, n, d = q.shape
+    def _dims(self, t):
+        if self.layout == "bnhd":
+            Bq, n, H, d = t.shape
+        else:
+            Bq, H, n, d = t.shape
         assert (Bq, H, n, d) == (self.B, self.H, self.n, self.d)
+        return Bq, H, n, d
+
+    def forward(self, q, k, v, out=None):
+        Bq, H, n, d = self._dims(q)
         for t in (q, k, v):
             assert t.is_cuda and t.is_contiguous() and t.dtype == self.wq.dtype and t.shape == q.shape
         if out is None:
@@ -74,8 +85,7 @@ class Layer:
         return out
 
     def backward(self, q, k, v, dout, dq=None, dk=None, dv=None):
-        Bq, H, n, d = q.shape
-        assert (Bq, H, n, d) == (self.B, self.H, self.n, self.d)
+        Bq, H, n, d = self._dims(q)
         for t in (q, k, v, dout):
             assert t.is_cuda and t.is_contiguous() and t.dtype == self.wq.dtype and t.shape == q.shape
         dq = torch.empty_like(q) if dq is None else dq

@@ -27,7 +27,7 @@ def test_header_constants_match_binding():
     header = open(os.path.join(ROOT, "include", "linattn.h")).read()
     consts = dict((m.group(1), int(m.group(2))) for m in re.finditer(r"#define\s+LINATTN_(\w+)\s+(-?\d+)", header))
     for name in ("OK", "E_NULL", "E_SHAPE", "E_DTYPE", "E_ALIGN", "E_PHI", "E_WORKSPACE", "E_HIP", "E_STATE",
-                 "E_ALIAS", "PHI_HEDGEHOG", "BF16", "F32"):
+                 "E_ALIAS", "PHI_HEDGEHOG", "BF16", "F32", "LAYOUT_BHND", "LAYOUT_BNHD"):
         assert consts[name] == getattr(L, name), name
     for code in range(0, -10, -1):
         assert L.linattn_strerror(code) != "unknown status"
@@ -54,6 +54,10 @@ def test_phi_create_rejects_bad_descriptors():
     assert mk(dtype=5) == L.E_DTYPE
     assert mk(H=0) == L.E_SHAPE
     assert mk(d=48) == L.E_SHAPE
+    assert mk(layout=2) == L.E_SHAPE
+    assert mk(layout=-1) == L.E_SHAPE
+    pid = mk(layout=L.LAYOUT_BNHD)
+    assert pid >= 16 and L.linattn_phi_destroy(pid) == L.OK
     assert mk(wq=None) == L.E_NULL
     assert mk(wk=None) == L.E_NULL
     assert mk(wq=P + 2) == L.E_ALIGN
