@@ -87,7 +87,9 @@ def bench_bwd(args):
     from paper_2510_08318_amd import synth, torch_glue as G
     x = synth.generate(args.workload, with_dout=True)
     q, k, v, wq, wk, dout = [G.to_device(t) for t in (x.q, x.k, x.v, x.wq, x.wk, x.dout)]
-    lay = G.Layer(wq, wk, x.B, x.n, want_wgrads=not args.no_wgrads)
+    if args.layout == "bnhd":
+        q, k, v, dout = [t.permute(0, 2, 1, 3).contiguous() for t in (q, k, v, dout)]
+    lay = G.Layer(wq, wk, x.B, x.n, want_wgrads=not args.no_wgrads, layout=args.layout)
     lay.forward(q, k, v)
     dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
 
@@ -111,7 +113,8 @@ def bench_bwd(args):
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": x.dtype, "data": "synthetic",
         "config": {"workload": f"{args.workload}: B={x.B} H={x.H} n={x.n} d={x.d} {x.dtype}, backward of Eq. 3 + Eq. 5, "
-                               f"state saved by the forward, weight gradients {'off' if args.no_wgrads else 'on'}"},
+                               f"state saved by the forward, weight gradients {'off' if args.no_wgrads else 'on'}"
+                               + (", [B,n,H,d] layout" if args.layout == "bnhd" else "")},
         "roofline": {"bound": "hbm", "kernel": "linattn_bwd (all kernels of one call)", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None},
     }
@@ -129,6 +132,8 @@ def main():
     ap.add_argument("--workload", default=None, help="configuration name in paper_2510_08318_amd.synth (default C3; C5 for --pass bwd)")
     ap.add_argument("--pass", dest="which", choices=("fwd", "bwd"), default="fwd")
     ap.add_argument("--no-wgrads", action="store_true", help="--pass bwd: skip the weight gradients")
+    ap.add_argument("--layout", choices=("bhnd", "bnhd"), default="bhnd",
+                    help="memory layout of q, k, v, out: [B,H,n,d] (default, the headline configuration) or [B,n,H,d]")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy kernel (reference reading for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
@@ -147,7 +152,9 @@ def main():
 
     x = synth.generate(args.workload)
     q, k, v, wq, wk = [G.to_device(t) for t in (x.q, x.k, x.v, x.wq, x.wk)]
-    lay = G.Layer(wq, wk, x.B, x.n)
+    if args.layout == "bnhd":
+        q, k, v = [t.permute(0, 2, 1, 3).contiguous() for t in (q, k, v)]
+    lay = G.Layer(wq, wk, x.B, x.n, layout=args.layout)
     out = torch.empty_like(q)
     stream = torch.cuda.current_stream().cuda_stream
 
@@ -208,7 +215,8 @@ def main():
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": x.dtype, "data": "synthetic",
-        "config": {"workload": f"{args.workload}: B={x.B} H={x.H} n={x.n} d={x.d} {x.dtype}, Hedgehog phi, non-causal",
+        "config": {"workload": f"{args.workload}: B={x.B} H={x.H} n={x.n} d={x.d} {x.dtype}, Hedgehog phi, non-causal"
+                               + (", [B,n,H,d] layout" if args.layout == "bnhd" else ""),
                    "head_tokens_per_s": round(tokens_per_s * x.H, 1)},
         "roofline": roofline,
     }
