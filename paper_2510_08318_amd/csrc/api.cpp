@@ -52,6 +52,12 @@ bool make_plan(int B, int H, int n, int d, int dtype, int layout, Plan* p) {
   }
   r.off_dstate = off;   off = up(off + (size_t)BH * r.state_elems * sizeof(float));
   r.off_gimg = off;     off = up(off + (size_t)BH * d * d * 2);
+  r.img_state_bytes = (size_t)(d / 16) * (d / 32 + 1) * 64 * 16;
+  r.off_simg = off;     off = up(off + (size_t)BH * r.img_state_bytes);
+  r.off_dsimg = off;    off = up(off + (size_t)BH * r.img_state_bytes);
+  r.off_dgimg = off;    off = up(off + (size_t)BH * d * d * 2);
+  r.off_wimg = off;     off = up(off + (size_t)H * 4 * d * d);
+  r.off_scales = off;   off = up(off + (size_t)BH * 2 * sizeof(float));
   r.bytes_no_wgrads = off;
   r.off_dwpart = off;   off = up(off + (size_t)BH * r.P * d * (d / 2) * sizeof(float));
   r.off_du_q = off;     off = up(off + (size_t)BH * n * (d / 2) * sizeof(float));
@@ -256,6 +262,11 @@ int linattn_bwd(const void* q, const void* k, const void* v, const void* dout,
   a.partials = reinterpret_cast<float*>(ws + plan.off_partials);
   a.dstate = reinterpret_cast<float*>(ws + plan.off_dstate);
   a.gimg = ws + plan.off_gimg;
+  a.simg = ws + plan.off_simg;
+  a.dsimg = ws + plan.off_dsimg;
+  a.dgimg = ws + plan.off_dgimg;
+  a.wimg = ws + plan.off_wimg;
+  a.scales = reinterpret_cast<float*>(ws + plan.off_scales);
   a.dw_part = reinterpret_cast<float*>(ws + plan.off_dwpart);
   a.du_q = reinterpret_cast<float*>(ws + plan.off_du_q);
   a.du_k = reinterpret_cast<float*>(ws + plan.off_du_k);

@@ -37,16 +37,72 @@ __device__ __forceinline__ void unpack_bf16x8(uint4 v, float* f) {
   f[6] = __builtin_bit_cast(float, v.w << 16); f[7] = __builtin_bit_cast(float, v.w & 0xffff0000u);
 }
 
-// ---- operand image of S for g ------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(256) void bwd_prep_kernel(const float* __restrict__ state, uint4* __restrict__ gimg) {
+// ---- operand images, built once per head ---------------------------------------------------
+// The two main kernels need, per (b,h), MFMA operand images of S (resp. dS) in two index orders
+// and, per head, two images of W~.  Building them costs scattered reads; done by every workgroup
+// of a head it dominated the kernels' fixed cost, so they are built once here and the main
+// kernels copy them into LDS with coalesced 16-byte loads.
+//   grid (B*H, 8): slice blockIdx.y of the entries of (b,h); the workgroups of batch item 0 also
+//   build the W~ images of their head (WQK = true: both W~_q and W~_k images into wimg).
+template <int D, bool WQK>
+__global__ __launch_bounds__(256) void bwd_prep_kernel(const float* __restrict__ state, uint4* __restrict__ gimg,
+                                                       uint4* __restrict__ simg, float* __restrict__ scale_out,
+                                                       const uint16_t* __restrict__ wq, const uint16_t* __restrict__ wk,
+                                                       uint4* __restrict__ wimg, int H) {
+  using C = Cfg<D>;
+  using L = ApplyLayout<D>;
   using G = GradLayout<D>;
+  constexpr int SIMG = L::KS * L::MBZ * 64;
+  constexpr int WB_IMG = (C::LOC / 8) * L::MB * 64;
+  // the state (and W~) is staged in LDS with coalesced loads; the scattered reads of the image
+  // entries then hit LDS
+  extern __shared__ uint4 prep_smem[];
+  float* S = reinterpret_cast<float*>(prep_smem);                         // [(D+1)*D]
+  uint16_t* sWq = reinterpret_cast<uint16_t*>(S + (D + 1) * D);          // [D*HALF], then W~_k
+  uint16_t* sWk = sWq + D * C::HALF;
   __shared__ float red[4];
   const int bh = blockIdx.x, tid = threadIdx.x;
-  const float* S = state + (size_t)bh * (D + 1) * D;
+  {
+    const uint4* g = reinterpret_cast<const uint4*>(state + (size_t)bh * (D + 1) * D);
+    for (int i = tid; i < (D + 1) * D / 4; i += 256) reinterpret_cast<uint4*>(S)[i] = g[i];
+    if constexpr (WQK) {
+      if (bh < H) {
+        const uint4* gq = reinterpret_cast<const uint4*>(wq + (size_t)bh * D * C::HALF);
+        const uint4* gk = reinterpret_cast<const uint4*>(wk + (size_t)bh * D * C::HALF);
+        for (int i = tid; i < D * C::HALF / 8; i += 256) {
+          reinterpret_cast<uint4*>(sWq)[i] = gq[i];
+          reinterpret_cast<uint4*>(sWk)[i] = gk[i];
+        }
+      }
+    }
+  }
+  __syncthreads();
   const float scale = head_scale<D, 256>(S, red, tid);      // every block of a head computes the same value
-  for (int idx = blockIdx.y * 256 + tid; idx < G::IMG; idx += 256 * gridDim.y)
-    gimg[(size_t)bh * G::IMG + idx] = grad_image_entry<D>(S, scale, idx);
+  if (blockIdx.y == 0 && tid == 0) scale_out[2 * bh] = scale;
+  const int first = blockIdx.y * 256 + tid, step = 256 * gridDim.y;
+  for (int idx = first; idx < G::IMG; idx += step) gimg[(size_t)bh * G::IMG + idx] = grad_image_entry<D>(S, scale, idx);
+  for (int idx = first; idx < SIMG; idx += step) simg[(size_t)bh * SIMG + idx] = state_image_entry<D>(S, scale, idx);
+  if constexpr (WQK) {
+    if (bh < H) {
+      static_assert(C::W_IMG == WB_IMG, "the four W~ images have one size");
+      uint4* dst = wimg + (size_t)bh * 4 * C::W_IMG;
+      for (int idx = first; idx < C::W_IMG; idx += step) {
+        dst[idx] = w_image_entry<D>(sWq, idx);
+        dst[C::W_IMG + idx] = w_image_t_entry<D>(sWq, idx);
+        dst[2 * C::W_IMG + idx] = w_image_entry<D>(sWk, idx);
+        dst[3 * C::W_IMG + idx] = w_image_t_entry<D>(sWk, idx);
+      }
+    }
+  }
+}
+
+template <int D>
+constexpr size_t prep_smem_bytes() { return (size_t)(D + 1) * D * sizeof(float) + 2 * (size_t)D * (D / 2) * 2; }
+
+// Copy n16 16-byte entries from global memory into LDS (all threads of the workgroup).
+template <int NTHREADS>
+__device__ __forceinline__ void copy_image(const uint4* __restrict__ src, uint4* dst, int n16, int tid) {
+  for (int i = tid; i < n16; i += NTHREADS) dst[i] = src[i];
 }
 
 // Softmax Jacobian of Eq. 5 for one token spread over a lane pair: gacc holds g in the GradLayout
@@ -120,7 +176,9 @@ __device__ __forceinline__ void store_half_row(uint16_t* base, size_t row_offset
 template <int D>
 __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ dout,
                                                    const uint16_t* __restrict__ wq, const float* __restrict__ state,
-                                                   const uint4* __restrict__ gimg, uint16_t* __restrict__ dq,
+                                                   const uint4* __restrict__ gimg, const uint4* __restrict__ simg,
+                                                   const uint4* __restrict__ wimg, const float* __restrict__ scales,
+                                                   uint16_t* __restrict__ dq,
                                                    float* __restrict__ partials, float* __restrict__ du_ws,
                                                    int H, int n, int P, Rows rw) {
   using C = Cfg<D>;
@@ -152,10 +210,10 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
   const uint4* gim = gimg + (size_t)bh * G::IMG;
   const int ntile = (n + kTile - 1) / kTile;
 
-  build_w_image<D, NT>(wq + (size_t)h * D * C::HALF, sWA, tid);
-  build_w_image_t<D, NT>(wq + (size_t)h * D * C::HALF, sWB, tid);
-  const float scale = head_scale<D, NT>(sb, sRed, tid);
-  build_state_image<D, NT>(sb, sSA, scale, tid);
+  copy_image<NT>(wimg + (size_t)h * 4 * C::W_IMG, sWA, C::W_IMG, tid);
+  copy_image<NT>(wimg + (size_t)h * 4 * C::W_IMG + C::W_IMG, sWB, WB_IMG, tid);
+  copy_image<NT>(simg + (size_t)bh * SA_IMG, sSA, SA_IMG, tid);
+  const float scale = scales[2 * bh];
   for (int i = tid; i < D; i += NT) sZ[i] = sb[D * D + i];
   __syncthreads();
 
@@ -368,6 +426,8 @@ constexpr int NTK = 512;     // 8 wavefronts, one workgroup per compute unit
 template <int D>
 __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                                                     const uint16_t* __restrict__ wk, const float* __restrict__ dstate,
+                                                    const uint4* __restrict__ dsimg, const uint4* __restrict__ dgimg,
+                                                    const uint4* __restrict__ wimg, const float* __restrict__ scales,
                                                     uint16_t* __restrict__ dk, uint16_t* __restrict__ dv,
                                                     float* __restrict__ du_ws, int H, int n, Rows rw) {
   using C = Cfg<D>;
@@ -394,11 +454,11 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
   uint16_t* dvb = dv + head_base(rw, bh, H);
   const float* ds = dstate + (size_t)bh * (D + 1) * D;
 
-  build_w_image<D, NTK>(wk + (size_t)h * D * C::HALF, sWA, tid);
-  build_w_image_t<D, NTK>(wk + (size_t)h * D * C::HALF, sWB, tid);
-  const float scale = head_scale<D, NTK>(ds, sRed, tid);
-  build_state_image<D, NTK>(ds, sVA, scale, tid);
-  for (int idx = tid; idx < G::IMG; idx += NTK) sGA[idx] = grad_image_entry<D>(ds, scale, idx);
+  copy_image<NTK>(wimg + (size_t)h * 4 * C::W_IMG + 2 * C::W_IMG, sWA, C::W_IMG, tid);
+  copy_image<NTK>(wimg + (size_t)h * 4 * C::W_IMG + 3 * C::W_IMG, sWB, WB_IMG, tid);
+  copy_image<NTK>(dsimg + (size_t)bh * SA_IMG, sVA, SA_IMG, tid);
+  copy_image<NTK>(dgimg + (size_t)bh * G::IMG, sGA, G::IMG, tid);
+  const float scale = scales[2 * bh + 1];
   for (int i = tid; i < D; i += NTK) sZ[i] = ds[D * D + i];
   __syncthreads();
   const float inv_scale = __builtin_amdgcn_rcpf(scale);    // exact: power of two
@@ -631,17 +691,26 @@ hipError_t set_smem(K kernel, size_t bytes) {
 template <int D>
 hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   hipError_t e;
-  bwd_prep_kernel<D><<<dim3(p.BH, 8), 256, 0, s>>>(a.state, (uint4*)a.gimg);
+  if ((e = set_smem(bwd_prep_kernel<D, true>, prep_smem_bytes<D>())) != hipSuccess) return e;
+  if ((e = set_smem(bwd_prep_kernel<D, false>, prep_smem_bytes<D>())) != hipSuccess) return e;
+  bwd_prep_kernel<D, true><<<dim3(p.BH, 8), 256, prep_smem_bytes<D>(), s>>>(a.state, (uint4*)a.gimg, (uint4*)a.simg, a.scales,
+                                                       (const uint16_t*)a.wq, (const uint16_t*)a.wk, (uint4*)a.wimg, p.H);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if ((e = set_smem(bwd_q_kernel<D>, q_smem<D>())) != hipSuccess) return e;
   bwd_q_kernel<D><<<dim3(p.P, p.BH), NT, q_smem<D>(), s>>>(
       (const uint16_t*)a.q, (const uint16_t*)a.dout, (const uint16_t*)a.wq, a.state, (const uint4*)a.gimg,
+      (const uint4*)a.simg, (const uint4*)a.wimg, a.scales,
       (uint16_t*)a.dq, a.partials, a.dwq ? a.du_q : nullptr, p.H, p.n, p.P, p.rows);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if ((e = launch_state_reduce(a.partials, a.dstate, p, s)) != hipSuccess) return e;
+  // images of dS: the second half of the scales array, no W~ images
+  bwd_prep_kernel<D, false><<<dim3(p.BH, 8), 256, prep_smem_bytes<D>(), s>>>(a.dstate, (uint4*)a.dgimg, (uint4*)a.dsimg, a.scales + 1,
+                                                        nullptr, nullptr, nullptr, p.H);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
   if ((e = set_smem(bwd_k_kernel<D>, k_smem<D>())) != hipSuccess) return e;
   bwd_k_kernel<D><<<dim3(p.KP, p.BH), NTK, k_smem<D>(), s>>>(
       (const uint16_t*)a.k, (const uint16_t*)a.v, (const uint16_t*)a.wk, a.dstate,
+      (const uint4*)a.dsimg, (const uint4*)a.dgimg, (const uint4*)a.wimg, a.scales,
       (uint16_t*)a.dk, (uint16_t*)a.dv, a.dwk ? a.du_k : nullptr, p.H, p.n, p.rows);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (a.dwq) {

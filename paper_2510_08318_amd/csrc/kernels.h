@@ -41,6 +41,13 @@ struct Plan {
   int KP;                 // workgroups per (b,h) of the key-side backward pass
   size_t off_dstate;      // fp32 [BH][(d+1)*d]   dS, dz
   size_t off_gimg;        // fp16 [BH][d*d]       operand image of S for dL/dphi(q) (bf16 mode)
+  // operand images built once per head by the backward's prep kernels (bf16 mode)
+  size_t img_state_bytes; // bytes of one query-pass-style image of a (d+1) x d state
+  size_t off_simg;        // [BH] image of S (as in the query pass), for the recomputed o
+  size_t off_dsimg;       // [BH] the same image of dS, for dv
+  size_t off_dgimg;       // fp16 [BH][d*d]       operand image of dS for dL/dphi(k)
+  size_t off_wimg;        // [H][4][d*d bytes]    W~_q image, W~_q transposed image, then the same for W~_k
+  size_t off_scales;      // fp32 [BH][2]         power-of-two scales of the S and dS images
   size_t off_dwpart;      // fp32 [BH][P][d*d/2]  partial dW~           (weight gradients only)
   size_t off_du_q;        // fp32 [BH][n][d/2]    dL/du of the query side (weight gradients only)
   size_t off_du_k;        // fp32 [BH][n][d/2]    dL/du of the key side   (weight gradients only)
@@ -60,6 +67,8 @@ struct BwdArgs {
   float *dwq, *dwk;       // nullable
   float *partials, *dstate, *dw_part, *du_q, *du_k;
   void* gimg;
+  void *simg, *dsimg, *dgimg, *wimg;
+  float* scales;
 };
 
 // ---- forward launchers (enqueue only) ---------------------------------------------------

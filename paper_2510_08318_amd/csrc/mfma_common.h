@@ -60,21 +60,23 @@ __device__ __forceinline__ void pair32(float x, float& lo, float& hi) {
 
 // W~ [D][D/2] bf16 (one head) -> LDS image of the A operands of U^T = W~^T X^T:
 // entry (ks, mb, lane=(m,g)) holds W~[16ks + 8g + e][owned_row<HALF>(mb, m)], e = 0..7.
+template <int D>
+__device__ __forceinline__ uint4 w_image_entry(const uint16_t* __restrict__ w, int idx) {
+  using C = Cfg<D>;
+  const int lane = idx % 64, mb = (idx / 64) % C::UM, ks = idx / (64 * C::UM);
+  const int m = lane % 32, g = lane / 32;
+  const int uf = owned_row<C::HALF>(mb, m);
+  uint32_t x[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) x[e] = w[(16 * ks + 8 * g + e) * C::HALF + uf];
+  uint4 r;
+  r.x = x[0] | (x[1] << 16); r.y = x[2] | (x[3] << 16);
+  r.z = x[4] | (x[5] << 16); r.w = x[6] | (x[7] << 16);
+  return r;
+}
 template <int D, int NTHREADS>
 __device__ __forceinline__ void build_w_image(const uint16_t* __restrict__ w, uint4* sWA, int tid) {
-  using C = Cfg<D>;
-  for (int idx = tid; idx < C::W_IMG; idx += NTHREADS) {
-    const int lane = idx % 64, mb = (idx / 64) % C::UM, ks = idx / (64 * C::UM);
-    const int m = lane % 32, g = lane / 32;
-    const int uf = owned_row<C::HALF>(mb, m);
-    uint32_t x[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) x[e] = w[(16 * ks + 8 * g + e) * C::HALF + uf];
-    uint4 r;
-    r.x = x[0] | (x[1] << 16); r.y = x[2] | (x[3] << 16);
-    r.z = x[4] | (x[5] << 16); r.w = x[6] | (x[7] << 16);
-    sWA[idx] = r;
-  }
+  for (int idx = tid; idx < Cfg<D>::W_IMG; idx += NTHREADS) sWA[idx] = w_image_entry<D>(w, idx);
 }
 
 // First half of Eq. 5 for the 32 tokens of one wavefront: U^T = W~^T X^T on bf16 MFMA.
@@ -253,24 +255,27 @@ __device__ __forceinline__ float head_scale(const float* __restrict__ S, float* 
 // (contraction over the features of phi): entry (ks, mb, lane=(m,g)) holds
 // scale * S[feature(ks,g,e)][channel(mb,m)], e = 0..7; the extra row block mb = MB holds
 // scale * z[feature] in rows 0 and 4 (one per lane group) and zeros elsewhere.
+template <int D>
+__device__ __forceinline__ uint4 state_image_entry(const float* __restrict__ S, float scale, int idx) {
+  using L = ApplyLayout<D>;
+  const int lane = idx % 64, mb = (idx / 64) % L::MBZ, ks = idx / (64 * L::MBZ);
+  const int m = lane % 32, g = lane / 32;
+  float x[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int f = L::feature(ks, g, e);
+    if (mb < L::MB) x[e] = scale * S[f * D + L::channel(mb, m)];
+    else x[e] = (m == 0 || m == 4) ? scale * S[D * D + f] : 0.f;
+  }
+  uint4 r;
+  r.x = pack_f16x2(x[0], x[1]); r.y = pack_f16x2(x[2], x[3]);
+  r.z = pack_f16x2(x[4], x[5]); r.w = pack_f16x2(x[6], x[7]);
+  return r;
+}
 template <int D, int NTHREADS>
 __device__ __forceinline__ void build_state_image(const float* __restrict__ S, uint4* sSA, float scale, int tid) {
   using L = ApplyLayout<D>;
-  for (int idx = tid; idx < L::KS * L::MBZ * 64; idx += NTHREADS) {
-    const int lane = idx % 64, mb = (idx / 64) % L::MBZ, ks = idx / (64 * L::MBZ);
-    const int m = lane % 32, g = lane / 32;
-    float x[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int f = L::feature(ks, g, e);
-      if (mb < L::MB) x[e] = scale * S[f * D + L::channel(mb, m)];
-      else x[e] = (m == 0 || m == 4) ? scale * S[D * D + f] : 0.f;
-    }
-    uint4 r;
-    r.x = pack_f16x2(x[0], x[1]); r.y = pack_f16x2(x[2], x[3]);
-    r.z = pack_f16x2(x[4], x[5]); r.w = pack_f16x2(x[6], x[7]);
-    sSA[idx] = r;
-  }
+  for (int idx = tid; idx < L::KS * L::MBZ * 64; idx += NTHREADS) sSA[idx] = state_image_entry<D>(S, scale, idx);
 }
 
 // Index maps of G^T = S Y^T (contraction over the d channels; rows = features of phi), used by the
@@ -308,23 +313,25 @@ __device__ __forceinline__ uint4 grad_image_entry(const float* __restrict__ S, f
 // W~ [D][D/2] bf16 (one head) -> LDS image (fp16, exact) of the A operands of dX^T = W~ dU^T
 // (contraction over the d/2 pre-softmax features): entry (ks, mb, lane=(m,g)) holds
 // W~[channel(mb,m)][g*LOC + 8ks + e], e = 0..7; ks < LOC/8, mb < D/32.
-template <int D, int NTHREADS>
-__device__ __forceinline__ void build_w_image_t(const uint16_t* __restrict__ w, uint4* sWB, int tid) {
+template <int D>
+__device__ __forceinline__ uint4 w_image_t_entry(const uint16_t* __restrict__ w, int idx) {
   using C = Cfg<D>;
   using L = ApplyLayout<D>;
-  constexpr int DK = C::LOC / 8;
-  for (int idx = tid; idx < DK * L::MB * 64; idx += NTHREADS) {
-    const int lane = idx % 64, mb = (idx / 64) % L::MB, ks = idx / (64 * L::MB);
-    const int m = lane % 32, g = lane / 32;
-    const uint16_t* row = w + L::channel(mb, m) * C::HALF + g * C::LOC + 8 * ks;
-    float x[8];
+  const int lane = idx % 64, mb = (idx / 64) % L::MB, ks = idx / (64 * L::MB);
+  const int m = lane % 32, g = lane / 32;
+  const uint16_t* row = w + L::channel(mb, m) * C::HALF + g * C::LOC + 8 * ks;
+  float x[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) x[e] = __builtin_bit_cast(float, (uint32_t)row[e] << 16);
-    uint4 r;
-    r.x = pack_f16x2(x[0], x[1]); r.y = pack_f16x2(x[2], x[3]);
-    r.z = pack_f16x2(x[4], x[5]); r.w = pack_f16x2(x[6], x[7]);
-    sWB[idx] = r;
-  }
+  for (int e = 0; e < 8; ++e) x[e] = __builtin_bit_cast(float, (uint32_t)row[e] << 16);
+  uint4 r;
+  r.x = pack_f16x2(x[0], x[1]); r.y = pack_f16x2(x[2], x[3]);
+  r.z = pack_f16x2(x[4], x[5]); r.w = pack_f16x2(x[6], x[7]);
+  return r;
+}
+template <int D, int NTHREADS>
+__device__ __forceinline__ void build_w_image_t(const uint16_t* __restrict__ w, uint4* sWB, int tid) {
+  constexpr int N = (Cfg<D>::LOC / 8) * ApplyLayout<D>::MB * 64;
+  for (int idx = tid; idx < N; idx += NTHREADS) sWB[idx] = w_image_t_entry<D>(w, idx);
 }
 
 template <int D>
