@@ -73,6 +73,9 @@ CONFIGS: Dict[str, Config] = {
     "C4": Config("C4", 2, 40, 75600, 128, "bf16", (1004, 1005), True, 0.001),
     # post-training step (forward + backward) at the 1.3B shape
     "C5": Config("C5", 1, 12, 32760, 128, "bf16", (1006,), True, 0.0, True),
+    # second architecture (the paper's App. on CogVideoX-2B: 30 heads of width 64; 49 frames at
+    # 480 x 720 -> 13 x 30 x 45 latent patches): exercises the d = 64 kernels at a real shape
+    "C6": Config("C6", 1, 30, 17550, 64, "bf16", (1007,), True, 0.0),
 }
 
 

@@ -167,3 +167,8 @@ def test_config3_wan_14b_720p_sampled():
 
 def test_config4_cfg_batch_sampled():
     _sampled_full_size("C4", [(0, 3), (1, 0), (1, 39)])
+
+
+def test_cogvideox_2b_shape_sampled():
+    """Second architecture (30 heads of width 64, 17550 tokens): the d = 64 kernels at a real shape."""
+    _sampled_full_size("C6", [(0, 0), (0, 13), (0, 29)])
