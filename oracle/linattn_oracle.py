@@ -28,6 +28,13 @@ Readings where the paper is silent: d is the head width and each head has its
 own W~; no bias, temperature, 1/sqrt(d) or epsilon (every entry of phi is
 positive, so the denominator is positive); the sum runs over all n tokens.
 
+Mixed attention of the selective-transfer stage (Sec. 4.1, Eq. 6): the layer's output is
+r' * s + (1 - r') * o, where o is the linear attention above, s is the softmax
+attention of the same q, k, v -- an INPUT here, it is never computed -- and
+r' = clip(r, 0, 1) (footnote to Eq. 6), one learnable scalar r per layer.  Reading of
+the clip's derivative: 1 for 0 <= r <= 1, 0 outside; the closed ends are needed
+because the paper initialises every r to exactly 1 and trains it from there.
+
 Pins: tests/test_oracle_pins.py (brute force, closed forms, invariants,
 scipy's softmax, finite differences).  No function here is unpinned.
 """
@@ -38,6 +45,7 @@ import numpy as np
 __all__ = [
     "to_f64", "phi", "state", "fwd", "fwd_bruteforce", "bwd", "fwd_bh", "bwd_bh",
     "state_bh", "finite_difference", "loss", "err_metric",
+    "clip01", "blend_fwd_bh", "blend_bwd_bh",
 ]
 
 
@@ -211,3 +219,31 @@ def err_metric(got: np.ndarray, ref: np.ndarray):
         m = float(np.abs(r2[s]).max())
         worst_norm = max(worst_norm, float(diff.max()) / (m if m > 0 else 1.0))
     return worst, worst_norm
+
+
+# ---- mixed attention (Eq. 6) -------------------------------------------------------------
+
+def clip01(r: float) -> float:
+    """r clipped into [0, 1] (footnote to Eq. 6)."""
+    return min(max(float(r), 0.0), 1.0)
+
+
+def blend_fwd_bh(q, k, v, wq, wk, s, r: float) -> np.ndarray:
+    """Eq. 6 with the softmax branch given: clip(r) * s + (1 - clip(r)) * linear attention."""
+    rb = clip01(r)
+    return rb * to_f64(s) + (1.0 - rb) * fwd_bh(q, k, v, wq, wk)
+
+
+def blend_bwd_bh(q, k, v, wq, wk, s, r: float, dout):
+    """Gradients of L = sum(dout * blend_fwd_bh(...)): dq, dk, dv, dWq, dWk, ds, dr.
+
+    The linear branch receives (1 - clip(r)) * dout; the softmax branch output s receives
+    clip(r) * dout; dr = sum(dout * (s - o)) inside the clip's range, 0 outside."""
+    rb = clip01(r)
+    do = to_f64(dout)
+    dq, dk, dv, dwq, dwk = bwd_bh(q, k, v, wq, wk, (1.0 - rb) * do)
+    o = fwd_bh(q, k, v, wq, wk)
+    inside = 0.0 <= float(r) <= 1.0
+    dr = float(np.sum(do * (to_f64(s) - o))) if inside else 0.0
+    return dq, dk, dv, dwq, dwk, rb * do, dr
+

@@ -292,3 +292,89 @@ def test_planted_gradient_mistakes_are_caught_by_fd():
     idx = np.unravel_index(np.abs(dk_bad - dk).argmax(), dk.shape)
     fd = O.finite_difference(q, k, v, Wq, Wk, dout, "k", tuple(int(i) for i in idx))
     assert abs(fd - dk[idx]) < 1e-6 * max(1e-3, abs(dk[idx])) and abs(fd - dk_bad[idx]) > 1e-4 * abs(dk[idx])
+
+
+# ---- mixed attention (Eq. 6) -------------------------------------------------------------
+
+def _blend_problem(seed=5, B=1, H=2, n=23, d=8):
+    g = np.random.default_rng(seed)
+    mk = lambda: g.standard_normal((B, H, n, d)) / np.sqrt(d)
+    q, k, v, s, dout = mk(), mk(), mk(), mk(), mk()
+    wq, wk = g.standard_normal((H, d, d // 2)), g.standard_normal((H, d, d // 2))
+    return q, k, v, wq, wk, s, dout
+
+
+def _blend_loss(q, k, v, wq, wk, s, r, dout):
+    return float(np.sum(dout * O.blend_fwd_bh(q, k, v, wq, wk, s, r)))
+
+
+def test_blend_is_eq6_written_out():
+    """Eq. 6 term by term, with the quadratic-cost forms of both branches on a tiny problem: the
+    second term is the left-hand side of Eq. 3, the first is handed in as s."""
+    q, k, v, wq, wk, s, _ = _blend_problem()
+    r = 0.37
+    got = O.blend_fwd_bh(q, k, v, wq, wk, s, r)
+    for h in range(q.shape[1]):
+        fq, fk = O.phi(q[0, h], wq[h]), O.phi(k[0, h], wk[h])
+        w = fq @ fk.T
+        lin = (w @ v[0, h]) / w.sum(axis=1, keepdims=True)
+        np.testing.assert_allclose(got[0, h], r * s[0, h] + (1 - r) * lin, rtol=1e-12, atol=1e-14)
+
+
+def test_blend_clipping_and_end_points():
+    q, k, v, wq, wk, s, dout = _blend_problem()
+    lin = O.fwd_bh(q, k, v, wq, wk)
+    np.testing.assert_array_equal(O.blend_fwd_bh(q, k, v, wq, wk, s, 0.0), lin)
+    np.testing.assert_array_equal(O.blend_fwd_bh(q, k, v, wq, wk, s, 1.0), s)
+    np.testing.assert_array_equal(O.blend_fwd_bh(q, k, v, wq, wk, s, 1.7), s)       # clipped (footnote to Eq. 6)
+    np.testing.assert_array_equal(O.blend_fwd_bh(q, k, v, wq, wk, s, -0.2), lin)
+    # r = 1 (the paper's initial value): the linear branch gets no gradient, s gets all of it, and r
+    # still moves (closed end of the clip)
+    dq, dk, dv, dwq, dwk, ds, dr = O.blend_bwd_bh(q, k, v, wq, wk, s, 1.0, dout)
+    assert not dq.any() and not dk.any() and not dv.any() and not dwq.any() and not dwk.any()
+    np.testing.assert_array_equal(ds, dout)
+    assert dr == pytest.approx(float(np.sum(dout * (s - lin))), rel=1e-12)
+    assert O.blend_bwd_bh(q, k, v, wq, wk, s, 1.7, dout)[6] == 0.0
+    assert O.blend_bwd_bh(q, k, v, wq, wk, s, -0.2, dout)[6] == 0.0
+    # r = 0: the plain backward
+    ref = O.bwd_bh(q, k, v, wq, wk, dout)
+    got = O.blend_bwd_bh(q, k, v, wq, wk, s, 0.0, dout)
+    for a, b in zip(got[:5], ref):
+        np.testing.assert_array_equal(a, b)
+    assert not got[5].any()
+
+
+def test_blend_gradients_match_finite_differences():
+    q, k, v, wq, wk, s, dout = _blend_problem(seed=9)
+    r = 0.3
+    dq, dk, dv, dwq, dwk, ds, dr = O.blend_bwd_bh(q, k, v, wq, wk, s, r, dout)
+    h = 1e-6
+    fd_r = (_blend_loss(q, k, v, wq, wk, s, r + h, dout) - _blend_loss(q, k, v, wq, wk, s, r - h, dout)) / (2 * h)
+    assert dr == pytest.approx(fd_r, rel=1e-7)
+    g = np.random.default_rng(3)
+    args = {"q": q, "k": k, "v": v, "wq": wq, "wk": wk, "s": s}
+    grads = {"q": dq, "k": dk, "v": dv, "wq": dwq, "wk": dwk, "s": ds}
+    for name, G in grads.items():
+        for _ in range(4):
+            idx = tuple(int(g.integers(n_)) for n_ in G.shape)
+            plus = {k_: a.copy() for k_, a in args.items()}
+            minus = {k_: a.copy() for k_, a in args.items()}
+            step = 1e-6 * max(1.0, abs(args[name][idx]))
+            plus[name][idx] += step
+            minus[name][idx] -= step
+            fd = (_blend_loss(plus["q"], plus["k"], plus["v"], plus["wq"], plus["wk"], plus["s"], r, dout)
+                  - _blend_loss(minus["q"], minus["k"], minus["v"], minus["wq"], minus["wk"], minus["s"], r, dout)) / (2 * step)
+            assert abs(fd - G[idx]) <= 1e-6 * max(abs(G[idx]), 1e-2 * np.abs(G).max()) + 1e-12, (name, idx, fd, G[idx])
+
+
+def test_blend_planted_mistakes_are_caught():
+    """dr with the branches swapped, or the linear branch not scaled by 1 - r, fail the FD pin."""
+    q, k, v, wq, wk, s, dout = _blend_problem(seed=9)
+    r, h = 0.3, 1e-6
+    fd_r = (_blend_loss(q, k, v, wq, wk, s, r + h, dout) - _blend_loss(q, k, v, wq, wk, s, r - h, dout)) / (2 * h)
+    lin = O.fwd_bh(q, k, v, wq, wk)
+    wrong_dr = float(np.sum(dout * (lin - s)))
+    assert abs(wrong_dr - fd_r) > 1e-3 * abs(fd_r)
+    unscaled = O.bwd_bh(q, k, v, wq, wk, dout)[0]
+    right = O.blend_bwd_bh(q, k, v, wq, wk, s, r, dout)[0]
+    assert np.abs(unscaled - right).max() > 0.1 * np.abs(right).max()
