@@ -90,6 +90,9 @@ def bench_bwd(args):
     if args.layout == "bnhd":
         q, k, v, dout = [t.permute(0, 2, 1, 3).contiguous() for t in (q, k, v, dout)]
     lay = G.Layer(wq, wk, x.B, x.n, want_wgrads=not args.no_wgrads, layout=args.layout)
+    if args.blend:
+        lay.set_blend((torch.randn(q.shape, device="cuda") * 0.1).to(q.dtype), torch.tensor([0.5], device="cuda"),
+                      torch.zeros(1, device="cuda"))
     lay.forward(q, k, v)
     dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
 
@@ -114,7 +117,8 @@ def bench_bwd(args):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": x.dtype, "data": "synthetic",
         "config": {"workload": f"{args.workload}: B={x.B} H={x.H} n={x.n} d={x.d} {x.dtype}, backward of Eq. 3 + Eq. 5, "
                                f"state saved by the forward, weight gradients {'off' if args.no_wgrads else 'on'}"
-                               + (", [B,n,H,d] layout" if args.layout == "bnhd" else "")},
+                               + (", [B,n,H,d] layout" if args.layout == "bnhd" else "")
+                               + (", mixed attention (Eq. 6, r = 0.5) with dL/dr" if args.blend else "")},
         "roofline": {"bound": "hbm", "kernel": "linattn_bwd (all kernels of one call)", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None},
     }
@@ -132,6 +136,8 @@ def main():
     ap.add_argument("--workload", default=None, help="configuration name in paper_2510_08318_amd.synth (default C3; C5 for --pass bwd)")
     ap.add_argument("--pass", dest="which", choices=("fwd", "bwd"), default="fwd")
     ap.add_argument("--no-wgrads", action="store_true", help="--pass bwd: skip the weight gradients")
+    ap.add_argument("--blend", action="store_true",
+                    help="mixed attention of Eq. 6: also read a softmax-branch tensor s and blend it with r = 0.5")
     ap.add_argument("--layout", choices=("bhnd", "bnhd"), default="bhnd",
                     help="memory layout of q, k, v, out: [B,H,n,d] (default, the headline configuration) or [B,n,H,d]")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -155,6 +161,8 @@ def main():
     if args.layout == "bnhd":
         q, k, v = [t.permute(0, 2, 1, 3).contiguous() for t in (q, k, v)]
     lay = G.Layer(wq, wk, x.B, x.n, layout=args.layout)
+    if args.blend:
+        lay.set_blend((torch.randn(q.shape, device="cuda") * 0.1).to(q.dtype), torch.tensor([0.5], device="cuda"))
     out = torch.empty_like(q)
     stream = torch.cuda.current_stream().cuda_stream
 
@@ -216,7 +224,8 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": x.dtype, "data": "synthetic",
         "config": {"workload": f"{args.workload}: B={x.B} H={x.H} n={x.n} d={x.d} {x.dtype}, Hedgehog phi, non-causal"
-                               + (", [B,n,H,d] layout" if args.layout == "bnhd" else ""),
+                               + (", [B,n,H,d] layout" if args.layout == "bnhd" else "")
+                               + (", mixed with a softmax-branch input (Eq. 6, r = 0.5)" if args.blend else ""),
                    "head_tokens_per_s": round(tokens_per_s * x.H, 1)},
         "roofline": roofline,
     }

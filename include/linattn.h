@@ -80,6 +80,19 @@ typedef struct linattn_phi_desc {
   size_t workspace_bytes;
   int layout;             /* LINATTN_LAYOUT_BHND (0) or LINATTN_LAYOUT_BNHD; the state, dW~ and the
                              workspace do not depend on it */
+  /* Mixed attention of the selective-transfer stage (Sec. 4.1, Eq. 6), active when blend_in and
+   * blend_r are both non-NULL (set only one: E_NULL):
+   *     out = r' * blend_in + (1 - r') * (Eq. 3),   r' = clip(*blend_r, 0, 1)  (footnote to Eq. 6)
+   * blend_in is the softmax-attention output of the same layer, computed by the caller: device,
+   * dtype and layout of out, must not overlap out.  blend_r: device, one fp32, read by the
+   * kernels (no host copy).  linattn_bwd then treats dout as the gradient of the blended output:
+   * dq, dk, dv, dW~ receive (1 - r') times the gradients of Eq. 3, and blend_dr (optional, device,
+   * one fp32) is OVERWRITTEN with dL/dr = sum(dout * (blend_in - o)) for 0 <= r <= 1 and 0 outside
+   * (the closed ends let r move from its initial value 1).  The gradient with respect to blend_in
+   * is r' * dout, an elementwise product left to the caller. */
+  const void *blend_in;
+  const float *blend_r;
+  float *blend_dr;
 } linattn_phi_desc;
 
 /* Register a descriptor; *phi_id_out receives a handle >= 16.  Host-only, no HIP call.
@@ -89,6 +102,11 @@ int linattn_phi_create(const linattn_phi_desc* desc, int* phi_id_out);
 
 /* Forget a handle.  E_PHI if it is not live.  Buffers stay the caller's. */
 int linattn_phi_destroy(int phi_id);
+
+/* Replace the three mixed-attention pointers of a live handle (blend_in changes every step).
+ * All NULL switches the blend off.  Host-only.  Errors: E_PHI, E_NULL (exactly one of blend_in,
+ * blend_r given, or blend_dr without them), E_ALIGN (blend_in not 16-byte aligned). */
+int linattn_phi_set_blend(int phi_id, const void* blend_in, const float* blend_r, float* blend_dr);
 
 /* Scratch bytes linattn_fwd, and linattn_bwd without weight gradients (dwq == dwk == NULL), need
  * for this problem (pure function of its arguments, no HIP call).  Returns 0 for an invalid

@@ -19,7 +19,7 @@ BF16, F32 = 1, 2
 LAYOUT_BHND, LAYOUT_BNHD = 0, 1
 
 EXPORTS = ("linattn_phi_create", "linattn_phi_destroy", "linattn_workspace_bytes", "linattn_workspace_bytes_wgrads",
-           "linattn_fwd", "linattn_bwd", "linattn_strerror", "linattn_set_stage_events")
+           "linattn_fwd", "linattn_bwd", "linattn_strerror", "linattn_set_stage_events", "linattn_phi_set_blend")
 
 
 class PhiDesc(ctypes.Structure):
@@ -30,6 +30,7 @@ class PhiDesc(ctypes.Structure):
         ("state", ctypes.c_void_p),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
         ("layout", ctypes.c_int),
+        ("blend_in", ctypes.c_void_p), ("blend_r", ctypes.c_void_p), ("blend_dr", ctypes.c_void_p),
     ]
 
 
@@ -53,6 +54,8 @@ def lib() -> ctypes.CDLL:
         L.linattn_phi_create.argtypes = [ctypes.POINTER(PhiDesc), ctypes.POINTER(ci)]
         L.linattn_phi_create.restype = ci
         L.linattn_phi_destroy.argtypes = [ci]
+        L.linattn_phi_set_blend.argtypes = [ci, vp, vp, vp]
+        L.linattn_phi_set_blend.restype = ci
         L.linattn_phi_destroy.restype = ci
         L.linattn_workspace_bytes.argtypes = [ci] * 6
         L.linattn_workspace_bytes.restype = ctypes.c_size_t
@@ -92,9 +95,11 @@ def linattn_workspace_bytes_wgrads(B: int, H: int, n: int, d: int, kind: int = P
 
 
 def linattn_phi_create(kind, dtype, H, d, wq, wk, dwq=None, dwk=None, state=None,
-                       workspace=None, workspace_bytes: int = 0, layout: int = 0, *, check: bool = True) -> int:
+                       workspace=None, workspace_bytes: int = 0, layout: int = 0,
+                       blend_in=None, blend_r=None, blend_dr=None, *, check: bool = True) -> int:
     desc = PhiDesc(int(kind), int(dtype), int(H), int(d), _ptr(wq), _ptr(wk), _ptr(dwq), _ptr(dwk),
-                   _ptr(state), _ptr(workspace), int(workspace_bytes), int(layout))
+                   _ptr(state), _ptr(workspace), int(workspace_bytes), int(layout),
+                   _ptr(blend_in), _ptr(blend_r), _ptr(blend_dr))
     out = ctypes.c_int(-1)
     st = lib().linattn_phi_create(ctypes.byref(desc), ctypes.byref(out))
     if st != OK:
@@ -102,6 +107,13 @@ def linattn_phi_create(kind, dtype, H, d, wq, wk, dwq=None, dwk=None, state=None
             raise LinattnError(st, "linattn_phi_create")
         return st
     return out.value
+
+
+def linattn_phi_set_blend(phi_id: int, blend_in=None, blend_r=None, blend_dr=None, *, check: bool = True) -> int:
+    st = lib().linattn_phi_set_blend(int(phi_id), _ptr(blend_in), _ptr(blend_r), _ptr(blend_dr))
+    if st != OK and check:
+        raise LinattnError(st, "linattn_phi_set_blend")
+    return st
 
 
 def linattn_phi_destroy(phi_id: int, *, check: bool = True) -> int:

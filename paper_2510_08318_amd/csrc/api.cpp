@@ -58,6 +58,7 @@ bool make_plan(int B, int H, int n, int d, int dtype, int layout, Plan* p) {
   r.off_dgimg = off;    off = up(off + (size_t)BH * d * d * 2);
   r.off_wimg = off;     off = up(off + (size_t)H * 4 * d * d);
   r.off_scales = off;   off = up(off + (size_t)BH * 2 * sizeof(float));
+  r.off_drpart = off;   off = up(off + (size_t)BH * r.P * sizeof(float));
   r.bytes_no_wgrads = off;
   r.off_dwpart = off;   off = up(off + (size_t)BH * r.P * d * (d / 2) * sizeof(float));
   r.off_du_q = off;     off = up(off + (size_t)BH * n * (d / 2) * sizeof(float));
@@ -87,6 +88,13 @@ inline void mark(int i, hipStream_t s) {
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_blend(const void* blend_in, const float* blend_r, const float* blend_dr) {
+  if ((blend_in == nullptr) != (blend_r == nullptr)) return LINATTN_E_NULL;
+  if (blend_dr && !blend_in) return LINATTN_E_NULL;
+  if (blend_in && (reinterpret_cast<uintptr_t>(blend_in) & 15u)) return LINATTN_E_ALIGN;
+  return LINATTN_OK;
+}
 
 bool overlaps(const void* a, const void* b, size_t bytes) {
   const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
@@ -173,6 +181,7 @@ int linattn_phi_create(const linattn_phi_desc* desc, int* phi_id_out) {
   if (desc->dwk && !aligned16(desc->dwk)) return LINATTN_E_ALIGN;
   if (desc->state && !aligned16(desc->state)) return LINATTN_E_ALIGN;
   if (desc->workspace && (reinterpret_cast<uintptr_t>(desc->workspace) & 255u)) return LINATTN_E_ALIGN;
+  if (int st = check_blend(desc->blend_in, desc->blend_r, desc->blend_dr)) return st;
   std::lock_guard<std::mutex> lk(g_mu);
   for (int i = 0; i < kMaxDesc; ++i) {
     if (!g_slots[i].live) {
@@ -183,6 +192,17 @@ int linattn_phi_create(const linattn_phi_desc* desc, int* phi_id_out) {
     }
   }
   return LINATTN_E_PHI;
+}
+
+int linattn_phi_set_blend(int phi_id, const void* blend_in, const float* blend_r, float* blend_dr) {
+  if (int st = check_blend(blend_in, blend_r, blend_dr)) return st;
+  std::lock_guard<std::mutex> lk(g_mu);
+  const int i = phi_id - kFirstId;
+  if (i < 0 || i >= kMaxDesc || !g_slots[i].live) return LINATTN_E_PHI;
+  g_slots[i].d.blend_in = blend_in;
+  g_slots[i].d.blend_r = blend_r;
+  g_slots[i].d.blend_dr = blend_dr;
+  return LINATTN_OK;
 }
 
 int linattn_phi_destroy(int phi_id) {
@@ -203,6 +223,7 @@ int linattn_fwd(const void* q, const void* k, const void* v, void* out,
   const size_t esz = desc.dtype == LINATTN_BF16 ? 2 : 4;
   const size_t bytes = (size_t)plan.BH * n * d * esz;
   if (overlaps(out, q, bytes) || overlaps(out, k, bytes) || overlaps(out, v, bytes)) return LINATTN_E_ALIAS;
+  if (desc.blend_in && overlaps(out, desc.blend_in, bytes)) return LINATTN_E_ALIAS;
 
   hipStream_t s = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(desc.workspace);
@@ -217,7 +238,8 @@ int linattn_fwd(const void* q, const void* k, const void* v, void* out,
     e = launch_state_reduce(partials, state, plan, s);
     if (e != hipSuccess) return LINATTN_E_HIP;
     mark(2, s);
-    e = launch_apply_f32((const float*)q, (const float*)desc.wq, state, (float*)out, plan, s);
+    e = launch_apply_f32((const float*)q, (const float*)desc.wq, state, (float*)out,
+                         (const float*)desc.blend_in, desc.blend_r, plan, s);
     if (e != hipSuccess) return LINATTN_E_HIP;
   } else {
     e = launch_state_partials_bf16(k, v, desc.wk, partials, plan, s);
@@ -226,7 +248,7 @@ int linattn_fwd(const void* q, const void* k, const void* v, void* out,
     e = launch_state_reduce(partials, state, plan, s);
     if (e != hipSuccess) return LINATTN_E_HIP;
     mark(2, s);
-    e = launch_apply_bf16(q, desc.wq, state, out, plan, s);
+    e = launch_apply_bf16(q, desc.wq, state, out, desc.blend_in, desc.blend_r, plan, s);
     if (e != hipSuccess) return LINATTN_E_HIP;
   }
   mark(3, s);
@@ -251,6 +273,7 @@ int linattn_bwd(const void* q, const void* k, const void* v, const void* dout,
       if (overlaps(outs[i], ins[j], bytes)) return LINATTN_E_ALIAS;
     for (int j = i + 1; j < 3; ++j)
       if (overlaps(outs[i], outs[j], bytes)) return LINATTN_E_ALIAS;
+    if (desc.blend_in && overlaps(outs[i], desc.blend_in, bytes)) return LINATTN_E_ALIAS;
   }
   char* ws = static_cast<char*>(desc.workspace);
   BwdArgs a{};
@@ -267,6 +290,8 @@ int linattn_bwd(const void* q, const void* k, const void* v, const void* dout,
   a.dgimg = ws + plan.off_dgimg;
   a.wimg = ws + plan.off_wimg;
   a.scales = reinterpret_cast<float*>(ws + plan.off_scales);
+  a.blend_in = desc.blend_in; a.blend_r = desc.blend_r; a.blend_dr = desc.blend_dr;
+  a.dr_part = reinterpret_cast<float*>(ws + plan.off_drpart);
   a.dw_part = reinterpret_cast<float*>(ws + plan.off_dwpart);
   a.du_q = reinterpret_cast<float*>(ws + plan.off_du_q);
   a.du_k = reinterpret_cast<float*>(ws + plan.off_du_k);

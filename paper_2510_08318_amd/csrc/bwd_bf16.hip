@@ -173,13 +173,17 @@ __device__ __forceinline__ void store_half_row(uint16_t* base, size_t row_offset
 }
 
 // ---- query side --------------------------------------------------------------------------
-template <int D>
+// BLEND: dout is the gradient of the mixed output of Eq. 6; the linear branch receives
+// (1 - r') dout, and the workgroup's part of dL/dr = sum dout . (s - o) goes to dr_part.
+template <int D, bool BLEND>
 __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ dout,
                                                    const uint16_t* __restrict__ wq, const float* __restrict__ state,
                                                    const uint4* __restrict__ gimg, const uint4* __restrict__ simg,
                                                    const uint4* __restrict__ wimg, const float* __restrict__ scales,
                                                    uint16_t* __restrict__ dq,
                                                    float* __restrict__ partials, float* __restrict__ du_ws,
+                                                   const uint16_t* __restrict__ blend, const float* __restrict__ rptr,
+                                                   float* __restrict__ dr_part,
                                                    int H, int n, int P, Rows rw) {
   using C = Cfg<D>;
   using L = ApplyLayout<D>;
@@ -206,6 +210,9 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
   const uint16_t* qb = q + head_base(rw, bh, H);
   const uint16_t* dob = dout + head_base(rw, bh, H);
   uint16_t* dqb = dq + head_base(rw, bh, H);
+  const uint16_t* bb = BLEND ? blend + head_base(rw, bh, H) : nullptr;
+  const float om = BLEND ? 1.f - fminf(fmaxf(*rptr, 0.f), 1.f) : 1.f;      // 1 - r'
+  float dr_acc = 0.f;
   const float* sb = state + (size_t)bh * (D + 1) * D;
   const uint4* gim = gimg + (size_t)bh * G::IMG;
   const int ntile = (n + kTile - 1) / kTile;
@@ -253,6 +260,22 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
 #pragma unroll
       for (int i = 0; i < D / 16; ++i) dor[i] = drow[i];
     }
+    // dL/dr gets dout . (s - o) = dout . s - delta, from the unscaled dout; everything downstream is
+    // linear in dout, so the factor 1 - r' is applied to the scalars that carry it (om below).
+    // dout . s is taken here, while few registers are live.
+    float ds_part = 0.f;
+    if constexpr (BLEND) {
+      const uint4* srow = reinterpret_cast<const uint4*>(bb + (size_t)tc * rw.sn + g * (D / 2));
+#pragma unroll
+      for (int i = 0; i < D / 16; ++i) {
+        float df[8], sf[8];
+        unpack_bf16x8(dor[i], df);
+        unpack_bf16x8(srow[i], sf);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) ds_part = fmaf(df[j], sf[j], ds_part);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
     f32x16 u[C::UM];
     project<D>(xq, sWA, lane, u);
     float pp[C::LOC], pm[C::LOC];
@@ -296,6 +319,9 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
     float delta = 0.f, dmax = 0.f;
 #pragma unroll
     for (int c = 0; c < D / 2; ++c) { delta = fmaf(dof[c], o[c], delta); dmax = fmaxf(dmax, fabsf(dof[c])); }
+    if constexpr (BLEND) {
+      if (valid) dr_acc += ds_part - delta;      // dout . (s - o) on this lane's channels
+    }
     float lo, hi;
     pair32(delta, lo, hi); delta = lo + hi;
     pair32(dmax, lo, hi); dmax = fmaxf(lo, hi);
@@ -319,8 +345,8 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
         for (int mb = 0; mb < G::GM; ++mb)
           ga[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(gim[(ks * G::GM + mb) * 64 + lane]), bop, ga[mb], 0, 0, 0);
       }
-      const float r1 = __builtin_amdgcn_rcpf(den_s * stok);          // 1 / (scale * stok * den)
-      const float r2 = delta * inv_den;
+      const float r1 = om * __builtin_amdgcn_rcpf(den_s * stok);     // (1 - r') / (scale * stok * den)
+      const float r2 = om * delta * inv_den;
 #pragma unroll
       for (int mb = 0; mb < G::GM; ++mb) {
         const int f0 = (mb < G::GM / 2 ? 0 : C::HALF) + g * C::LOC + 16 * (mb % (G::GM / 2));
@@ -347,7 +373,7 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
 
     // operands of the sums over tokens
     if (tile == p) {
-      float m = valid ? dmax * inv_den : 0.f;
+      float m = valid ? dmax * inv_den * om : 0.f;
       for (int k = 32; k >= 1; k >>= 1) m = fmaxf(m, __shfl_xor(m, k, 64));
       if (lane == 0) sRed[w] = m;
       __syncthreads();
@@ -368,7 +394,7 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
         *reinterpret_cast<uint4*>(rowp + (((g * CPH + c) ^ psw) * 16)) = a;
         *reinterpret_cast<uint4*>(rowp + (((C::CH / 2 + g * CPH + c) ^ psw) * 16)) = b;
       }
-      const float sc = valid ? inv_den * gamma : 0.f;
+      const float sc = valid ? inv_den * gamma * om : 0.f;
       char* drowp = sDO + prow * RS;
 #pragma unroll
       for (int c = 0; c < D / 16; ++c) {
@@ -417,6 +443,13 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
   if (do_z && c == 0) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) dst[D * D + 32 * zmb + 8 * (r / 4) + 4 * g + (r % 4)] = zacc[r] * ig;
+  }
+  if constexpr (BLEND) {
+    for (int k = 32; k >= 1; k >>= 1) dr_acc += __shfl_xor(dr_acc, k, 64);
+    __syncthreads();
+    if (lane == 0) sRed[w] = dr_acc;
+    __syncthreads();
+    if (tid == 0) dr_part[(size_t)bh * P + p] = (sRed[0] + sRed[1]) + (sRed[2] + sRed[3]);
   }
 }
 
@@ -696,12 +729,23 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   bwd_prep_kernel<D, true><<<dim3(p.BH, 8), 256, prep_smem_bytes<D>(), s>>>(a.state, (uint4*)a.gimg, (uint4*)a.simg, a.scales,
                                                        (const uint16_t*)a.wq, (const uint16_t*)a.wk, (uint4*)a.wimg, p.H);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  if ((e = set_smem(bwd_q_kernel<D>, q_smem<D>())) != hipSuccess) return e;
-  bwd_q_kernel<D><<<dim3(p.P, p.BH), NT, q_smem<D>(), s>>>(
-      (const uint16_t*)a.q, (const uint16_t*)a.dout, (const uint16_t*)a.wq, a.state, (const uint4*)a.gimg,
-      (const uint4*)a.simg, (const uint4*)a.wimg, a.scales,
-      (uint16_t*)a.dq, a.partials, a.dwq ? a.du_q : nullptr, p.H, p.n, p.P, p.rows);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (a.blend_in) {
+    if ((e = set_smem(bwd_q_kernel<D, true>, q_smem<D>())) != hipSuccess) return e;
+    bwd_q_kernel<D, true><<<dim3(p.P, p.BH), NT, q_smem<D>(), s>>>(
+        (const uint16_t*)a.q, (const uint16_t*)a.dout, (const uint16_t*)a.wq, a.state, (const uint4*)a.gimg,
+        (const uint4*)a.simg, (const uint4*)a.wimg, a.scales,
+        (uint16_t*)a.dq, a.partials, a.dwq ? a.du_q : nullptr,
+        (const uint16_t*)a.blend_in, a.blend_r, a.dr_part, p.H, p.n, p.P, p.rows);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (a.blend_dr && (e = launch_dr_reduce(a.dr_part, p.BH * p.P, a.blend_r, a.blend_dr, s)) != hipSuccess) return e;
+  } else {
+    if ((e = set_smem(bwd_q_kernel<D, false>, q_smem<D>())) != hipSuccess) return e;
+    bwd_q_kernel<D, false><<<dim3(p.P, p.BH), NT, q_smem<D>(), s>>>(
+        (const uint16_t*)a.q, (const uint16_t*)a.dout, (const uint16_t*)a.wq, a.state, (const uint4*)a.gimg,
+        (const uint4*)a.simg, (const uint4*)a.wimg, a.scales,
+        (uint16_t*)a.dq, a.partials, a.dwq ? a.du_q : nullptr, nullptr, nullptr, nullptr, p.H, p.n, p.P, p.rows);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
   if ((e = launch_state_reduce(a.partials, a.dstate, p, s)) != hipSuccess) return e;
   // images of dS: the second half of the scales array, no W~ images
   bwd_prep_kernel<D, false><<<dim3(p.BH, 8), 256, prep_smem_bytes<D>(), s>>>(a.dstate, (uint4*)a.dgimg, (uint4*)a.dsimg, a.scales + 1,

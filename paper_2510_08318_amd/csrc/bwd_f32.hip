@@ -54,7 +54,10 @@ template <int D>
 __global__ __launch_bounds__(NT) void bwd_q_f32_kernel(const float* __restrict__ q, const float* __restrict__ dout,
                                                        const float* __restrict__ wq, const float* __restrict__ state,
                                                        float* __restrict__ dq, float* __restrict__ partials,
-                                                       float* __restrict__ du_ws, int H, int n, int P, int chunk, Rows rw) {
+                                                       float* __restrict__ du_ws,
+                                                       const float* __restrict__ blend, const float* __restrict__ rptr,
+                                                       float* __restrict__ dr_part,
+                                                       int H, int n, int P, int chunk, Rows rw) {
   constexpr int HALF = D / 2;
   constexpr int BLK = D / 16;
   constexpr int SS = D + 1;                 // row stride of the state copy (bank spread)
@@ -76,6 +79,10 @@ __global__ __launch_bounds__(NT) void bwd_q_f32_kernel(const float* __restrict__
   const float* qb = q + head_base(rw, bh, H);
   const float* dob = dout + head_base(rw, bh, H);
   float* dqb = dq + head_base(rw, bh, H);
+  // mixed attention (Eq. 6), off when blend is null: dout is the gradient of the mixed output
+  const float* bb = blend ? blend + head_base(rw, bh, H) : nullptr;
+  const float om = blend ? 1.f - fminf(fmaxf(*rptr, 0.f), 1.f) : 1.f;
+  float dr_acc = 0.f;
   const float* wb = wq + (size_t)h * D * HALF;
   const float* sb = state + (size_t)bh * (D + 1) * D;
   for (int i = tid; i < D * HALF; i += NT) sW[i] = wb[i];
@@ -119,6 +126,15 @@ __global__ __launch_bounds__(NT) void bwd_q_f32_kernel(const float* __restrict__
     if (tid < TB) {
       float dl = 0.f;
       for (int c = 0; c < D; ++c) dl = fmaf(sDO[tid * D + c], sG[tid * D + c], dl);
+      if (bb) {
+        if (tid < n_valid) {
+          float ds = 0.f;
+          for (int c = 0; c < D; ++c) ds = fmaf(sDO[tid * D + c], bb[(size_t)(t0 + tid) * rw.sn + c], ds);
+          dr_acc += ds - dl;
+        }
+        for (int c = 0; c < D; ++c) sDO[tid * D + c] *= om;
+        dl *= om;
+      }
       sDel[tid] = dl;
     }
     __syncthreads();
@@ -167,6 +183,16 @@ __global__ __launch_bounds__(NT) void bwd_q_f32_kernel(const float* __restrict__
 #pragma unroll
     for (int j = 0; j < BLK; ++j) dst[(f0 + i) * D + c0 + j] = acc[i][j];
   if (tid < D) dst[D * D + tid] = zacc;
+  if (bb) {
+    __syncthreads();
+    if (tid < TB) sC[tid] = dr_acc;
+    __syncthreads();
+    if (tid == 0) {
+      float t = 0.f;
+      for (int i = 0; i < TB; ++i) t += sC[i];
+      dr_part[(size_t)bh * P + p] = t;
+    }
+  }
 }
 
 template <int D>
@@ -242,7 +268,10 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   const dim3 grid(p.P, p.BH);
   if ((e = hipFuncSetAttribute((const void*)bwd_q_f32_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)q_smem<D>())) != hipSuccess) return e;
   bwd_q_f32_kernel<D><<<grid, NT, q_smem<D>(), s>>>((const float*)a.q, (const float*)a.dout, (const float*)a.wq, a.state,
-                                                    (float*)a.dq, a.partials, a.dwq ? a.du_q : nullptr, p.H, p.n, p.P, p.chunk, p.rows);
+                                                    (float*)a.dq, a.partials, a.dwq ? a.du_q : nullptr,
+                                                    (const float*)a.blend_in, a.blend_r, a.dr_part, p.H, p.n, p.P, p.chunk, p.rows);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (a.blend_in && a.blend_dr && (e = launch_dr_reduce(a.dr_part, p.BH * p.P, a.blend_r, a.blend_dr, s)) != hipSuccess) return e;
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if ((e = launch_state_reduce(a.partials, a.dstate, p, s)) != hipSuccess) return e;
   if ((e = hipFuncSetAttribute((const void*)bwd_k_f32_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)k_smem<D>())) != hipSuccess) return e;

@@ -27,9 +27,12 @@ namespace {
 // wavefront-private LDS transpose so that every store instruction writes whole 256-byte rows.
 constexpr int NT3 = 768;         // 12 wavefronts, one workgroup per compute unit
 
-template <int D>
+// BLEND: mixed attention (Sec. 4.1, Eq. 6): out = r' s + (1 - r') o with the softmax-branch output
+// s read on the lane's own channels (its half row, contiguous) and r' = clip(*rptr, 0, 1).
+template <int D, bool BLEND>
 __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ wq,
                                                          const float* __restrict__ state, uint16_t* __restrict__ out,
+                                                         const uint16_t* __restrict__ blend, const float* __restrict__ rptr,
                                                          int H, int n, Rows rw) {
   using C = Cfg<D>;
   using L = ApplyLayout<D>;
@@ -49,6 +52,8 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
   const int bh = blockIdx.y, h = bh % H;
   const uint16_t* qb = q + head_base(rw, bh, H);
   uint16_t* ob = out + head_base(rw, bh, H);
+  const uint16_t* bb = BLEND ? blend + head_base(rw, bh, H) : nullptr;
+  const float rb = BLEND ? fminf(fmaxf(*rptr, 0.f), 1.f) : 0.f;
 
   {
     // The state and W~ of this (b,h) are first copied into LDS with coalesced 16-byte loads (the
@@ -92,6 +97,11 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
     load_block(b + stride < nblk ? b + stride : b);  // next block's rows fly during the rest of this one
     uint32_t pk[C::NPK];
     softmax_pair_ratio<D>(u, pk);
+    const uint4* srow = nullptr;            // the lane's half row of the softmax branch
+    if constexpr (BLEND) {
+      const int t = b * 32 + (lane % 32);
+      srow = reinterpret_cast<const uint4*>(bb + (size_t)(t < n ? t : n - 1) * rw.sn + g * (D / 2));
+    }
 
     // out^T = S^T phi^T in two passes over the channel row blocks: the first also carries the
     // normaliser block, so 1/den is known before anything is scaled
@@ -99,6 +109,13 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
     float inv = 0.f;
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
+      // this pass's pieces of the softmax branch are requested before its MFMAs and used after them
+      uint4 sv[BLEND ? 2 * HB : 1];
+      if constexpr (BLEND) {
+#pragma unroll
+        for (int i = 0; i < 2 * HB; ++i)
+          if (2 * pass * HB + i < D / 16) sv[i] = srow[2 * pass * HB + i];
+      }
       f32x16 o[HB], dn;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -129,11 +146,24 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
       for (int i = 0; i < HB; ++i) {
         const int mb = pass * HB + i;
         if (mb < L::MB) {
+          float y[16];
+#pragma unroll
+          for (int r = 0; r < 16; ++r) y[r] = o[i][r] * inv;
+          if constexpr (BLEND) {
+            const uint32_t sw[8] = {sv[2 * i].x, sv[2 * i].y, sv[2 * i].z, sv[2 * i].w,
+                                    sv[2 * i + 1].x, sv[2 * i + 1].y, sv[2 * i + 1].z, sv[2 * i + 1].w};
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+              const float s0 = __builtin_bit_cast(float, sw[j] << 16), s1 = __builtin_bit_cast(float, sw[j] & 0xffff0000u);
+              y[2 * j] = fmaf(rb, s0 - y[2 * j], y[2 * j]);
+              y[2 * j + 1] = fmaf(rb, s1 - y[2 * j + 1], y[2 * j + 1]);
+            }
+          }
           uint4 a, c;
-          a.x = pack_bf16x2(o[i][0] * inv, o[i][1] * inv);   a.y = pack_bf16x2(o[i][2] * inv, o[i][3] * inv);
-          a.z = pack_bf16x2(o[i][4] * inv, o[i][5] * inv);   a.w = pack_bf16x2(o[i][6] * inv, o[i][7] * inv);
-          c.x = pack_bf16x2(o[i][8] * inv, o[i][9] * inv);   c.y = pack_bf16x2(o[i][10] * inv, o[i][11] * inv);
-          c.z = pack_bf16x2(o[i][12] * inv, o[i][13] * inv); c.w = pack_bf16x2(o[i][14] * inv, o[i][15] * inv);
+          a.x = pack_bf16x2(y[0], y[1]);   a.y = pack_bf16x2(y[2], y[3]);
+          a.z = pack_bf16x2(y[4], y[5]);   a.w = pack_bf16x2(y[6], y[7]);
+          c.x = pack_bf16x2(y[8], y[9]);   c.y = pack_bf16x2(y[10], y[11]);
+          c.z = pack_bf16x2(y[12], y[13]); c.w = pack_bf16x2(y[14], y[15]);
           *reinterpret_cast<uint4*>(srowp + (((g * (C::CH / 2) + 2 * mb) ^ ssw) * 16)) = a;
           *reinterpret_cast<uint4*>(srowp + (((g * (C::CH / 2) + 2 * mb + 1) ^ ssw) * 16)) = c;
         }
@@ -426,20 +456,27 @@ hipError_t launch_state_partials_bf16(const void* k, const void* v, const void* 
   return hipGetLastError();
 }
 
-hipError_t launch_apply_bf16(const void* q, const void* wq, const float* state, void* out,
-                             const Plan& p, hipStream_t s) {
-  dim3 grid(p.QP, p.BH), block(NT3);
+namespace {
+
+template <int D, bool BLEND>
+hipError_t run_apply(const void* q, const void* wq, const float* state, void* out, const void* blend_in,
+                     const float* blend_r, const Plan& p, hipStream_t s) {
   hipError_t e;
-  if (p.d == 128) {
-    if ((e = set_smem(apply_bf16_kernel<128>, apply_smem<128>())) != hipSuccess) return e;
-    apply_bf16_kernel<128><<<grid, block, apply_smem<128>(), s>>>(
-        (const uint16_t*)q, (const uint16_t*)wq, state, (uint16_t*)out, p.H, p.n, p.rows);
-  } else {
-    if ((e = set_smem(apply_bf16_kernel<64>, apply_smem<64>())) != hipSuccess) return e;
-    apply_bf16_kernel<64><<<grid, block, apply_smem<64>(), s>>>(
-        (const uint16_t*)q, (const uint16_t*)wq, state, (uint16_t*)out, p.H, p.n, p.rows);
-  }
+  if ((e = set_smem(apply_bf16_kernel<D, BLEND>, apply_smem<D>())) != hipSuccess) return e;
+  apply_bf16_kernel<D, BLEND><<<dim3(p.QP, p.BH), NT3, apply_smem<D>(), s>>>(
+      (const uint16_t*)q, (const uint16_t*)wq, state, (uint16_t*)out, (const uint16_t*)blend_in, blend_r, p.H, p.n, p.rows);
   return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_apply_bf16(const void* q, const void* wq, const float* state, void* out,
+                             const void* blend_in, const float* blend_r, const Plan& p, hipStream_t s) {
+  if (p.d == 128)
+    return blend_in ? run_apply<128, true>(q, wq, state, out, blend_in, blend_r, p, s)
+                    : run_apply<128, false>(q, wq, state, out, nullptr, nullptr, p, s);
+  return blend_in ? run_apply<64, true>(q, wq, state, out, blend_in, blend_r, p, s)
+                  : run_apply<64, false>(q, wq, state, out, nullptr, nullptr, p, s);
 }
 
 }  // namespace linattn

@@ -76,6 +76,7 @@ __global__ __launch_bounds__(NT) void state_partials_f32_kernel(const float* __r
 template <int D>
 __global__ __launch_bounds__(NT) void apply_f32_kernel(const float* __restrict__ q, const float* __restrict__ wq,
                                                        const float* __restrict__ state, float* __restrict__ out,
+                                                       const float* __restrict__ blend, const float* __restrict__ rptr,
                                                        int H, int n, int chunk, Rows rw) {
   constexpr int HALF = D / 2;
   extern __shared__ float smem[];
@@ -90,6 +91,9 @@ __global__ __launch_bounds__(NT) void apply_f32_kernel(const float* __restrict__
   const int t_end = min(n, t_begin + chunk);
   const float* qb = q + head_base(rw, bh, H);
   float* ob = out + head_base(rw, bh, H);
+  // mixed attention (Eq. 6): out = r' s + (1 - r') o with r' = clip(r, 0, 1); off when blend is null
+  const float* bb = blend ? blend + head_base(rw, bh, H) : nullptr;
+  const float rb = blend ? fminf(fmaxf(*rptr, 0.f), 1.f) : 0.f;
   const float* wb = wq + (size_t)h * D * HALF;
   const float* sb = state + (size_t)bh * (D + 1) * D;
   for (int i = tid; i < D * HALF; i += NT) sW[i] = wb[i];
@@ -119,7 +123,11 @@ __global__ __launch_bounds__(NT) void apply_f32_kernel(const float* __restrict__
     if (t < t_end) {
       const float inv = 1.0f / den;
 #pragma unroll
-      for (int j = 0; j < D / 8; ++j) ob[(size_t)t * rw.sn + cb + 8 * j] = acc[j] * inv;
+      for (int j = 0; j < D / 8; ++j) {
+        float val = acc[j] * inv;
+        if (bb) val = fmaf(rb, bb[(size_t)t * rw.sn + cb + 8 * j] - val, val);
+        ob[(size_t)t * rw.sn + cb + 8 * j] = val;
+      }
     }
   }
 }
@@ -148,17 +156,17 @@ hipError_t launch_state_partials_f32(const float* k, const float* v, const float
 }
 
 hipError_t launch_apply_f32(const float* q, const float* wq, const float* state, float* out,
-                            const Plan& p, hipStream_t s) {
+                            const float* blend_in, const float* blend_r, const Plan& p, hipStream_t s) {
   dim3 grid(p.QP, p.BH), block(NT);
   hipError_t e;
   if (p.d == 128) {
     e = hipFuncSetAttribute((const void*)apply_f32_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)apply_smem<128>());
     if (e != hipSuccess) return e;
-    apply_f32_kernel<128><<<grid, block, apply_smem<128>(), s>>>(q, wq, state, out, p.H, p.n, p.qchunk, p.rows);
+    apply_f32_kernel<128><<<grid, block, apply_smem<128>(), s>>>(q, wq, state, out, blend_in, blend_r, p.H, p.n, p.qchunk, p.rows);
   } else {
     e = hipFuncSetAttribute((const void*)apply_f32_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)apply_smem<64>());
     if (e != hipSuccess) return e;
-    apply_f32_kernel<64><<<grid, block, apply_smem<64>(), s>>>(q, wq, state, out, p.H, p.n, p.qchunk, p.rows);
+    apply_f32_kernel<64><<<grid, block, apply_smem<64>(), s>>>(q, wq, state, out, blend_in, blend_r, p.H, p.n, p.qchunk, p.rows);
   }
   return hipGetLastError();
 }

@@ -48,6 +48,7 @@ struct Plan {
   size_t off_dgimg;       // fp16 [BH][d*d]       operand image of dS for dL/dphi(k)
   size_t off_wimg;        // [H][4][d*d bytes]    W~_q image, W~_q transposed image, then the same for W~_k
   size_t off_scales;      // fp32 [BH][2]         power-of-two scales of the S and dS images
+  size_t off_drpart;      // fp32 [BH][P]         per-workgroup parts of dL/dr (mixed attention, Eq. 6)
   size_t off_dwpart;      // fp32 [BH][P][d*d/2]  partial dW~           (weight gradients only)
   size_t off_du_q;        // fp32 [BH][n][d/2]    dL/du of the query side (weight gradients only)
   size_t off_du_k;        // fp32 [BH][n][d/2]    dL/du of the key side   (weight gradients only)
@@ -69,6 +70,11 @@ struct BwdArgs {
   void* gimg;
   void *simg, *dsimg, *dgimg, *wimg;
   float* scales;
+  // mixed attention (Eq. 6): softmax-branch output, the layer's r, dL/dr; all null when off
+  const void* blend_in;
+  const float* blend_r;
+  float* blend_dr;
+  float* dr_part;
 };
 
 // ---- forward launchers (enqueue only) ---------------------------------------------------
@@ -81,9 +87,9 @@ hipError_t launch_state_partials_bf16(const void* k, const void* v, const void* 
 hipError_t launch_state_reduce(const float* partials, float* state, const Plan& p, hipStream_t s);
 // phi(Q) S / (phi(Q) . z) and the store of out (Eq. 3, right-hand side).
 hipError_t launch_apply_f32(const float* q, const float* wq, const float* state, float* out,
-                            const Plan& p, hipStream_t s);
+                            const float* blend_in, const float* blend_r, const Plan& p, hipStream_t s);
 hipError_t launch_apply_bf16(const void* q, const void* wq, const float* state, void* out,
-                             const Plan& p, hipStream_t s);
+                             const void* blend_in, const float* blend_r, const Plan& p, hipStream_t s);
 
 // ---- backward launchers (enqueue only) --------------------------------------------------
 // dw[H][d][d/2] = sum over batch and tokens of x^T du; x is [B,H,n,d] bf16 or fp32, du fp32 [B,H,n,d/2].
@@ -92,5 +98,7 @@ hipError_t launch_dw_reduce(const float* part, float* dw, const Plan& p, hipStre
 hipError_t launch_dw(const void* x, bool x_is_bf16, const float* du, float* part, float* dw, const Plan& p, hipStream_t s);
 hipError_t launch_bwd_bf16(const BwdArgs& a, const Plan& p, hipStream_t s);
 hipError_t launch_bwd_f32(const BwdArgs& a, const Plan& p, hipStream_t s);
+// dr = sum of the count parts in a fixed order if 0 <= *r <= 1, else 0 (Eq. 6, clipped r).
+hipError_t launch_dr_reduce(const float* part, int count, const float* r, float* dr, hipStream_t s);
 
 }  // namespace linattn

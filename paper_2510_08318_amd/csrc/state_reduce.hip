@@ -95,7 +95,31 @@ __global__ __launch_bounds__(256) void dw_reduce_kernel(const float* __restrict_
   dw[(size_t)h * elems + e] = acc;
 }
 
+// dL/dr of the mixed attention (Eq. 6): the per-workgroup parts summed in a fixed order by one
+// workgroup; zero outside the clip's range [0, 1].
+__global__ __launch_bounds__(256) void dr_reduce_kernel(const float* __restrict__ part, int count,
+                                                        const float* __restrict__ r, float* __restrict__ dr) {
+  __shared__ float red[256];
+  float acc = 0.f;
+  for (int i = threadIdx.x; i < count; i += 256) acc += part[i];
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int m = 128; m >= 1; m >>= 1) {
+    if ((int)threadIdx.x < m) red[threadIdx.x] += red[threadIdx.x + m];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const float rv = *r;
+    *dr = (rv >= 0.f && rv <= 1.f) ? red[0] : 0.f;
+  }
+}
+
 }  // namespace
+
+hipError_t launch_dr_reduce(const float* part, int count, const float* r, float* dr, hipStream_t s) {
+  dr_reduce_kernel<<<1, 256, 0, s>>>(part, count, r, dr);
+  return hipGetLastError();
+}
 
 hipError_t launch_state_reduce(const float* partials, float* state, const Plan& p, hipStream_t s) {
   const int elems = (int)p.state_elems;

@@ -53,6 +53,16 @@ class Layer:
                                             self.dwq, self.dwk, self.state, self.workspace, self.workspace_bytes,
                                             B_.LAYOUT_BNHD if layout == "bnhd" else B_.LAYOUT_BHND)
 
+    def set_blend(self, s=None, r=None, dr=None):
+        """Mixed attention (Eq. 6): s = softmax-branch output (dtype and layout of out), r = device fp32[1],
+        dr = optional device fp32[1] receiving dL/dr in backward.  All None switches it off."""
+        if s is not None:
+            assert s.is_cuda and s.is_contiguous() and s.dtype == self.wq.dtype
+            assert r.is_cuda and r.dtype == torch.float32 and r.numel() == 1
+            assert dr is None or (dr.is_cuda and dr.dtype == torch.float32 and dr.numel() == 1)
+        self._blend = (s, r, dr)          # keep the buffers alive
+        B_.linattn_phi_set_blend(self.phi_id, s, r, dr)
+
     def close(self):
         if self.phi_id is not None:
             B_.linattn_phi_destroy(self.phi_id)

@@ -128,3 +128,28 @@ def test_descriptor_table_reuses_slots():
     again = L.linattn_phi_create(L.PHI_HEDGEHOG, L.F32, 1, 64, P, P)
     assert again in ids
     L.linattn_phi_destroy(again)
+
+
+def test_blend_pointers_are_checked_on_the_host():
+    mk = lambda **kw: L.linattn_phi_create(**{**dict(kind=L.PHI_HEDGEHOG, dtype=L.BF16, H=2, d=64, wq=P, wk=P + 4096), **kw}, check=False)
+    assert mk(blend_in=P + 65536) == L.E_NULL                       # softmax branch without r
+    assert mk(blend_r=P + 65536) == L.E_NULL                        # r without the softmax branch
+    assert mk(blend_dr=P + 65536) == L.E_NULL                       # dr without either
+    assert mk(blend_in=P + 65536 + 2, blend_r=P + 4) == L.E_ALIGN
+    pid = mk(blend_in=P + 65536, blend_r=P + 4, blend_dr=P + 8)
+    assert pid >= 16
+    assert L.linattn_phi_set_blend(pid, None, None, None, check=False) == L.OK
+    assert L.linattn_phi_set_blend(pid, P + 65536, None, None, check=False) == L.E_NULL
+    assert L.linattn_phi_set_blend(pid, P + 65536, P + 4, None, check=False) == L.OK
+    assert L.linattn_phi_set_blend(9999, None, None, None, check=False) == L.E_PHI
+    assert L.linattn_phi_destroy(pid) == L.OK
+
+
+def test_blend_input_may_not_alias_the_output():
+    B, H, n, d = 1, 2, 256, 64
+    ws = L.linattn_workspace_bytes(B, H, n, d, L.PHI_HEDGEHOG, L.BF16)
+    q, k, v, out = P + (8 << 20), P + (9 << 20), P + (10 << 20), P + (11 << 20)
+    pid = L.linattn_phi_create(L.PHI_HEDGEHOG, L.BF16, H, d, P, P + 8192, workspace=P + (1 << 20), workspace_bytes=ws,
+                               blend_in=out + 64, blend_r=P + 16)
+    assert L.linattn_fwd(q, k, v, out, B, H, n, d, pid, None, check=False) == L.E_ALIAS
+    L.linattn_phi_destroy(pid)
