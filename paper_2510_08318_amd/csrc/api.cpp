@@ -39,9 +39,22 @@ bool make_plan(int B, int H, int n, int d, int dtype, int layout, Plan* p) {
     r.QP = QP;
   }
   r.state_elems = (size_t)(d + 1) * d;
+  {
+    Split sp{};
+    sp.ntile = tiles;
+    sp.T = (long long)BH * tiles;
+    sp.G = BH > kSlots ? (int)BH : (int)(sp.T < kSlots ? sp.T : kSlots);
+    sp.PS = 1;
+    for (long long bh = 0; bh < BH; ++bh) {
+      const int cnt = split_owner(sp, (bh + 1) * tiles - 1) - split_owner(sp, bh * tiles) + 1;
+      if (cnt > sp.PS) sp.PS = cnt;
+    }
+    r.split = sp;
+  }
   auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
   size_t off = 0;
-  r.off_partials = off; off = up(off + (size_t)BH * r.P * r.state_elems * sizeof(float));
+  const int slots = r.P > r.split.PS ? r.P : r.split.PS;
+  r.off_partials = off; off = up(off + (size_t)BH * slots * r.state_elems * sizeof(float));
   r.off_state = off;    off = up(off + (size_t)BH * r.state_elems * sizeof(float));
   {
     const int nblk = (n + 31) / 32;
@@ -245,7 +258,7 @@ int linattn_fwd(const void* q, const void* k, const void* v, void* out,
     e = launch_state_partials_bf16(k, v, desc.wk, partials, plan, s);
     if (e != hipSuccess) return LINATTN_E_HIP;
     mark(1, s);
-    e = launch_state_reduce(partials, state, plan, s);
+    e = launch_state_reduce_split(partials, state, plan, s);
     if (e != hipSuccess) return LINATTN_E_HIP;
     mark(2, s);
     e = launch_apply_bf16(q, desc.wq, state, out, desc.blend_in, desc.blend_r, plan, s);

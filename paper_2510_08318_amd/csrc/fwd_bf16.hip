@@ -215,10 +215,13 @@ __device__ __forceinline__ int tr_offset_g4(int col0, int lane, int j) {
   return r * RS + (((col / 8) ^ swz<D>(r)) * 16) + (col % 8) * 2;
 }
 
+// One segment of a workgroup's tile range: tiles tile0 .. tile0+nt-1 of one (b,h), whose K and V
+// rows start at kb, vb and whose W~_k is wkh; the partial state goes to dst.  Every thread of the
+// workgroup calls it (it contains workgroup barriers).
 template <int D>
-__global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-                                                                const uint16_t* __restrict__ wk, float* __restrict__ partials,
-                                                                int H, int n, int P, Rows rw) {
+__device__ __forceinline__ void state_segment(const uint16_t* __restrict__ kb, const uint16_t* __restrict__ vb,
+                                              const uint16_t* __restrict__ wkh, float* __restrict__ dst,
+                                              int tile0, int nt, int n, Rows rw) {
   using C = Cfg<D>;
   constexpr int RS = D * 2;
   constexpr int WMN = D / 64;
@@ -234,13 +237,8 @@ __global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* 
   const int w = __builtin_amdgcn_readfirstlane(tid / 64);
   const int role = w / 4, pw = w % 4;            // role 0: phi, role 1: acc
   const int g = lane / 32;
-  const int bh = blockIdx.y, p = blockIdx.x, h = bh % H;
-  const uint16_t* kb = k + head_base(rw, bh, H);
-  const uint16_t* vb = v + head_base(rw, bh, H);
-  const int ntile = (n + kTile - 1) / kTile;
-  const int nt = (ntile - p + P - 1) / P;        // tiles of this workgroup: p, p+P, ...
 
-  build_w_image<D, NT1>(wk + (size_t)h * D * C::HALF, sWA, tid);
+  build_w_image<D, NT1>(wkh, sWA, tid);
   __syncthreads();
 
   if (role == 0) {
@@ -273,11 +271,11 @@ __global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* 
     // projection has consumed it
     auto phi_step = [&](uint4 (&x)[C::UK], int it) {
       if (it < nt) {
-        const int tile = p + it * P;
+        const int tile = tile0 + it;
         const bool valid = (tile * kTile + prow) < n;
         f32x16 u[C::UM];
         project<D>(x, sWA, lane, u);
-        if (it + 2 < nt) load_k(x, tile + 2 * P);
+        if (it + 2 < nt) load_k(x, tile + 2);
         uint32_t pk[C::NPK];
         softmax_pair<D>(u, valid, pk);
         // turn phi from "token per lane" to "feature slot per lane" with an MFMA against the 0/1
@@ -313,8 +311,8 @@ __global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* 
       __syncthreads();
     };
     uint4 xa[C::UK], xc[C::UK];
-    load_k(xa, p);
-    if (nt > 1) load_k(xc, p + P);
+    load_k(xa, tile0);
+    if (nt > 1) load_k(xc, tile0 + 1);
     for (int it = 0; it <= nt; it += 2) {       // nt + 1 barriers in total, as in the acc branch
       phi_step(xa, it);
       if (it + 1 <= nt) phi_step(xc, it + 1);
@@ -367,7 +365,7 @@ __global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* 
           hv.z = bf16x2_to_f16x2(vr[i].z); hv.w = bf16x2_to_f16x2(vr[i].w);
           *reinterpret_cast<uint4*>(sV + rv * RS + ((c ^ swz<D>(rv)) * 16)) = hv;
         }
-        if (it + 2 < nt) load_v(vr, p + (it + 2) * P);
+        if (it + 2 < nt) load_v(vr, tile0 + it + 2);
       }
       if (it >= 1) {
         // operands are requested OPA k-steps before the MFMAs that use them.
@@ -399,13 +397,12 @@ __global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* 
       __syncthreads();
     };
     uint4 va[VPT], vc[VPT];
-    load_v(va, p);
-    if (nt > 1) load_v(vc, p + P);
+    load_v(va, tile0);
+    if (nt > 1) load_v(vc, tile0 + 1);
     for (int it = 0; it <= nt; it += 2) {
       acc_step(va, it);
       if (it + 1 <= nt) acc_step(vc, it + 1);
     }
-    float* dst = partials + ((size_t)bh * P + p) * (size_t)(D + 1) * D;
     const int c = lane % 32;
 #pragma unroll
     for (int i = 0; i < WMN; ++i)
@@ -419,9 +416,29 @@ __global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* 
   }
   // z: the four phi wavefronts, in a fixed order
   __syncthreads();
-  if (tid < D) {
-    float* dst = partials + ((size_t)bh * P + p) * (size_t)(D + 1) * D;
+  if (tid < D)
     dst[D * D + turned_feature<D>(tid / 32, tid % 32)] = (zred[tid] + zred[2 * D + tid]) + (zred[D + tid] + zred[3 * D + tid]);
+  __syncthreads();                               // the next segment reuses every LDS region
+}
+
+// Grid: Split::G workgroups; workgroup g takes the tiles [lo(g), lo(g+1)) of the call's (b,h)-major
+// tile sequence, one segment per head it touches (at most two).
+template <int D>
+__global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+                                                                const uint16_t* __restrict__ wk, float* __restrict__ partials,
+                                                                int H, int n, Split sp, Rows rw) {
+  const int g = blockIdx.x;
+  long long lo = split_lo(sp, g);
+  const long long hi = split_lo(sp, g + 1);
+  while (lo < hi) {
+    const int bh = (int)(lo / sp.ntile);
+    const long long head0 = (long long)bh * sp.ntile;
+    const long long seg_hi = hi < head0 + sp.ntile ? hi : head0 + sp.ntile;
+    const int slot = g - split_owner(sp, head0);
+    state_segment<D>(k + head_base(rw, bh, H), v + head_base(rw, bh, H), wk + (size_t)(bh % H) * D * (D / 2),
+                     partials + ((size_t)bh * sp.PS + slot) * (size_t)(D + 1) * D,
+                     (int)(lo - head0), (int)(seg_hi - lo), n, rw);
+    lo = seg_hi;
   }
 }
 
@@ -442,16 +459,16 @@ hipError_t set_smem(K kernel, size_t bytes) {
 
 hipError_t launch_state_partials_bf16(const void* k, const void* v, const void* wk, float* partials,
                                       const Plan& p, hipStream_t s) {
-  dim3 grid(p.P, p.BH), block(NT1);
+  dim3 grid(p.split.G), block(NT1);
   hipError_t e;
   if (p.d == 128) {
     if ((e = set_smem(state_partials_ws_kernel<128>, state_ws_smem<128>())) != hipSuccess) return e;
     state_partials_ws_kernel<128><<<grid, block, state_ws_smem<128>(), s>>>(
-        (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)wk, partials, p.H, p.n, p.P, p.rows);
+        (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)wk, partials, p.H, p.n, p.split, p.rows);
   } else {
     if ((e = set_smem(state_partials_ws_kernel<64>, state_ws_smem<64>())) != hipSuccess) return e;
     state_partials_ws_kernel<64><<<grid, block, state_ws_smem<64>(), s>>>(
-        (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)wk, partials, p.H, p.n, p.P, p.rows);
+        (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)wk, partials, p.H, p.n, p.split, p.rows);
   }
   return hipGetLastError();
 }

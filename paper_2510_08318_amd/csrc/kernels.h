@@ -25,17 +25,38 @@ __host__ __device__ inline size_t head_base(const Rows& r, int bh, int H) {
   return (size_t)(bh / H) * r.sb + (size_t)(bh % H) * r.sh;
 }
 
+// Split of the bf16 state pass: the T = B*H*ntile 128-token tiles of a call, in (b,h)-major order,
+// are dealt to G workgroups in contiguous ranges [lo(g), lo(g+1)), lo(g) = floor(g*T/G), so that
+// every compute unit gets the same share whatever B*H is (a per-head split leaves
+// 256 mod B*H units idle).  T/G <= ntile, so a range touches at most two heads; a workgroup
+// writes one partial state per head it touches, into slot g - owner(first tile of the head).
+struct Split {
+  int G;            // workgroups
+  int ntile;        // tiles per (b,h)
+  long long T;      // tiles in all
+  int PS;           // partial slots per (b,h) (the largest number of workgroups touching one head)
+};
+__host__ __device__ inline long long split_lo(const Split& s, int g) { return (long long)g * s.T / s.G; }
+// the workgroup whose range holds tile x
+__host__ __device__ inline int split_owner(const Split& s, long long x) {
+  int g = (int)(x * s.G / s.T);
+  while (g + 1 < s.G && split_lo(s, g + 1) <= x) ++g;
+  while (g > 0 && split_lo(s, g) > x) --g;
+  return g;
+}
+
 // How one call is cut into workgroups and where its scratch regions sit in the workspace.
 struct Plan {
   int B, H, n, d;
   int BH;
   Rows rows;        // memory layout of the token tensors
-  int P;            // split-n factor of the state pass (partials per (b,h))
+  Split split;      // bf16 forward state pass
+  int P;            // split-n factor (partials per (b,h)) of the fp32 state pass and of the backward
   int chunk;        // tokens per split, a multiple of kTile (fp32 kernels; the bf16 ones deal tiles round-robin)
   int QP;           // workgroups per (b,h) of the query pass
   int qchunk;       // tokens per workgroup of the fp32 query pass
   size_t state_elems;     // (d+1)*d
-  size_t off_partials;    // fp32 [BH][P][(d+1)*d]
+  size_t off_partials;    // fp32 [BH][max(P, split.PS)][(d+1)*d]
   size_t off_state;       // fp32 [BH][(d+1)*d]   (used when the caller gave no state buffer)
   // backward only
   int KP;                 // workgroups per (b,h) of the key-side backward pass
@@ -85,6 +106,8 @@ hipError_t launch_state_partials_bf16(const void* k, const void* v, const void* 
                                       const Plan& p, hipStream_t s);
 // Fixed-order sum of the partials into the exported state layout [BH][d+1][d] fp32.
 hipError_t launch_state_reduce(const float* partials, float* state, const Plan& p, hipStream_t s);
+// The same for the partials of the bf16 forward state pass (slots per head follow Plan::split).
+hipError_t launch_state_reduce_split(const float* partials, float* state, const Plan& p, hipStream_t s);
 // phi(Q) S / (phi(Q) . z) and the store of out (Eq. 3, right-hand side).
 hipError_t launch_apply_f32(const float* q, const float* wq, const float* state, float* out,
                             const float* blend_in, const float* blend_r, const Plan& p, hipStream_t s);

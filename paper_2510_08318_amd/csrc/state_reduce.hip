@@ -26,6 +26,40 @@ __global__ __launch_bounds__(256) void state_reduce_kernel(const float* __restri
   state[(size_t)bh * elems + e] = acc;
 }
 
+// The same for the flattened split of the bf16 forward: head bh owns the slots of the workgroups
+// whose tile ranges touch it, in ascending workgroup order.
+__global__ __launch_bounds__(256) void state_reduce_split_kernel(const float* __restrict__ partials, float* __restrict__ state,
+                                                                 Split sp, int elems) {
+  __shared__ int s_cnt;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  const int bh = blockIdx.y;
+  if (threadIdx.x == 0)
+    s_cnt = split_owner(sp, (long long)(bh + 1) * sp.ntile - 1) - split_owner(sp, (long long)bh * sp.ntile) + 1;
+  __syncthreads();
+  if (e >= elems) return;
+  const int cnt = s_cnt;
+  const float* src = partials + (size_t)bh * sp.PS * elems + e;
+  float acc = 0.f;
+  int p = 0;
+  for (; p + 8 <= cnt; p += 8) {
+    float t[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) t[i] = src[(size_t)(p + i) * elems];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc += t[i];
+  }
+  if (p + 4 <= cnt) {
+    float t[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) t[i] = src[(size_t)(p + i) * elems];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc += t[i];
+    p += 4;
+  }
+  for (; p < cnt; ++p) acc += src[(size_t)p * elems];
+  state[(size_t)bh * elems + e] = acc;
+}
+
 // ---- dW~ = sum_{b, i} x_i^T du_i ------------------------------------------------------------
 // Partial sums per (b,h) and token split (fp32 FMA, LDS tiles), then a fixed-order reduction over
 // splits and batch items.
@@ -124,6 +158,12 @@ hipError_t launch_dr_reduce(const float* part, int count, const float* r, float*
 hipError_t launch_state_reduce(const float* partials, float* state, const Plan& p, hipStream_t s) {
   const int elems = (int)p.state_elems;
   state_reduce_kernel<<<dim3((elems + 255) / 256, p.BH), 256, 0, s>>>(partials, state, p.P, elems);
+  return hipGetLastError();
+}
+
+hipError_t launch_state_reduce_split(const float* partials, float* state, const Plan& p, hipStream_t s) {
+  const int elems = (int)p.state_elems;
+  state_reduce_split_kernel<<<dim3((elems + 255) / 256, p.BH), 256, 0, s>>>(partials, state, p.split, elems);
   return hipGetLastError();
 }
 
