@@ -633,10 +633,11 @@ __global__ __launch_bounds__(NT) void dw_mfma_kernel(const uint16_t* __restrict_
     for (int b = 0; b < NB; ++b) offB[b][j] = tr_offset<HALF>(32 * b, lane, j);
   }
   float gamma = 1.f;
-  for (int tile = p; tile < ntile; tile += P) {
+  uint4 xr[XPT];
+  float4 ur[UPT][2];
+  // the next tile's rows are requested while the current one is contracted
+  auto load_tile = [&](int tile) {
     const int t0 = tile * kTile;
-    uint4 xr[XPT];
-    float4 ur[UPT][2];
 #pragma unroll
     for (int i = 0; i < XPT; ++i) {
       const int idx = tid + NT * i, r = idx / (D / 8), c = idx % (D / 8);
@@ -651,6 +652,9 @@ __global__ __launch_bounds__(NT) void dw_mfma_kernel(const uint16_t* __restrict_
       ur[i][0] = t < n ? src[0] : make_float4(0.f, 0.f, 0.f, 0.f);
       ur[i][1] = t < n ? src[1] : make_float4(0.f, 0.f, 0.f, 0.f);
     }
+  };
+  if (p < ntile) load_tile(p);
+  for (int tile = p; tile < ntile; tile += P) {
     if (tile == p) {
       float m = 0.f;
 #pragma unroll
@@ -681,6 +685,7 @@ __global__ __launch_bounds__(NT) void dw_mfma_kernel(const uint16_t* __restrict_
       hv.z = pack_f16x2(ur[i][1].x * gamma, ur[i][1].y * gamma); hv.w = pack_f16x2(ur[i][1].z * gamma, ur[i][1].w * gamma);
       *reinterpret_cast<uint4*>(sU + r * RSU + ((c ^ swz<HALF>(r)) * 16)) = hv;
     }
+    if (tile + P < ntile) load_tile(tile + P);
     __syncthreads();
     if (active) {
 #pragma unroll
