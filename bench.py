@@ -196,11 +196,16 @@ def main():
     L.linattn_set_stage_events(None)
     torch.cuda.synchronize()
     stage_ms = [0.0, 0.0, 0.0]
+    per_call = []
     for four in evs:
+        tot = 0.0
         for i in range(3):
             ms = ctypes.c_float()
             assert hip.hipEventElapsedTime(ctypes.byref(ms), four[i], four[i + 1]) == 0
             stage_ms[i] += ms.value / args.steps
+            tot += ms.value
+        per_call.append(tot)
+    per_call.sort()
     for four in evs:
         for e in four:
             hip.hipEventDestroy(e)
@@ -216,7 +221,9 @@ def main():
                 "traffic": MEASURED_TRAFFIC.get((args.workload, dom)),
                 "stage_ms": [round(t, 4) for t in stage_ms],
                 "path_GBps": round(4 * x.d * esz * head_tokens / (sum(stage_ms) * 1e-3) / 1e9, 1),
-                "path_frac": round(4 * x.d * esz * head_tokens / (sum(stage_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+                "path_frac": round(4 * x.d * esz * head_tokens / (sum(stage_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                # one call = first to last stage event; distribution over the K event-bracketed calls
+                "call_ms_median": round(per_call[len(per_call) // 2], 4), "call_ms_min": round(per_call[0], 4)}
 
     res = {
         "metric": "linear-attn fwd tokens/s (Wan-14B 720p shape)" if args.workload == "C3" else f"linear-attn fwd tokens/s ({args.workload})",
