@@ -378,3 +378,26 @@ def test_blend_planted_mistakes_are_caught():
     unscaled = O.bwd_bh(q, k, v, wq, wk, dout)[0]
     right = O.blend_bwd_bh(q, k, v, wq, wk, s, r, dout)[0]
     assert np.abs(unscaled - right).max() > 0.1 * np.abs(right).max()
+
+
+def test_hand_computed_two_token_fixture():
+    """tests/golden/two_tokens_d4_by_hand.txt: Eq. 3 + Eq. 5 worked out by hand in exact rationals."""
+    import os
+    rows = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "two_tokens_d4_by_hand.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                name, *vals = line.split()
+                rows[name] = np.array([float(t) for t in vals])
+    ln3 = np.log(3.0)
+    W = np.zeros((4, 2)); W[0, 0] = 1.0
+    q = np.array([[ln3, 0, 0, 0], [0, 0, 0, 0.0]])
+    k = np.array([[ln3, 0, 0, 0], [-ln3, 0, 0, 0.0]])
+    v = np.stack([rows["v_1"], rows["v_2"]])
+    out = O.fwd(q, k, v, W, W)
+    np.testing.assert_allclose(out, np.stack([rows["o_1"], rows["o_2"]]), rtol=0, atol=1e-14)
+    np.testing.assert_allclose(O.fwd_bruteforce(q, k, v, W, W), out, rtol=0, atol=1e-14)
+    S, z = O.state(k, v, W)
+    np.testing.assert_allclose(z, rows["z"], atol=1e-15)
+    np.testing.assert_allclose(S, np.stack([rows[f"S_row_{i}"] for i in range(4)]), atol=1e-14)
+    np.testing.assert_allclose(O.phi(q, W) @ z, [rows["den_1"][0], rows["den_2"][0]], atol=1e-15)
