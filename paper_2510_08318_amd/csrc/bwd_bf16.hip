@@ -44,6 +44,9 @@ __device__ __forceinline__ void unpack_bf16x8(uint4 v, float* f) {
 // kernels copy them into LDS with coalesced 16-byte loads.
 //   grid (B*H, 8): slice blockIdx.y of the entries of (b,h); the workgroups of batch item 0 also
 //   build the W~ images of their head (WQK = true: both W~_q and W~_k images into wimg).
+//   WQK = true is the pass over S (image simg in the A-operand order of the query pass: the query
+//   side wants o on the lane's own token); WQK = false is the pass over dS, whose image is in the
+//   B-operand order of dv = phi(k) dS with the tokens on the accumulator rows.
 template <int D, bool WQK>
 __global__ __launch_bounds__(256) void bwd_prep_kernel(const float* __restrict__ state, uint4* __restrict__ gimg,
                                                        uint4* __restrict__ simg, float* __restrict__ scale_out,
@@ -81,7 +84,7 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(const float* __restrict__
   if (blockIdx.y == 0 && tid == 0) scale_out[2 * bh] = scale;
   const int first = blockIdx.y * 256 + tid, step = 256 * gridDim.y;
   for (int idx = first; idx < G::IMG; idx += step) gimg[(size_t)bh * G::IMG + idx] = grad_image_entry<D>(S, scale, idx);
-  for (int idx = first; idx < SIMG; idx += step) simg[(size_t)bh * SIMG + idx] = state_image_entry<D>(S, scale, idx);
+  for (int idx = first; idx < SIMG; idx += step) simg[(size_t)bh * SIMG + idx] = state_image_entry<D, !WQK>(S, scale, idx);
   if constexpr (WQK) {
     if (bh < H) {
       static_assert(C::W_IMG == WB_IMG, "the four W~ images have one size");
@@ -122,12 +125,29 @@ __device__ __forceinline__ void phi_jacobian(const float (&gp)[Cfg<D>::LOC], con
   for (int j = 0; j < C::LOC; ++j) du[j] = pp[j] * (gp[j] - cp) - pm[j] * (gm[j] - cm);
 }
 
-// dx^T = W~ du^T for one token block: du is scaled per token to [1,2), cast to fp16, contracted
-// with the W~ image, unscaled, rounded to bf16 and packed: xo[mb*8 .. mb*8+7] are the 16 channels
-// g*D/2 + 16*mb + r of the lane's token.
+// Maximum of x over the wavefront, given x already equal in lanes l and l^32: DPP steps inside each
+// row of 16 lanes, then the two rows of the low half are combined through scalar registers.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float wave_max_paired(float x) {
+  x = fmaxf(x, dpp_move<0xB1>(x));      // quad_perm [1,0,3,2]
+  x = fmaxf(x, dpp_move<0x4E>(x));      // quad_perm [2,3,0,1]
+  x = fmaxf(x, dpp_move<0x124>(x));     // row_ror 4
+  x = fmaxf(x, dpp_move<0x128>(x));     // row_ror 8
+  const float a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 0));
+  const float b = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 16));
+  return fmaxf(a, b);
+}
+
+// dx = du W~^T for one block of 32 tokens, tokens on the accumulator rows: du is scaled by one power
+// of two per block (its largest magnitude lands in [1,2)), cast to fp16 and fed as the A operand
+// (lane (t,g) holds features g*LOC + 8ks + e of token t); the B operands are the W~ image.
+// acc[mb][r] of lane (c,g) is its * dx[token 8*(r/4) + 4g + r%4][channel MB*c + mb].
 template <int D>
 __device__ __forceinline__ void du_to_dx(const float (&du)[Cfg<D>::LOC], const uint4* sWB, int lane,
-                                         uint32_t (&xo)[D / 4]) {
+                                         f32x16 (&acc)[D / 32], float& its) {
   using C = Cfg<D>;
   using L = ApplyLayout<D>;
   constexpr int DK = C::LOC / 8;
@@ -136,11 +156,10 @@ __device__ __forceinline__ void du_to_dx(const float (&du)[Cfg<D>::LOC], const u
   for (int j = 0; j < C::LOC; ++j) m = fmaxf(m, fabsf(du[j]));
   float lo, hi;
   pair32(m, lo, hi); m = fmaxf(lo, hi);
-  const float ts = pow2_normaliser(m);
+  const float ts = pow2_normaliser(wave_max_paired(m));
   uint32_t dub[C::LOC / 2];
 #pragma unroll
   for (int j = 0; j < C::LOC / 2; ++j) dub[j] = pack_f16x2(du[2 * j] * ts, du[2 * j + 1] * ts);
-  f32x16 acc[L::MB];
 #pragma unroll
   for (int mb = 0; mb < L::MB; ++mb)
 #pragma unroll
@@ -148,27 +167,45 @@ __device__ __forceinline__ void du_to_dx(const float (&du)[Cfg<D>::LOC], const u
   const uint4* wb = sWB + lane + opaque_zero();
 #pragma unroll
   for (int ks = 0; ks < DK; ++ks) {
-    uint4 bq; bq.x = dub[4 * ks]; bq.y = dub[4 * ks + 1]; bq.z = dub[4 * ks + 2]; bq.w = dub[4 * ks + 3];
-    const f16x8 bop = as_f16x8(bq);
+    uint4 aq; aq.x = dub[4 * ks]; aq.y = dub[4 * ks + 1]; aq.z = dub[4 * ks + 2]; aq.w = dub[4 * ks + 3];
+    const f16x8 aop = as_f16x8(aq);
 #pragma unroll
     for (int mb = 0; mb < L::MB; ++mb)
-      acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(wb[(ks * L::MB + mb) * 64]), bop, acc[mb], 0, 0, 0);
+      acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop, as_f16x8(wb[(ks * L::MB + mb) * 64]), acc[mb], 0, 0, 0);
   }
-  const float its = __builtin_amdgcn_rcpf(ts);     // exact: ts is a power of two
-#pragma unroll
-  for (int mb = 0; mb < L::MB; ++mb)
-#pragma unroll
-    for (int j = 0; j < 8; ++j) xo[mb * 8 + j] = pack_bf16x2(acc[mb][2 * j] * its, acc[mb][2 * j + 1] * its);
+  its = __builtin_amdgcn_rcpf(ts);     // exact: ts is a power of two
 }
 
-// The lane's half row (channels g*D/2 .. +D/2-1 of token t) as packed bf16: D/16 stores of 16 bytes.
+// Accumulators with tokens on the rows (lane (c,g), register r: token t0 + 8*(r/4) + 4g + r%4,
+// channels MB*c .. MB*c + MB-1 in acc[0..MB-1]) -> mul * acc as bf16 rows of base.  Every store
+// instruction writes two whole rows of d channels.
 template <int D>
-__device__ __forceinline__ void store_half_row(uint16_t* base, size_t row_offset, int g, const uint32_t (&xo)[D / 4]) {
-  uint4* row = reinterpret_cast<uint4*>(base + row_offset + g * (D / 2));
+__device__ __forceinline__ void store_token_rows(uint16_t* base, size_t sn, int t0, int n, int lane,
+                                                 const f32x16 (&acc)[D / 32], float mul) {
+  constexpr int MB = D / 32;
+  static_assert(MB == 2 || MB == 4, "head width 64 or 128");
+  const int c = lane % 32, g = lane / 32;
+  char* ub = reinterpret_cast<char*>(base + (size_t)t0 * sn);
+  const uint32_t lo = ((uint32_t)(4 * g) * (uint32_t)sn + (uint32_t)(MB * c)) * 2u;
+  auto put = [&](int r) {
+    const int row = 8 * (r / 4) + (r % 4);
+    char* dst = ub + (size_t)row * sn * 2 + lo;
+    if constexpr (MB == 4) {
+      uint2 v;
+      v.x = pack_bf16x2(acc[0][r] * mul, acc[1][r] * mul);
+      v.y = pack_bf16x2(acc[2][r] * mul, acc[3][r] * mul);
+      *reinterpret_cast<uint2*>(dst) = v;
+    } else {
+      *reinterpret_cast<uint32_t*>(dst) = pack_bf16x2(acc[0][r] * mul, acc[1][r] * mul);
+    }
+  };
+  if (t0 + 32 <= n) {
 #pragma unroll
-  for (int i = 0; i < D / 16; ++i) {
-    uint4 v; v.x = xo[4 * i]; v.y = xo[4 * i + 1]; v.z = xo[4 * i + 2]; v.w = xo[4 * i + 3];
-    row[i] = v;
+    for (int r = 0; r < 16; ++r) put(r);
+  } else {
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      if (t0 + 8 * (r / 4) + (r % 4) + 4 * g < n) put(r);
   }
 }
 
@@ -360,10 +397,13 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
     float du[C::LOC];
     phi_jacobian<D>(gp, gm, pp, pm, du);
 
-    uint32_t xo[D / 4];
-    du_to_dx<D>(du, sWB, lane, xo);
+    {
+      f32x16 xa[L::MB];
+      float its;
+      du_to_dx<D>(du, sWB, lane, xa, its);
+      store_token_rows<D>(dqb, rw.sn, tile * kTile + 32 * w, n, lane, xa, its);
+    }
     if (valid) {
-      store_half_row<D>(dqb, (size_t)t * rw.sn, g, xo);
       if (du_ws) {
         float4* drow = reinterpret_cast<float4*>(du_ws + ((size_t)bh * n + t) * C::HALF + g * C::LOC);
 #pragma unroll
@@ -527,7 +567,7 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
     uint32_t pk[C::NPK];
     softmax_full<D>(u, pp, pm, pk);
 
-    // dv = phi(k) dS on the lane's channels
+    // dv = phi(k) dS, tokens on the accumulator rows
     {
       f32x16 va[L::MB];
 #pragma unroll
@@ -537,18 +577,13 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
       const uint4* sva = sVA + lane + opaque_zero();
 #pragma unroll
       for (int ks = 0; ks < L::KS; ++ks) {
-        uint4 bq; bq.x = pk[4 * ks]; bq.y = pk[4 * ks + 1]; bq.z = pk[4 * ks + 2]; bq.w = pk[4 * ks + 3];
-        const f16x8 bop = as_f16x8(bq);
+        uint4 aq; aq.x = pk[4 * ks]; aq.y = pk[4 * ks + 1]; aq.z = pk[4 * ks + 2]; aq.w = pk[4 * ks + 3];
+        const f16x8 aop = as_f16x8(aq);
 #pragma unroll
         for (int mb = 0; mb < L::MB; ++mb)
-          va[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(sva[(ks * L::MBZ + mb) * 64]), bop, va[mb], 0, 0, 0);
+          va[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop, as_f16x8(sva[(ks * L::MBZ + mb) * 64]), va[mb], 0, 0, 0);
       }
-      uint32_t xo[D / 4];
-#pragma unroll
-      for (int mb = 0; mb < L::MB; ++mb)
-#pragma unroll
-        for (int j = 0; j < 8; ++j) xo[mb * 8 + j] = pack_bf16x2(va[mb][2 * j] * inv_scale, va[mb][2 * j + 1] * inv_scale);
-      if (valid) store_half_row<D>(dvb, (size_t)t * rw.sn, g, xo);
+      store_token_rows<D>(dvb, rw.sn, b * 32, n, lane, va, inv_scale);
     }
 
     // g = v dS^T + dz, rows laid out like phi
@@ -582,10 +617,13 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
     }
     float du[C::LOC];
     phi_jacobian<D>(gp, gm, pp, pm, du);
-    uint32_t xo[D / 4];
-    du_to_dx<D>(du, sWB, lane, xo);
+    {
+      f32x16 xa[L::MB];
+      float its;
+      du_to_dx<D>(du, sWB, lane, xa, its);
+      store_token_rows<D>(dkb, rw.sn, b * 32, n, lane, xa, its);
+    }
     if (valid) {
-      store_half_row<D>(dkb, (size_t)t * rw.sn, g, xo);
       if (du_ws) {
         float4* drow = reinterpret_cast<float4*>(du_ws + ((size_t)bh * n + t) * C::HALF + g * C::LOC);
 #pragma unroll

@@ -255,7 +255,9 @@ __device__ __forceinline__ float head_scale(const float* __restrict__ S, float* 
 // (contraction over the features of phi): entry (ks, mb, lane=(m,g)) holds
 // scale * S[feature(ks,g,e)][channel(mb,m)], e = 0..7; the extra row block mb = MB holds
 // scale * z[feature] in rows 0 and 4 (one per lane group) and zeros elsewhere.
-template <int D>
+// COLS: the same registers read as B operands of Y = phi S (lane (c,g) holds column c), with the
+// channels dealt out by ApplyLayout::channel_cols; the extra block is left zero.
+template <int D, bool COLS = false>
 __device__ __forceinline__ uint4 state_image_entry(const float* __restrict__ S, float scale, int idx) {
   using L = ApplyLayout<D>;
   const int lane = idx % 64, mb = (idx / 64) % L::MBZ, ks = idx / (64 * L::MBZ);
@@ -264,8 +266,8 @@ __device__ __forceinline__ uint4 state_image_entry(const float* __restrict__ S, 
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     const int f = L::feature(ks, g, e);
-    if (mb < L::MB) x[e] = scale * S[f * D + L::channel(mb, m)];
-    else x[e] = (m == 0 || m == 4) ? scale * S[D * D + f] : 0.f;
+    if (mb < L::MB) x[e] = scale * S[f * D + (COLS ? L::channel_cols(mb, m) : L::channel(mb, m))];
+    else x[e] = (!COLS && (m == 0 || m == 4)) ? scale * S[D * D + f] : 0.f;
   }
   uint4 r;
   r.x = pack_f16x2(x[0], x[1]); r.y = pack_f16x2(x[2], x[3]);
@@ -310,16 +312,16 @@ __device__ __forceinline__ uint4 grad_image_entry(const float* __restrict__ S, f
   return r;
 }
 
-// W~ [D][D/2] bf16 (one head) -> LDS image (fp16, exact) of the A operands of dX^T = W~ dU^T
-// (contraction over the d/2 pre-softmax features): entry (ks, mb, lane=(m,g)) holds
-// W~[channel(mb,m)][g*LOC + 8ks + e], e = 0..7; ks < LOC/8, mb < D/32.
+// W~ [D][D/2] bf16 (one head) -> LDS image (fp16, exact) of the B operands of dX = dU W~^T
+// (contraction over the d/2 pre-softmax features, tokens on the accumulator rows): entry
+// (ks, mb, lane=(c,g)) holds W~[channel_cols(mb,c)][g*LOC + 8ks + e], e = 0..7; ks < LOC/8, mb < D/32.
 template <int D>
 __device__ __forceinline__ uint4 w_image_t_entry(const uint16_t* __restrict__ w, int idx) {
   using C = Cfg<D>;
   using L = ApplyLayout<D>;
   const int lane = idx % 64, mb = (idx / 64) % L::MB, ks = idx / (64 * L::MB);
   const int m = lane % 32, g = lane / 32;
-  const uint16_t* row = w + L::channel(mb, m) * C::HALF + g * C::LOC + 8 * ks;
+  const uint16_t* row = w + L::channel_cols(mb, m) * C::HALF + g * C::LOC + 8 * ks;
   float x[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) x[e] = __builtin_bit_cast(float, (uint32_t)row[e] << 16);

@@ -70,6 +70,10 @@ struct ApplyLayout {
   }
   // Output channel carried by A-operand row m of row block mb.
   __device__ static constexpr int channel(int mb, int m) { return owned_row<D>(mb, m); }
+  // Output channel carried by B-operand column c of column block mb when the operands are swapped
+  // (Y = phi S, tokens on the accumulator rows): a lane then holds MB adjacent channels of each of
+  // its 16 token rows, and 32 lanes cover one whole row of d channels.
+  __device__ static constexpr int channel_cols(int mb, int c) { return MB * c + mb; }
 };
 
 }  // namespace linattn
