@@ -74,8 +74,15 @@ bool make_plan(int B, int H, int n, int d, int dtype, int layout, Plan* p) {
   r.off_drpart = off;   off = up(off + (size_t)BH * r.P * sizeof(float));
   r.bytes_no_wgrads = off;
   r.off_dwpart = off;   off = up(off + (size_t)BH * r.P * d * (d / 2) * sizeof(float));
-  r.off_du_q = off;     off = up(off + (size_t)BH * n * (d / 2) * sizeof(float));
-  r.off_du_k = off;     off = up(off + (size_t)BH * n * (d / 2) * sizeof(float));
+  {
+    // fp32 mode keeps dL/du as fp32 rows; bf16 mode keeps fp16 operand images of 32-token blocks,
+    // followed by one fp32 scale per block
+    const size_t nblk = ((size_t)n + 31) / 32;
+    r.du_bytes = dtype == LINATTN_BF16 ? up((size_t)BH * nblk * 32 * (d / 2) * 2) + (size_t)BH * nblk * sizeof(float)
+                                       : (size_t)BH * n * (d / 2) * sizeof(float);
+  }
+  r.off_du_q = off;     off = up(off + r.du_bytes);
+  r.off_du_k = off;     off = up(off + r.du_bytes);
   r.total_bytes = off;
   *p = r;
   return true;

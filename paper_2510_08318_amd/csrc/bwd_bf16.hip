@@ -145,21 +145,65 @@ __device__ __forceinline__ float wave_max_paired(float x) {
 // of two per block (its largest magnitude lands in [1,2)), cast to fp16 and fed as the A operand
 // (lane (t,g) holds features g*LOC + 8ks + e of token t); the B operands are the W~ image.
 // acc[mb][r] of lane (c,g) is its * dx[token 8*(r/4) + 4g + r%4][channel MB*c + mb].
+//
+// du_blk != nullptr: the scaled fp16 du of the block is also written out for the dW~ kernel, as the
+// B operands of a contraction over the tokens.  A second MFMA against 0/1 selection operands turns
+// it (exactly) so that a lane holds one feature and 16 tokens; entry (ks2, j, lane=(c,g)) of the
+// block's image holds feature 32j + c of tokens 16*ks2 + {4g .. 4g+3, 8+4g .. 8+4g+3}.  Rows of
+// tokens that do not exist are zero.  *du_its receives the inverse scale (0 for an all-zero block).
 template <int D>
-__device__ __forceinline__ void du_to_dx(const float (&du)[Cfg<D>::LOC], const uint4* sWB, int lane,
-                                         f32x16 (&acc)[D / 32], float& its) {
+__device__ __forceinline__ void du_to_dx(const float (&du)[Cfg<D>::LOC], const uint4* sWB, int lane, bool valid,
+                                         uint4* du_blk, float* du_its, f32x16 (&acc)[D / 32], float& its) {
   using C = Cfg<D>;
   using L = ApplyLayout<D>;
   constexpr int DK = C::LOC / 8;
   float m = 0.f;
 #pragma unroll
   for (int j = 0; j < C::LOC; ++j) m = fmaxf(m, fabsf(du[j]));
+  if (!valid) m = 0.f;
   float lo, hi;
   pair32(m, lo, hi); m = fmaxf(lo, hi);
-  const float ts = pow2_normaliser(wave_max_paired(m));
+  m = wave_max_paired(m);
+  const float ts = valid ? pow2_normaliser(m) : 0.f;
   uint32_t dub[C::LOC / 2];
 #pragma unroll
   for (int j = 0; j < C::LOC / 2; ++j) dub[j] = pack_f16x2(du[2 * j] * ts, du[2 * j + 1] * ts);
+  its = __builtin_amdgcn_rcpf(pow2_normaliser(m));     // exact: a power of two
+  if (du_blk) {
+    constexpr int NB = C::HALF / 32;
+    const int c = lane % 32, g = lane / 32;
+    f32x16 ta[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) ta[j][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < DK; ++ks) {
+      uint4 aq; aq.x = dub[4 * ks]; aq.y = dub[4 * ks + 1]; aq.z = dub[4 * ks + 2]; aq.w = dub[4 * ks + 3];
+      const f16x8 aop = as_f16x8(aq);
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        // B[k = 8g + e][column c] = 1 where the feature behind row k, g*LOC + 8ks + e, is 32j + c
+        const int f = 32 * j + c, rem = f % C::LOC;
+        const uint32_t one = (g == f / C::LOC) ? ((rem & 1) ? 0x3C000000u : 0x00003C00u) : 0u;
+        const int slot = (rem >> 1) - 4 * ks;
+        uint4 sq;
+        sq.x = slot == 0 ? one : 0u; sq.y = slot == 1 ? one : 0u;
+        sq.z = slot == 2 ? one : 0u; sq.w = slot == 3 ? one : 0u;
+        ta[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop, as_f16x8(sq), ta[j], 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        uint4 o;
+        o.x = pack_f16x2(ta[j][8 * ks2], ta[j][8 * ks2 + 1]);     o.y = pack_f16x2(ta[j][8 * ks2 + 2], ta[j][8 * ks2 + 3]);
+        o.z = pack_f16x2(ta[j][8 * ks2 + 4], ta[j][8 * ks2 + 5]); o.w = pack_f16x2(ta[j][8 * ks2 + 6], ta[j][8 * ks2 + 7]);
+        du_blk[(ks2 * NB + j) * 64 + lane] = o;
+      }
+    if (lane == 0) *du_its = m > 0.f ? its : 0.f;
+  }
 #pragma unroll
   for (int mb = 0; mb < L::MB; ++mb)
 #pragma unroll
@@ -173,7 +217,6 @@ __device__ __forceinline__ void du_to_dx(const float (&du)[Cfg<D>::LOC], const u
     for (int mb = 0; mb < L::MB; ++mb)
       acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop, as_f16x8(wb[(ks * L::MB + mb) * 64]), acc[mb], 0, 0, 0);
   }
-  its = __builtin_amdgcn_rcpf(ts);     // exact: ts is a power of two
 }
 
 // Accumulators with tokens on the rows (lane (c,g), register r: token t0 + 8*(r/4) + 4g + r%4,
@@ -218,7 +261,7 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
                                                    const uint4* __restrict__ gimg, const uint4* __restrict__ simg,
                                                    const uint4* __restrict__ wimg, const float* __restrict__ scales,
                                                    uint16_t* __restrict__ dq,
-                                                   float* __restrict__ partials, float* __restrict__ du_ws,
+                                                   float* __restrict__ partials, uint4* __restrict__ du_img, float* __restrict__ du_its,
                                                    const uint16_t* __restrict__ blend, const float* __restrict__ rptr,
                                                    float* __restrict__ dr_part,
                                                    int H, int n, int P, Rows rw) {
@@ -229,6 +272,7 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
   constexpr int WMN = D / 64;
   constexpr int SA_IMG = L::KS * L::MBZ * 64;
   constexpr int WB_IMG = (C::LOC / 8) * L::MB * 64;
+  constexpr int DU_BLK = 2 * (C::HALF / 32) * 64;          // 16-byte entries of one block's du image
   extern __shared__ uint4 smem[];
   uint4* sWA = smem;
   uint4* sSA = sWA + C::W_IMG;
@@ -253,6 +297,7 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
   const float* sb = state + (size_t)bh * (D + 1) * D;
   const uint4* gim = gimg + (size_t)bh * G::IMG;
   const int ntile = (n + kTile - 1) / kTile;
+  const int nblk = (n + 31) / 32;
 
   copy_image<NT>(wimg + (size_t)h * 4 * C::W_IMG, sWA, C::W_IMG, tid);
   copy_image<NT>(wimg + (size_t)h * 4 * C::W_IMG + C::W_IMG, sWB, WB_IMG, tid);
@@ -364,6 +409,42 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
     pair32(dmax, lo, hi); dmax = fmaxf(lo, hi);
     const float stok = pow2_normaliser(dmax);
 
+    // operands of the sums over tokens, parked now so that phi and dO need not stay in registers
+    // through the rest of the block
+    if (tile == p) {
+      float m = valid ? dmax * inv_den * om : 0.f;
+      for (int k = 32; k >= 1; k >>= 1) m = fmaxf(m, __shfl_xor(m, k, 64));
+      if (lane == 0) sRed[w] = m;
+      __syncthreads();
+      m = fmaxf(fmaxf(sRed[0], sRed[1]), fmaxf(sRed[2], sRed[3]));
+      gamma = 16.f * pow2_normaliser(m);
+    }
+    __syncthreads();                             // previous tile's operand reads are done
+    {
+      char* rowp = sPhi + prow * RS;
+      constexpr int CPH = C::LOC / 8;
+#pragma unroll
+      for (int c = 0; c < CPH; ++c) {
+        uint4 a, b;
+        a.x = pk[4 * c]; a.y = pk[4 * c + 1]; a.z = pk[4 * c + 2]; a.w = pk[4 * c + 3];
+        b.x = pk[C::LOC / 2 + 4 * c]; b.y = pk[C::LOC / 2 + 4 * c + 1];
+        b.z = pk[C::LOC / 2 + 4 * c + 2]; b.w = pk[C::LOC / 2 + 4 * c + 3];
+        if (!valid) { a = make_uint4(0, 0, 0, 0); b = a; }
+        *reinterpret_cast<uint4*>(rowp + (((g * CPH + c) ^ psw) * 16)) = a;
+        *reinterpret_cast<uint4*>(rowp + (((C::CH / 2 + g * CPH + c) ^ psw) * 16)) = b;
+      }
+      const float sc = valid ? inv_den * gamma * om : 0.f;
+      char* drowp = sDO + prow * RS;
+#pragma unroll
+      for (int c = 0; c < D / 16; ++c) {
+        uint4 a;
+        a.x = pack_f16x2(dof[8 * c] * sc, dof[8 * c + 1] * sc);     a.y = pack_f16x2(dof[8 * c + 2] * sc, dof[8 * c + 3] * sc);
+        a.z = pack_f16x2(dof[8 * c + 4] * sc, dof[8 * c + 5] * sc); a.w = pack_f16x2(dof[8 * c + 6] * sc, dof[8 * c + 7] * sc);
+        *reinterpret_cast<uint4*>(drowp + (((g * (C::CH / 2) + c) ^ psw) * 16)) = a;
+      }
+      if (g == 0) sW16[prow] = (uint16_t)(pack_f16x2(valid ? -delta * sc : 0.f, 0.f) & 0xffffu);
+    }
+
     // g = (dO S^T - delta z) / den, rows laid out like phi
     float gp[C::LOC], gm[C::LOC];
     {
@@ -400,51 +481,13 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
     {
       f32x16 xa[L::MB];
       float its;
-      du_to_dx<D>(du, sWB, lane, xa, its);
-      store_token_rows<D>(dqb, rw.sn, tile * kTile + 32 * w, n, lane, xa, its);
-    }
-    if (valid) {
-      if (du_ws) {
-        float4* drow = reinterpret_cast<float4*>(du_ws + ((size_t)bh * n + t) * C::HALF + g * C::LOC);
-#pragma unroll
-        for (int i = 0; i < C::LOC / 4; ++i) drow[i] = make_float4(du[4 * i], du[4 * i + 1], du[4 * i + 2], du[4 * i + 3]);
-      }
+      const int blk = tile * (kTile / 32) + w;
+      const bool keep = du_img != nullptr && blk * 32 < n;
+      du_to_dx<D>(du, sWB, lane, valid, keep ? du_img + ((size_t)bh * nblk + blk) * DU_BLK : nullptr,
+                  du_its + (size_t)bh * nblk + blk, xa, its);
+      store_token_rows<D>(dqb, rw.sn, blk * 32, n, lane, xa, its);
     }
 
-    // operands of the sums over tokens
-    if (tile == p) {
-      float m = valid ? dmax * inv_den * om : 0.f;
-      for (int k = 32; k >= 1; k >>= 1) m = fmaxf(m, __shfl_xor(m, k, 64));
-      if (lane == 0) sRed[w] = m;
-      __syncthreads();
-      m = fmaxf(fmaxf(sRed[0], sRed[1]), fmaxf(sRed[2], sRed[3]));
-      gamma = 16.f * pow2_normaliser(m);
-    }
-    __syncthreads();                             // previous tile's operand reads are done
-    {
-      char* rowp = sPhi + prow * RS;
-      constexpr int CPH = C::LOC / 8;
-#pragma unroll
-      for (int c = 0; c < CPH; ++c) {
-        uint4 a, b;
-        a.x = pk[4 * c]; a.y = pk[4 * c + 1]; a.z = pk[4 * c + 2]; a.w = pk[4 * c + 3];
-        b.x = pk[C::LOC / 2 + 4 * c]; b.y = pk[C::LOC / 2 + 4 * c + 1];
-        b.z = pk[C::LOC / 2 + 4 * c + 2]; b.w = pk[C::LOC / 2 + 4 * c + 3];
-        if (!valid) { a = make_uint4(0, 0, 0, 0); b = a; }
-        *reinterpret_cast<uint4*>(rowp + (((g * CPH + c) ^ psw) * 16)) = a;
-        *reinterpret_cast<uint4*>(rowp + (((C::CH / 2 + g * CPH + c) ^ psw) * 16)) = b;
-      }
-      const float sc = valid ? inv_den * gamma * om : 0.f;
-      char* drowp = sDO + prow * RS;
-#pragma unroll
-      for (int c = 0; c < D / 16; ++c) {
-        uint4 a;
-        a.x = pack_f16x2(dof[8 * c] * sc, dof[8 * c + 1] * sc);     a.y = pack_f16x2(dof[8 * c + 2] * sc, dof[8 * c + 3] * sc);
-        a.z = pack_f16x2(dof[8 * c + 4] * sc, dof[8 * c + 5] * sc); a.w = pack_f16x2(dof[8 * c + 6] * sc, dof[8 * c + 7] * sc);
-        *reinterpret_cast<uint4*>(drowp + (((g * (C::CH / 2) + c) ^ psw) * 16)) = a;
-      }
-      if (g == 0) sW16[prow] = (uint16_t)(pack_f16x2(valid ? -delta * sc : 0.f, 0.f) & 0xffffu);
-    }
     __syncthreads();
 #pragma unroll
     for (int ks = 0; ks < kTile / 16; ++ks) {
@@ -502,13 +545,14 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
                                                     const uint4* __restrict__ dsimg, const uint4* __restrict__ dgimg,
                                                     const uint4* __restrict__ wimg, const float* __restrict__ scales,
                                                     uint16_t* __restrict__ dk, uint16_t* __restrict__ dv,
-                                                    float* __restrict__ du_ws, int H, int n, Rows rw) {
+                                                    uint4* __restrict__ du_img, float* __restrict__ du_its, int H, int n, Rows rw) {
   using C = Cfg<D>;
   using L = ApplyLayout<D>;
   using G = GradLayout<D>;
   constexpr int NW = NTK / 64;
   constexpr int SA_IMG = L::KS * L::MBZ * 64;
   constexpr int WB_IMG = (C::LOC / 8) * L::MB * 64;
+  constexpr int DU_BLK = 2 * (C::HALF / 32) * 64;          // 16-byte entries of one block's du image
   extern __shared__ uint4 smem[];
   uint4* sWA = smem;
   uint4* sVA = sWA + C::W_IMG;             // image of dS^T for dv (contraction over features)
@@ -538,7 +582,7 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
 
   const int nblk = (n + 31) / 32;
   const int stride = gridDim.x * NW;
-  uint4 xk[C::UK], vr[D / 16], vnext[D / 16];
+  uint4 xk[C::UK], vr[D / 16];
   auto load_k = [&](int b) {
     const int t = b * 32 + (lane % 32);
     const int tc = t < n ? t : (n - 1);
@@ -551,18 +595,17 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
     const int tc = t < n ? t : (n - 1);
     const uint4* vrow = reinterpret_cast<const uint4*>(vb + (size_t)tc * rw.sn + g * (D / 2));
 #pragma unroll
-    for (int i = 0; i < D / 16; ++i) vnext[i] = vrow[i];
+    for (int i = 0; i < D / 16; ++i) vr[i] = vrow[i];
   };
   int b = blockIdx.x * NW + w;
-  if (b < nblk) { load_k(b); load_v(b); }
+  if (b < nblk) load_k(b);
   for (; b < nblk; b += stride) {
     const int t = b * 32 + (lane % 32);
     const bool valid = t < n;
-#pragma unroll
-    for (int i = 0; i < D / 16; ++i) vr[i] = vnext[i];
+    load_v(b);                                        // wanted after the projection, the softmax and dv
     f32x16 u[C::UM];
     project<D>(xk, sWA, lane, u);
-    if (b + stride < nblk) { load_k(b + stride); load_v(b + stride); }   // next block flies during this one
+    if (b + stride < nblk) load_k(b + stride);        // next block's k flies during this one
     float pp[C::LOC], pm[C::LOC];
     uint32_t pk[C::NPK];
     softmax_full<D>(u, pp, pm, pk);
@@ -620,59 +663,58 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
     {
       f32x16 xa[L::MB];
       float its;
-      du_to_dx<D>(du, sWB, lane, xa, its);
+      du_to_dx<D>(du, sWB, lane, valid, du_img ? du_img + ((size_t)bh * nblk + b) * DU_BLK : nullptr,
+                  du_its + (size_t)bh * nblk + b, xa, its);
       store_token_rows<D>(dkb, rw.sn, b * 32, n, lane, xa, its);
-    }
-    if (valid) {
-      if (du_ws) {
-        float4* drow = reinterpret_cast<float4*>(du_ws + ((size_t)bh * n + t) * C::HALF + g * C::LOC);
-#pragma unroll
-        for (int i = 0; i < C::LOC / 4; ++i) drow[i] = make_float4(du[4 * i], du[4 * i + 1], du[4 * i + 2], du[4 * i + 3]);
-      }
     }
   }
 }
 
 // ---- dW~ = sum_{b, i} x_i^T du_i on MFMA -----------------------------------------------------
-// x [BH][n][D] bf16, du [BH][n][D/2] fp32 (written by the kernels above).  Per 128-token tile both
-// are parked in LDS as fp16 (du times one power of two per workgroup, taken from its first tile)
-// and contracted over the tokens with transposing reads; wavefront w owns the channel rows
-// 32w .. 32w+31.  Partials per (b,h) and split are reduced in a fixed order afterwards.
+// x [BH][n][D] bf16; du as written by du_to_dx: per 32-token block the fp16 B operands of the
+// contraction over the tokens, scaled by a power of two per block, with the inverse scales in
+// du_its.  Per 128-token tile x is parked in LDS as fp16 and read with transposing reads in the
+// token order of the du operands, which come straight from global memory and are brought to one
+// common power-of-two scale per workgroup (taken from its first tile).  Wavefront w owns the
+// feature block w % NB and RB 32-channel row blocks.  Partials per (b,h) and split are reduced in
+// a fixed order afterwards.
 template <int D>
-__global__ __launch_bounds__(NT) void dw_mfma_kernel(const uint16_t* __restrict__ x, const float* __restrict__ du,
+__global__ __launch_bounds__(NT) void dw_mfma_kernel(const uint16_t* __restrict__ x, const uint4* __restrict__ du_img,
+                                                     const float* __restrict__ du_its,
                                                      float* __restrict__ part, int H, int n, int P, Rows rw) {
   constexpr int HALF = D / 2;
-  constexpr int RSX = D * 2, RSU = HALF * 2;
+  constexpr int RSX = D * 2;
   constexpr int NB = HALF / 32;                 // 32-column blocks of du
+  constexpr int RB = D / 64;                    // row blocks per wavefront
   constexpr int XPT = (kTile * (D / 8)) / NT;   // 16-byte chunks of the x tile per thread
-  constexpr int UPT = (kTile * (HALF / 8)) / NT;
+  constexpr int BPT = kTile / 32;               // du blocks per tile
+  constexpr int DU_BLK = 2 * NB * 64;
   __shared__ __attribute__((aligned(16))) char sX[kTile * RSX];
-  __shared__ __attribute__((aligned(16))) char sU[kTile * RSU];
-  __shared__ float sRed[4];
   const int tid = threadIdx.x, lane = tid % 64;
   const int w = __builtin_amdgcn_readfirstlane(tid / 64);
   const int g = lane / 32;
   const int bh = blockIdx.y, p = blockIdx.x;
   const uint16_t* xb = x + head_base(rw, bh, H);
-  const float* ub = du + (size_t)bh * n * HALF;
   const int ntile = (n + kTile - 1) / kTile;
-  const bool active = w < D / 32;
+  const int nblk = (n + 31) / 32;
+  const uint4* ub = du_img + (size_t)bh * nblk * DU_BLK + lane;
+  const float* sb = du_its + (size_t)bh * nblk;
+  const int fb = w % NB, row0 = (w / NB) * RB;
+  const bool active = row0 < D / 32;
 
-  f32x16 acc[NB];
+  f32x16 acc[RB];
 #pragma unroll
-  for (int j = 0; j < NB; ++j)
+  for (int j = 0; j < RB; ++j)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
-  int offA[2], offB[NB][2];
+  int offA[RB][2];
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    offA[j] = tr_offset<D>(32 * (active ? w : 0), lane, j);
+  for (int i = 0; i < RB; ++i)
 #pragma unroll
-    for (int b = 0; b < NB; ++b) offB[b][j] = tr_offset<HALF>(32 * b, lane, j);
-  }
+    for (int j = 0; j < 2; ++j) offA[i][j] = tr_offset_g4<D>(32 * (active ? row0 + i : 0), lane, j);
   float gamma = 1.f;
-  uint4 xr[XPT];
-  float4 ur[UPT][2];
+  uint4 xr[XPT], ur[2 * BPT];
+  float its[BPT];
   // the next tile's rows are requested while the current one is contracted
   auto load_tile = [&](int tile) {
     const int t0 = tile * kTile;
@@ -683,12 +725,13 @@ __global__ __launch_bounds__(NT) void dw_mfma_kernel(const uint16_t* __restrict_
       xr[i] = t < n ? ld_nt(reinterpret_cast<const uint4*>(xb + (size_t)t * rw.sn) + c) : make_uint4(0, 0, 0, 0);
     }
 #pragma unroll
-    for (int i = 0; i < UPT; ++i) {
-      const int idx = tid + NT * i, r = idx / (HALF / 8), c = idx % (HALF / 8);
-      const int t = t0 + r;
-      const float4* src = reinterpret_cast<const float4*>(ub + (size_t)t * HALF) + 2 * c;
-      ur[i][0] = t < n ? src[0] : make_float4(0.f, 0.f, 0.f, 0.f);
-      ur[i][1] = t < n ? src[1] : make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int i = 0; i < BPT; ++i) {
+      const int blk = tile * BPT + i;
+      const bool there = blk < nblk;
+      its[i] = there ? sb[blk] : 0.f;
+#pragma unroll
+      for (int ks2 = 0; ks2 < 2; ++ks2)
+        ur[2 * i + ks2] = there ? ub[((size_t)blk * 2 * NB + ks2 * NB + fb) * 64] : make_uint4(0, 0, 0, 0);
     }
   };
   if (p < ntile) load_tile(p);
@@ -696,15 +739,8 @@ __global__ __launch_bounds__(NT) void dw_mfma_kernel(const uint16_t* __restrict_
     if (tile == p) {
       float m = 0.f;
 #pragma unroll
-      for (int i = 0; i < UPT; ++i)
-#pragma unroll
-        for (int k2 = 0; k2 < 2; ++k2)
-          m = fmaxf(m, fmaxf(fmaxf(fabsf(ur[i][k2].x), fabsf(ur[i][k2].y)), fmaxf(fabsf(ur[i][k2].z), fabsf(ur[i][k2].w))));
-      for (int k2 = 32; k2 >= 1; k2 >>= 1) m = fmaxf(m, __shfl_xor(m, k2, 64));
-      if (lane == 0) sRed[w] = m;
-      __syncthreads();
-      m = fmaxf(fmaxf(sRed[0], sRed[1]), fmaxf(sRed[2], sRed[3]));
-      gamma = 16.f * pow2_normaliser(m);
+      for (int i = 0; i < BPT; ++i) m = fmaxf(m, its[i]);
+      gamma = m > 0.f ? 16.f * __builtin_amdgcn_rcpf(m) : 1.f;      // m is a power of two
     }
     __syncthreads();                              // previous tile's operand reads are done
 #pragma unroll
@@ -715,24 +751,22 @@ __global__ __launch_bounds__(NT) void dw_mfma_kernel(const uint16_t* __restrict_
       hv.z = bf16x2_to_f16x2(xr[i].z); hv.w = bf16x2_to_f16x2(xr[i].w);
       *reinterpret_cast<uint4*>(sX + r * RSX + ((c ^ swz<D>(r)) * 16)) = hv;
     }
+    f16x8 bo[2 * BPT];
 #pragma unroll
-    for (int i = 0; i < UPT; ++i) {
-      const int idx = tid + NT * i, r = idx / (HALF / 8), c = idx % (HALF / 8);
-      uint4 hv;
-      hv.x = pack_f16x2(ur[i][0].x * gamma, ur[i][0].y * gamma); hv.y = pack_f16x2(ur[i][0].z * gamma, ur[i][0].w * gamma);
-      hv.z = pack_f16x2(ur[i][1].x * gamma, ur[i][1].y * gamma); hv.w = pack_f16x2(ur[i][1].z * gamma, ur[i][1].w * gamma);
-      *reinterpret_cast<uint4*>(sU + r * RSU + ((c ^ swz<HALF>(r)) * 16)) = hv;
+    for (int i = 0; i < BPT; ++i) {
+      const _Float16 f = (_Float16)(gamma * its[i]);        // a power of two, or 0 for an all-zero block
+#pragma unroll
+      for (int ks2 = 0; ks2 < 2; ++ks2) bo[2 * i + ks2] = as_f16x8(ur[2 * i + ks2]) * f;
     }
     if (tile + P < ntile) load_tile(tile + P);
     __syncthreads();
     if (active) {
 #pragma unroll
       for (int ks = 0; ks < kTile / 16; ++ks) {
-        const f16x8 a = read_tr(sX + ks * 16 * RSX, offA[0], offA[1]);
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
-          const f16x8 bo = read_tr(sU + ks * 16 * RSU, offB[b][0], offB[b][1]);
-          acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bo, acc[b], 0, 0, 0);
+        for (int i = 0; i < RB; ++i) {
+          const f16x8 a = read_tr(sX + ks * 16 * RSX, offA[i][0], offA[i][1]);
+          acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bo[ks], acc[i], 0, 0, 0);
         }
       }
     }
@@ -742,10 +776,10 @@ __global__ __launch_bounds__(NT) void dw_mfma_kernel(const uint16_t* __restrict_
     float* dst = part + ((size_t)bh * P + p) * (size_t)D * HALF;
     const int c = lane % 32;
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
+    for (int i = 0; i < RB; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r)
-        dst[(32 * w + 8 * (r / 4) + 4 * g + (r % 4)) * HALF + 32 * b + c] = acc[b][r] * ig;
+        dst[(32 * (row0 + i) + 8 * (r / 4) + 4 * g + (r % 4)) * HALF + 32 * fb + c] = acc[i][r] * ig;
   }
 }
 
@@ -767,6 +801,12 @@ hipError_t set_smem(K kernel, size_t bytes) {
 template <int D>
 hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   hipError_t e;
+  // a dL/du region: the blocks' operand images, then (256-byte aligned) one inverse scale per block
+  const size_t du_img_bytes = ((size_t)p.BH * ((p.n + 31) / 32) * 32 * (D / 2) * 2 + 255) & ~(size_t)255;
+  uint4* duq = reinterpret_cast<uint4*>(a.du_q);
+  uint4* duk = reinterpret_cast<uint4*>(a.du_k);
+  float* duq_its = reinterpret_cast<float*>(reinterpret_cast<char*>(a.du_q) + du_img_bytes);
+  float* duk_its = reinterpret_cast<float*>(reinterpret_cast<char*>(a.du_k) + du_img_bytes);
   if ((e = set_smem(bwd_prep_kernel<D, true>, prep_smem_bytes<D>())) != hipSuccess) return e;
   if ((e = set_smem(bwd_prep_kernel<D, false>, prep_smem_bytes<D>())) != hipSuccess) return e;
   bwd_prep_kernel<D, true><<<dim3(p.BH, 8), 256, prep_smem_bytes<D>(), s>>>(a.state, (uint4*)a.gimg, (uint4*)a.simg, a.scales,
@@ -777,7 +817,7 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
     bwd_q_kernel<D, true><<<dim3(p.P, p.BH), NT, q_smem<D>(), s>>>(
         (const uint16_t*)a.q, (const uint16_t*)a.dout, (const uint16_t*)a.wq, a.state, (const uint4*)a.gimg,
         (const uint4*)a.simg, (const uint4*)a.wimg, a.scales,
-        (uint16_t*)a.dq, a.partials, a.dwq ? a.du_q : nullptr,
+        (uint16_t*)a.dq, a.partials, a.dwq ? duq : nullptr, duq_its,
         (const uint16_t*)a.blend_in, a.blend_r, a.dr_part, p.H, p.n, p.P, p.rows);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (a.blend_dr && (e = launch_dr_reduce(a.dr_part, p.BH * p.P, a.blend_r, a.blend_dr, s)) != hipSuccess) return e;
@@ -786,7 +826,7 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
     bwd_q_kernel<D, false><<<dim3(p.P, p.BH), NT, q_smem<D>(), s>>>(
         (const uint16_t*)a.q, (const uint16_t*)a.dout, (const uint16_t*)a.wq, a.state, (const uint4*)a.gimg,
         (const uint4*)a.simg, (const uint4*)a.wimg, a.scales,
-        (uint16_t*)a.dq, a.partials, a.dwq ? a.du_q : nullptr, nullptr, nullptr, nullptr, p.H, p.n, p.P, p.rows);
+        (uint16_t*)a.dq, a.partials, a.dwq ? duq : nullptr, duq_its, nullptr, nullptr, nullptr, p.H, p.n, p.P, p.rows);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if ((e = launch_state_reduce(a.partials, a.dstate, p, s)) != hipSuccess) return e;
@@ -798,15 +838,15 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   bwd_k_kernel<D><<<dim3(p.KP, p.BH), NTK, k_smem<D>(), s>>>(
       (const uint16_t*)a.k, (const uint16_t*)a.v, (const uint16_t*)a.wk, a.dstate,
       (const uint4*)a.dsimg, (const uint4*)a.dgimg, (const uint4*)a.wimg, a.scales,
-      (uint16_t*)a.dk, (uint16_t*)a.dv, a.dwk ? a.du_k : nullptr, p.H, p.n, p.rows);
+      (uint16_t*)a.dk, (uint16_t*)a.dv, a.dwk ? duk : nullptr, duk_its, p.H, p.n, p.rows);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (a.dwq) {
-    dw_mfma_kernel<D><<<dim3(p.P, p.BH), NT, 0, s>>>((const uint16_t*)a.q, a.du_q, a.dw_part, p.H, p.n, p.P, p.rows);
+    dw_mfma_kernel<D><<<dim3(p.P, p.BH), NT, 0, s>>>((const uint16_t*)a.q, duq, duq_its, a.dw_part, p.H, p.n, p.P, p.rows);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if ((e = launch_dw_reduce(a.dw_part, a.dwq, p, s)) != hipSuccess) return e;
   }
   if (a.dwk) {
-    dw_mfma_kernel<D><<<dim3(p.P, p.BH), NT, 0, s>>>((const uint16_t*)a.k, a.du_k, a.dw_part, p.H, p.n, p.P, p.rows);
+    dw_mfma_kernel<D><<<dim3(p.P, p.BH), NT, 0, s>>>((const uint16_t*)a.k, duk, duk_its, a.dw_part, p.H, p.n, p.P, p.rows);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if ((e = launch_dw_reduce(a.dw_part, a.dwk, p, s)) != hipSuccess) return e;
   }

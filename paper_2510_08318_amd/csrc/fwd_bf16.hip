@@ -207,17 +207,6 @@ __device__ __forceinline__ int turned_feature(int fb, int n) {
   return half * (D / 2) + ((n % 16) / 8) * (D / 4) + 8 * (2 * b + n / 16) + (n % 8);
 }
 
-// Byte offset of this lane's address for a transposing read of the V operand of k-step 0 in the
-// token order of the turned phi: j = 0: tile rows 4g .. 4g+3, j = 1: rows 8+4g .. 8+4g+3
-// (g = lane/32); columns col0 + lane%32.
-template <int D>
-__device__ __forceinline__ int tr_offset_g4(int col0, int lane, int j) {
-  constexpr int RS = D * 2;
-  const int r = 4 * (lane / 32) + ((lane % 16) / 4) + 8 * j;
-  const int col = col0 + 16 * ((lane / 16) % 2) + 4 * (lane % 4);
-  return r * RS + (((col / 8) ^ swz<D>(r)) * 16) + (col % 8) * 2;
-}
-
 // One segment of a workgroup's tile range: tiles tile0 .. tile0+nt-1 of one (b,h), whose K and V
 // rows start at kb, vb and whose W~_k is wkh; the partial state goes to dst.  Every thread of the
 // workgroup calls it (it contains workgroup barriers).

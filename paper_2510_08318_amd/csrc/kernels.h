@@ -71,8 +71,11 @@ struct Plan {
   size_t off_scales;      // fp32 [BH][2]         power-of-two scales of the S and dS images
   size_t off_drpart;      // fp32 [BH][P]         per-workgroup parts of dL/dr (mixed attention, Eq. 6)
   size_t off_dwpart;      // fp32 [BH][P][d*d/2]  partial dW~           (weight gradients only)
-  size_t off_du_q;        // fp32 [BH][n][d/2]    dL/du of the query side (weight gradients only)
-  size_t off_du_k;        // fp32 [BH][n][d/2]    dL/du of the key side   (weight gradients only)
+  size_t du_bytes;        // bytes of one dL/du region
+  size_t off_du_q;        // dL/du of the query side (weight gradients only): fp32 [BH][n][d/2] in fp32 mode;
+                          // in bf16 mode fp16 [BH][ceil(n/32)][32*d/2] operand images of 32-token blocks, each
+                          // scaled by a power of two, then (256-byte aligned) fp32 [BH][ceil(n/32)] inverse scales
+  size_t off_du_k;        // the same for the key side
   size_t bytes_no_wgrads; // workspace needed by forward and by backward without dW~
   size_t total_bytes;
 };

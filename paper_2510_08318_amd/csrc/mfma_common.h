@@ -353,6 +353,17 @@ __device__ __forceinline__ int tr_offset(int col0, int lane, int j) {
   return r * RS + (((col / 8) ^ swz<D>(r)) * 16) + (col % 8) * 2;
 }
 
+// Byte offset of this lane's address for a transposing read of an operand of k-step 0 in the
+// token order of a turned operand (the 16 tokens behind a lane's accumulator registers):
+// j = 0: tile rows 4g .. 4g+3, j = 1: rows 8+4g .. 8+4g+3 (g = lane/32); columns col0 + lane%32.
+template <int D>
+__device__ __forceinline__ int tr_offset_g4(int col0, int lane, int j) {
+  constexpr int RS = D * 2;
+  const int r = 4 * (lane / 32) + ((lane % 16) / 4) + 8 * j;
+  const int col = col0 + 16 * ((lane / 16) % 2) + 4 * (lane % 4);
+  return r * RS + (((col / 8) ^ swz<D>(r)) * 16) + (col % 8) * 2;
+}
+
 __device__ __forceinline__ f16x8 read_tr(const char* tile, int off0, int off1) {
   struct { s16x4 lo, hi; } v;
   v.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(tile + off0));
