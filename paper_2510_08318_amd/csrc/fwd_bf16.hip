@@ -23,12 +23,27 @@ namespace {
 // ------------------------------------------------------------------------------------------
 // Query pass.  A wavefront owns 32-token blocks b = p*NW + w, stepping by (gridDim.x * NW), so
 // the workgroups of a head sweep its tokens together.  Per block: load Q rows straight into the
-// B operand, phi, out^T = S^T phi^T (+ the z row block for the normaliser), scale, bf16, then a
-// wavefront-private LDS transpose so that every store instruction writes whole 256-byte rows.
+// B operand of the projection (a lane owns a token), phi; phi then is the A operand of
+// out = phi S, which puts the tokens on the accumulator rows and the channels on the lanes: a lane
+// holds MB adjacent channels of 16 tokens and every store instruction writes two whole rows.  One
+// more column block of the S image carries z in every column, so the same lanes get phi . z.
+template <int MB> struct RowPiece;
+template <> struct RowPiece<4> { typedef uint2 type; };
+template <> struct RowPiece<2> { typedef uint32_t type; };
+__device__ __forceinline__ uint32_t piece_word(const uint2& p, int i) { return i ? p.y : p.x; }
+__device__ __forceinline__ uint32_t piece_word(const uint32_t& p, int) { return p; }
+__device__ __forceinline__ void set_piece_word(uint2& p, int i, uint32_t v) { if (i) p.y = v; else p.x = v; }
+__device__ __forceinline__ void set_piece_word(uint32_t& p, int, uint32_t v) { p = v; }
+__device__ __forceinline__ void st_nt(uint2* p, uint2 v) {
+  typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+  __builtin_nontemporal_store(__builtin_bit_cast(u32x2, v), reinterpret_cast<u32x2*>(p));
+}
+__device__ __forceinline__ void st_nt(uint32_t* p, uint32_t v) { __builtin_nontemporal_store(v, p); }
+
 constexpr int NT3 = 768;         // 12 wavefronts, one workgroup per compute unit
 
 // BLEND: mixed attention (Sec. 4.1, Eq. 6): out = r' s + (1 - r') o with the softmax-branch output
-// s read on the lane's own channels (its half row, contiguous) and r' = clip(*rptr, 0, 1).
+// s read in the same pieces as out is stored, and r' = clip(*rptr, 0, 1).
 template <int D, bool BLEND>
 __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ wq,
                                                          const float* __restrict__ state, uint16_t* __restrict__ out,
@@ -38,13 +53,12 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
   using L = ApplyLayout<D>;
   constexpr int NW = NT3 / 64;
   constexpr int SA_IMG = L::KS * L::MBZ * 64;
-  constexpr int RS = D * 2;                 // bytes per output row
-  constexpr int RPI = 64 / C::CH;           // rows one store instruction covers
-  constexpr int HB = (L::MB + 1) / 2;       // channel row blocks per accumulation pass (two passes)
+  constexpr int HB = L::MB / 2;             // channel column blocks per accumulation pass (two passes)
+  using Piece = typename RowPiece<L::MB>::type;   // a lane's MB adjacent bf16 channels of one token
   extern __shared__ uint4 smem[];
   uint4* sWA = smem;
   uint4* sSA = sWA + C::W_IMG;
-  char* sOut = reinterpret_cast<char*>(sSA + SA_IMG);   // [NW][32 rows][RS], swizzled chunks
+  char* sStage = reinterpret_cast<char*>(sSA + SA_IMG); // staging area of the prologue
 
   const int tid = threadIdx.x, lane = tid % 64;
   const int w = __builtin_amdgcn_readfirstlane(tid / 64);
@@ -56,10 +70,9 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
   const float rb = BLEND ? fminf(fmaxf(*rptr, 0.f), 1.f) : 0.f;
 
   {
-    // The state and W~ of this (b,h) are first copied into LDS with coalesced 16-byte loads (the
-    // output staging area is free until the main loop), then turned into the operand images from
-    // there: the scattered reads the images need would cost tens of microseconds from global memory.
-    float* stS = reinterpret_cast<float*>(sOut);
+    // The state and W~ of this (b,h) are first copied into LDS with coalesced 16-byte loads,
+    // then turned into the operand images from there: the scattered reads the images need would cost tens of microseconds from global memory.
+    float* stS = reinterpret_cast<float*>(sStage);
     uint16_t* stW = reinterpret_cast<uint16_t*>(stS + (D + 1) * D);
     float* red = reinterpret_cast<float*>(stW + D * C::HALF);
     const uint4* gS = reinterpret_cast<const uint4*>(state + (size_t)bh * (D + 1) * D);
@@ -69,16 +82,14 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
     __syncthreads();
     const float scale = head_scale<D, NT3>(stS, red, tid);
     build_w_image<D, NT3>(stW, sWA, tid);
-    build_state_image<D, NT3>(stS, sSA, scale, tid);
+    build_state_image<D, NT3, true>(stS, sSA, scale, tid);
   }
   __syncthreads();
 
   const int nblk = (n + 31) / 32;
   const int stride = gridDim.x * NW;
-  char* stage = sOut + w * (32 * RS);
-  const int srow = lane % 32;
-  char* srowp = stage + srow * RS;
-  const int ssw = swz_out<D>(srow);
+  const int c = lane % 32;
+  const uint32_t lane_off = ((uint32_t)(4 * g) * (uint32_t)rw.sn + (uint32_t)(L::MB * c)) * 2u;   // bytes
 
   uint4 x[C::UK];
   auto load_block = [&](int b) {
@@ -94,28 +105,39 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
   for (; b < nblk; b += stride) {
     f32x16 u[C::UM];
     project<D>(x, sWA, lane, u);
-    load_block(b + stride < nblk ? b + stride : b);  // next block's rows fly during the rest of this one
+    // next block's rows fly during the rest of this one (BLEND: the pieces of s take their registers,
+    // so each 16-byte piece of the next rows is requested in the second pass as the k-step that
+    // frees a piece of phi has been issued)
+    if constexpr (!BLEND) load_block(b + stride < nblk ? b + stride : b);
     uint32_t pk[C::NPK];
     softmax_pair_ratio<D>(u, pk);
-    const uint4* srow = nullptr;            // the lane's half row of the softmax branch
+    // register r of an accumulator is token b*32 + 8*(r/4) + 4g + r%4; the lane's MB channels of it
+    // are MB*c .. MB*c + MB-1, two bytes each
+    const bool full = b * 32 + 32 <= n;
+    Piece sv[BLEND ? 16 : 1];               // the same pieces of the softmax branch
     if constexpr (BLEND) {
-      const int t = b * 32 + (lane % 32);
-      srow = reinterpret_cast<const uint4*>(bb + (size_t)(t < n ? t : n - 1) * rw.sn + g * (D / 2));
+      const char* sb = reinterpret_cast<const char*>(bb + (size_t)(b * 32) * rw.sn) + lane_off;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = 8 * (r / 4) + (r % 4);
+        const bool there = full || b * 32 + row + 4 * g < n;
+        sv[r] = there ? *reinterpret_cast<const Piece*>(sb + (size_t)row * rw.sn * 2) : Piece{};
+      }
     }
 
-    // out^T = S^T phi^T in two passes over the channel row blocks: the first also carries the
-    // normaliser block, so 1/den is known before anything is scaled
+    const uint4* next_row = nullptr;
+    if constexpr (BLEND) {
+      const int bn = b + stride < nblk ? b + stride : b;
+      const int t = bn * 32 + (lane % 32);
+      next_row = reinterpret_cast<const uint4*>(qb + (size_t)(t < n ? t : n - 1) * rw.sn);
+    }
+    // out = phi S in two passes over the lane's channels; the first also carries the block whose
+    // every column is z, so each lane gets the normalisers of its 16 tokens
     const uint4* ssa = sSA + lane + opaque_zero();
-    float inv = 0.f;
+    float inv[16], keep[16];
+    Piece word[16];
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
-      // this pass's pieces of the softmax branch are requested before its MFMAs and used after them
-      uint4 sv[BLEND ? 2 * HB : 1];
-      if constexpr (BLEND) {
-#pragma unroll
-        for (int i = 0; i < 2 * HB; ++i)
-          if (2 * pass * HB + i < D / 16) sv[i] = srow[2 * pass * HB + i];
-      }
       f32x16 o[HB], dn;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -125,67 +147,59 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
       }
 #pragma unroll
       for (int ks = 0; ks < L::KS; ++ks) {
-        uint4 bq; bq.x = pk[4 * ks]; bq.y = pk[4 * ks + 1]; bq.z = pk[4 * ks + 2]; bq.w = pk[4 * ks + 3];
-        const f16x8 bop = as_f16x8(bq);
+        uint4 aq; aq.x = pk[4 * ks]; aq.y = pk[4 * ks + 1]; aq.z = pk[4 * ks + 2]; aq.w = pk[4 * ks + 3];
+        const f16x8 aop = as_f16x8(aq);
+#pragma unroll
+        for (int i = 0; i < HB; ++i)
+          o[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop, as_f16x8(ssa[(ks * L::MBZ + pass * HB + i) * 64]), o[i], 0, 0, 0);
+        if (pass == 0) dn = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop, as_f16x8(ssa[(ks * L::MBZ + L::MB) * 64]), dn, 0, 0, 0);
+        if constexpr (BLEND) {
+          static_assert(C::UK == L::KS, "one piece of x per k-step");
+          if (pass == 1) x[ks] = next_row[2 * ks + g];
+        }
+      }
+      if (pass == 0) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) inv[r] = __builtin_amdgcn_rcpf(dn[r]);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float y[HB];
 #pragma unroll
         for (int i = 0; i < HB; ++i) {
-          const int mb = pass * HB + i;
-          if (mb < L::MB) {
-            const f16x8 a = as_f16x8(ssa[(ks * L::MBZ + mb) * 64]);
-            o[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bop, o[i], 0, 0, 0);
-          }
-        }
-        if (pass == 0) {
-          const f16x8 az = as_f16x8(ssa[(ks * L::MBZ + L::MB) * 64]);
-          dn = __builtin_amdgcn_mfma_f32_32x32x16_f16(az, bop, dn, 0, 0, 0);
-        }
-      }
-      if (pass == 0) inv = __builtin_amdgcn_rcpf(dn[0]);
-      // lane (t, g) owns channels g*D/2 + 16*mb + r of its token: 16-byte chunks g*CH/2 + 2*mb, +1
-#pragma unroll
-      for (int i = 0; i < HB; ++i) {
-        const int mb = pass * HB + i;
-        if (mb < L::MB) {
-          float y[16];
-#pragma unroll
-          for (int r = 0; r < 16; ++r) y[r] = o[i][r] * inv;
+          y[i] = o[i][r] * inv[r];
           if constexpr (BLEND) {
-            const uint32_t sw[8] = {sv[2 * i].x, sv[2 * i].y, sv[2 * i].z, sv[2 * i].w,
-                                    sv[2 * i + 1].x, sv[2 * i + 1].y, sv[2 * i + 1].z, sv[2 * i + 1].w};
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-              const float s0 = __builtin_bit_cast(float, sw[j] << 16), s1 = __builtin_bit_cast(float, sw[j] & 0xffff0000u);
-              y[2 * j] = fmaf(rb, s0 - y[2 * j], y[2 * j]);
-              y[2 * j + 1] = fmaf(rb, s1 - y[2 * j + 1], y[2 * j + 1]);
-            }
+            const int ch = pass * HB + i;                         // which of the lane's MB channels
+            const uint32_t sw = piece_word(sv[r], ch / 2);
+            const float sf = (ch % 2) ? __builtin_bit_cast(float, sw & 0xffff0000u) : __builtin_bit_cast(float, sw << 16);
+            y[i] = fmaf(rb, sf - y[i], y[i]);
           }
-          uint4 a, c;
-          a.x = pack_bf16x2(y[0], y[1]);   a.y = pack_bf16x2(y[2], y[3]);
-          a.z = pack_bf16x2(y[4], y[5]);   a.w = pack_bf16x2(y[6], y[7]);
-          c.x = pack_bf16x2(y[8], y[9]);   c.y = pack_bf16x2(y[10], y[11]);
-          c.z = pack_bf16x2(y[12], y[13]); c.w = pack_bf16x2(y[14], y[15]);
-          *reinterpret_cast<uint4*>(srowp + (((g * (C::CH / 2) + 2 * mb) ^ ssw) * 16)) = a;
-          *reinterpret_cast<uint4*>(srowp + (((g * (C::CH / 2) + 2 * mb + 1) ^ ssw) * 16)) = c;
+        }
+        if constexpr (HB == 2) {
+          set_piece_word(word[r], pass, pack_bf16x2(y[0], y[1]));
+        } else {
+          if (pass == 0) keep[r] = y[0];
+          else set_piece_word(word[r], 0, pack_bf16x2(keep[r], y[0]));
         }
       }
     }
-    __builtin_amdgcn_wave_barrier();
     {
-      // read back row-major: instruction i covers rows i*RPI .. i*RPI + RPI-1 completely.  The stores
-      // are non-temporal: with ordinary stores the tail of out stays dirty in the last-level cache
-      // and is written back under whatever kernel runs next (measured: the next call's state pass
-      // loses 30 us, this pass gains 20 us)
-      const int rl = lane / C::CH, pc = lane % C::CH;
+      // Every store instruction writes two whole rows.  The stores are non-temporal: with ordinary
+      // stores the tail of out stays dirty in the last-level cache and is written back under
+      // whatever kernel runs next (measured: the next call's state pass loses 30 us, this pass
+      // gains 20 us)
+      char* ub = reinterpret_cast<char*>(ob + (size_t)(b * 32) * rw.sn) + lane_off;
+      if (full) {
 #pragma unroll
-      for (int i = 0; i < 32 / RPI; ++i) {
-        const int row = i * RPI + rl;
-        const uint4 v = *reinterpret_cast<const uint4*>(stage + row * RS + pc * 16);
-        const int tt = b * 32 + row;
-        const int lc = pc ^ swz_out<D>(row);
-        if (tt < n) st_nt(reinterpret_cast<uint4*>(ob + (size_t)tt * rw.sn) + lc, v);   // streamed: see below
+        for (int r = 0; r < 16; ++r) st_nt(reinterpret_cast<Piece*>(ub + (size_t)(8 * (r / 4) + (r % 4)) * rw.sn * 2), word[r]);
+      } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = 8 * (r / 4) + (r % 4);
+          if (b * 32 + row + 4 * g < n) st_nt(reinterpret_cast<Piece*>(ub + (size_t)row * rw.sn * 2), word[r]);
+        }
       }
     }
-    __builtin_amdgcn_wave_barrier();
   }
 }
 
@@ -439,7 +453,9 @@ constexpr size_t state_ws_smem() { return sizeof(uint4) * Cfg<D>::W_IMG + 4 * (s
 
 template <int D>
 constexpr size_t apply_smem() {
-  return sizeof(uint4) * (Cfg<D>::W_IMG + ApplyLayout<D>::KS * ApplyLayout<D>::MBZ * 64) + (size_t)(NT3 / 64) * 32 * D * 2;
+  // the images, then the prologue's staging of the fp32 state, W~ and a few reduction slots
+  return sizeof(uint4) * (Cfg<D>::W_IMG + ApplyLayout<D>::KS * ApplyLayout<D>::MBZ * 64)
+       + (size_t)(D + 1) * D * sizeof(float) + (size_t)D * (D / 2) * 2 + 64 * sizeof(float);
 }
 
 template <typename K>

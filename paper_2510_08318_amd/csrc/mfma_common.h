@@ -256,7 +256,8 @@ __device__ __forceinline__ float head_scale(const float* __restrict__ S, float* 
 // scale * S[feature(ks,g,e)][channel(mb,m)], e = 0..7; the extra row block mb = MB holds
 // scale * z[feature] in rows 0 and 4 (one per lane group) and zeros elsewhere.
 // COLS: the same registers read as B operands of Y = phi S (lane (c,g) holds column c), with the
-// channels dealt out by ApplyLayout::channel_cols; the extra block is left zero.
+// channels dealt out by ApplyLayout::channel_cols; the extra block then holds scale * z[feature] in
+// every column, so each lane of the product receives phi . z of its own token rows.
 template <int D, bool COLS = false>
 __device__ __forceinline__ uint4 state_image_entry(const float* __restrict__ S, float scale, int idx) {
   using L = ApplyLayout<D>;
@@ -267,17 +268,17 @@ __device__ __forceinline__ uint4 state_image_entry(const float* __restrict__ S, 
   for (int e = 0; e < 8; ++e) {
     const int f = L::feature(ks, g, e);
     if (mb < L::MB) x[e] = scale * S[f * D + (COLS ? L::channel_cols(mb, m) : L::channel(mb, m))];
-    else x[e] = (!COLS && (m == 0 || m == 4)) ? scale * S[D * D + f] : 0.f;
+    else x[e] = (COLS || m == 0 || m == 4) ? scale * S[D * D + f] : 0.f;
   }
   uint4 r;
   r.x = pack_f16x2(x[0], x[1]); r.y = pack_f16x2(x[2], x[3]);
   r.z = pack_f16x2(x[4], x[5]); r.w = pack_f16x2(x[6], x[7]);
   return r;
 }
-template <int D, int NTHREADS>
+template <int D, int NTHREADS, bool COLS = false>
 __device__ __forceinline__ void build_state_image(const float* __restrict__ S, uint4* sSA, float scale, int tid) {
   using L = ApplyLayout<D>;
-  for (int idx = tid; idx < L::KS * L::MBZ * 64; idx += NTHREADS) sSA[idx] = state_image_entry<D>(S, scale, idx);
+  for (int idx = tid; idx < L::KS * L::MBZ * 64; idx += NTHREADS) sSA[idx] = state_image_entry<D, COLS>(S, scale, idx);
 }
 
 // Index maps of G^T = S Y^T (contraction over the d channels; rows = features of phi), used by the
