@@ -39,7 +39,7 @@ def _hip():
     return lib
 
 
-def cpu_baseline(x, budget_s: float = 12.0):
+def cpu_baseline(x, budget_s: float = 12.0, relu: bool = False):
     """The oracle as it stands, on a bounded sample: whole heads of the same workload."""
     from oracle import linattn_oracle as O
     try:
@@ -50,7 +50,11 @@ def cpu_baseline(x, budget_s: float = 12.0):
     done = 0
     t0 = time.perf_counter()
     for h in range(x.H):
-        O.fwd(O.to_f64(x.q[0, h]), O.to_f64(x.k[0, h]), O.to_f64(x.v[0, h]), O.to_f64(x.wq[h]), O.to_f64(x.wk[h]))
+        if relu:
+            from oracle import relu_oracle as R
+            R.relu_fwd(O.to_f64(x.q[0, h]), O.to_f64(x.k[0, h]), O.to_f64(x.v[0, h]))
+        else:
+            O.fwd(O.to_f64(x.q[0, h]), O.to_f64(x.k[0, h]), O.to_f64(x.v[0, h]), O.to_f64(x.wq[h]), O.to_f64(x.wk[h]))
         done += 1
         if time.perf_counter() - t0 > budget_s:
             break
@@ -60,7 +64,7 @@ def cpu_baseline(x, budget_s: float = 12.0):
             "sample": f"{done} of {x.H} heads of batch item 0, all {x.n} tokens, fp64 numpy, {dt:.1f} s"}
 
 
-def cpu_baseline_bwd(x, budget_s: float = 12.0):
+def cpu_baseline_bwd(x, budget_s: float = 12.0, relu: bool = False):
     """The oracle's backward (forward recomputed inside it), whole heads of the same workload."""
     from oracle import linattn_oracle as O
     try:
@@ -71,8 +75,12 @@ def cpu_baseline_bwd(x, budget_s: float = 12.0):
     done = 0
     t0 = time.perf_counter()
     for h in range(x.H):
-        O.bwd(O.to_f64(x.q[0, h]), O.to_f64(x.k[0, h]), O.to_f64(x.v[0, h]), O.to_f64(x.wq[h]), O.to_f64(x.wk[h]),
-              O.to_f64(x.dout[0, h]))
+        if relu:
+            from oracle import relu_oracle as R
+            R.relu_bwd(O.to_f64(x.q[0, h]), O.to_f64(x.k[0, h]), O.to_f64(x.v[0, h]), O.to_f64(x.dout[0, h]))
+        else:
+            O.bwd(O.to_f64(x.q[0, h]), O.to_f64(x.k[0, h]), O.to_f64(x.v[0, h]), O.to_f64(x.wq[h]), O.to_f64(x.wk[h]),
+                  O.to_f64(x.dout[0, h]))
         done += 1
         if time.perf_counter() - t0 > budget_s:
             break
@@ -89,7 +97,11 @@ def bench_bwd(args):
     q, k, v, wq, wk, dout = [G.to_device(t) for t in (x.q, x.k, x.v, x.wq, x.wk, x.dout)]
     if args.layout == "bnhd":
         q, k, v, dout = [t.permute(0, 2, 1, 3).contiguous() for t in (q, k, v, dout)]
-    lay = G.Layer(wq, wk, x.B, x.n, want_wgrads=not args.no_wgrads, layout=args.layout)
+    relu = args.phi == "relu"
+    if relu:
+        lay = G.ReluLayer(x.H, x.d, x.B, x.n, q.dtype, layout=args.layout)
+    else:
+        lay = G.Layer(wq, wk, x.B, x.n, want_wgrads=not args.no_wgrads, layout=args.layout)
     if args.blend:
         lay.set_blend((torch.randn(q.shape, device="cuda") * 0.1).to(q.dtype), torch.tensor([0.5], device="cuda"),
                       torch.zeros(1, device="cuda"))
@@ -115,15 +127,16 @@ def bench_bwd(args):
         "metric": f"linear-attn bwd tokens/s ({args.workload})", "value": round(x.B * x.n / dt, 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": x.dtype, "data": "synthetic",
-        "config": {"workload": f"{args.workload}: B={x.B} H={x.H} n={x.n} d={x.d} {x.dtype}, backward of Eq. 3 + Eq. 5, "
-                               f"state saved by the forward, weight gradients {'off' if args.no_wgrads else 'on'}"
+        "config": {"workload": f"{args.workload}: B={x.B} H={x.H} n={x.n} d={x.d} {x.dtype}, "
+                               + ("backward of Eq. 3 with the ReLU map, state saved by the forward" if relu else
+                                  f"backward of Eq. 3 + Eq. 5, state saved by the forward, weight gradients {'off' if args.no_wgrads else 'on'}")
                                + (", [B,n,H,d] layout" if args.layout == "bnhd" else "")
                                + (", mixed attention (Eq. 6, r = 0.5) with dL/dr" if args.blend else "")},
         "roofline": {"bound": "hbm", "kernel": "linattn_bwd (all kernels of one call)", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None},
     }
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline_bwd(x)
+        res["cpu_baseline"] = cpu_baseline_bwd(x, relu=relu)
     lay.close()
     print(json.dumps(res), flush=True)
 
@@ -140,6 +153,8 @@ def main():
                     help="mixed attention of Eq. 6: also read a softmax-branch tensor s and blend it with r = 0.5")
     ap.add_argument("--layout", choices=("bhnd", "bnhd"), default="bhnd",
                     help="memory layout of q, k, v, out: [B,H,n,d] (default, the headline configuration) or [B,n,H,d]")
+    ap.add_argument("--phi", choices=("hedgehog", "relu"), default="hedgehog",
+                    help="feature map: Eq. 5 (default, the headline configuration) or the weight-free max(x, 0) of the kernel-function ablation")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy kernel (reference reading for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
@@ -160,7 +175,8 @@ def main():
     q, k, v, wq, wk = [G.to_device(t) for t in (x.q, x.k, x.v, x.wq, x.wk)]
     if args.layout == "bnhd":
         q, k, v = [t.permute(0, 2, 1, 3).contiguous() for t in (q, k, v)]
-    lay = G.Layer(wq, wk, x.B, x.n, layout=args.layout)
+    relu = args.phi == "relu"
+    lay = G.ReluLayer(x.H, x.d, x.B, x.n, q.dtype, layout=args.layout) if relu else G.Layer(wq, wk, x.B, x.n, layout=args.layout)
     if args.blend:
         lay.set_blend((torch.randn(q.shape, device="cuda") * 0.1).to(q.dtype), torch.tensor([0.5], device="cuda"))
     out = torch.empty_like(q)
@@ -218,7 +234,7 @@ def main():
     achieved = stage_bytes[dom] / (stage_ms[dom] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": names[dom], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC.get((args.workload, dom)),
+                "traffic": None if (relu or args.blend or args.layout != "bhnd") else MEASURED_TRAFFIC.get((args.workload, dom)),
                 "stage_ms": [round(t, 4) for t in stage_ms],
                 "path_GBps": round(4 * x.d * esz * head_tokens / (sum(stage_ms) * 1e-3) / 1e9, 1),
                 "path_frac": round(4 * x.d * esz * head_tokens / (sum(stage_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
@@ -226,11 +242,12 @@ def main():
                 "call_ms_median": round(per_call[len(per_call) // 2], 4), "call_ms_min": round(per_call[0], 4)}
 
     res = {
-        "metric": "linear-attn fwd tokens/s (Wan-14B 720p shape)" if args.workload == "C3" else f"linear-attn fwd tokens/s ({args.workload})",
+        "metric": "linear-attn fwd tokens/s (Wan-14B 720p shape)" if args.workload == "C3" and not relu
+                  else f"linear-attn fwd tokens/s ({args.workload}{', ReLU map' if relu else ''})",
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": x.dtype, "data": "synthetic",
-        "config": {"workload": f"{args.workload}: B={x.B} H={x.H} n={x.n} d={x.d} {x.dtype}, Hedgehog phi, non-causal"
+        "config": {"workload": f"{args.workload}: B={x.B} H={x.H} n={x.n} d={x.d} {x.dtype}, {'ReLU' if relu else 'Hedgehog'} phi, non-causal"
                                + (", [B,n,H,d] layout" if args.layout == "bnhd" else "")
                                + (", mixed with a softmax-branch input (Eq. 6, r = 0.5)" if args.blend else ""),
                    "head_tokens_per_s": round(tokens_per_s * x.H, 1)},
@@ -244,7 +261,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(x)
+        res["cpu_baseline"] = cpu_baseline(x, relu=relu)
     lay.close()
     print(json.dumps(res), flush=True)
 

@@ -52,6 +52,13 @@ extern "C" {
 
 /* feature-map kinds */
 #define LINATTN_PHI_HEDGEHOG  1   /* Eq. 5 */
+#define LINATTN_PHI_RELU      2   /* phi(x) = max(x, 0) on the d channels, no weights: the "ReLU" row of the
+                                     paper's ablation of kernel functions (appendix "Ablation for Kernel
+                                     Function").  The paper gives the name only; this library's reading:
+                                     o_i = phi(q_i) S / (phi(q_i) . z + 1e-6), because a row of q or k can be
+                                     all non-positive (such a query gets o_i = 0); the derivative of max(x, 0)
+                                     at 0 is 0.  Descriptor: wq, wk, dwq, dwk and the three blend pointers
+                                     must be NULL (E_PHI otherwise); state rows are the d channels of k. */
 
 /* dtypes */
 #define LINATTN_BF16  1
@@ -67,7 +74,7 @@ extern "C" {
  * paper's argument list.  The struct is copied by linattn_phi_create.
  */
 typedef struct linattn_phi_desc {
-  int kind;               /* LINATTN_PHI_HEDGEHOG */
+  int kind;               /* LINATTN_PHI_HEDGEHOG or LINATTN_PHI_RELU */
   int dtype;              /* LINATTN_BF16 or LINATTN_F32: type of q,k,v,out,dout,dq,dk,dv,wq,wk */
   int H, d;               /* wq, wk: device, [H, d, d/2] contiguous, one map per head (Eq. 5) */
   const void *wq, *wk;

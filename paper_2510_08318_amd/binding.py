@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(HERE, "liblinattn.so")
 OK = 0
 E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_PHI, E_WORKSPACE, E_HIP, E_STATE, E_ALIAS = range(-1, -10, -1)
 PHI_HEDGEHOG = 1
+PHI_RELU = 2
 BF16, F32 = 1, 2
 LAYOUT_BHND, LAYOUT_BNHD = 0, 1
 

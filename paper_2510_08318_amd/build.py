@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblinattn.so")
-SOURCES = ["api.cpp", "fwd_f32.hip", "fwd_bf16.hip", "state_reduce.hip", "bwd_bf16.hip", "bwd_f32.hip"]
+SOURCES = ["api.cpp", "fwd_f32.hip", "fwd_bf16.hip", "state_reduce.hip", "bwd_bf16.hip", "bwd_f32.hip", "relu_bf16.hip"]
 # Packed-fp32 VALU forms are switched off for every device compilation.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -138,6 +138,7 @@ int check_call(const void* const* tensors, int n_tensors, int B, int H, int n, i
     if (!tensors[i]) return LINATTN_E_NULL;
   if (H != desc->H || d != desc->d) return LINATTN_E_SHAPE;
   if (!make_plan(B, H, n, d, desc->dtype, desc->layout, plan)) return LINATTN_E_SHAPE;
+  plan->kind = desc->kind;
   for (int i = 0; i < n_tensors; ++i)
     if (!aligned16(tensors[i])) return LINATTN_E_ALIGN;
   const size_t need = (want_wgrads && (desc->dwq || desc->dwk)) ? plan->total_bytes : plan->bytes_no_wgrads;
@@ -176,13 +177,14 @@ int linattn_set_stage_events(void* const* events) {
 }
 
 size_t linattn_workspace_bytes(int B, int H, int n, int d, int kind, int dtype) {
-  if (kind != LINATTN_PHI_HEDGEHOG) return 0;
+  if (kind != LINATTN_PHI_HEDGEHOG && kind != LINATTN_PHI_RELU) return 0;
   Plan p;
   if (!make_plan(B, H, n, d, dtype, LINATTN_LAYOUT_BHND, &p)) return 0;
   return p.bytes_no_wgrads;
 }
 
 size_t linattn_workspace_bytes_wgrads(int B, int H, int n, int d, int kind, int dtype) {
+  if (kind == LINATTN_PHI_RELU) return linattn_workspace_bytes(B, H, n, d, kind, dtype);    // no weights
   if (kind != LINATTN_PHI_HEDGEHOG) return 0;
   Plan p;
   if (!make_plan(B, H, n, d, dtype, LINATTN_LAYOUT_BHND, &p)) return 0;
@@ -191,14 +193,19 @@ size_t linattn_workspace_bytes_wgrads(int B, int H, int n, int d, int kind, int 
 
 int linattn_phi_create(const linattn_phi_desc* desc, int* phi_id_out) {
   if (!desc || !phi_id_out) return LINATTN_E_NULL;
-  if (desc->kind != LINATTN_PHI_HEDGEHOG) return LINATTN_E_PHI;
+  if (desc->kind != LINATTN_PHI_HEDGEHOG && desc->kind != LINATTN_PHI_RELU) return LINATTN_E_PHI;
   if (desc->dtype != LINATTN_BF16 && desc->dtype != LINATTN_F32) return LINATTN_E_DTYPE;
   if (desc->H <= 0 || (desc->d != 64 && desc->d != 128)) return LINATTN_E_SHAPE;
   if (desc->layout != LINATTN_LAYOUT_BHND && desc->layout != LINATTN_LAYOUT_BNHD) return LINATTN_E_SHAPE;
-  if (!desc->wq || !desc->wk) return LINATTN_E_NULL;
-  if (!aligned16(desc->wq) || !aligned16(desc->wk)) return LINATTN_E_ALIGN;
-  if (desc->dwq && !aligned16(desc->dwq)) return LINATTN_E_ALIGN;
-  if (desc->dwk && !aligned16(desc->dwk)) return LINATTN_E_ALIGN;
+  if (desc->kind == LINATTN_PHI_RELU) {
+    // weight-free: nothing to point at, and no mixed attention with this map
+    if (desc->wq || desc->wk || desc->dwq || desc->dwk || desc->blend_in || desc->blend_r || desc->blend_dr) return LINATTN_E_PHI;
+  } else {
+    if (!desc->wq || !desc->wk) return LINATTN_E_NULL;
+    if (!aligned16(desc->wq) || !aligned16(desc->wk)) return LINATTN_E_ALIGN;
+    if (desc->dwq && !aligned16(desc->dwq)) return LINATTN_E_ALIGN;
+    if (desc->dwk && !aligned16(desc->dwk)) return LINATTN_E_ALIGN;
+  }
   if (desc->state && !aligned16(desc->state)) return LINATTN_E_ALIGN;
   if (desc->workspace && (reinterpret_cast<uintptr_t>(desc->workspace) & 255u)) return LINATTN_E_ALIGN;
   if (int st = check_blend(desc->blend_in, desc->blend_r, desc->blend_dr)) return st;
@@ -219,6 +226,7 @@ int linattn_phi_set_blend(int phi_id, const void* blend_in, const float* blend_r
   std::lock_guard<std::mutex> lk(g_mu);
   const int i = phi_id - kFirstId;
   if (i < 0 || i >= kMaxDesc || !g_slots[i].live) return LINATTN_E_PHI;
+  if (g_slots[i].d.kind == LINATTN_PHI_RELU && blend_in) return LINATTN_E_PHI;
   g_slots[i].d.blend_in = blend_in;
   g_slots[i].d.blend_r = blend_r;
   g_slots[i].d.blend_dr = blend_dr;
@@ -262,10 +270,11 @@ int linattn_fwd(const void* q, const void* k, const void* v, void* out,
                          (const float*)desc.blend_in, desc.blend_r, plan, s);
     if (e != hipSuccess) return LINATTN_E_HIP;
   } else {
-    e = launch_state_partials_bf16(k, v, desc.wk, partials, plan, s);
+    const bool relu = desc.kind == LINATTN_PHI_RELU;
+    e = relu ? launch_relu_state_bf16(k, v, partials, plan, s) : launch_state_partials_bf16(k, v, desc.wk, partials, plan, s);
     if (e != hipSuccess) return LINATTN_E_HIP;
     mark(1, s);
-    e = launch_state_reduce_split(partials, state, plan, s);
+    e = relu ? launch_state_reduce(partials, state, plan, s) : launch_state_reduce_split(partials, state, plan, s);
     if (e != hipSuccess) return LINATTN_E_HIP;
     mark(2, s);
     e = launch_apply_bf16(q, desc.wq, state, out, desc.blend_in, desc.blend_r, plan, s);
@@ -316,7 +325,9 @@ int linattn_bwd(const void* q, const void* k, const void* v, const void* dout,
   a.du_q = reinterpret_cast<float*>(ws + plan.off_du_q);
   a.du_k = reinterpret_cast<float*>(ws + plan.off_du_k);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const hipError_t e = desc.dtype == LINATTN_BF16 ? launch_bwd_bf16(a, plan, s) : launch_bwd_f32(a, plan, s);
+  if (desc.kind == LINATTN_PHI_RELU) { a.dwq = nullptr; a.dwk = nullptr; }
+  const hipError_t e = desc.dtype == LINATTN_F32 ? launch_bwd_f32(a, plan, s)
+                     : desc.kind == LINATTN_PHI_RELU ? launch_relu_bwd_bf16(a, plan, s) : launch_bwd_bf16(a, plan, s);
   return e == hipSuccess ? LINATTN_OK : LINATTN_E_HIP;
 }
 

@@ -25,18 +25,6 @@
 namespace linattn {
 namespace {
 
-// power of two p with p * m in [1, 2) (m > 0), 1 for m == 0 or non-finite
-__device__ __forceinline__ float pow2_normaliser(float m) {
-  return (m > 0.f && m < 3.0e38f) ? ldexpf(1.0f, -ilogbf(m)) : 1.0f;
-}
-
-__device__ __forceinline__ void unpack_bf16x8(uint4 v, float* f) {
-  f[0] = __builtin_bit_cast(float, v.x << 16); f[1] = __builtin_bit_cast(float, v.x & 0xffff0000u);
-  f[2] = __builtin_bit_cast(float, v.y << 16); f[3] = __builtin_bit_cast(float, v.y & 0xffff0000u);
-  f[4] = __builtin_bit_cast(float, v.z << 16); f[5] = __builtin_bit_cast(float, v.z & 0xffff0000u);
-  f[6] = __builtin_bit_cast(float, v.w << 16); f[7] = __builtin_bit_cast(float, v.w & 0xffff0000u);
-}
-
 // ---- operand images, built once per head ---------------------------------------------------
 // The two main kernels need, per (b,h), MFMA operand images of S (resp. dS) in two index orders
 // and, per head, two images of W~.  Building them costs scattered reads; done by every workgroup
@@ -102,12 +90,6 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(const float* __restrict__
 template <int D>
 constexpr size_t prep_smem_bytes() { return (size_t)(D + 1) * D * sizeof(float) + 2 * (size_t)D * (D / 2) * 2; }
 
-// Copy n16 16-byte entries from global memory into LDS (all threads of the workgroup).
-template <int NTHREADS>
-__device__ __forceinline__ void copy_image(const uint4* __restrict__ src, uint4* dst, int n16, int tid) {
-  for (int i = tid; i < n16; i += NTHREADS) dst[i] = src[i];
-}
-
 // Softmax Jacobian of Eq. 5 for one token spread over a lane pair: gacc holds g in the GradLayout
 // row order (first GM/2 blocks the softmax(+u) half, then the softmax(-u) half), already scaled.
 template <int D>
@@ -123,22 +105,6 @@ __device__ __forceinline__ void phi_jacobian(const float (&gp)[Cfg<D>::LOC], con
   pair32(cm, lo, hi); cm = lo + hi;
 #pragma unroll
   for (int j = 0; j < C::LOC; ++j) du[j] = pp[j] * (gp[j] - cp) - pm[j] * (gm[j] - cm);
-}
-
-// Maximum of x over the wavefront, given x already equal in lanes l and l^32: DPP steps inside each
-// row of 16 lanes, then the two rows of the low half are combined through scalar registers.
-template <int CTRL>
-__device__ __forceinline__ float dpp_move(float v) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
-}
-__device__ __forceinline__ float wave_max_paired(float x) {
-  x = fmaxf(x, dpp_move<0xB1>(x));      // quad_perm [1,0,3,2]
-  x = fmaxf(x, dpp_move<0x4E>(x));      // quad_perm [2,3,0,1]
-  x = fmaxf(x, dpp_move<0x124>(x));     // row_ror 4
-  x = fmaxf(x, dpp_move<0x128>(x));     // row_ror 8
-  const float a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 0));
-  const float b = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 16));
-  return fmaxf(a, b);
 }
 
 // dx = du W~^T for one block of 32 tokens, tokens on the accumulator rows: du is scaled by one power
@@ -216,39 +182,6 @@ __device__ __forceinline__ void du_to_dx(const float (&du)[Cfg<D>::LOC], const u
 #pragma unroll
     for (int mb = 0; mb < L::MB; ++mb)
       acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop, as_f16x8(wb[(ks * L::MB + mb) * 64]), acc[mb], 0, 0, 0);
-  }
-}
-
-// Accumulators with tokens on the rows (lane (c,g), register r: token t0 + 8*(r/4) + 4g + r%4,
-// channels MB*c .. MB*c + MB-1 in acc[0..MB-1]) -> mul * acc as bf16 rows of base.  Every store
-// instruction writes two whole rows of d channels.
-template <int D>
-__device__ __forceinline__ void store_token_rows(uint16_t* base, size_t sn, int t0, int n, int lane,
-                                                 const f32x16 (&acc)[D / 32], float mul) {
-  constexpr int MB = D / 32;
-  static_assert(MB == 2 || MB == 4, "head width 64 or 128");
-  const int c = lane % 32, g = lane / 32;
-  char* ub = reinterpret_cast<char*>(base + (size_t)t0 * sn);
-  const uint32_t lo = ((uint32_t)(4 * g) * (uint32_t)sn + (uint32_t)(MB * c)) * 2u;
-  auto put = [&](int r) {
-    const int row = 8 * (r / 4) + (r % 4);
-    char* dst = ub + (size_t)row * sn * 2 + lo;
-    if constexpr (MB == 4) {
-      uint2 v;
-      v.x = pack_bf16x2(acc[0][r] * mul, acc[1][r] * mul);
-      v.y = pack_bf16x2(acc[2][r] * mul, acc[3][r] * mul);
-      *reinterpret_cast<uint2*>(dst) = v;
-    } else {
-      *reinterpret_cast<uint32_t*>(dst) = pack_bf16x2(acc[0][r] * mul, acc[1][r] * mul);
-    }
-  };
-  if (t0 + 32 <= n) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) put(r);
-  } else {
-#pragma unroll
-    for (int r = 0; r < 16; ++r)
-      if (t0 + 8 * (r / 4) + (r % 4) + 4 * g < n) put(r);
   }
 }
 

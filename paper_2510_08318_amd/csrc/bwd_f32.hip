@@ -50,7 +50,7 @@ __device__ __forceinline__ void dx_tile(const float* sDU, const float* sW, float
   }
 }
 
-template <int D>
+template <int D, int KIND>
 __global__ __launch_bounds__(NT) void bwd_q_f32_kernel(const float* __restrict__ q, const float* __restrict__ dout,
                                                        const float* __restrict__ wq, const float* __restrict__ state,
                                                        float* __restrict__ dq, float* __restrict__ partials,
@@ -85,7 +85,8 @@ __global__ __launch_bounds__(NT) void bwd_q_f32_kernel(const float* __restrict__
   float dr_acc = 0.f;
   const float* wb = wq + (size_t)h * D * HALF;
   const float* sb = state + (size_t)bh * (D + 1) * D;
-  for (int i = tid; i < D * HALF; i += NT) sW[i] = wb[i];
+  if constexpr (KIND == kPhiHedgehog)
+    for (int i = tid; i < D * HALF; i += NT) sW[i] = wb[i];
   for (int i = tid; i < (D + 1) * D; i += NT) sS[(i / D) * SS + (i % D)] = sb[i];
 
   float acc[BLK][BLK];
@@ -107,11 +108,12 @@ __global__ __launch_bounds__(NT) void bwd_q_f32_kernel(const float* __restrict__
       sDO[r * D + c] = valid ? dob[(size_t)(t0 + r) * rw.sn + c] : 0.f;
     }
     __syncthreads();
-    phi_tile<D, TB>(sX, sW, sPhi, tid, n_valid);     // rows >= n_valid are zero
+    phi_tile<D, TB, KIND>(sX, sW, sPhi, tid, n_valid);     // rows >= n_valid are zero
     // o = phi S / den  -> sG, den -> sDen
     {
       float den = 0.f;
       for (int f = 0; f < D; ++f) den = fmaf(sPhi[tt * D + f], sS[D * SS + f], den);
+      if constexpr (KIND == kPhiRelu) den += kReluEps;
       const float inv = tt < n_valid ? 1.0f / den : 0.f;
 #pragma unroll 1
       for (int j = 0; j < D / TPT; ++j) {
@@ -159,8 +161,17 @@ __global__ __launch_bounds__(NT) void bwd_q_f32_kernel(const float* __restrict__
       if (cb == 0) sDel[tt] = dl * inv;
     }
     __syncthreads();
-    jacobian_tile<D>(sG, sPhi, sDU, sC, tid);
-    dx_tile<D>(sDU, sW, dqb, rw.sn, du_ws ? du_ws + (size_t)bh * n * HALF : nullptr, t0, n_valid, tid);
+    if constexpr (KIND == kPhiRelu) {
+      // dq = g where q > 0 (this thread wrote these entries of sG itself)
+      if (tt < n_valid)
+        for (int j = 0; j < D / TPT; ++j) {
+          const int c = cb + TPT * j;
+          dqb[(size_t)(t0 + tt) * rw.sn + c] = sX[tt * (D + 1) + c] > 0.f ? sG[tt * D + c] : 0.f;
+        }
+    } else {
+      jacobian_tile<D>(sG, sPhi, sDU, sC, tid);
+      dx_tile<D>(sDU, sW, dqb, rw.sn, du_ws ? du_ws + (size_t)bh * n * HALF : nullptr, t0, n_valid, tid);
+    }
     // dS += phi^T (dO / den), dz -= phi * (delta / den)
     for (int r = 0; r < TB; ++r) {
       float a[BLK], b[BLK];
@@ -195,7 +206,7 @@ __global__ __launch_bounds__(NT) void bwd_q_f32_kernel(const float* __restrict__
   }
 }
 
-template <int D>
+template <int D, int KIND>
 __global__ __launch_bounds__(NT) void bwd_k_f32_kernel(const float* __restrict__ k, const float* __restrict__ v,
                                                        const float* __restrict__ wk, const float* __restrict__ dstate,
                                                        float* __restrict__ dk, float* __restrict__ dv,
@@ -221,7 +232,8 @@ __global__ __launch_bounds__(NT) void bwd_k_f32_kernel(const float* __restrict__
   float* dvb = dv + head_base(rw, bh, H);
   const float* wb = wk + (size_t)h * D * HALF;
   const float* sb = dstate + (size_t)bh * (D + 1) * D;
-  for (int i = tid; i < D * HALF; i += NT) sW[i] = wb[i];
+  if constexpr (KIND == kPhiHedgehog)
+    for (int i = tid; i < D * HALF; i += NT) sW[i] = wb[i];
   for (int i = tid; i < (D + 1) * D; i += NT) sS[(i / D) * SS + (i % D)] = sb[i];
   const int tt = tid / TPT, cb = tid % TPT;
 
@@ -235,7 +247,7 @@ __global__ __launch_bounds__(NT) void bwd_k_f32_kernel(const float* __restrict__
       sV[r * D + c] = valid ? vb[(size_t)(t0 + r) * rw.sn + c] : 0.f;
     }
     __syncthreads();
-    phi_tile<D, TB>(sX, sW, sPhi, tid, n_valid);
+    phi_tile<D, TB, KIND>(sX, sW, sPhi, tid, n_valid);
     // dv = phi dS ; g = v dS^T + dz
 #pragma unroll 1
     for (int j = 0; j < D / TPT; ++j) {
@@ -248,8 +260,16 @@ __global__ __launch_bounds__(NT) void bwd_k_f32_kernel(const float* __restrict__
       sG[tt * D + f] = gsum + sS[D * SS + f];
     }
     __syncthreads();
-    jacobian_tile<D>(sG, sPhi, sDU, sC, tid);
-    dx_tile<D>(sDU, sW, dkb, rw.sn, du_ws ? du_ws + (size_t)bh * n * HALF : nullptr, t0, n_valid, tid);
+    if constexpr (KIND == kPhiRelu) {
+      if (tt < n_valid)
+        for (int j = 0; j < D / TPT; ++j) {
+          const int c = cb + TPT * j;
+          dkb[(size_t)(t0 + tt) * rw.sn + c] = sX[tt * (D + 1) + c] > 0.f ? sG[tt * D + c] : 0.f;
+        }
+    } else {
+      jacobian_tile<D>(sG, sPhi, sDU, sC, tid);
+      dx_tile<D>(sDU, sW, dkb, rw.sn, du_ws ? du_ws + (size_t)bh * n * HALF : nullptr, t0, n_valid, tid);
+    }
   }
 }
 
@@ -262,31 +282,34 @@ constexpr size_t k_smem() {
   return sizeof(float) * (D * (D / 2) + (D + 1) * (D + 1) + TB * (D + 1) + 3 * TB * D + TB * (D / 2) + 2 * TB);
 }
 
-template <int D>
+template <int D, int KIND>
 hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   hipError_t e;
   const dim3 grid(p.P, p.BH);
-  if ((e = hipFuncSetAttribute((const void*)bwd_q_f32_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)q_smem<D>())) != hipSuccess) return e;
-  bwd_q_f32_kernel<D><<<grid, NT, q_smem<D>(), s>>>((const float*)a.q, (const float*)a.dout, (const float*)a.wq, a.state,
+  if ((e = hipFuncSetAttribute((const void*)bwd_q_f32_kernel<D, KIND>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)q_smem<D>())) != hipSuccess) return e;
+  bwd_q_f32_kernel<D, KIND><<<grid, NT, q_smem<D>(), s>>>((const float*)a.q, (const float*)a.dout, (const float*)a.wq, a.state,
                                                     (float*)a.dq, a.partials, a.dwq ? a.du_q : nullptr,
                                                     (const float*)a.blend_in, a.blend_r, a.dr_part, p.H, p.n, p.P, p.chunk, p.rows);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (a.blend_in && a.blend_dr && (e = launch_dr_reduce(a.dr_part, p.BH * p.P, a.blend_r, a.blend_dr, s)) != hipSuccess) return e;
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if ((e = launch_state_reduce(a.partials, a.dstate, p, s)) != hipSuccess) return e;
-  if ((e = hipFuncSetAttribute((const void*)bwd_k_f32_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)k_smem<D>())) != hipSuccess) return e;
-  bwd_k_f32_kernel<D><<<grid, NT, k_smem<D>(), s>>>((const float*)a.k, (const float*)a.v, (const float*)a.wk, a.dstate,
+  if ((e = hipFuncSetAttribute((const void*)bwd_k_f32_kernel<D, KIND>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)k_smem<D>())) != hipSuccess) return e;
+  bwd_k_f32_kernel<D, KIND><<<grid, NT, k_smem<D>(), s>>>((const float*)a.k, (const float*)a.v, (const float*)a.wk, a.dstate,
                                                     (float*)a.dk, (float*)a.dv, a.dwk ? a.du_k : nullptr, p.H, p.n, p.chunk, p.rows);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  if (a.dwq && (e = launch_dw(a.q, false, a.du_q, a.dw_part, a.dwq, p, s)) != hipSuccess) return e;
-  if (a.dwk && (e = launch_dw(a.k, false, a.du_k, a.dw_part, a.dwk, p, s)) != hipSuccess) return e;
+  if constexpr (KIND == kPhiHedgehog) {
+    if (a.dwq && (e = launch_dw(a.q, false, a.du_q, a.dw_part, a.dwq, p, s)) != hipSuccess) return e;
+    if (a.dwk && (e = launch_dw(a.k, false, a.du_k, a.dw_part, a.dwk, p, s)) != hipSuccess) return e;
+  }
   return hipSuccess;
 }
 
 }  // namespace
 
 hipError_t launch_bwd_f32(const BwdArgs& a, const Plan& p, hipStream_t s) {
-  return p.d == 128 ? run_bwd<128>(a, p, s) : run_bwd<64>(a, p, s);
+  if (p.kind == kPhiRelu) return p.d == 128 ? run_bwd<128, kPhiRelu>(a, p, s) : run_bwd<64, kPhiRelu>(a, p, s);
+  return p.d == 128 ? run_bwd<128, kPhiHedgehog>(a, p, s) : run_bwd<64, kPhiHedgehog>(a, p, s);
 }
 
 }  // namespace linattn

@@ -1,6 +1,7 @@
 // Building blocks of the fp32 (no bf16/fp16 anywhere) kernels: plain FMA on LDS tiles.
 #pragma once
 #include <hip/hip_runtime.h>
+#include "kernels.h"
 
 namespace linattn {
 namespace f32 {
@@ -18,10 +19,19 @@ __device__ __forceinline__ float wave_sum(float x) {
 
 // Eq. 5 on a tile of TT tokens (TT = 16 or 32): sX [TT][D+1] holds the tokens, sW [D][D/2] the map; on return
 // sPhi [TT][D] holds softmax(u) then softmax(-u) per token, rows >= n_valid are zero.
+// KIND = kPhiRelu: sPhi = max(sX, 0) instead, sW is not read.
 // Contains __syncthreads(); every thread of the workgroup must call it.
-template <int D, int TT>
+template <int D, int TT, int KIND>
 __device__ __forceinline__ void phi_tile(const float* sX, const float* sW, float* sPhi, int tid, int n_valid) {
   constexpr int HALF = D / 2;
+  if constexpr (KIND == kPhiRelu) {
+    for (int i = tid; i < TT * D; i += NT) {
+      const int tt = i / D, c = i % D;
+      sPhi[i] = tt < n_valid ? fmaxf(sX[tt * (D + 1) + c], 0.f) : 0.f;
+    }
+    __syncthreads();
+    return;
+  }
   {
     constexpr int FB = NT / TT;                  // feature groups
     const int tt = tid % TT, fb = tid / TT;

@@ -44,7 +44,9 @@ constexpr int NT3 = 768;         // 12 wavefronts, one workgroup per compute uni
 
 // BLEND: mixed attention (Sec. 4.1, Eq. 6): out = r' s + (1 - r') o with the softmax-branch output
 // s read in the same pieces as out is stored, and r' = clip(*rptr, 0, 1).
-template <int D, bool BLEND>
+// KIND = kPhiRelu: phi(q) = max(q, 0) straight from the loaded rows (no projection, no W~), features
+// in channel order, kReluEps in the denominator.
+template <int D, bool BLEND, int KIND>
 __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ wq,
                                                          const float* __restrict__ state, uint16_t* __restrict__ out,
                                                          const uint16_t* __restrict__ blend, const float* __restrict__ rptr,
@@ -69,6 +71,7 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
   const uint16_t* bb = BLEND ? blend + head_base(rw, bh, H) : nullptr;
   const float rb = BLEND ? fminf(fmaxf(*rptr, 0.f), 1.f) : 0.f;
 
+  float scale;
   {
     // The state and W~ of this (b,h) are first copied into LDS with coalesced 16-byte loads,
     // then turned into the operand images from there: the scattered reads the images need would cost tens of microseconds from global memory.
@@ -78,13 +81,15 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
     const uint4* gS = reinterpret_cast<const uint4*>(state + (size_t)bh * (D + 1) * D);
     const uint4* gW = reinterpret_cast<const uint4*>(wq + (size_t)h * D * C::HALF);
     for (int i = tid; i < (D + 1) * D / 4; i += NT3) reinterpret_cast<uint4*>(stS)[i] = gS[i];
-    for (int i = tid; i < D * C::HALF / 8; i += NT3) reinterpret_cast<uint4*>(stW)[i] = gW[i];
+    if constexpr (KIND == kPhiHedgehog)
+      for (int i = tid; i < D * C::HALF / 8; i += NT3) reinterpret_cast<uint4*>(stW)[i] = gW[i];
     __syncthreads();
-    const float scale = head_scale<D, NT3>(stS, red, tid);
-    build_w_image<D, NT3>(stW, sWA, tid);
-    build_state_image<D, NT3, true>(stS, sSA, scale, tid);
+    scale = head_scale<D, NT3>(stS, red, tid);
+    if constexpr (KIND == kPhiHedgehog) build_w_image<D, NT3>(stW, sWA, tid);
+    build_state_image<D, NT3, true, KIND>(stS, sSA, scale, tid);
   }
   __syncthreads();
+  const float den_eps = KIND == kPhiRelu ? scale * kReluEps : 0.f;    // the image carries scale * z
 
   const int nblk = (n + 31) / 32;
   const int stride = gridDim.x * NW;
@@ -103,14 +108,24 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
   int b = blockIdx.x * NW + w;
   if (b < nblk) load_block(b);
   for (; b < nblk; b += stride) {
-    f32x16 u[C::UM];
-    project<D>(x, sWA, lane, u);
-    // next block's rows fly during the rest of this one (BLEND: the pieces of s take their registers,
-    // so each 16-byte piece of the next rows is requested in the second pass as the k-step that
-    // frees a piece of phi has been issued)
-    if constexpr (!BLEND) load_block(b + stride < nblk ? b + stride : b);
     uint32_t pk[C::NPK];
-    softmax_pair_ratio<D>(u, pk);
+    if constexpr (KIND == kPhiRelu) {
+      static_assert(C::NPK == 4 * C::UK, "one 16-byte piece of phi per piece of the row");
+#pragma unroll
+      for (int ks = 0; ks < C::UK; ++ks) {
+        const uint4 f = relu_f16x8(x[ks]);
+        pk[4 * ks] = f.x; pk[4 * ks + 1] = f.y; pk[4 * ks + 2] = f.z; pk[4 * ks + 3] = f.w;
+      }
+      if constexpr (!BLEND) load_block(b + stride < nblk ? b + stride : b);
+    } else {
+      f32x16 u[C::UM];
+      project<D>(x, sWA, lane, u);
+      // next block's rows fly during the rest of this one (BLEND: the pieces of s take their
+      // registers, so each 16-byte piece of the next rows is requested in the second pass as the
+      // k-step that frees a piece of phi has been issued)
+      if constexpr (!BLEND) load_block(b + stride < nblk ? b + stride : b);
+      softmax_pair_ratio<D>(u, pk);
+    }
     // register r of an accumulator is token b*32 + 8*(r/4) + 4g + r%4; the lane's MB channels of it
     // are MB*c .. MB*c + MB-1, two bytes each
     const bool full = b * 32 + 32 <= n;
@@ -160,7 +175,7 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
       }
       if (pass == 0) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) inv[r] = __builtin_amdgcn_rcpf(dn[r]);
+        for (int r = 0; r < 16; ++r) inv[r] = __builtin_amdgcn_rcpf(dn[r] + den_eps);
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -483,12 +498,12 @@ hipError_t launch_state_partials_bf16(const void* k, const void* v, const void* 
 
 namespace {
 
-template <int D, bool BLEND>
+template <int D, bool BLEND, int KIND>
 hipError_t run_apply(const void* q, const void* wq, const float* state, void* out, const void* blend_in,
                      const float* blend_r, const Plan& p, hipStream_t s) {
   hipError_t e;
-  if ((e = set_smem(apply_bf16_kernel<D, BLEND>, apply_smem<D>())) != hipSuccess) return e;
-  apply_bf16_kernel<D, BLEND><<<dim3(p.QP, p.BH), NT3, apply_smem<D>(), s>>>(
+  if ((e = set_smem(apply_bf16_kernel<D, BLEND, KIND>, apply_smem<D>())) != hipSuccess) return e;
+  apply_bf16_kernel<D, BLEND, KIND><<<dim3(p.QP, p.BH), NT3, apply_smem<D>(), s>>>(
       (const uint16_t*)q, (const uint16_t*)wq, state, (uint16_t*)out, (const uint16_t*)blend_in, blend_r, p.H, p.n, p.rows);
   return hipGetLastError();
 }
@@ -497,11 +512,14 @@ hipError_t run_apply(const void* q, const void* wq, const float* state, void* ou
 
 hipError_t launch_apply_bf16(const void* q, const void* wq, const float* state, void* out,
                              const void* blend_in, const float* blend_r, const Plan& p, hipStream_t s) {
+  if (p.kind == kPhiRelu)      // the dispatch has refused a blend with this map
+    return p.d == 128 ? run_apply<128, false, kPhiRelu>(q, nullptr, state, out, nullptr, nullptr, p, s)
+                      : run_apply<64, false, kPhiRelu>(q, nullptr, state, out, nullptr, nullptr, p, s);
   if (p.d == 128)
-    return blend_in ? run_apply<128, true>(q, wq, state, out, blend_in, blend_r, p, s)
-                    : run_apply<128, false>(q, wq, state, out, nullptr, nullptr, p, s);
-  return blend_in ? run_apply<64, true>(q, wq, state, out, blend_in, blend_r, p, s)
-                  : run_apply<64, false>(q, wq, state, out, nullptr, nullptr, p, s);
+    return blend_in ? run_apply<128, true, kPhiHedgehog>(q, wq, state, out, blend_in, blend_r, p, s)
+                    : run_apply<128, false, kPhiHedgehog>(q, wq, state, out, nullptr, nullptr, p, s);
+  return blend_in ? run_apply<64, true, kPhiHedgehog>(q, wq, state, out, blend_in, blend_r, p, s)
+                  : run_apply<64, false, kPhiHedgehog>(q, wq, state, out, nullptr, nullptr, p, s);
 }
 
 }  // namespace linattn

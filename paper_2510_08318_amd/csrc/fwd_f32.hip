@@ -10,7 +10,7 @@ namespace {
 using namespace f32;
 constexpr int TT = 32;        // tokens per tile
 
-template <int D>
+template <int D, int KIND>
 __global__ __launch_bounds__(NT) void state_partials_f32_kernel(const float* __restrict__ k, const float* __restrict__ v,
                                                                 const float* __restrict__ wk, float* __restrict__ partials,
                                                                 int H, int n, int P, int chunk, Rows rw) {
@@ -29,7 +29,8 @@ __global__ __launch_bounds__(NT) void state_partials_f32_kernel(const float* __r
   const float* kb = k + head_base(rw, bh, H);
   const float* vb = v + head_base(rw, bh, H);
   const float* wb = wk + (size_t)h * D * HALF;
-  for (int i = tid; i < D * HALF; i += NT) sW[i] = wb[i];
+  if constexpr (KIND == kPhiHedgehog)
+    for (int i = tid; i < D * HALF; i += NT) sW[i] = wb[i];
 
   float acc[BLK][BLK];
 #pragma unroll
@@ -49,7 +50,7 @@ __global__ __launch_bounds__(NT) void state_partials_f32_kernel(const float* __r
       sV[tt * D + c] = valid ? vb[(size_t)t * rw.sn + c] : 0.f;
     }
     __syncthreads();
-    phi_tile<D, TT>(sX, sW, sPhi, tid, t_end - t0);
+    phi_tile<D, TT, KIND>(sX, sW, sPhi, tid, t_end - t0);
     for (int tt = 0; tt < TT; ++tt) {
       float a[BLK], b[BLK];
 #pragma unroll
@@ -73,7 +74,7 @@ __global__ __launch_bounds__(NT) void state_partials_f32_kernel(const float* __r
   if (tid < D) dst[D * D + tid] = zacc;
 }
 
-template <int D>
+template <int D, int KIND>
 __global__ __launch_bounds__(NT) void apply_f32_kernel(const float* __restrict__ q, const float* __restrict__ wq,
                                                        const float* __restrict__ state, float* __restrict__ out,
                                                        const float* __restrict__ blend, const float* __restrict__ rptr,
@@ -96,7 +97,8 @@ __global__ __launch_bounds__(NT) void apply_f32_kernel(const float* __restrict__
   const float rb = blend ? fminf(fmaxf(*rptr, 0.f), 1.f) : 0.f;
   const float* wb = wq + (size_t)h * D * HALF;
   const float* sb = state + (size_t)bh * (D + 1) * D;
-  for (int i = tid; i < D * HALF; i += NT) sW[i] = wb[i];
+  if constexpr (KIND == kPhiHedgehog)
+    for (int i = tid; i < D * HALF; i += NT) sW[i] = wb[i];
   for (int i = tid; i < (D + 1) * D; i += NT) sS[i] = sb[i];
 
   const int tt = tid / 8, cb = tid % 8;
@@ -108,7 +110,7 @@ __global__ __launch_bounds__(NT) void apply_f32_kernel(const float* __restrict__
       sX[r * (D + 1) + c] = (t < t_end) ? qb[(size_t)t * rw.sn + c] : 0.f;
     }
     __syncthreads();
-    phi_tile<D, TT>(sX, sW, sPhi, tid, t_end - t0);
+    phi_tile<D, TT, KIND>(sX, sW, sPhi, tid, t_end - t0);
     float acc[D / 8];
 #pragma unroll
     for (int j = 0; j < D / 8; ++j) acc[j] = 0.f;
@@ -121,7 +123,7 @@ __global__ __launch_bounds__(NT) void apply_f32_kernel(const float* __restrict__
     }
     const int t = t0 + tt;
     if (t < t_end) {
-      const float inv = 1.0f / den;
+      const float inv = 1.0f / (KIND == kPhiRelu ? den + kReluEps : den);
 #pragma unroll
       for (int j = 0; j < D / 8; ++j) {
         float val = acc[j] * inv;
@@ -137,38 +139,38 @@ constexpr size_t state_smem() { return sizeof(float) * (D * (D / 2) + TT * (D + 
 template <int D>
 constexpr size_t apply_smem() { return sizeof(float) * (D * (D / 2) + (D + 1) * D + TT * (D + 1) + TT * D); }
 
+template <int D, int KIND>
+hipError_t run_state(const float* k, const float* v, const float* wk, float* partials, const Plan& p, hipStream_t s) {
+  hipError_t e = hipFuncSetAttribute((const void*)state_partials_f32_kernel<D, KIND>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)state_smem<D>());
+  if (e != hipSuccess) return e;
+  state_partials_f32_kernel<D, KIND><<<dim3(p.P, p.BH), NT, state_smem<D>(), s>>>(k, v, wk, partials, p.H, p.n, p.P, p.chunk, p.rows);
+  return hipGetLastError();
+}
+template <int D, int KIND>
+hipError_t run_apply(const float* q, const float* wq, const float* state, float* out,
+                     const float* blend_in, const float* blend_r, const Plan& p, hipStream_t s) {
+  hipError_t e = hipFuncSetAttribute((const void*)apply_f32_kernel<D, KIND>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)apply_smem<D>());
+  if (e != hipSuccess) return e;
+  apply_f32_kernel<D, KIND><<<dim3(p.QP, p.BH), NT, apply_smem<D>(), s>>>(q, wq, state, out, blend_in, blend_r, p.H, p.n, p.qchunk, p.rows);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_state_partials_f32(const float* k, const float* v, const float* wk, float* partials,
                                      const Plan& p, hipStream_t s) {
-  dim3 grid(p.P, p.BH), block(NT);
-  hipError_t e;
-  if (p.d == 128) {
-    e = hipFuncSetAttribute((const void*)state_partials_f32_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)state_smem<128>());
-    if (e != hipSuccess) return e;
-    state_partials_f32_kernel<128><<<grid, block, state_smem<128>(), s>>>(k, v, wk, partials, p.H, p.n, p.P, p.chunk, p.rows);
-  } else {
-    e = hipFuncSetAttribute((const void*)state_partials_f32_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)state_smem<64>());
-    if (e != hipSuccess) return e;
-    state_partials_f32_kernel<64><<<grid, block, state_smem<64>(), s>>>(k, v, wk, partials, p.H, p.n, p.P, p.chunk, p.rows);
-  }
-  return hipGetLastError();
+  if (p.kind == kPhiRelu)
+    return p.d == 128 ? run_state<128, kPhiRelu>(k, v, wk, partials, p, s) : run_state<64, kPhiRelu>(k, v, wk, partials, p, s);
+  return p.d == 128 ? run_state<128, kPhiHedgehog>(k, v, wk, partials, p, s) : run_state<64, kPhiHedgehog>(k, v, wk, partials, p, s);
 }
 
 hipError_t launch_apply_f32(const float* q, const float* wq, const float* state, float* out,
                             const float* blend_in, const float* blend_r, const Plan& p, hipStream_t s) {
-  dim3 grid(p.QP, p.BH), block(NT);
-  hipError_t e;
-  if (p.d == 128) {
-    e = hipFuncSetAttribute((const void*)apply_f32_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)apply_smem<128>());
-    if (e != hipSuccess) return e;
-    apply_f32_kernel<128><<<grid, block, apply_smem<128>(), s>>>(q, wq, state, out, blend_in, blend_r, p.H, p.n, p.qchunk, p.rows);
-  } else {
-    e = hipFuncSetAttribute((const void*)apply_f32_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)apply_smem<64>());
-    if (e != hipSuccess) return e;
-    apply_f32_kernel<64><<<grid, block, apply_smem<64>(), s>>>(q, wq, state, out, blend_in, blend_r, p.H, p.n, p.qchunk, p.rows);
-  }
-  return hipGetLastError();
+  if (p.kind == kPhiRelu)
+    return p.d == 128 ? run_apply<128, kPhiRelu>(q, wq, state, out, blend_in, blend_r, p, s)
+                      : run_apply<64, kPhiRelu>(q, wq, state, out, blend_in, blend_r, p, s);
+  return p.d == 128 ? run_apply<128, kPhiHedgehog>(q, wq, state, out, blend_in, blend_r, p, s)
+                    : run_apply<64, kPhiHedgehog>(q, wq, state, out, blend_in, blend_r, p, s);
 }
 
 }  // namespace linattn

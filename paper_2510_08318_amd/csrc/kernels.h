@@ -13,6 +13,11 @@ constexpr int kTile = 128;
 constexpr int kSlots = 256;
 // Compute units of the gfx950 parts this library targets (MI355X / MI350X).
 constexpr int kCUs = 256;
+// Feature maps (the values of LINATTN_PHI_*): Eq. 5, and the weight-free phi(x) = max(x, 0) of the
+// kernel-function ablation.  The ReLU map can give phi(q) . z = 0, so its denominator carries
+// kReluEps.
+constexpr int kPhiHedgehog = 1, kPhiRelu = 2;
+constexpr float kReluEps = 1e-6f;
 
 // Where the rows of q, k, v, out (and dout, dq, dk, dv) sit in memory, in elements: element
 // (b, h, t, c) is at b*sb + h*sh + t*sn + c.  [B,H,n,d]: sb = H*n*d, sh = n*d, sn = d;
@@ -48,6 +53,7 @@ __host__ __device__ inline int split_owner(const Split& s, long long x) {
 // How one call is cut into workgroups and where its scratch regions sit in the workspace.
 struct Plan {
   int B, H, n, d;
+  int kind;         // kPhiHedgehog or kPhiRelu (set by the dispatch, not by make_plan)
   int BH;
   Rows rows;        // memory layout of the token tensors
   Split split;      // bf16 forward state pass
@@ -107,6 +113,8 @@ hipError_t launch_state_partials_f32(const float* k, const float* v, const float
                                      const Plan& p, hipStream_t s);
 hipError_t launch_state_partials_bf16(const void* k, const void* v, const void* wk, float* partials,
                                       const Plan& p, hipStream_t s);
+// The same for the ReLU map (bf16): partials [BH][P][(d+1)*d], to be summed by launch_state_reduce.
+hipError_t launch_relu_state_bf16(const void* k, const void* v, float* partials, const Plan& p, hipStream_t s);
 // Fixed-order sum of the partials into the exported state layout [BH][d+1][d] fp32.
 hipError_t launch_state_reduce(const float* partials, float* state, const Plan& p, hipStream_t s);
 // The same for the partials of the bf16 forward state pass (slots per head follow Plan::split).
@@ -124,6 +132,7 @@ hipError_t launch_dw_reduce(const float* part, float* dw, const Plan& p, hipStre
 hipError_t launch_dw(const void* x, bool x_is_bf16, const float* du, float* part, float* dw, const Plan& p, hipStream_t s);
 hipError_t launch_bwd_bf16(const BwdArgs& a, const Plan& p, hipStream_t s);
 hipError_t launch_bwd_f32(const BwdArgs& a, const Plan& p, hipStream_t s);
+hipError_t launch_relu_bwd_bf16(const BwdArgs& a, const Plan& p, hipStream_t s);
 // dr = sum of the count parts in a fixed order if 0 <= *r <= 1, else 0 (Eq. 6, clipped r).
 hipError_t launch_dr_reduce(const float* part, int count, const float* r, float* dr, hipStream_t s);
 

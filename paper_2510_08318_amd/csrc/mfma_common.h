@@ -258,7 +258,8 @@ __device__ __forceinline__ float head_scale(const float* __restrict__ S, float* 
 // COLS: the same registers read as B operands of Y = phi S (lane (c,g) holds column c), with the
 // channels dealt out by ApplyLayout::channel_cols; the extra block then holds scale * z[feature] in
 // every column, so each lane of the product receives phi . z of its own token rows.
-template <int D, bool COLS = false>
+// KIND = kPhiRelu: the features are the d channels in their plain order, 16ks + 8g + e.
+template <int D, bool COLS = false, int KIND = kPhiHedgehog>
 __device__ __forceinline__ uint4 state_image_entry(const float* __restrict__ S, float scale, int idx) {
   using L = ApplyLayout<D>;
   const int lane = idx % 64, mb = (idx / 64) % L::MBZ, ks = idx / (64 * L::MBZ);
@@ -266,7 +267,7 @@ __device__ __forceinline__ uint4 state_image_entry(const float* __restrict__ S, 
   float x[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    const int f = L::feature(ks, g, e);
+    const int f = KIND == kPhiRelu ? 16 * ks + 8 * g + e : L::feature(ks, g, e);
     if (mb < L::MB) x[e] = scale * S[f * D + (COLS ? L::channel_cols(mb, m) : L::channel(mb, m))];
     else x[e] = (COLS || m == 0 || m == 4) ? scale * S[D * D + f] : 0.f;
   }
@@ -275,10 +276,10 @@ __device__ __forceinline__ uint4 state_image_entry(const float* __restrict__ S, 
   r.z = pack_f16x2(x[4], x[5]); r.w = pack_f16x2(x[6], x[7]);
   return r;
 }
-template <int D, int NTHREADS, bool COLS = false>
+template <int D, int NTHREADS, bool COLS = false, int KIND = kPhiHedgehog>
 __device__ __forceinline__ void build_state_image(const float* __restrict__ S, uint4* sSA, float scale, int tid) {
   using L = ApplyLayout<D>;
-  for (int idx = tid; idx < L::KS * L::MBZ * 64; idx += NTHREADS) sSA[idx] = state_image_entry<D, COLS>(S, scale, idx);
+  for (int idx = tid; idx < L::KS * L::MBZ * 64; idx += NTHREADS) sSA[idx] = state_image_entry<D, COLS, KIND>(S, scale, idx);
 }
 
 // Index maps of G^T = S Y^T (contraction over the d channels; rows = features of phi), used by the
@@ -370,6 +371,83 @@ __device__ __forceinline__ f16x8 read_tr(const char* tile, int off0, int off1) {
   v.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(tile + off0));
   v.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(tile + off1));
   return __builtin_bit_cast(f16x8, v);
+}
+
+// power of two p with p * m in [1, 2) (m > 0), 1 for m == 0 or non-finite
+__device__ __forceinline__ float pow2_normaliser(float m) {
+  return (m > 0.f && m < 3.0e38f) ? ldexpf(1.0f, -ilogbf(m)) : 1.0f;
+}
+
+__device__ __forceinline__ void unpack_bf16x8(uint4 v, float* f) {
+  f[0] = __builtin_bit_cast(float, v.x << 16); f[1] = __builtin_bit_cast(float, v.x & 0xffff0000u);
+  f[2] = __builtin_bit_cast(float, v.y << 16); f[3] = __builtin_bit_cast(float, v.y & 0xffff0000u);
+  f[4] = __builtin_bit_cast(float, v.z << 16); f[5] = __builtin_bit_cast(float, v.z & 0xffff0000u);
+  f[6] = __builtin_bit_cast(float, v.w << 16); f[7] = __builtin_bit_cast(float, v.w & 0xffff0000u);
+}
+
+// max(x, 0) on a packed pair of bf16 (-0 becomes +0).
+__device__ __forceinline__ uint32_t relu_bf16x2(uint32_t u) { return u & ~(((u & 0x80008000u) >> 15) * 0xffffu); }
+// Eight bf16 of a row -> fp16 of max(x, 0): an MFMA operand piece of the ReLU map.
+__device__ __forceinline__ uint4 relu_f16x8(uint4 x) {
+  uint4 r;
+  r.x = bf16x2_to_f16x2(relu_bf16x2(x.x)); r.y = bf16x2_to_f16x2(relu_bf16x2(x.y));
+  r.z = bf16x2_to_f16x2(relu_bf16x2(x.z)); r.w = bf16x2_to_f16x2(relu_bf16x2(x.w));
+  return r;
+}
+
+// Copy n16 16-byte entries from global memory into LDS (all threads of the workgroup).
+template <int NTHREADS>
+__device__ __forceinline__ void copy_image(const uint4* __restrict__ src, uint4* dst, int n16, int tid) {
+  for (int i = tid; i < n16; i += NTHREADS) dst[i] = src[i];
+}
+
+// Maximum of x over the wavefront, given x already equal in lanes l and l^32: DPP steps inside each
+// row of 16 lanes, then the two rows of the low half are combined through scalar registers.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float wave_max_paired(float x) {
+  x = fmaxf(x, dpp_move<0xB1>(x));      // quad_perm [1,0,3,2]
+  x = fmaxf(x, dpp_move<0x4E>(x));      // quad_perm [2,3,0,1]
+  x = fmaxf(x, dpp_move<0x124>(x));     // row_ror 4
+  x = fmaxf(x, dpp_move<0x128>(x));     // row_ror 8
+  const float a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 0));
+  const float b = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 16));
+  return fmaxf(a, b);
+}
+
+// Accumulators with tokens on the rows (lane (c,g), register r: token t0 + 8*(r/4) + 4g + r%4,
+// channels MB*c .. MB*c + MB-1 in acc[0..MB-1]) -> mul * acc as bf16 rows of base.  Every store
+// instruction writes two whole rows of d channels.
+template <int D>
+__device__ __forceinline__ void store_token_rows(uint16_t* base, size_t sn, int t0, int n, int lane,
+                                                 const f32x16 (&acc)[D / 32], float mul) {
+  constexpr int MB = D / 32;
+  static_assert(MB == 2 || MB == 4, "head width 64 or 128");
+  const int c = lane % 32, g = lane / 32;
+  char* ub = reinterpret_cast<char*>(base + (size_t)t0 * sn);
+  const uint32_t lo = ((uint32_t)(4 * g) * (uint32_t)sn + (uint32_t)(MB * c)) * 2u;
+  auto put = [&](int r) {
+    const int row = 8 * (r / 4) + (r % 4);
+    char* dst = ub + (size_t)row * sn * 2 + lo;
+    if constexpr (MB == 4) {
+      uint2 v;
+      v.x = pack_bf16x2(acc[0][r] * mul, acc[1][r] * mul);
+      v.y = pack_bf16x2(acc[2][r] * mul, acc[3][r] * mul);
+      *reinterpret_cast<uint2*>(dst) = v;
+    } else {
+      *reinterpret_cast<uint32_t*>(dst) = pack_bf16x2(acc[0][r] * mul, acc[1][r] * mul);
+    }
+  };
+  if (t0 + 32 <= n) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) put(r);
+  } else {
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      if (t0 + 8 * (r / 4) + (r % 4) + 4 * g < n) put(r);
+  }
 }
 
 }  // namespace linattn

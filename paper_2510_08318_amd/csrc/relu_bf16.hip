@@ -1,0 +1,603 @@
+// ReLU feature map, bf16 I/O: phi(x) = max(x, 0) on the d channels of a head (the "ReLU" row of
+// the paper's ablation of kernel functions), put into Eq. 3 with kReluEps in the denominator.
+// This file holds the state pass and the backward; the query pass is apply_bf16_kernel<.., kPhiRelu>
+// in fwd_bf16.hip.
+//
+// With no projection and no softmax the map costs a sign test, so every kernel here is the plain
+// contraction of Eq. 3 (or of its chain rule) on fp16 MFMA operands with fp32 accumulation:
+//   relu_state_kernel  : S_p = sum_j phi(k_j)^T v_j, z_p = sum_j phi(k_j) over the tiles of a split
+//   relu_prep_kernel   : MFMA operand images of a state (S or dS), built once per head
+//   relu_bwd_q_kernel  : den, G = dO S^T, delta, dq; split-n partials of dS, dz
+//   relu_bwd_k_kernel  : dv = phi(k) dS, dk = (v dS^T + dz) where k > 0
+// Gradients (chain rule through Eq. 3, then the mask of max(x, 0), whose derivative at 0 is taken as 0):
+//   den_i = phi(q_i).z + eps, o_i = phi(q_i) S / den_i, delta_i = dO_i . o_i
+//   dphi(q_i) = (S dO_i - delta_i z) / den_i;  dS = sum_i phi(q_i)^T dO_i / den_i;  dz = -sum_i phi(q_i) delta_i / den_i
+//   dphi(k_j) = dS v_j + dz;  dv_j = dS^T phi(k_j)
+// Operands that are gradients are scaled by powers of two before the cast to fp16, as in bwd_bf16.hip.
+#include "kernels.h"
+#include "mfma_common.h"
+
+namespace linattn {
+namespace {
+
+// ---- state pass -------------------------------------------------------------------------------
+// grid (P, BH), 4 wavefronts.  Workgroup p of a head takes the 128-token tiles p, p+P, ...: K (through
+// max(.,0)) and V are parked in LDS as fp16 and contracted over the tokens with transposing reads;
+// wavefront (mi, ni) owns the feature rows 32*WMN*mi .. and the channel columns 32*WMN*ni .. of S.
+// z = phi(K)^T 1 rides along as one more MFMA per k-step against an operand of ones.
+template <int D>
+__global__ __launch_bounds__(NT) void relu_state_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+                                                        float* __restrict__ partials, int H, int n, int P, Rows rw) {
+  constexpr int RS = D * 2;
+  constexpr int WMN = D / 64;
+  constexpr int XPT = (kTile * (D / 8)) / NT;   // 16-byte chunks of a tile per thread
+  extern __shared__ uint4 smem[];
+  char* sK = reinterpret_cast<char*>(smem);      // [kTile][D] fp16, swizzled chunks
+  char* sV = sK + kTile * RS;
+
+  const int tid = threadIdx.x, lane = tid % 64;
+  const int w = __builtin_amdgcn_readfirstlane(tid / 64);
+  const int g = lane / 32;
+  const int mi = w / 2, ni = w % 2;
+  const int bh = blockIdx.y, p = blockIdx.x;
+  const uint16_t* kb = k + head_base(rw, bh, H);
+  const uint16_t* vb = v + head_base(rw, bh, H);
+  const int ntile = (n + kTile - 1) / kTile;
+
+  f32x16 s[WMN][WMN], zacc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    zacc[r] = 0.f;
+#pragma unroll
+    for (int i = 0; i < WMN; ++i)
+#pragma unroll
+      for (int j = 0; j < WMN; ++j) s[i][j][r] = 0.f;
+  }
+  const int zmb = (WMN == 2) ? (2 * mi + ni) : mi;      // the 32-feature block whose z this wavefront sums
+  const bool do_z = (WMN == 2) || (ni == 0);
+  int offA[WMN][2], offB[WMN][2];
+#pragma unroll
+  for (int i = 0; i < WMN; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      offA[i][j] = tr_offset<D>(32 * (mi * WMN + i), lane, j);
+      offB[i][j] = tr_offset<D>(32 * (ni * WMN + i), lane, j);
+    }
+  uint4 ones;
+  ones.x = ones.y = ones.z = ones.w = 0x3C003C00u;
+  const f16x8 one_op = as_f16x8(ones);
+
+  uint4 kr[XPT], vr[XPT];
+  auto load_tile = [&](int tile) {
+    const int t0 = tile * kTile;
+#pragma unroll
+    for (int i = 0; i < XPT; ++i) {
+      const int idx = tid + NT * i, r = idx / (D / 8), c = idx % (D / 8);
+      const int t = t0 + r;
+      const bool there = t < n;
+      kr[i] = there ? ld_nt(reinterpret_cast<const uint4*>(kb + (size_t)t * rw.sn) + c) : make_uint4(0, 0, 0, 0);
+      vr[i] = there ? ld_nt(reinterpret_cast<const uint4*>(vb + (size_t)t * rw.sn) + c) : make_uint4(0, 0, 0, 0);
+    }
+  };
+  if (p < ntile) load_tile(p);
+  for (int tile = p; tile < ntile; tile += P) {
+    __syncthreads();                              // previous tile's operand reads are done
+#pragma unroll
+    for (int i = 0; i < XPT; ++i) {
+      const int idx = tid + NT * i, r = idx / (D / 8), c = idx % (D / 8);
+      uint4 hv;
+      hv.x = bf16x2_to_f16x2(vr[i].x); hv.y = bf16x2_to_f16x2(vr[i].y);
+      hv.z = bf16x2_to_f16x2(vr[i].z); hv.w = bf16x2_to_f16x2(vr[i].w);
+      *reinterpret_cast<uint4*>(sK + r * RS + ((c ^ swz<D>(r)) * 16)) = relu_f16x8(kr[i]);
+      *reinterpret_cast<uint4*>(sV + r * RS + ((c ^ swz<D>(r)) * 16)) = hv;
+    }
+    if (tile + P < ntile) load_tile(tile + P);    // next tile flies during the contraction
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < kTile / 16; ++ks) {
+      f16x8 a[WMN], b[WMN];
+#pragma unroll
+      for (int i = 0; i < WMN; ++i) a[i] = read_tr(sK + ks * 16 * RS, offA[i][0], offA[i][1]);
+#pragma unroll
+      for (int j = 0; j < WMN; ++j) b[j] = read_tr(sV + ks * 16 * RS, offB[j][0], offB[j][1]);
+#pragma unroll
+      for (int i = 0; i < WMN; ++i)
+#pragma unroll
+        for (int j = 0; j < WMN; ++j) s[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], s[i][j], 0, 0, 0);
+      if (WMN == 2) {
+        if (ni == 0) zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], one_op, zacc, 0, 0, 0);
+        else zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[WMN - 1], one_op, zacc, 0, 0, 0);
+      } else if (do_z) {
+        zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], one_op, zacc, 0, 0, 0);
+      }
+    }
+  }
+
+  float* dst = partials + ((size_t)bh * P + p) * (size_t)(D + 1) * D;
+  const int c = lane % 32;
+#pragma unroll
+  for (int i = 0; i < WMN; ++i)
+#pragma unroll
+    for (int j = 0; j < WMN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int f = 32 * (mi * WMN + i) + 8 * (r / 4) + 4 * g + (r % 4);
+        dst[f * D + 32 * (ni * WMN + j) + c] = s[i][j][r];
+      }
+  if (do_z && c == 0) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dst[D * D + 32 * zmb + 8 * (r / 4) + 4 * g + (r % 4)] = zacc[r];
+  }
+}
+
+// ---- operand images of a state, built once per head ------------------------------------------------
+// For M = S or dS ([D+1][D] fp32, row D = z or dz), both scaled by one power of two per head:
+//   cimg: B operands of Y = phi M (contraction over the features): state_image_entry<D, true, kPhiRelu>
+//   timg: B operands of G = X M^T (contraction over the channels, columns = features):
+//         entry (ks, mb, lane=(c,g)) holds M[channel_cols(mb,c)][16ks + 8g + e], e = 0..7
+// grid (BH, 8): slice blockIdx.y of the entries.
+template <int D>
+__global__ __launch_bounds__(256) void relu_prep_kernel(const float* __restrict__ state, uint4* __restrict__ cimg,
+                                                        uint4* __restrict__ timg, float* __restrict__ scale_out) {
+  using L = ApplyLayout<D>;
+  constexpr int CIMG = L::KS * L::MBZ * 64, TIMG = L::KS * L::MB * 64;
+  extern __shared__ uint4 prep_stage[];
+  float* S = reinterpret_cast<float*>(prep_stage);                        // [(D+1)*D]
+  __shared__ float red[4];
+  const int bh = blockIdx.x, tid = threadIdx.x;
+  {
+    const uint4* gsrc = reinterpret_cast<const uint4*>(state + (size_t)bh * (D + 1) * D);
+    for (int i = tid; i < (D + 1) * D / 4; i += 256) reinterpret_cast<uint4*>(S)[i] = gsrc[i];
+  }
+  __syncthreads();
+  const float scale = head_scale<D, 256>(S, red, tid);      // every block of a head computes the same value
+  if (blockIdx.y == 0 && tid == 0) scale_out[2 * bh] = scale;      // [BH][2]: S, dS
+  const int first = blockIdx.y * 256 + tid, step = 256 * gridDim.y;
+  for (int idx = first; idx < CIMG; idx += step) cimg[(size_t)bh * CIMG + idx] = state_image_entry<D, true, kPhiRelu>(S, scale, idx);
+  for (int idx = first; idx < TIMG; idx += step) {
+    const int lane = idx % 64, mb = (idx / 64) % L::MB, ks = idx / (64 * L::MB);
+    const int c = lane % 32, g = lane / 32;
+    const float* row = S + L::channel_cols(mb, c) * D + 16 * ks + 8 * g;
+    uint4 r;
+    r.x = pack_f16x2(scale * row[0], scale * row[1]); r.y = pack_f16x2(scale * row[2], scale * row[3]);
+    r.z = pack_f16x2(scale * row[4], scale * row[5]); r.w = pack_f16x2(scale * row[6], scale * row[7]);
+    timg[(size_t)bh * TIMG + idx] = r;
+  }
+}
+
+// Sum of x over the 32 lanes that share lane/32 (every one of them receives it): DPP inside each
+// row of 16 lanes, then the two rows of a half are exchanged with one permlane16 swap.
+__device__ __forceinline__ float half_wave_sum(float x) {
+  x += dpp_move<0xB1>(x);      // quad_perm [1,0,3,2]
+  x += dpp_move<0x4E>(x);      // quad_perm [2,3,0,1]
+  x += dpp_move<0x124>(x);     // row_ror 4
+  x += dpp_move<0x128>(x);     // row_ror 8
+  const uint32_t u = __builtin_bit_cast(uint32_t, x);
+  auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);   // rows 1, 3 of the first <-> rows 0, 2 of the second
+  return __builtin_bit_cast(float, (uint32_t)r[0]) + __builtin_bit_cast(float, (uint32_t)r[1]);
+}
+
+// One channel (0..3, or 0..1 for d = 64) of a lane's piece of a row, as float.
+__device__ __forceinline__ float piece_elem(const uint2& p, int i) {
+  const uint32_t wv = i < 2 ? p.x : p.y;
+  return (i % 2) ? __builtin_bit_cast(float, wv & 0xffff0000u) : __builtin_bit_cast(float, wv << 16);
+}
+__device__ __forceinline__ float piece_elem(const uint32_t& p, int i) {
+  return i ? __builtin_bit_cast(float, p & 0xffff0000u) : __builtin_bit_cast(float, p << 16);
+}
+template <int MB> struct RowPieceT;
+template <> struct RowPieceT<4> { typedef uint2 type; };
+template <> struct RowPieceT<2> { typedef uint32_t type; };
+
+// Rows of x (bf16) in the layout of an accumulator with the tokens on its rows: piece r of lane (c,g)
+// is token t0 + 8*(r/4) + 4g + r%4, channels MB*c .. MB*c + MB-1.  Rows past n read as row n-1.
+template <int D, typename Piece>
+__device__ __forceinline__ void load_row_pieces(const uint16_t* base, size_t sn, int t0, int n, int lane, Piece (&out)[16]) {
+  constexpr int MB = D / 32;
+  const int c = lane % 32, g = lane / 32;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    int t = t0 + 8 * (r / 4) + 4 * g + (r % 4);
+    t = t < n ? t : n - 1;
+    out[r] = *reinterpret_cast<const Piece*>(base + (size_t)t * sn + MB * c);
+  }
+}
+
+// ---- query side of the backward -------------------------------------------------------------------
+// grid (P, BH), 4 wavefronts; wavefront w of a tile owns its tokens 32w .. 32w+31.  Per block:
+//   A operands straight from the loaded rows (a lane owns a token): phi(q) and ts * dO (ts: one power
+//   of two per block);  dn = phi(q) . (scale z) on the accumulator rows (one MFMA column block of z),
+//   ga = ts * scale * dO S^T with the tokens on the rows and the features on the lanes; q once more in
+//   that layout for the mask and for delta = sum_f G_f phi_f / den (a sum over the 32 lanes); dq rows
+//   are stored from the accumulators.  Then phi(q) and gamma * dO / den go to LDS as fp16 and the
+//   four wavefronts contract them over the tile's tokens into dS (dz: one more MFMA per k-step).
+template <int D>
+__global__ __launch_bounds__(NT) void relu_bwd_q_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ dout,
+                                                        const float* __restrict__ state, const uint4* __restrict__ cimg,
+                                                        const uint4* __restrict__ timg, const float* __restrict__ scale_ptr,
+                                                        uint16_t* __restrict__ dq, float* __restrict__ partials,
+                                                        int H, int n, int P, Rows rw) {
+  using C = Cfg<D>;
+  using L = ApplyLayout<D>;
+  using Piece = typename RowPieceT<L::MB>::type;
+  constexpr int RS = D * 2;
+  constexpr int WMN = D / 64;
+  constexpr int CIMG = L::KS * L::MBZ * 64, TIMG = L::KS * L::MB * 64;
+  extern __shared__ uint4 smem[];
+  uint4* sZB = smem;                                       // [KS][64] the z column block of cimg
+  uint4* sT = sZB + L::KS * 64;                            // [KS][MB][64] timg
+  char* sPhi = reinterpret_cast<char*>(sT + TIMG);         // [kTile][D] fp16: phi(q)
+  char* sDO = sPhi + kTile * RS;                           // [kTile][D] fp16: gamma * dO / den
+  uint16_t* sW16 = reinterpret_cast<uint16_t*>(sDO + kTile * RS);   // [kTile] fp16: -gamma * delta / den
+  float* sRow = reinterpret_cast<float*>(sW16 + kTile);    // [4 wavefronts][2][32] per-token scalars
+  float* sRed = sRow + 4 * 64;                             // [8]
+
+  const int tid = threadIdx.x, lane = tid % 64;
+  const int w = __builtin_amdgcn_readfirstlane(tid / 64);
+  const int g = lane / 32, c = lane % 32;
+  const int mi = w / 2, ni = w % 2;
+  const int bh = blockIdx.y, p = blockIdx.x;
+  const uint16_t* qb = q + head_base(rw, bh, H);
+  const uint16_t* dob = dout + head_base(rw, bh, H);
+  uint16_t* dqb = dq + head_base(rw, bh, H);
+  const float* sb = state + (size_t)bh * (D + 1) * D;
+  const int ntile = (n + kTile - 1) / kTile;
+
+  for (int i = tid; i < L::KS * 64; i += NT)
+    sZB[i] = cimg[(size_t)bh * CIMG + ((i / 64) * L::MBZ + L::MB) * 64 + (i % 64)];
+  copy_image<NT>(timg + (size_t)bh * TIMG, sT, TIMG, tid);
+  const float scale = scale_ptr[2 * bh];
+  float zl[L::MB];                                         // z of the lane's features
+#pragma unroll
+  for (int mb = 0; mb < L::MB; ++mb) zl[mb] = sb[D * D + L::channel_cols(mb, c)];
+  __syncthreads();
+
+  f32x16 s[WMN][WMN], zacc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    zacc[r] = 0.f;
+#pragma unroll
+    for (int i = 0; i < WMN; ++i)
+#pragma unroll
+      for (int j = 0; j < WMN; ++j) s[i][j][r] = 0.f;
+  }
+  const int zmb = (WMN == 2) ? (2 * mi + ni) : mi;
+  const bool do_z = (WMN == 2) || (ni == 0);
+  int offA[WMN][2], offB[WMN][2];
+#pragma unroll
+  for (int i = 0; i < WMN; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      offA[i][j] = tr_offset<D>(32 * (mi * WMN + i), lane, j);
+      offB[i][j] = tr_offset<D>(32 * (ni * WMN + i), lane, j);
+    }
+  const int prow = 32 * w + (lane % 32);
+  const int psw = swz<D>(prow);
+  float* myRow = sRow + w * 64;
+  float gamma = 1.f;
+
+  for (int tile = p; tile < ntile; tile += P) {
+    const int t0 = tile * kTile + 32 * w;
+    const int t = tile * kTile + prow;
+    const bool valid = t < n;
+    const int tc = valid ? t : (n - 1);
+    uint4 xq[C::UK], dor[C::UK];
+    {
+      const uint4* row = reinterpret_cast<const uint4*>(qb + (size_t)tc * rw.sn);
+      const uint4* drow = reinterpret_cast<const uint4*>(dob + (size_t)tc * rw.sn);
+#pragma unroll
+      for (int ks = 0; ks < C::UK; ++ks) { xq[ks] = row[2 * ks + g]; dor[ks] = drow[2 * ks + g]; }
+    }
+    Piece qrow[16];
+    load_row_pieces<D>(qb, rw.sn, t0, n, lane, qrow);
+
+    // block scale of dO
+    float dmax = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < C::UK; ++ks) {
+      float f[8];
+      unpack_bf16x8(dor[ks], f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dmax = fmaxf(dmax, fabsf(f[e]));
+    }
+    if (!valid) dmax = 0.f;
+    float lo, hi;
+    pair32(dmax, lo, hi); dmax = fmaxf(lo, hi);              // the token's largest |dO|
+    const float ts = pow2_normaliser(wave_max_paired(dmax));
+
+    // den and G on the accumulator rows
+    f32x16 ga[L::MB], dn;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      dn[r] = 0.f;
+#pragma unroll
+      for (int mb = 0; mb < L::MB; ++mb) ga[mb][r] = 0.f;
+    }
+    const uint4* szb = sZB + lane + opaque_zero();
+    const uint4* st = sT + lane + opaque_zero();
+#pragma unroll
+    for (int ks = 0; ks < L::KS; ++ks) {
+      dn = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(relu_f16x8(xq[ks])), as_f16x8(szb[ks * 64]), dn, 0, 0, 0);
+      float f[8];
+      unpack_bf16x8(dor[ks], f);
+      uint4 aq;
+      aq.x = pack_f16x2(f[0] * ts, f[1] * ts); aq.y = pack_f16x2(f[2] * ts, f[3] * ts);
+      aq.z = pack_f16x2(f[4] * ts, f[5] * ts); aq.w = pack_f16x2(f[6] * ts, f[7] * ts);
+      const f16x8 aop = as_f16x8(aq);
+#pragma unroll
+      for (int mb = 0; mb < L::MB; ++mb)
+        ga[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop, as_f16x8(st[(ks * L::MB + mb) * 64]), ga[mb], 0, 0, 0);
+    }
+    // per row: a = 1 / (scale * den), delta = (sum_f G_f phi_f) / den; dq = (G - delta z) / den where q > 0
+    const float its = __builtin_amdgcn_rcpf(ts);                // exact: a power of two
+    const float den_eps = scale * kReluEps;
+    float arow[16], drow_[16];
+    f32x16 dqa[L::MB];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float part = 0.f;
+#pragma unroll
+      for (int mb = 0; mb < L::MB; ++mb) part = fmaf(ga[mb][r], fmaxf(piece_elem(qrow[r], mb), 0.f), part);
+      const float sum = half_wave_sum(part);                    // ts * scale * dO . (phi S)
+      const float a = __builtin_amdgcn_rcpf(dn[r] + den_eps);   // 1 / (scale * den)
+      const float delta = sum * a * its;
+      arow[r] = a;
+      drow_[r] = delta;
+#pragma unroll
+      for (int mb = 0; mb < L::MB; ++mb) {
+        const float val = ga[mb][r] * (a * its) - delta * (scale * a) * zl[mb];
+        dqa[mb][r] = piece_elem(qrow[r], mb) > 0.f ? val : 0.f;
+      }
+    }
+    store_token_rows<D>(dqb, rw.sn, t0, n, lane, dqa, 1.f);
+
+    // the per-token scalars back onto the lanes that own the tokens
+    if (c == 0) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = 8 * (r / 4) + 4 * g + (r % 4);
+        myRow[row] = arow[r];
+        myRow[32 + row] = drow_[r];
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+    const float a_t = myRow[lane % 32];
+    const float delta_t = myRow[32 + (lane % 32)];
+    __builtin_amdgcn_wave_barrier();
+    const float inv_den = scale * a_t;                          // 1 / den
+    // a query with phi(q) = 0 adds nothing to dS and dz, but its 1 / den = 1 / eps would set the
+    // common scale gamma and push every other token's operand into the fp16 subnormals
+    bool live;
+    {
+      uint32_t any = 0;
+#pragma unroll
+      for (int ks = 0; ks < C::UK; ++ks) {
+        const uint4 f = relu_f16x8(xq[ks]);
+        any |= f.x | f.y | f.z | f.w;
+      }
+      auto r2 = __builtin_amdgcn_permlane32_swap(any, any, false, false);
+      live = valid && (((uint32_t)r2[0] | (uint32_t)r2[1]) != 0);
+    }
+
+    // operands of the sums over tokens
+    if (tile == p) {
+      float m = live ? dmax * inv_den : 0.f;
+      for (int k2 = 32; k2 >= 1; k2 >>= 1) m = fmaxf(m, __shfl_xor(m, k2, 64));
+      if (lane == 0) sRed[w] = m;
+      __syncthreads();
+      m = fmaxf(fmaxf(sRed[0], sRed[1]), fmaxf(sRed[2], sRed[3]));
+      gamma = 16.f * pow2_normaliser(m);
+    }
+    __syncthreads();                             // previous tile's operand reads are done
+    {
+      char* rowp = sPhi + prow * RS;
+      char* drowp = sDO + prow * RS;
+      const float sc = live ? inv_den * gamma : 0.f;
+#pragma unroll
+      for (int ks = 0; ks < C::UK; ++ks) {
+        uint4 a = relu_f16x8(xq[ks]);
+        if (!live) a = make_uint4(0, 0, 0, 0);
+        *reinterpret_cast<uint4*>(rowp + (((2 * ks + g) ^ psw) * 16)) = a;
+        float f[8];
+        unpack_bf16x8(dor[ks], f);
+        uint4 b;
+        b.x = pack_f16x2(f[0] * sc, f[1] * sc); b.y = pack_f16x2(f[2] * sc, f[3] * sc);
+        b.z = pack_f16x2(f[4] * sc, f[5] * sc); b.w = pack_f16x2(f[6] * sc, f[7] * sc);
+        *reinterpret_cast<uint4*>(drowp + (((2 * ks + g) ^ psw) * 16)) = b;
+      }
+      if (g == 0) sW16[prow] = (uint16_t)(pack_f16x2(live ? -delta_t * sc : 0.f, 0.f) & 0xffffu);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < kTile / 16; ++ks) {
+      f16x8 a[WMN], b[WMN];
+#pragma unroll
+      for (int i = 0; i < WMN; ++i) a[i] = read_tr(sPhi + ks * 16 * RS, offA[i][0], offA[i][1]);
+#pragma unroll
+      for (int j = 0; j < WMN; ++j) b[j] = read_tr(sDO + ks * 16 * RS, offB[j][0], offB[j][1]);
+#pragma unroll
+      for (int i = 0; i < WMN; ++i)
+#pragma unroll
+        for (int j = 0; j < WMN; ++j) s[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], s[i][j], 0, 0, 0);
+      // dz row block: B operand = the 8 tokens' weights, the same in every column
+      const f16x8 wop = as_f16x8(*reinterpret_cast<const uint4*>(sW16 + 16 * ks + 8 * g));
+      if (WMN == 2) {
+        if (ni == 0) zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], wop, zacc, 0, 0, 0);
+        else zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[WMN - 1], wop, zacc, 0, 0, 0);
+      } else if (do_z) {
+        zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], wop, zacc, 0, 0, 0);
+      }
+    }
+  }
+
+  const float ig = __builtin_amdgcn_rcpf(gamma);    // exact: gamma is a power of two
+  float* dst = partials + ((size_t)bh * P + p) * (size_t)(D + 1) * D;
+#pragma unroll
+  for (int i = 0; i < WMN; ++i)
+#pragma unroll
+    for (int j = 0; j < WMN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int f = 32 * (mi * WMN + i) + 8 * (r / 4) + 4 * g + (r % 4);
+        dst[f * D + 32 * (ni * WMN + j) + c] = s[i][j][r] * ig;
+      }
+  if (do_z && c == 0) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dst[D * D + 32 * zmb + 8 * (r / 4) + 4 * g + (r % 4)] = zacc[r] * ig;
+  }
+}
+
+// ---- key side of the backward ---------------------------------------------------------------------
+// grid (KP, BH), 8 wavefronts, each on its own 32-token blocks.  Both products have the tokens on
+// the accumulator rows: dv = phi(k) dS (B operands: cimg of dS) and g = v dS^T + dz (timg of dS);
+// dk = g where k > 0, with k read once more in the accumulator layout for the mask.
+constexpr int NTK = 512;
+template <int D>
+__global__ __launch_bounds__(NTK) void relu_bwd_k_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+                                                         const float* __restrict__ dstate, const uint4* __restrict__ cimg,
+                                                         const uint4* __restrict__ timg, const float* __restrict__ scale_ptr,
+                                                         uint16_t* __restrict__ dk, uint16_t* __restrict__ dv,
+                                                         int H, int n, Rows rw) {
+  using C = Cfg<D>;
+  using L = ApplyLayout<D>;
+  using Piece = typename RowPieceT<L::MB>::type;
+  constexpr int NW = NTK / 64;
+  constexpr int CIMG = L::KS * L::MBZ * 64, TIMG = L::KS * L::MB * 64;
+  extern __shared__ uint4 smem[];
+  uint4* sC = smem;
+  uint4* sT = sC + CIMG;
+
+  const int tid = threadIdx.x, lane = tid % 64;
+  const int w = __builtin_amdgcn_readfirstlane(tid / 64);
+  const int g = lane / 32, c = lane % 32;
+  const int bh = blockIdx.y;
+  const uint16_t* kb = k + head_base(rw, bh, H);
+  const uint16_t* vb = v + head_base(rw, bh, H);
+  uint16_t* dkb = dk + head_base(rw, bh, H);
+  uint16_t* dvb = dv + head_base(rw, bh, H);
+  const float* ds = dstate + (size_t)bh * (D + 1) * D;
+
+  copy_image<NTK>(cimg + (size_t)bh * CIMG, sC, CIMG, tid);
+  copy_image<NTK>(timg + (size_t)bh * TIMG, sT, TIMG, tid);
+  const float inv_scale = __builtin_amdgcn_rcpf(scale_ptr[2 * bh]);    // exact: power of two
+  float dzl[L::MB];
+#pragma unroll
+  for (int mb = 0; mb < L::MB; ++mb) dzl[mb] = ds[D * D + L::channel_cols(mb, c)];
+  __syncthreads();
+
+  const int nblk = (n + 31) / 32;
+  const int stride = gridDim.x * NW;
+  for (int b = blockIdx.x * NW + w; b < nblk; b += stride) {
+    const int t = b * 32 + (lane % 32);
+    const int tc = t < n ? t : (n - 1);
+    uint4 xk[C::UK], xv[C::UK];
+    {
+      const uint4* row = reinterpret_cast<const uint4*>(kb + (size_t)tc * rw.sn);
+      const uint4* vrow = reinterpret_cast<const uint4*>(vb + (size_t)tc * rw.sn);
+#pragma unroll
+      for (int ks = 0; ks < C::UK; ++ks) { xk[ks] = row[2 * ks + g]; xv[ks] = vrow[2 * ks + g]; }
+    }
+    Piece krow[16];
+    load_row_pieces<D>(kb, rw.sn, b * 32, n, lane, krow);
+    {
+      f32x16 va[L::MB];
+#pragma unroll
+      for (int mb = 0; mb < L::MB; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) va[mb][r] = 0.f;
+      const uint4* sc = sC + lane + opaque_zero();
+#pragma unroll
+      for (int ks = 0; ks < L::KS; ++ks) {
+        const f16x8 aop = as_f16x8(relu_f16x8(xk[ks]));
+#pragma unroll
+        for (int mb = 0; mb < L::MB; ++mb)
+          va[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop, as_f16x8(sc[(ks * L::MBZ + mb) * 64]), va[mb], 0, 0, 0);
+      }
+      store_token_rows<D>(dvb, rw.sn, b * 32, n, lane, va, inv_scale);
+    }
+    {
+      f32x16 ga[L::MB];
+#pragma unroll
+      for (int mb = 0; mb < L::MB; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) ga[mb][r] = 0.f;
+      const uint4* st = sT + lane + opaque_zero();
+#pragma unroll
+      for (int ks = 0; ks < L::KS; ++ks) {
+        uint4 aq;
+        aq.x = bf16x2_to_f16x2(xv[ks].x); aq.y = bf16x2_to_f16x2(xv[ks].y);
+        aq.z = bf16x2_to_f16x2(xv[ks].z); aq.w = bf16x2_to_f16x2(xv[ks].w);
+        const f16x8 aop = as_f16x8(aq);
+#pragma unroll
+        for (int mb = 0; mb < L::MB; ++mb)
+          ga[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop, as_f16x8(st[(ks * L::MB + mb) * 64]), ga[mb], 0, 0, 0);
+      }
+#pragma unroll
+      for (int mb = 0; mb < L::MB; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          ga[mb][r] = piece_elem(krow[r], mb) > 0.f ? fmaf(ga[mb][r], inv_scale, dzl[mb]) : 0.f;
+      store_token_rows<D>(dkb, rw.sn, b * 32, n, lane, ga, 1.f);
+    }
+  }
+}
+
+template <typename K>
+hipError_t set_smem(K kernel, size_t bytes) {
+  return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+template <int D>
+constexpr size_t state_smem() { return 2 * (size_t)kTile * D * 2; }
+template <int D>
+constexpr size_t prep_smem() { return (size_t)(D + 1) * D * sizeof(float); }
+template <int D>
+constexpr size_t q_smem() {
+  return sizeof(uint4) * (ApplyLayout<D>::KS * 64 + ApplyLayout<D>::KS * ApplyLayout<D>::MB * 64)
+       + 2 * (size_t)kTile * D * 2 + kTile * 2 + (4 * 64 + 8) * sizeof(float);
+}
+template <int D>
+constexpr size_t k_smem() {
+  return sizeof(uint4) * (ApplyLayout<D>::KS * ApplyLayout<D>::MBZ * 64 + ApplyLayout<D>::KS * ApplyLayout<D>::MB * 64);
+}
+
+template <int D>
+hipError_t run_state(const void* k, const void* v, float* partials, const Plan& p, hipStream_t s) {
+  hipError_t e;
+  if ((e = set_smem(relu_state_kernel<D>, state_smem<D>())) != hipSuccess) return e;
+  relu_state_kernel<D><<<dim3(p.P, p.BH), NT, state_smem<D>(), s>>>((const uint16_t*)k, (const uint16_t*)v, partials,
+                                                                   p.H, p.n, p.P, p.rows);
+  return hipGetLastError();
+}
+
+template <int D>
+hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
+  hipError_t e;
+  if ((e = set_smem(relu_prep_kernel<D>, prep_smem<D>())) != hipSuccess) return e;
+  relu_prep_kernel<D><<<dim3(p.BH, 8), 256, prep_smem<D>(), s>>>(a.state, (uint4*)a.simg, (uint4*)a.gimg, a.scales);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if ((e = set_smem(relu_bwd_q_kernel<D>, q_smem<D>())) != hipSuccess) return e;
+  relu_bwd_q_kernel<D><<<dim3(p.P, p.BH), NT, q_smem<D>(), s>>>(
+      (const uint16_t*)a.q, (const uint16_t*)a.dout, a.state, (const uint4*)a.simg, (const uint4*)a.gimg, a.scales,
+      (uint16_t*)a.dq, a.partials, p.H, p.n, p.P, p.rows);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if ((e = launch_state_reduce(a.partials, a.dstate, p, s)) != hipSuccess) return e;
+  relu_prep_kernel<D><<<dim3(p.BH, 8), 256, prep_smem<D>(), s>>>(a.dstate, (uint4*)a.dsimg, (uint4*)a.dgimg, a.scales + 1);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if ((e = set_smem(relu_bwd_k_kernel<D>, k_smem<D>())) != hipSuccess) return e;
+  relu_bwd_k_kernel<D><<<dim3(p.KP, p.BH), NTK, k_smem<D>(), s>>>(
+      (const uint16_t*)a.k, (const uint16_t*)a.v, a.dstate, (const uint4*)a.dsimg, (const uint4*)a.dgimg, a.scales + 1,
+      (uint16_t*)a.dk, (uint16_t*)a.dv, p.H, p.n, p.rows);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_relu_state_bf16(const void* k, const void* v, float* partials, const Plan& p, hipStream_t s) {
+  return p.d == 128 ? run_state<128>(k, v, partials, p, s) : run_state<64>(k, v, partials, p, s);
+}
+
+hipError_t launch_relu_bwd_bf16(const BwdArgs& a, const Plan& p, hipStream_t s) {
+  return p.d == 128 ? run_bwd<128>(a, p, s) : run_bwd<64>(a, p, s);
+}
+
+}  // namespace linattn

@@ -24,6 +24,56 @@ def to_host_f64(t: torch.Tensor) -> np.ndarray:
     return t.detach().to("cpu").to(torch.float64).numpy()
 
 
+class ReluLayer:
+    """Buffers + descriptor of one linear-attention layer with the weight-free map phi(x) = max(x, 0)
+    (the "ReLU" row of the paper's ablation of kernel functions)."""
+
+    def __init__(self, H: int, d: int, B: int, n: int, dtype: torch.dtype, *, layout: str = "bhnd", device="cuda"):
+        assert layout in ("bhnd", "bnhd") and dtype in (torch.bfloat16, torch.float32)
+        self.layout, self.H, self.d, self.B, self.n, self.tdtype = layout, H, d, B, n, dtype
+        self.dtype = B_.BF16 if dtype == torch.bfloat16 else B_.F32
+        self.state = torch.empty((B, H, d + 1, d), dtype=torch.float32, device=device)
+        self.workspace_bytes = B_.linattn_workspace_bytes(B, H, n, d, B_.PHI_RELU, self.dtype)
+        if self.workspace_bytes == 0:
+            raise ValueError("unsupported shape")
+        self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=device)
+        assert self.workspace.data_ptr() % 256 == 0
+        self.phi_id = B_.linattn_phi_create(B_.PHI_RELU, self.dtype, H, d, None, None, None, None, self.state,
+                                            self.workspace, self.workspace_bytes,
+                                            B_.LAYOUT_BNHD if layout == "bnhd" else B_.LAYOUT_BHND)
+
+    def close(self):
+        if self.phi_id is not None:
+            B_.linattn_phi_destroy(self.phi_id)
+            self.phi_id = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, *ts):
+        shape = (self.B, self.n, self.H, self.d) if self.layout == "bnhd" else (self.B, self.H, self.n, self.d)
+        for t in ts:
+            assert t.is_cuda and t.is_contiguous() and t.dtype == self.tdtype and tuple(t.shape) == shape
+
+    def forward(self, q, k, v, out=None):
+        self._check(q, k, v)
+        out = torch.empty_like(q) if out is None else out
+        B_.linattn_fwd(q, k, v, out, self.B, self.H, self.n, self.d, self.phi_id, torch.cuda.current_stream().cuda_stream)
+        return out
+
+    def backward(self, q, k, v, dout, dq=None, dk=None, dv=None):
+        self._check(q, k, v, dout)
+        dq = torch.empty_like(q) if dq is None else dq
+        dk = torch.empty_like(q) if dk is None else dk
+        dv = torch.empty_like(q) if dv is None else dv
+        B_.linattn_bwd(q, k, v, dout, dq, dk, dv, self.B, self.H, self.n, self.d, self.phi_id,
+                       torch.cuda.current_stream().cuda_stream)
+        return dq, dk, dv
+
+
 class Layer:
     """Buffers + descriptor of one linear-attention layer (Eq. 3 with the map of Eq. 5)."""
 

@@ -27,7 +27,7 @@ def test_header_constants_match_binding():
     header = open(os.path.join(ROOT, "include", "linattn.h")).read()
     consts = dict((m.group(1), int(m.group(2))) for m in re.finditer(r"#define\s+LINATTN_(\w+)\s+(-?\d+)", header))
     for name in ("OK", "E_NULL", "E_SHAPE", "E_DTYPE", "E_ALIGN", "E_PHI", "E_WORKSPACE", "E_HIP", "E_STATE",
-                 "E_ALIAS", "PHI_HEDGEHOG", "BF16", "F32", "LAYOUT_BHND", "LAYOUT_BNHD"):
+                 "E_ALIAS", "PHI_HEDGEHOG", "PHI_RELU", "BF16", "F32", "LAYOUT_BHND", "LAYOUT_BNHD"):
         assert consts[name] == getattr(L, name), name
     for code in range(0, -10, -1):
         assert L.linattn_strerror(code) != "unknown status"
@@ -153,3 +153,22 @@ def test_blend_input_may_not_alias_the_output():
                                blend_in=out + 64, blend_r=P + 16)
     assert L.linattn_fwd(q, k, v, out, B, H, n, d, pid, None, check=False) == L.E_ALIAS
     L.linattn_phi_destroy(pid)
+
+
+def test_relu_descriptors_take_no_weights_and_no_blend():
+    mk = lambda **kw: L.linattn_phi_create(**{**dict(kind=L.PHI_RELU, dtype=L.BF16, H=2, d=64, wq=None, wk=None), **kw}, check=False)
+    assert mk(wq=P) == L.E_PHI
+    assert mk(dwk=P) == L.E_PHI
+    assert mk(blend_in=P + 65536, blend_r=P + 4) == L.E_PHI
+    assert mk(d=48) == L.E_SHAPE
+    pid = mk()
+    assert pid >= 16
+    assert L.linattn_phi_set_blend(pid, P + 65536, P + 4, None, check=False) == L.E_PHI
+    assert L.linattn_phi_set_blend(pid, None, None, None, check=False) == L.OK
+    # same scratch with and without "weight gradients": there are none
+    a = L.linattn_workspace_bytes(1, 12, 32760, 128, L.PHI_RELU, L.BF16)
+    assert a > 0 and a == L.linattn_workspace_bytes_wgrads(1, 12, 32760, 128, L.PHI_RELU, L.BF16)
+    assert L.linattn_workspace_bytes(1, 12, 32760, 128, 3, L.BF16) == 0
+    # a call without workspace is refused on the host
+    assert L.linattn_fwd(P, P + (1 << 20), P + (2 << 20), P + (3 << 20), 1, 2, 100, 64, pid, None, check=False) == L.E_WORKSPACE
+    assert L.linattn_phi_destroy(pid) == L.OK
