@@ -274,7 +274,7 @@ int linattn_fwd(const void* q, const void* k, const void* v, void* out,
     e = relu ? launch_relu_state_bf16(k, v, partials, plan, s) : launch_state_partials_bf16(k, v, desc.wk, partials, plan, s);
     if (e != hipSuccess) return LINATTN_E_HIP;
     mark(1, s);
-    e = relu ? launch_state_reduce(partials, state, plan, s) : launch_state_reduce_split(partials, state, plan, s);
+    e = launch_state_reduce_split(partials, state, plan, s);
     if (e != hipSuccess) return LINATTN_E_HIP;
     mark(2, s);
     e = launch_apply_bf16(q, desc.wq, state, out, desc.blend_in, desc.blend_r, plan, s);

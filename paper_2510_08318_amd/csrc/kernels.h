@@ -113,7 +113,7 @@ hipError_t launch_state_partials_f32(const float* k, const float* v, const float
                                      const Plan& p, hipStream_t s);
 hipError_t launch_state_partials_bf16(const void* k, const void* v, const void* wk, float* partials,
                                       const Plan& p, hipStream_t s);
-// The same for the ReLU map (bf16): partials [BH][P][(d+1)*d], to be summed by launch_state_reduce.
+// The same for the ReLU map (bf16); partial slots per head follow Plan::split as well.
 hipError_t launch_relu_state_bf16(const void* k, const void* v, float* partials, const Plan& p, hipStream_t s);
 // Fixed-order sum of the partials into the exported state layout [BH][d+1][d] fp32.
 hipError_t launch_state_reduce(const float* partials, float* state, const Plan& p, hipStream_t s);

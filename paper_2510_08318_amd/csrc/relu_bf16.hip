@@ -21,13 +21,14 @@ namespace linattn {
 namespace {
 
 // ---- state pass -------------------------------------------------------------------------------
-// grid (P, BH), 4 wavefronts.  Workgroup p of a head takes the 128-token tiles p, p+P, ...: K (through
+// 4 wavefronts.  One segment = the 128-token tiles tile0 .. tile0+nt-1 of one (b,h): K (through
 // max(.,0)) and V are parked in LDS as fp16 and contracted over the tokens with transposing reads;
 // wavefront (mi, ni) owns the feature rows 32*WMN*mi .. and the channel columns 32*WMN*ni .. of S.
-// z = phi(K)^T 1 rides along as one more MFMA per k-step against an operand of ones.
+// z = phi(K)^T 1 rides along as one more MFMA per k-step against an operand of ones.  Every thread
+// of the workgroup calls it (it contains workgroup barriers).
 template <int D>
-__global__ __launch_bounds__(NT) void relu_state_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-                                                        float* __restrict__ partials, int H, int n, int P, Rows rw) {
+__device__ __forceinline__ void relu_state_segment(const uint16_t* __restrict__ kb, const uint16_t* __restrict__ vb,
+                                                   float* __restrict__ dst, int tile0, int nt, int n, Rows rw) {
   constexpr int RS = D * 2;
   constexpr int WMN = D / 64;
   constexpr int XPT = (kTile * (D / 8)) / NT;   // 16-byte chunks of a tile per thread
@@ -39,10 +40,7 @@ __global__ __launch_bounds__(NT) void relu_state_kernel(const uint16_t* __restri
   const int w = __builtin_amdgcn_readfirstlane(tid / 64);
   const int g = lane / 32;
   const int mi = w / 2, ni = w % 2;
-  const int bh = blockIdx.y, p = blockIdx.x;
-  const uint16_t* kb = k + head_base(rw, bh, H);
-  const uint16_t* vb = v + head_base(rw, bh, H);
-  const int ntile = (n + kTile - 1) / kTile;
+  const int tile_end = tile0 + nt;
 
   f32x16 s[WMN][WMN], zacc;
 #pragma unroll
@@ -79,8 +77,8 @@ __global__ __launch_bounds__(NT) void relu_state_kernel(const uint16_t* __restri
       vr[i] = there ? ld_nt(reinterpret_cast<const uint4*>(vb + (size_t)t * rw.sn) + c) : make_uint4(0, 0, 0, 0);
     }
   };
-  if (p < ntile) load_tile(p);
-  for (int tile = p; tile < ntile; tile += P) {
+  load_tile(tile0);
+  for (int tile = tile0; tile < tile_end; ++tile) {
     __syncthreads();                              // previous tile's operand reads are done
 #pragma unroll
     for (int i = 0; i < XPT; ++i) {
@@ -91,7 +89,7 @@ __global__ __launch_bounds__(NT) void relu_state_kernel(const uint16_t* __restri
       *reinterpret_cast<uint4*>(sK + r * RS + ((c ^ swz<D>(r)) * 16)) = relu_f16x8(kr[i]);
       *reinterpret_cast<uint4*>(sV + r * RS + ((c ^ swz<D>(r)) * 16)) = hv;
     }
-    if (tile + P < ntile) load_tile(tile + P);    // next tile flies during the contraction
+    if (tile + 1 < tile_end) load_tile(tile + 1); // next tile flies during the contraction
     __syncthreads();
 #pragma unroll
     for (int ks = 0; ks < kTile / 16; ++ks) {
@@ -113,7 +111,6 @@ __global__ __launch_bounds__(NT) void relu_state_kernel(const uint16_t* __restri
     }
   }
 
-  float* dst = partials + ((size_t)bh * P + p) * (size_t)(D + 1) * D;
   const int c = lane % 32;
 #pragma unroll
   for (int i = 0; i < WMN; ++i)
@@ -127,6 +124,28 @@ __global__ __launch_bounds__(NT) void relu_state_kernel(const uint16_t* __restri
   if (do_z && c == 0) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) dst[D * D + 32 * zmb + 8 * (r / 4) + 4 * g + (r % 4)] = zacc[r];
+  }
+  __syncthreads();                               // the next segment reuses the LDS tiles
+}
+
+// Grid: Split::G workgroups; workgroup g takes the tiles [lo(g), lo(g+1)) of the call's (b,h)-major
+// tile sequence, one segment per head it touches (at most two), so every compute unit gets the same
+// share whatever B*H is.  Partials: [BH][Split::PS][(d+1)*d], summed by the split reduction.
+template <int D>
+__global__ __launch_bounds__(NT) void relu_state_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+                                                        float* __restrict__ partials, int H, int n, Split sp, Rows rw) {
+  const int gi = blockIdx.x;
+  long long lo = split_lo(sp, gi);
+  const long long hi = split_lo(sp, gi + 1);
+  while (lo < hi) {
+    const int bh = (int)(lo / sp.ntile);
+    const long long head0 = (long long)bh * sp.ntile;
+    const long long seg_hi = hi < head0 + sp.ntile ? hi : head0 + sp.ntile;
+    const int slot = gi - split_owner(sp, head0);
+    relu_state_segment<D>(k + head_base(rw, bh, H), v + head_base(rw, bh, H),
+                          partials + ((size_t)bh * sp.PS + slot) * (size_t)(D + 1) * D,
+                          (int)(lo - head0), (int)(seg_hi - lo), n, rw);
+    lo = seg_hi;
   }
 }
 
@@ -564,8 +583,8 @@ template <int D>
 hipError_t run_state(const void* k, const void* v, float* partials, const Plan& p, hipStream_t s) {
   hipError_t e;
   if ((e = set_smem(relu_state_kernel<D>, state_smem<D>())) != hipSuccess) return e;
-  relu_state_kernel<D><<<dim3(p.P, p.BH), NT, state_smem<D>(), s>>>((const uint16_t*)k, (const uint16_t*)v, partials,
-                                                                   p.H, p.n, p.P, p.rows);
+  relu_state_kernel<D><<<dim3(p.split.G), NT, state_smem<D>(), s>>>((const uint16_t*)k, (const uint16_t*)v, partials,
+                                                                   p.H, p.n, p.split, p.rows);
   return hipGetLastError();
 }
 
