@@ -436,8 +436,9 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
       // dz row block: B operand = the 8 tokens' weights, the same in every column
       const f16x8 wop = as_f16x8(*reinterpret_cast<const uint4*>(sW16 + 16 * ks + 8 * g));
       if (WMN == 2) {
-        if (ni == 0) zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], wop, zacc, 0, 0, 0);
-        else zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[WMN - 1], wop, zacc, 0, 0, 0);
+        // a select, not a branch: branches inside the loop make the compiler's waits conservative
+        const f16x8 az = ni == 0 ? a[0] : a[WMN - 1];
+        zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(az, wop, zacc, 0, 0, 0);
       } else if (do_z) {
         zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], wop, zacc, 0, 0, 0);
       }

@@ -65,31 +65,39 @@ __device__ __forceinline__ void relu_state_segment(const uint16_t* __restrict__ 
   ones.x = ones.y = ones.z = ones.w = 0x3C003C00u;
   const f16x8 one_op = as_f16x8(ones);
 
-  uint4 kr[XPT], vr[XPT];
-  auto load_tile = [&](int tile) {
+  // Loads are branch-free (rows past n read row n-1 and are zeroed on their way into LDS; after the
+  // last tile of a segment that tile is requested once more and ignored): a load behind a branch
+  // makes the compiler wait for every outstanding load at the join.
+  // Tiles kept in flight per workgroup, and how often the loop body repeats them.  Measured at the
+  // Wan-14B 720p shape: one tile 287 us, two 276 us, three 295 us, four 290 us.  The compiler waits
+  // for every outstanding load at the top of the loop, so only an unrolled body overlaps them.
+  constexpr int DEPTH = 2, UNROLL = 2;
+  uint4 kr[DEPTH][XPT], vr[DEPTH][XPT];
+  auto load_tile = [&](uint4 (&kx)[XPT], uint4 (&vx)[XPT], int tile) {
+    tile = tile < tile_end ? tile : tile_end - 1;
     const int t0 = tile * kTile;
 #pragma unroll
     for (int i = 0; i < XPT; ++i) {
       const int idx = tid + NT * i, r = idx / (D / 8), c = idx % (D / 8);
-      const int t = t0 + r;
-      const bool there = t < n;
-      kr[i] = there ? ld_nt(reinterpret_cast<const uint4*>(kb + (size_t)t * rw.sn) + c) : make_uint4(0, 0, 0, 0);
-      vr[i] = there ? ld_nt(reinterpret_cast<const uint4*>(vb + (size_t)t * rw.sn) + c) : make_uint4(0, 0, 0, 0);
+      const int t = t0 + r < n ? t0 + r : n - 1;
+      kx[i] = ld_nt(reinterpret_cast<const uint4*>(kb + (size_t)t * rw.sn) + c);
+      vx[i] = ld_nt(reinterpret_cast<const uint4*>(vb + (size_t)t * rw.sn) + c);
     }
   };
-  load_tile(tile0);
-  for (int tile = tile0; tile < tile_end; ++tile) {
+  auto consume = [&](uint4 (&kx)[XPT], uint4 (&vx)[XPT], int tile, bool real) {
     __syncthreads();                              // previous tile's operand reads are done
 #pragma unroll
     for (int i = 0; i < XPT; ++i) {
       const int idx = tid + NT * i, r = idx / (D / 8), c = idx % (D / 8);
-      uint4 hv;
-      hv.x = bf16x2_to_f16x2(vr[i].x); hv.y = bf16x2_to_f16x2(vr[i].y);
-      hv.z = bf16x2_to_f16x2(vr[i].z); hv.w = bf16x2_to_f16x2(vr[i].w);
-      *reinterpret_cast<uint4*>(sK + r * RS + ((c ^ swz<D>(r)) * 16)) = relu_f16x8(kr[i]);
+      const bool there = real && tile * kTile + r < n;
+      uint4 hk = relu_f16x8(kx[i]), hv;
+      hv.x = bf16x2_to_f16x2(vx[i].x); hv.y = bf16x2_to_f16x2(vx[i].y);
+      hv.z = bf16x2_to_f16x2(vx[i].z); hv.w = bf16x2_to_f16x2(vx[i].w);
+      if (!there) { hk = make_uint4(0, 0, 0, 0); hv = hk; }
+      *reinterpret_cast<uint4*>(sK + r * RS + ((c ^ swz<D>(r)) * 16)) = hk;
       *reinterpret_cast<uint4*>(sV + r * RS + ((c ^ swz<D>(r)) * 16)) = hv;
     }
-    if (tile + 1 < tile_end) load_tile(tile + 1); // next tile flies during the contraction
+    load_tile(kx, vx, tile + DEPTH);
     __syncthreads();
 #pragma unroll
     for (int ks = 0; ks < kTile / 16; ++ks) {
@@ -103,14 +111,25 @@ __device__ __forceinline__ void relu_state_segment(const uint16_t* __restrict__ 
 #pragma unroll
         for (int j = 0; j < WMN; ++j) s[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], s[i][j], 0, 0, 0);
       if (WMN == 2) {
-        if (ni == 0) zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], one_op, zacc, 0, 0, 0);
-        else zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[WMN - 1], one_op, zacc, 0, 0, 0);
+        // a select, not a branch: branches inside the loop make the compiler's waits conservative
+        const f16x8 az = ni == 0 ? a[0] : a[WMN - 1];
+        zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(az, one_op, zacc, 0, 0, 0);
       } else if (do_z) {
         zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], one_op, zacc, 0, 0, 0);
       }
     }
+  };
+#pragma unroll
+  for (int j = 0; j < DEPTH; ++j) load_tile(kr[j], vr[j], tile0 + j);
+  for (int tile = tile0; tile < tile_end; tile += UNROLL * DEPTH) {
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+      for (int j = 0; j < DEPTH; ++j) {
+        const int tl = tile + u * DEPTH + j;
+        consume(kr[j], vr[j], tl, tl < tile_end);     // a padding step adds zeros
+      }
   }
-
   const int c = lane % 32;
 #pragma unroll
   for (int i = 0; i < WMN; ++i)
@@ -441,8 +460,9 @@ __global__ __launch_bounds__(NT) void relu_bwd_q_kernel(const uint16_t* __restri
       // dz row block: B operand = the 8 tokens' weights, the same in every column
       const f16x8 wop = as_f16x8(*reinterpret_cast<const uint4*>(sW16 + 16 * ks + 8 * g));
       if (WMN == 2) {
-        if (ni == 0) zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], wop, zacc, 0, 0, 0);
-        else zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[WMN - 1], wop, zacc, 0, 0, 0);
+        // a select, not a branch: branches inside the loop make the compiler's waits conservative
+        const f16x8 az = ni == 0 ? a[0] : a[WMN - 1];
+        zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(az, wop, zacc, 0, 0, 0);
       } else if (do_z) {
         zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], wop, zacc, 0, 0, 0);
       }
