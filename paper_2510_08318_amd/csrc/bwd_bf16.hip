@@ -386,15 +386,29 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
       for (int mb = 0; mb < G::GM; ++mb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) ga[mb][r] = 0.f;
+      // the S image of this product stays in global memory (LDS is full); its operands are
+      // requested GPF k-steps ahead, otherwise every MFMA waits for its own load
+      constexpr int GPF = 3;
+      uint4 gop[G::KS][G::GM];
+#pragma unroll
+      for (int ks = 0; ks < GPF; ++ks)
+#pragma unroll
+        for (int mb = 0; mb < G::GM; ++mb) gop[ks][mb] = gim[(ks * G::GM + mb) * 64 + lane];
 #pragma unroll
       for (int ks = 0; ks < G::KS; ++ks) {
+        if (ks + GPF < G::KS) {
+#pragma unroll
+          for (int mb = 0; mb < G::GM; ++mb) gop[ks + GPF][mb] = gim[((ks + GPF) * G::GM + mb) * 64 + lane];
+        }
+        __builtin_amdgcn_sched_barrier(0);
         uint4 bq;
         bq.x = pack_f16x2(dof[8 * ks] * stok, dof[8 * ks + 1] * stok);     bq.y = pack_f16x2(dof[8 * ks + 2] * stok, dof[8 * ks + 3] * stok);
         bq.z = pack_f16x2(dof[8 * ks + 4] * stok, dof[8 * ks + 5] * stok); bq.w = pack_f16x2(dof[8 * ks + 6] * stok, dof[8 * ks + 7] * stok);
         const f16x8 bop = as_f16x8(bq);
 #pragma unroll
         for (int mb = 0; mb < G::GM; ++mb)
-          ga[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(gim[(ks * G::GM + mb) * 64 + lane]), bop, ga[mb], 0, 0, 0);
+          ga[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(gop[ks][mb]), bop, ga[mb], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
       const float r1 = om * __builtin_amdgcn_rcpf(den_s * stok);     // (1 - r') / (scale * stok * den)
       const float r2 = om * delta * inv_den;
