@@ -175,14 +175,13 @@ __device__ __forceinline__ void du_to_dx(const float (&du)[Cfg<D>::LOC], const u
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[mb][r] = 0.f;
   const uint4* wb = sWB + lane + opaque_zero();
-#pragma unroll
-  for (int ks = 0; ks < DK; ++ks) {
-    uint4 aq; aq.x = dub[4 * ks]; aq.y = dub[4 * ks + 1]; aq.z = dub[4 * ks + 2]; aq.w = dub[4 * ks + 3];
-    const f16x8 aop = as_f16x8(aq);
-#pragma unroll
-    for (int mb = 0; mb < L::MB; ++mb)
-      acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop, as_f16x8(wb[(ks * L::MB + mb) * 64]), acc[mb], 0, 0, 0);
-  }
+  pipelined_operands<DK * L::MB, 3>(
+      [&](int i) { return wb[i * 64]; },
+      [&](int i, uint4 b) {
+        const int ks = i / L::MB, mb = i % L::MB;
+        uint4 aq; aq.x = dub[4 * ks]; aq.y = dub[4 * ks + 1]; aq.z = dub[4 * ks + 2]; aq.w = dub[4 * ks + 3];
+        acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(aq), as_f16x8(b), acc[mb], 0, 0, 0);
+      });
 }
 
 // ---- query side --------------------------------------------------------------------------
@@ -292,7 +291,7 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
       __builtin_amdgcn_sched_barrier(0);
     }
     f32x16 u[C::UM];
-    project<D>(xq, sWA, lane, u);
+    project<D, 3>(xq, sWA, lane, u);
     float pp[C::LOC], pm[C::LOC];
     uint32_t pk[C::NPK];
     softmax_full<D>(u, pp, pm, pk);
@@ -309,15 +308,14 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
         for (int mb = 0; mb < L::MB; ++mb) oa[mb][r] = 0.f;
       }
       const uint4* ssa = sSA + lane + opaque_zero();
-#pragma unroll
-      for (int ks = 0; ks < L::KS; ++ks) {
-        uint4 bq; bq.x = pk[4 * ks]; bq.y = pk[4 * ks + 1]; bq.z = pk[4 * ks + 2]; bq.w = pk[4 * ks + 3];
-        const f16x8 bop = as_f16x8(bq);
-#pragma unroll
-        for (int mb = 0; mb < L::MB; ++mb)
-          oa[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(ssa[(ks * L::MBZ + mb) * 64]), bop, oa[mb], 0, 0, 0);
-        dn = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(ssa[(ks * L::MBZ + L::MB) * 64]), bop, dn, 0, 0, 0);
-      }
+      pipelined_operands<L::KS * L::MBZ, 3>(
+          [&](int i) { return ssa[i * 64]; },
+          [&](int i, uint4 a) {
+            const int ks = i / L::MBZ, mb = i % L::MBZ;
+            uint4 bq; bq.x = pk[4 * ks]; bq.y = pk[4 * ks + 1]; bq.z = pk[4 * ks + 2]; bq.w = pk[4 * ks + 3];
+            if (mb < L::MB) oa[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a), as_f16x8(bq), oa[mb], 0, 0, 0);
+            else dn = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a), as_f16x8(bq), dn, 0, 0, 0);
+          });
       den_s = dn[0];
       const float inv = __builtin_amdgcn_rcpf(den_s);
 #pragma unroll

@@ -79,11 +79,29 @@ __device__ __forceinline__ void build_w_image(const uint16_t* __restrict__ w, ui
   for (int idx = tid; idx < Cfg<D>::W_IMG; idx += NTHREADS) sWA[idx] = w_image_entry<D>(w, idx);
 }
 
+// N uses (MFMAs) of 16-byte operands that come from LDS or global memory, each requested AHEAD uses
+// before it is needed.  Left to itself the compiler, short of registers, issues read, wait, MFMA,
+// read, wait, MFMA: with one or two wavefronts per SIMD nothing hides those waits.
+template <int N, int AHEAD, typename Load, typename Use>
+__device__ __forceinline__ void pipelined_operands(Load load, Use use) {
+  uint4 op[N];
+#pragma unroll
+  for (int i = 0; i < AHEAD && i < N; ++i) op[i] = load(i);
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    if (i + AHEAD < N) op[i + AHEAD] = load(i + AHEAD);
+    __builtin_amdgcn_sched_barrier(0);
+    use(i, op[i]);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 // First half of Eq. 5 for the 32 tokens of one wavefront: U^T = W~^T X^T on bf16 MFMA.
 // xb[ks] is this lane's B operand (8 channels of its token per k-step).  On return the lane holds
 // u[mb][r] = pre-softmax feature g*LOC + 16*mb + r of its token.  xb is dead afterwards, so the
 // caller can refill it with the next block while the softmax runs.
-template <int D>
+// AHEAD > 0: the W~ operands are requested that many MFMAs ahead (pipelined_operands).
+template <int D, int AHEAD = 0>
 __device__ __forceinline__ void project(const uint4 (&xb)[Cfg<D>::UK], const uint4* sWA, int lane,
                                         f32x16 (&u)[Cfg<D>::UM]) {
   using C = Cfg<D>;
@@ -92,6 +110,14 @@ __device__ __forceinline__ void project(const uint4 (&xb)[Cfg<D>::UK], const uin
 #pragma unroll
     for (int r = 0; r < 16; ++r) u[mb][r] = 0.f;
   const uint4* wa = sWA + lane + opaque_zero();
+  if constexpr (AHEAD > 0) {
+    pipelined_operands<C::UK * C::UM, AHEAD>(
+        [&](int i) { return wa[i * 64]; },
+        [&](int i, uint4 a) {
+          u[i % C::UM] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), as_bf16x8(xb[i / C::UM]), u[i % C::UM], 0, 0, 0);
+        });
+    return;
+  }
 #pragma unroll
   for (int ks = 0; ks < C::UK; ++ks) {
     const bf16x8 b = as_bf16x8(xb[ks]);
