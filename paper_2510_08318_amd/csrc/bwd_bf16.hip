@@ -117,7 +117,8 @@ __device__ __forceinline__ void phi_jacobian(const float (&gp)[Cfg<D>::LOC], con
 // it (exactly) so that a lane holds one feature and 16 tokens; entry (ks2, j, lane=(c,g)) of the
 // block's image holds feature 32j + c of tokens 16*ks2 + {4g .. 4g+3, 8+4g .. 8+4g+3}.  Rows of
 // tokens that do not exist are zero.  *du_its receives the inverse scale (0 for an all-zero block).
-template <int D>
+// AHEAD: lookahead of the W~ operand reads of dx (pipelined_operands).
+template <int D, int AHEAD>
 __device__ __forceinline__ void du_to_dx(const float (&du)[Cfg<D>::LOC], const uint4* sWB, int lane, bool valid,
                                          uint4* du_blk, float* du_its, f32x16 (&acc)[D / 32], float& its) {
   using C = Cfg<D>;
@@ -175,7 +176,7 @@ __device__ __forceinline__ void du_to_dx(const float (&du)[Cfg<D>::LOC], const u
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[mb][r] = 0.f;
   const uint4* wb = sWB + lane + opaque_zero();
-  pipelined_operands<DK * L::MB, 3>(
+  pipelined_operands<DK * L::MB, AHEAD>(
       [&](int i) { return wb[i * 64]; },
       [&](int i, uint4 b) {
         const int ks = i / L::MB, mb = i % L::MB;
@@ -428,33 +429,14 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
       float its;
       const int blk = tile * (kTile / 32) + w;
       const bool keep = du_img != nullptr && blk * 32 < n;
-      du_to_dx<D>(du, sWB, lane, valid, keep ? du_img + ((size_t)bh * nblk + blk) * DU_BLK : nullptr,
+      du_to_dx<D, 3>(du, sWB, lane, valid, keep ? du_img + ((size_t)bh * nblk + blk) * DU_BLK : nullptr,
                   du_its + (size_t)bh * nblk + blk, xa, its);
       store_token_rows<D>(dqb, rw.sn, blk * 32, n, lane, xa, its);
     }
 
     __syncthreads();
-#pragma unroll
-    for (int ks = 0; ks < kTile / 16; ++ks) {
-      f16x8 a[WMN], b[WMN];
-#pragma unroll
-      for (int i = 0; i < WMN; ++i) a[i] = read_tr(sPhi + ks * 16 * RS, offA[i][0], offA[i][1]);
-#pragma unroll
-      for (int j = 0; j < WMN; ++j) b[j] = read_tr(sDO + ks * 16 * RS, offB[j][0], offB[j][1]);
-#pragma unroll
-      for (int i = 0; i < WMN; ++i)
-#pragma unroll
-        for (int j = 0; j < WMN; ++j) s[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], s[i][j], 0, 0, 0);
-      // dz row block: B operand = the 8 tokens' weights, the same in every column
-      const f16x8 wop = as_f16x8(*reinterpret_cast<const uint4*>(sW16 + 16 * ks + 8 * g));
-      if (WMN == 2) {
-        // a select, not a branch: branches inside the loop make the compiler's waits conservative
-        const f16x8 az = ni == 0 ? a[0] : a[WMN - 1];
-        zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(az, wop, zacc, 0, 0, 0);
-      } else if (do_z) {
-        zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], wop, zacc, 0, 0, 0);
-      }
-    }
+    contract_tile<D>(sPhi, sDO, offA, offB, s, zacc, ni != 0, do_z,
+                     [&](int ks) { return as_f16x8(*reinterpret_cast<const uint4*>(sW16 + 16 * ks + 8 * g)); });
   }
 
   const float ig = __builtin_amdgcn_rcpf(gamma);    // exact: gamma is a power of two
@@ -484,6 +466,10 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
 
 // ---- key side ----------------------------------------------------------------------------
 constexpr int NTK = 512;     // 8 wavefronts, one workgroup per compute unit
+// Operand lookahead of the key-side MFMA phases.  With two wavefronts per SIMD the other wavefront
+// hides the LDS latency and registers are what is short: reading each operand right before its
+// MFMA (0) measured 101.5 us, one ahead 102.9, three ahead 106.7, the compiler's own order 105.
+constexpr int KAHEAD = 0;
 
 template <int D>
 __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
@@ -564,14 +550,13 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
 #pragma unroll
         for (int r = 0; r < 16; ++r) va[mb][r] = 0.f;
       const uint4* sva = sVA + lane + opaque_zero();
-#pragma unroll
-      for (int ks = 0; ks < L::KS; ++ks) {
-        uint4 aq; aq.x = pk[4 * ks]; aq.y = pk[4 * ks + 1]; aq.z = pk[4 * ks + 2]; aq.w = pk[4 * ks + 3];
-        const f16x8 aop = as_f16x8(aq);
-#pragma unroll
-        for (int mb = 0; mb < L::MB; ++mb)
-          va[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop, as_f16x8(sva[(ks * L::MBZ + mb) * 64]), va[mb], 0, 0, 0);
-      }
+      pipelined_operands<L::KS * L::MB, KAHEAD>(
+          [&](int i) { return sva[((i / L::MB) * L::MBZ + i % L::MB) * 64]; },
+          [&](int i, uint4 b) {
+            const int ks = i / L::MB, mb = i % L::MB;
+            uint4 aq; aq.x = pk[4 * ks]; aq.y = pk[4 * ks + 1]; aq.z = pk[4 * ks + 2]; aq.w = pk[4 * ks + 3];
+            va[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(aq), as_f16x8(b), va[mb], 0, 0, 0);
+          });
       store_token_rows<D>(dvb, rw.sn, b * 32, n, lane, va, inv_scale);
     }
 
@@ -584,16 +569,15 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
 #pragma unroll
         for (int r = 0; r < 16; ++r) ga[mb][r] = 0.f;
       const uint4* sga = sGA + lane + opaque_zero();
-#pragma unroll
-      for (int ks = 0; ks < G::KS; ++ks) {
-        uint4 bq;
-        bq.x = bf16x2_to_f16x2(vr[ks].x); bq.y = bf16x2_to_f16x2(vr[ks].y);
-        bq.z = bf16x2_to_f16x2(vr[ks].z); bq.w = bf16x2_to_f16x2(vr[ks].w);
-        const f16x8 bop = as_f16x8(bq);
-#pragma unroll
-        for (int mb = 0; mb < G::GM; ++mb)
-          ga[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(sga[(ks * G::GM + mb) * 64]), bop, ga[mb], 0, 0, 0);
-      }
+      pipelined_operands<G::KS * G::GM, KAHEAD>(
+          [&](int i) { return sga[i * 64]; },
+          [&](int i, uint4 a) {
+            const int ks = i / G::GM, mb = i % G::GM;
+            uint4 bq;
+            bq.x = bf16x2_to_f16x2(vr[ks].x); bq.y = bf16x2_to_f16x2(vr[ks].y);
+            bq.z = bf16x2_to_f16x2(vr[ks].z); bq.w = bf16x2_to_f16x2(vr[ks].w);
+            ga[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a), as_f16x8(bq), ga[mb], 0, 0, 0);
+          });
 #pragma unroll
       for (int mb = 0; mb < G::GM; ++mb) {
         const int f0 = (mb < G::GM / 2 ? 0 : C::HALF) + g * C::LOC + 16 * (mb % (G::GM / 2));
@@ -609,7 +593,7 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
     {
       f32x16 xa[L::MB];
       float its;
-      du_to_dx<D>(du, sWB, lane, valid, du_img ? du_img + ((size_t)bh * nblk + b) * DU_BLK : nullptr,
+      du_to_dx<D, KAHEAD>(du, sWB, lane, valid, du_img ? du_img + ((size_t)bh * nblk + b) * DU_BLK : nullptr,
                   du_its + (size_t)bh * nblk + b, xa, its);
       store_token_rows<D>(dkb, rw.sn, b * 32, n, lane, xa, its);
     }

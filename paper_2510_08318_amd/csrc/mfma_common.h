@@ -81,7 +81,8 @@ __device__ __forceinline__ void build_w_image(const uint16_t* __restrict__ w, ui
 
 // N uses (MFMAs) of 16-byte operands that come from LDS or global memory, each requested AHEAD uses
 // before it is needed.  Left to itself the compiler, short of registers, issues read, wait, MFMA,
-// read, wait, MFMA: with one or two wavefronts per SIMD nothing hides those waits.
+// read, wait, MFMA: with one wavefront per SIMD nothing hides those waits.  AHEAD = 0 keeps that
+// order but fences it, so that a single operand is live at a time.
 template <int N, int AHEAD, typename Load, typename Use>
 __device__ __forceinline__ void pipelined_operands(Load load, Use use) {
   uint4 op[N];
@@ -473,6 +474,44 @@ __device__ __forceinline__ void store_token_rows(uint16_t* base, size_t sn, int 
 #pragma unroll
     for (int r = 0; r < 16; ++r)
       if (t0 + 8 * (r / 4) + (r % 4) + 4 * g < n) put(r);
+  }
+}
+
+// One 128-token tile of a split-n sum over tokens: s[i][j] += A_i^T B_j and zacc += A_z^T w, with A
+// and B fp16 tiles [kTile][D] in LDS (swizzled 16-byte chunks) read by transposing reads, the
+// operands of k-step ks+1 requested before the MFMAs of k-step ks.  wop(ks) returns the B operand
+// of the z sum for that k-step (per-token weights, the same in every column); z_hi picks which of
+// the wavefront's A blocks feeds it, do_z whether this wavefront owns a z block at all.
+template <int D, typename WOp>
+__device__ __forceinline__ void contract_tile(const char* sA, const char* sB, const int (&offA)[D / 64][2],
+                                              const int (&offB)[D / 64][2], f32x16 (&s)[D / 64][D / 64],
+                                              f32x16& zacc, bool z_hi, bool do_z, WOp wop) {
+  constexpr int RS = D * 2, WMN = D / 64, KSN = kTile / 16;
+  f16x8 a[KSN][WMN], b[KSN][WMN], wv[KSN];
+  auto request = [&](int kn) {
+#pragma unroll
+    for (int i = 0; i < WMN; ++i) a[kn][i] = read_tr(sA + kn * 16 * RS, offA[i][0], offA[i][1]);
+#pragma unroll
+    for (int j = 0; j < WMN; ++j) b[kn][j] = read_tr(sB + kn * 16 * RS, offB[j][0], offB[j][1]);
+    wv[kn] = wop(kn);
+  };
+  request(0);
+#pragma unroll
+  for (int ks = 0; ks < KSN; ++ks) {
+    if (ks + 1 < KSN) request(ks + 1);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < WMN; ++i)
+#pragma unroll
+      for (int j = 0; j < WMN; ++j) s[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[ks][i], b[ks][j], s[i][j], 0, 0, 0);
+    if (WMN == 2) {
+      // a select, not a branch: branches inside the loop make the compiler's waits conservative
+      const f16x8 az = z_hi ? a[ks][WMN - 1] : a[ks][0];
+      zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(az, wv[ks], zacc, 0, 0, 0);
+    } else if (do_z) {
+      zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[ks][0], wv[ks], zacc, 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 

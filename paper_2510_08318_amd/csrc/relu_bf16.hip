@@ -99,25 +99,7 @@ __device__ __forceinline__ void relu_state_segment(const uint16_t* __restrict__ 
     }
     load_tile(kx, vx, tile + DEPTH);
     __syncthreads();
-#pragma unroll
-    for (int ks = 0; ks < kTile / 16; ++ks) {
-      f16x8 a[WMN], b[WMN];
-#pragma unroll
-      for (int i = 0; i < WMN; ++i) a[i] = read_tr(sK + ks * 16 * RS, offA[i][0], offA[i][1]);
-#pragma unroll
-      for (int j = 0; j < WMN; ++j) b[j] = read_tr(sV + ks * 16 * RS, offB[j][0], offB[j][1]);
-#pragma unroll
-      for (int i = 0; i < WMN; ++i)
-#pragma unroll
-        for (int j = 0; j < WMN; ++j) s[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], s[i][j], 0, 0, 0);
-      if (WMN == 2) {
-        // a select, not a branch: branches inside the loop make the compiler's waits conservative
-        const f16x8 az = ni == 0 ? a[0] : a[WMN - 1];
-        zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(az, one_op, zacc, 0, 0, 0);
-      } else if (do_z) {
-        zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], one_op, zacc, 0, 0, 0);
-      }
-    }
+    contract_tile<D>(sK, sV, offA, offB, s, zacc, ni != 0, do_z, [&](int) { return one_op; });
   };
 #pragma unroll
   for (int j = 0; j < DEPTH; ++j) load_tile(kr[j], vr[j], tile0 + j);
@@ -353,19 +335,22 @@ __global__ __launch_bounds__(NT) void relu_bwd_q_kernel(const uint16_t* __restri
     }
     const uint4* szb = sZB + lane + opaque_zero();
     const uint4* st = sT + lane + opaque_zero();
-#pragma unroll
-    for (int ks = 0; ks < L::KS; ++ks) {
-      dn = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(relu_f16x8(xq[ks])), as_f16x8(szb[ks * 64]), dn, 0, 0, 0);
-      float f[8];
-      unpack_bf16x8(dor[ks], f);
-      uint4 aq;
-      aq.x = pack_f16x2(f[0] * ts, f[1] * ts); aq.y = pack_f16x2(f[2] * ts, f[3] * ts);
-      aq.z = pack_f16x2(f[4] * ts, f[5] * ts); aq.w = pack_f16x2(f[6] * ts, f[7] * ts);
-      const f16x8 aop = as_f16x8(aq);
-#pragma unroll
-      for (int mb = 0; mb < L::MB; ++mb)
-        ga[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop, as_f16x8(st[(ks * L::MB + mb) * 64]), ga[mb], 0, 0, 0);
-    }
+    pipelined_operands<L::KS, 3>(
+        [&](int ks) { return szb[ks * 64]; },
+        [&](int ks, uint4 b) {
+          dn = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(relu_f16x8(xq[ks])), as_f16x8(b), dn, 0, 0, 0);
+        });
+    pipelined_operands<L::KS * L::MB, 3>(
+        [&](int i) { return st[i * 64]; },
+        [&](int i, uint4 b) {
+          const int ks = i / L::MB, mb = i % L::MB;
+          float f[8];
+          unpack_bf16x8(dor[ks], f);
+          uint4 aq;
+          aq.x = pack_f16x2(f[0] * ts, f[1] * ts); aq.y = pack_f16x2(f[2] * ts, f[3] * ts);
+          aq.z = pack_f16x2(f[4] * ts, f[5] * ts); aq.w = pack_f16x2(f[6] * ts, f[7] * ts);
+          ga[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(aq), as_f16x8(b), ga[mb], 0, 0, 0);
+        });
     // per row: a = 1 / (scale * den), delta = (sum_f G_f phi_f) / den; dq = (G - delta z) / den where q > 0
     const float its = __builtin_amdgcn_rcpf(ts);                // exact: a power of two
     const float den_eps = scale * kReluEps;
@@ -446,27 +431,8 @@ __global__ __launch_bounds__(NT) void relu_bwd_q_kernel(const uint16_t* __restri
       if (g == 0) sW16[prow] = (uint16_t)(pack_f16x2(live ? -delta_t * sc : 0.f, 0.f) & 0xffffu);
     }
     __syncthreads();
-#pragma unroll
-    for (int ks = 0; ks < kTile / 16; ++ks) {
-      f16x8 a[WMN], b[WMN];
-#pragma unroll
-      for (int i = 0; i < WMN; ++i) a[i] = read_tr(sPhi + ks * 16 * RS, offA[i][0], offA[i][1]);
-#pragma unroll
-      for (int j = 0; j < WMN; ++j) b[j] = read_tr(sDO + ks * 16 * RS, offB[j][0], offB[j][1]);
-#pragma unroll
-      for (int i = 0; i < WMN; ++i)
-#pragma unroll
-        for (int j = 0; j < WMN; ++j) s[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], s[i][j], 0, 0, 0);
-      // dz row block: B operand = the 8 tokens' weights, the same in every column
-      const f16x8 wop = as_f16x8(*reinterpret_cast<const uint4*>(sW16 + 16 * ks + 8 * g));
-      if (WMN == 2) {
-        // a select, not a branch: branches inside the loop make the compiler's waits conservative
-        const f16x8 az = ni == 0 ? a[0] : a[WMN - 1];
-        zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(az, wop, zacc, 0, 0, 0);
-      } else if (do_z) {
-        zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], wop, zacc, 0, 0, 0);
-      }
-    }
+    contract_tile<D>(sPhi, sDO, offA, offB, s, zacc, ni != 0, do_z,
+                     [&](int ks) { return as_f16x8(*reinterpret_cast<const uint4*>(sW16 + 16 * ks + 8 * g)); });
   }
 
   const float ig = __builtin_amdgcn_rcpf(gamma);    // exact: gamma is a power of two
