@@ -35,8 +35,11 @@ namespace {
 //   WQK = true is the pass over S (image simg in the A-operand order of the query pass: the query
 //   side wants o on the lane's own token); WQK = false is the pass over dS, whose image is in the
 //   B-operand order of dv = phi(k) dS with the tokens on the accumulator rows.
+// 512 threads: staging the state is latency, not bandwidth (256 threads: 16.8 + 10.8 us for the two
+// passes at config 5, 512: 11.9 + 8.3 us, 1024 the same; more slices per head change nothing).
+constexpr int PT = 512, PREP_Y = 8;
 template <int D, bool WQK>
-__global__ __launch_bounds__(256) void bwd_prep_kernel(const float* __restrict__ state, uint4* __restrict__ gimg,
+__global__ __launch_bounds__(PT) void bwd_prep_kernel(const float* __restrict__ state, uint4* __restrict__ gimg,
                                                        uint4* __restrict__ simg, float* __restrict__ scale_out,
                                                        const uint16_t* __restrict__ wq, const uint16_t* __restrict__ wk,
                                                        uint4* __restrict__ wimg, int H) {
@@ -51,16 +54,16 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(const float* __restrict__
   float* S = reinterpret_cast<float*>(prep_smem);                         // [(D+1)*D]
   uint16_t* sWq = reinterpret_cast<uint16_t*>(S + (D + 1) * D);          // [D*HALF], then W~_k
   uint16_t* sWk = sWq + D * C::HALF;
-  __shared__ float red[4];
+  __shared__ float red[PT / 64];
   const int bh = blockIdx.x, tid = threadIdx.x;
   {
     const uint4* g = reinterpret_cast<const uint4*>(state + (size_t)bh * (D + 1) * D);
-    for (int i = tid; i < (D + 1) * D / 4; i += 256) reinterpret_cast<uint4*>(S)[i] = g[i];
+    for (int i = tid; i < (D + 1) * D / 4; i += PT) reinterpret_cast<uint4*>(S)[i] = g[i];
     if constexpr (WQK) {
       if (bh < H) {
         const uint4* gq = reinterpret_cast<const uint4*>(wq + (size_t)bh * D * C::HALF);
         const uint4* gk = reinterpret_cast<const uint4*>(wk + (size_t)bh * D * C::HALF);
-        for (int i = tid; i < D * C::HALF / 8; i += 256) {
+        for (int i = tid; i < D * C::HALF / 8; i += PT) {
           reinterpret_cast<uint4*>(sWq)[i] = gq[i];
           reinterpret_cast<uint4*>(sWk)[i] = gk[i];
         }
@@ -68,9 +71,9 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(const float* __restrict__
     }
   }
   __syncthreads();
-  const float scale = head_scale<D, 256>(S, red, tid);      // every block of a head computes the same value
+  const float scale = head_scale<D, PT>(S, red, tid);      // every block of a head computes the same value
   if (blockIdx.y == 0 && tid == 0) scale_out[2 * bh] = scale;
-  const int first = blockIdx.y * 256 + tid, step = 256 * gridDim.y;
+  const int first = blockIdx.y * PT + tid, step = PT * gridDim.y;
   for (int idx = first; idx < G::IMG; idx += step) gimg[(size_t)bh * G::IMG + idx] = grad_image_entry<D>(S, scale, idx);
   for (int idx = first; idx < SIMG; idx += step) simg[(size_t)bh * SIMG + idx] = state_image_entry<D, !WQK>(S, scale, idx);
   if constexpr (WQK) {
@@ -739,7 +742,7 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   float* duk_its = reinterpret_cast<float*>(reinterpret_cast<char*>(a.du_k) + du_img_bytes);
   if ((e = set_smem(bwd_prep_kernel<D, true>, prep_smem_bytes<D>())) != hipSuccess) return e;
   if ((e = set_smem(bwd_prep_kernel<D, false>, prep_smem_bytes<D>())) != hipSuccess) return e;
-  bwd_prep_kernel<D, true><<<dim3(p.BH, 8), 256, prep_smem_bytes<D>(), s>>>(a.state, (uint4*)a.gimg, (uint4*)a.simg, a.scales,
+  bwd_prep_kernel<D, true><<<dim3(p.BH, PREP_Y), PT, prep_smem_bytes<D>(), s>>>(a.state, (uint4*)a.gimg, (uint4*)a.simg, a.scales,
                                                        (const uint16_t*)a.wq, (const uint16_t*)a.wk, (uint4*)a.wimg, p.H);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (a.blend_in) {
@@ -761,7 +764,7 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   }
   if ((e = launch_state_reduce(a.partials, a.dstate, p, s)) != hipSuccess) return e;
   // images of dS: the second half of the scales array, no W~ images
-  bwd_prep_kernel<D, false><<<dim3(p.BH, 8), 256, prep_smem_bytes<D>(), s>>>(a.dstate, (uint4*)a.dgimg, (uint4*)a.dsimg, a.scales + 1,
+  bwd_prep_kernel<D, false><<<dim3(p.BH, PREP_Y), PT, prep_smem_bytes<D>(), s>>>(a.dstate, (uint4*)a.dgimg, (uint4*)a.dsimg, a.scales + 1,
                                                         nullptr, nullptr, nullptr, p.H);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if ((e = set_smem(bwd_k_kernel<D>, k_smem<D>())) != hipSuccess) return e;

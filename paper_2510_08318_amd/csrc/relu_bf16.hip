@@ -156,23 +156,24 @@ __global__ __launch_bounds__(NT) void relu_state_kernel(const uint16_t* __restri
 //   timg: B operands of G = X M^T (contraction over the channels, columns = features):
 //         entry (ks, mb, lane=(c,g)) holds M[channel_cols(mb,c)][16ks + 8g + e], e = 0..7
 // grid (BH, 8): slice blockIdx.y of the entries.
+constexpr int PT = 512;      // threads of the image builder (staging the state is latency-bound)
 template <int D>
-__global__ __launch_bounds__(256) void relu_prep_kernel(const float* __restrict__ state, uint4* __restrict__ cimg,
+__global__ __launch_bounds__(PT) void relu_prep_kernel(const float* __restrict__ state, uint4* __restrict__ cimg,
                                                         uint4* __restrict__ timg, float* __restrict__ scale_out) {
   using L = ApplyLayout<D>;
   constexpr int CIMG = L::KS * L::MBZ * 64, TIMG = L::KS * L::MB * 64;
   extern __shared__ uint4 prep_stage[];
   float* S = reinterpret_cast<float*>(prep_stage);                        // [(D+1)*D]
-  __shared__ float red[4];
+  __shared__ float red[PT / 64];
   const int bh = blockIdx.x, tid = threadIdx.x;
   {
     const uint4* gsrc = reinterpret_cast<const uint4*>(state + (size_t)bh * (D + 1) * D);
-    for (int i = tid; i < (D + 1) * D / 4; i += 256) reinterpret_cast<uint4*>(S)[i] = gsrc[i];
+    for (int i = tid; i < (D + 1) * D / 4; i += PT) reinterpret_cast<uint4*>(S)[i] = gsrc[i];
   }
   __syncthreads();
-  const float scale = head_scale<D, 256>(S, red, tid);      // every block of a head computes the same value
+  const float scale = head_scale<D, PT>(S, red, tid);      // every block of a head computes the same value
   if (blockIdx.y == 0 && tid == 0) scale_out[2 * bh] = scale;      // [BH][2]: S, dS
-  const int first = blockIdx.y * 256 + tid, step = 256 * gridDim.y;
+  const int first = blockIdx.y * PT + tid, step = PT * gridDim.y;
   for (int idx = first; idx < CIMG; idx += step) cimg[(size_t)bh * CIMG + idx] = state_image_entry<D, true, kPhiRelu>(S, scale, idx);
   for (int idx = first; idx < TIMG; idx += step) {
     const int lane = idx % 64, mb = (idx / 64) % L::MB, ks = idx / (64 * L::MB);
@@ -578,7 +579,7 @@ template <int D>
 hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   hipError_t e;
   if ((e = set_smem(relu_prep_kernel<D>, prep_smem<D>())) != hipSuccess) return e;
-  relu_prep_kernel<D><<<dim3(p.BH, 8), 256, prep_smem<D>(), s>>>(a.state, (uint4*)a.simg, (uint4*)a.gimg, a.scales);
+  relu_prep_kernel<D><<<dim3(p.BH, 8), PT, prep_smem<D>(), s>>>(a.state, (uint4*)a.simg, (uint4*)a.gimg, a.scales);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if ((e = set_smem(relu_bwd_q_kernel<D>, q_smem<D>())) != hipSuccess) return e;
   relu_bwd_q_kernel<D><<<dim3(p.P, p.BH), NT, q_smem<D>(), s>>>(
@@ -586,7 +587,7 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
       (uint16_t*)a.dq, a.partials, p.H, p.n, p.P, p.rows);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if ((e = launch_state_reduce(a.partials, a.dstate, p, s)) != hipSuccess) return e;
-  relu_prep_kernel<D><<<dim3(p.BH, 8), 256, prep_smem<D>(), s>>>(a.dstate, (uint4*)a.dsimg, (uint4*)a.dgimg, a.scales + 1);
+  relu_prep_kernel<D><<<dim3(p.BH, 8), PT, prep_smem<D>(), s>>>(a.dstate, (uint4*)a.dsimg, (uint4*)a.dgimg, a.scales + 1);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if ((e = set_smem(relu_bwd_k_kernel<D>, k_smem<D>())) != hipSuccess) return e;
   relu_bwd_k_kernel<D><<<dim3(p.KP, p.BH), NTK, k_smem<D>(), s>>>(
