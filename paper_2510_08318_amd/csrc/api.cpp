@@ -73,7 +73,7 @@ bool make_plan(int B, int H, int n, int d, int dtype, int layout, Plan* p) {
   r.off_scales = off;   off = up(off + (size_t)BH * 2 * sizeof(float));
   r.off_drpart = off;   off = up(off + (size_t)BH * r.P * sizeof(float));
   r.bytes_no_wgrads = off;
-  r.off_dwpart = off;   off = up(off + (size_t)BH * r.P * d * (d / 2) * sizeof(float));
+  r.off_dwpart = off;   off = up(off + 2 * (size_t)BH * r.P * d * (d / 2) * sizeof(float));
   {
     // fp32 mode keeps dL/du as fp32 rows; bf16 mode keeps fp16 operand images of 32-token blocks,
     // followed by one fp32 scale per block

@@ -611,10 +611,23 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
 // common power-of-two scale per workgroup (taken from its first tile).  Wavefront w owns the
 // feature block w % NB and RB 32-channel row blocks.  Partials per (b,h) and split are reduced in
 // a fixed order afterwards.
+// Both sides (W~_q from q and its du, W~_k from k and its du) run in one launch, side = blockIdx.z:
+// twice the workgroups per compute unit hide each other's waits.
+struct DwSide {
+  const uint16_t* x;
+  const uint4* du_img;
+  const float* du_its;
+  float* part;
+};
+struct DwSides {
+  DwSide s[2];
+};
 template <int D>
-__global__ __launch_bounds__(NT) void dw_mfma_kernel(const uint16_t* __restrict__ x, const uint4* __restrict__ du_img,
-                                                     const float* __restrict__ du_its,
-                                                     float* __restrict__ part, int H, int n, int P, Rows rw) {
+__global__ __launch_bounds__(NT) void dw_mfma_kernel(DwSides sides, int H, int n, int P, Rows rw) {
+  const uint16_t* __restrict__ x = sides.s[blockIdx.z].x;
+  const uint4* __restrict__ du_img = sides.s[blockIdx.z].du_img;
+  const float* __restrict__ du_its = sides.s[blockIdx.z].du_its;
+  float* __restrict__ part = sides.s[blockIdx.z].part;
   constexpr int HALF = D / 2;
   constexpr int RSX = D * 2;
   constexpr int NB = HALF / 32;                 // 32-column blocks of du
@@ -773,15 +786,17 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
       (const uint4*)a.dsimg, (const uint4*)a.dgimg, (const uint4*)a.wimg, a.scales,
       (uint16_t*)a.dk, (uint16_t*)a.dv, a.dwk ? duk : nullptr, duk_its, p.H, p.n, p.rows);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  if (a.dwq) {
-    dw_mfma_kernel<D><<<dim3(p.P, p.BH), NT, 0, s>>>((const uint16_t*)a.q, duq, duq_its, a.dw_part, p.H, p.n, p.P, p.rows);
+  if (a.dwq || a.dwk) {
+    // partial sums of the two sides sit one behind the other in the dW~ partial region
+    const size_t side_elems = (size_t)p.BH * p.P * D * (D / 2);
+    DwSides sides{};
+    float* outs[2];
+    int ns = 0;
+    if (a.dwq) { sides.s[ns] = DwSide{(const uint16_t*)a.q, duq, duq_its, a.dw_part + ns * side_elems}; outs[ns++] = a.dwq; }
+    if (a.dwk) { sides.s[ns] = DwSide{(const uint16_t*)a.k, duk, duk_its, a.dw_part + ns * side_elems}; outs[ns++] = a.dwk; }
+    dw_mfma_kernel<D><<<dim3(p.P, p.BH, ns), NT, 0, s>>>(sides, p.H, p.n, p.P, p.rows);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    if ((e = launch_dw_reduce(a.dw_part, a.dwq, p, s)) != hipSuccess) return e;
-  }
-  if (a.dwk) {
-    dw_mfma_kernel<D><<<dim3(p.P, p.BH), NT, 0, s>>>((const uint16_t*)a.k, duk, duk_its, a.dw_part, p.H, p.n, p.P, p.rows);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    if ((e = launch_dw_reduce(a.dw_part, a.dwk, p, s)) != hipSuccess) return e;
+    if ((e = launch_dw_reduce2(sides.s[0].part, outs[0], ns > 1 ? sides.s[1].part : nullptr, ns > 1 ? outs[1] : nullptr, p, s)) != hipSuccess) return e;
   }
   return hipSuccess;
 }

@@ -76,7 +76,7 @@ struct Plan {
   size_t off_wimg;        // [H][4][d*d bytes]    W~_q image, W~_q transposed image, then the same for W~_k
   size_t off_scales;      // fp32 [BH][2]         power-of-two scales of the S and dS images
   size_t off_drpart;      // fp32 [BH][P]         per-workgroup parts of dL/dr (mixed attention, Eq. 6)
-  size_t off_dwpart;      // fp32 [BH][P][d*d/2]  partial dW~           (weight gradients only)
+  size_t off_dwpart;      // fp32 [2][BH][P][d*d/2] partial dW~ of the two sides (weight gradients only)
   size_t du_bytes;        // bytes of one dL/du region
   size_t off_du_q;        // dL/du of the query side (weight gradients only): fp32 [BH][n][d/2] in fp32 mode;
                           // in bf16 mode fp16 [BH][ceil(n/32)][32*d/2] operand images of 32-token blocks, each
@@ -129,6 +129,8 @@ hipError_t launch_apply_bf16(const void* q, const void* wq, const float* state, 
 // dw[H][d][d/2] = sum over batch and tokens of x^T du; x is [B,H,n,d] bf16 or fp32, du fp32 [B,H,n,d/2].
 // dw[h][e] = sum over b, then over the P splits, of part[(b*H+h)][p][e].
 hipError_t launch_dw_reduce(const float* part, float* dw, const Plan& p, hipStream_t s);
+// The same for two (partials, output) pairs in one launch; the second pair may be null.
+hipError_t launch_dw_reduce2(const float* part0, float* dw0, const float* part1, float* dw1, const Plan& p, hipStream_t s);
 hipError_t launch_dw(const void* x, bool x_is_bf16, const float* du, float* part, float* dw, const Plan& p, hipStream_t s);
 hipError_t launch_bwd_bf16(const BwdArgs& a, const Plan& p, hipStream_t s);
 hipError_t launch_bwd_f32(const BwdArgs& a, const Plan& p, hipStream_t s);
