@@ -71,7 +71,7 @@ bool make_plan(int B, int H, int n, int d, int dtype, int layout, Plan* p) {
   r.off_dgimg = off;    off = up(off + (size_t)BH * d * d * 2);
   r.off_wimg = off;     off = up(off + (size_t)H * 4 * d * d);
   r.off_scales = off;   off = up(off + (size_t)BH * 2 * sizeof(float));
-  r.off_drpart = off;   off = up(off + (size_t)BH * r.P * sizeof(float));
+  r.off_drpart = off;   off = up(off + ((size_t)BH * r.P + kDotParts) * sizeof(float));
   r.bytes_no_wgrads = off;
   r.off_dwpart = off;   off = up(off + 2 * (size_t)BH * r.P * d * (d / 2) * sizeof(float));
   {

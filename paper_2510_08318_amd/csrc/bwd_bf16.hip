@@ -190,7 +190,8 @@ __device__ __forceinline__ void du_to_dx(const float (&du)[Cfg<D>::LOC], const u
 
 // ---- query side --------------------------------------------------------------------------
 // BLEND: dout is the gradient of the mixed output of Eq. 6; the linear branch receives
-// (1 - r') dout, and the workgroup's part of dL/dr = sum dout . (s - o) goes to dr_part.
+// (1 - r') dout, and the workgroup's part of -sum dout . o goes to dr_part (dL/dr = sum dout . (s - o);
+// the sum dout . s is a separate streaming dot product, taken only when dL/dr is asked for).
 template <int D, bool BLEND>
 __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ dout,
                                                    const uint16_t* __restrict__ wq, const float* __restrict__ state,
@@ -227,7 +228,6 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
   const uint16_t* qb = q + head_base(rw, bh, H);
   const uint16_t* dob = dout + head_base(rw, bh, H);
   uint16_t* dqb = dq + head_base(rw, bh, H);
-  const uint16_t* bb = BLEND ? blend + head_base(rw, bh, H) : nullptr;
   const float om = BLEND ? 1.f - fminf(fmaxf(*rptr, 0.f), 1.f) : 1.f;      // 1 - r'
   float dr_acc = 0.f;
   const float* sb = state + (size_t)bh * (D + 1) * D;
@@ -281,19 +281,6 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
     // dL/dr gets dout . (s - o) = dout . s - delta, from the unscaled dout; everything downstream is
     // linear in dout, so the factor 1 - r' is applied to the scalars that carry it (om below).
     // dout . s is taken here, while few registers are live.
-    float ds_part = 0.f;
-    if constexpr (BLEND) {
-      const uint4* srow = reinterpret_cast<const uint4*>(bb + (size_t)tc * rw.sn + g * (D / 2));
-#pragma unroll
-      for (int i = 0; i < D / 16; ++i) {
-        float df[8], sf[8];
-        unpack_bf16x8(dor[i], df);
-        unpack_bf16x8(srow[i], sf);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) ds_part = fmaf(df[j], sf[j], ds_part);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-    }
     f32x16 u[C::UM];
     project<D, 3>(xq, sWA, lane, u);
     float pp[C::LOC], pm[C::LOC];
@@ -337,7 +324,7 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
 #pragma unroll
     for (int c = 0; c < D / 2; ++c) { delta = fmaf(dof[c], o[c], delta); dmax = fmaxf(dmax, fabsf(dof[c])); }
     if constexpr (BLEND) {
-      if (valid) dr_acc += ds_part - delta;      // dout . (s - o) on this lane's channels
+      if (valid) dr_acc -= delta;      // the -dout . o part of dout . (s - o), on this lane's channels
     }
     float lo, hi;
     pair32(delta, lo, hi); delta = lo + hi;
@@ -766,7 +753,10 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
         (uint16_t*)a.dq, a.partials, a.dwq ? duq : nullptr, duq_its,
         (const uint16_t*)a.blend_in, a.blend_r, a.dr_part, p.H, p.n, p.P, p.rows);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    if (a.blend_dr && (e = launch_dr_reduce(a.dr_part, p.BH * p.P, a.blend_r, a.blend_dr, s)) != hipSuccess) return e;
+    if (a.blend_dr) {
+      if ((e = launch_dot_bf16(a.dout, a.blend_in, (size_t)p.BH * p.n * D, a.dr_part + (size_t)p.BH * p.P, s)) != hipSuccess) return e;
+      if ((e = launch_dr_reduce(a.dr_part, p.BH * p.P + kDotParts, a.blend_r, a.blend_dr, s)) != hipSuccess) return e;
+    }
   } else {
     if ((e = set_smem(bwd_q_kernel<D, false>, q_smem<D>())) != hipSuccess) return e;
     bwd_q_kernel<D, false><<<dim3(p.P, p.BH), NT, q_smem<D>(), s>>>(

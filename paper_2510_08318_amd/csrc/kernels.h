@@ -18,6 +18,8 @@ constexpr int kCUs = 256;
 // kReluEps.
 constexpr int kPhiHedgehog = 1, kPhiRelu = 2;
 constexpr float kReluEps = 1e-6f;
+// Workgroups (= partial sums) of the streaming dot product sum(dout * s) of the mixed attention's dL/dr.
+constexpr int kDotParts = 1024;
 
 // Where the rows of q, k, v, out (and dout, dq, dk, dv) sit in memory, in elements: element
 // (b, h, t, c) is at b*sb + h*sh + t*sn + c.  [B,H,n,d]: sb = H*n*d, sh = n*d, sn = d;
@@ -75,7 +77,7 @@ struct Plan {
   size_t off_dgimg;       // fp16 [BH][d*d]       operand image of dS for dL/dphi(k)
   size_t off_wimg;        // [H][4][d*d bytes]    W~_q image, W~_q transposed image, then the same for W~_k
   size_t off_scales;      // fp32 [BH][2]         power-of-two scales of the S and dS images
-  size_t off_drpart;      // fp32 [BH][P]         per-workgroup parts of dL/dr (mixed attention, Eq. 6)
+  size_t off_drpart;      // fp32 [BH][P] + [kDotParts]: per-workgroup parts of dL/dr (mixed attention, Eq. 6)
   size_t off_dwpart;      // fp32 [2][BH][P][d*d/2] partial dW~ of the two sides (weight gradients only)
   size_t du_bytes;        // bytes of one dL/du region
   size_t off_du_q;        // dL/du of the query side (weight gradients only): fp32 [BH][n][d/2] in fp32 mode;
@@ -135,6 +137,8 @@ hipError_t launch_dw(const void* x, bool x_is_bf16, const float* du, float* part
 hipError_t launch_bwd_bf16(const BwdArgs& a, const Plan& p, hipStream_t s);
 hipError_t launch_bwd_f32(const BwdArgs& a, const Plan& p, hipStream_t s);
 hipError_t launch_relu_bwd_bf16(const BwdArgs& a, const Plan& p, hipStream_t s);
+// part[0 .. kDotParts-1] = partial sums of sum_i a[i] * b[i] over two contiguous bf16 arrays (elems % 8 == 0).
+hipError_t launch_dot_bf16(const void* a, const void* b, size_t elems, float* part, hipStream_t s);
 // dr = sum of the count parts in a fixed order if 0 <= *r <= 1, else 0 (Eq. 6, clipped r).
 hipError_t launch_dr_reduce(const float* part, int count, const float* r, float* dr, hipStream_t s);
 

@@ -152,7 +152,48 @@ __global__ __launch_bounds__(256) void dr_reduce_kernel(const float* __restrict_
   }
 }
 
+__device__ __forceinline__ uint4 ld_nt16(const uint4* p) {
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  return __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p)));
+}
+
+// part[blockIdx.x] = sum over this workgroup's share of a[i] * b[i], both bf16 arrays of n16 16-byte
+// pieces; fixed grid and fixed order inside a workgroup, so the result is reproducible.
+__global__ __launch_bounds__(256) void dot_bf16_kernel(const uint4* __restrict__ a, const uint4* __restrict__ b,
+                                                       size_t n16, float* __restrict__ part) {
+  __shared__ float red[4];
+  float acc = 0.f;
+  auto term = [&](uint4 x, uint4 y) {
+    const uint32_t xs[4] = {x.x, x.y, x.z, x.w}, ys[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      acc = fmaf(__builtin_bit_cast(float, xs[j] << 16), __builtin_bit_cast(float, ys[j] << 16), acc);
+      acc = fmaf(__builtin_bit_cast(float, xs[j] & 0xffff0000u), __builtin_bit_cast(float, ys[j] & 0xffff0000u), acc);
+    }
+  };
+  // four pieces of each array in flight per thread; the tail one piece at a time
+  const size_t stride = (size_t)gridDim.x * 256;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    uint4 x[4], y[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) { x[u] = ld_nt16(a + i + u * stride); y[u] = ld_nt16(b + i + u * stride); }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) term(x[u], y[u]);
+  }
+  for (; i < n16; i += stride) term(a[i], b[i]);
+  for (int m = 32; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
+  if (threadIdx.x % 64 == 0) red[threadIdx.x / 64] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) part[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
 }  // namespace
+
+hipError_t launch_dot_bf16(const void* a, const void* b, size_t elems, float* part, hipStream_t s) {
+  dot_bf16_kernel<<<kDotParts, 256, 0, s>>>((const uint4*)a, (const uint4*)b, elems / 8, part);
+  return hipGetLastError();
+}
 
 hipError_t launch_dr_reduce(const float* part, int count, const float* r, float* dr, hipStream_t s) {
   dr_reduce_kernel<<<1, 256, 0, s>>>(part, count, r, dr);
