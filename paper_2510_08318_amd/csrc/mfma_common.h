@@ -477,12 +477,22 @@ __device__ __forceinline__ void store_token_rows(uint16_t* base, size_t sn, int 
   }
 }
 
+// 32x32x16 MFMA on operands carried as f16x8 registers whose bits are fp16 or (BF16) bf16.
+template <bool BF16>
+__device__ __forceinline__ f32x16 mfma16(f16x8 a, f16x8 b, f32x16 c) {
+  if constexpr (BF16)
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+}
+
 // One 128-token tile of a split-n sum over tokens: s[i][j] += A_i^T B_j and zacc += A_z^T w, with A
 // and B fp16 tiles [kTile][D] in LDS (swizzled 16-byte chunks) read by transposing reads, the
 // operands of k-step ks+1 requested before the MFMAs of k-step ks.  wop(ks) returns the B operand
 // of the z sum for that k-step (per-token weights, the same in every column); z_hi picks which of
 // the wavefront's A blocks feeds it, do_z whether this wavefront owns a z block at all.
-template <int D, typename WOp>
+// BF16: the tiles and wop's operands hold bf16 instead of fp16 (same bits per element, bf16 MFMA).
+template <int D, bool BF16 = false, typename WOp>
 __device__ __forceinline__ void contract_tile(const char* sA, const char* sB, const int (&offA)[D / 64][2],
                                               const int (&offB)[D / 64][2], f32x16 (&s)[D / 64][D / 64],
                                               f32x16& zacc, bool z_hi, bool do_z, WOp wop) {
@@ -503,13 +513,13 @@ __device__ __forceinline__ void contract_tile(const char* sA, const char* sB, co
 #pragma unroll
     for (int i = 0; i < WMN; ++i)
 #pragma unroll
-      for (int j = 0; j < WMN; ++j) s[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[ks][i], b[ks][j], s[i][j], 0, 0, 0);
+      for (int j = 0; j < WMN; ++j) s[i][j] = mfma16<BF16>(a[ks][i], b[ks][j], s[i][j]);
     if (WMN == 2) {
       // a select, not a branch: branches inside the loop make the compiler's waits conservative
       const f16x8 az = z_hi ? a[ks][WMN - 1] : a[ks][0];
-      zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(az, wv[ks], zacc, 0, 0, 0);
+      zacc = mfma16<BF16>(az, wv[ks], zacc);
     } else if (do_z) {
-      zacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[ks][0], wv[ks], zacc, 0, 0, 0);
+      zacc = mfma16<BF16>(a[ks][0], wv[ks], zacc);
     }
     __builtin_amdgcn_sched_barrier(0);
   }

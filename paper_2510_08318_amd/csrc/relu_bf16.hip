@@ -22,7 +22,8 @@ namespace {
 
 // ---- state pass -------------------------------------------------------------------------------
 // 4 wavefronts.  One segment = the 128-token tiles tile0 .. tile0+nt-1 of one (b,h): K (through
-// max(.,0)) and V are parked in LDS as fp16 and contracted over the tokens with transposing reads;
+// max(.,0)) and V are parked in LDS as they are, bf16 (no conversion: the kernel's time is its own
+// instruction stream, not HBM), and contracted over the tokens with transposing reads on bf16 MFMA;
 // wavefront (mi, ni) owns the feature rows 32*WMN*mi .. and the channel columns 32*WMN*ni .. of S.
 // z = phi(K)^T 1 rides along as one more MFMA per k-step against an operand of ones.  Every thread
 // of the workgroup calls it (it contains workgroup barriers).
@@ -33,7 +34,7 @@ __device__ __forceinline__ void relu_state_segment(const uint16_t* __restrict__ 
   constexpr int WMN = D / 64;
   constexpr int XPT = (kTile * (D / 8)) / NT;   // 16-byte chunks of a tile per thread
   extern __shared__ uint4 smem[];
-  char* sK = reinterpret_cast<char*>(smem);      // [kTile][D] fp16, swizzled chunks
+  char* sK = reinterpret_cast<char*>(smem);      // [kTile][D] bf16, swizzled chunks
   char* sV = sK + kTile * RS;
 
   const int tid = threadIdx.x, lane = tid % 64;
@@ -62,7 +63,7 @@ __device__ __forceinline__ void relu_state_segment(const uint16_t* __restrict__ 
       offB[i][j] = tr_offset<D>(32 * (ni * WMN + i), lane, j);
     }
   uint4 ones;
-  ones.x = ones.y = ones.z = ones.w = 0x3C003C00u;
+  ones.x = ones.y = ones.z = ones.w = 0x3F803F80u;      // bf16 1.0
   const f16x8 one_op = as_f16x8(ones);
 
   // Loads are branch-free (rows past n read row n-1 and are zeroed on their way into LDS; after the
@@ -90,16 +91,16 @@ __device__ __forceinline__ void relu_state_segment(const uint16_t* __restrict__ 
     for (int i = 0; i < XPT; ++i) {
       const int idx = tid + NT * i, r = idx / (D / 8), c = idx % (D / 8);
       const bool there = real && tile * kTile + r < n;
-      uint4 hk = relu_f16x8(kx[i]), hv;
-      hv.x = bf16x2_to_f16x2(vx[i].x); hv.y = bf16x2_to_f16x2(vx[i].y);
-      hv.z = bf16x2_to_f16x2(vx[i].z); hv.w = bf16x2_to_f16x2(vx[i].w);
+      // the tiles stay bf16 (the products of a bf16 MFMA are exact): K through the sign test, V as it is
+      uint4 hk, hv = vx[i];
+      hk.x = relu_bf16x2(kx[i].x); hk.y = relu_bf16x2(kx[i].y); hk.z = relu_bf16x2(kx[i].z); hk.w = relu_bf16x2(kx[i].w);
       if (!there) { hk = make_uint4(0, 0, 0, 0); hv = hk; }
       *reinterpret_cast<uint4*>(sK + r * RS + ((c ^ swz<D>(r)) * 16)) = hk;
       *reinterpret_cast<uint4*>(sV + r * RS + ((c ^ swz<D>(r)) * 16)) = hv;
     }
     load_tile(kx, vx, tile + DEPTH);
     __syncthreads();
-    contract_tile<D>(sK, sV, offA, offB, s, zacc, ni != 0, do_z, [&](int) { return one_op; });
+    contract_tile<D, true>(sK, sV, offA, offB, s, zacc, ni != 0, do_z, [&](int) { return one_op; });
   };
 #pragma unroll
   for (int j = 0; j < DEPTH; ++j) load_tile(kr[j], vr[j], tile0 + j);
