@@ -413,7 +413,13 @@ __device__ __forceinline__ void unpack_bf16x8(uint4 v, float* f) {
 }
 
 // max(x, 0) on a packed pair of bf16 (-0 becomes +0).
-__device__ __forceinline__ uint32_t relu_bf16x2(uint32_t u) { return u & ~(((u & 0x80008000u) >> 15) * 0xffffu); }
+// As 16-bit integers the negative bf16 values are exactly the negative numbers, so one packed
+// signed maximum with 0 does it.
+__device__ __forceinline__ uint32_t relu_bf16x2(uint32_t u) {
+  typedef short s16x2 __attribute__((ext_vector_type(2)));
+  const s16x2 z = {0, 0};
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(s16x2, u), z));
+}
 // Eight bf16 of a row -> fp16 of max(x, 0): an MFMA operand piece of the ReLU map.
 __device__ __forceinline__ uint4 relu_f16x8(uint4 x) {
   uint4 r;

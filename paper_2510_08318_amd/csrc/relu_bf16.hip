@@ -74,29 +74,51 @@ __device__ __forceinline__ void relu_state_segment(const uint16_t* __restrict__ 
   // for every outstanding load at the top of the loop, so only an unrolled body overlaps them.
   constexpr int DEPTH = 2, UNROLL = 2;
   uint4 kr[DEPTH][XPT], vr[DEPTH][XPT];
+  // Addresses: a wavefront-uniform tile pointer (scalar registers) plus a 32-bit byte offset per
+  // thread and piece that is computed once (15 vector instructions per load otherwise, a quarter
+  // of this kernel's instruction stream).  Rows past n are redirected to row n-1 with one minimum
+  // per load.
+  static_assert(NT % (D / 8) == 0, "a thread keeps its chunk column");
+  uint32_t voff[XPT];
+#pragma unroll
+  for (int i = 0; i < XPT; ++i)
+    voff[i] = (uint32_t)(((tid + NT * i) / (D / 8)) * rw.sn + (tid % (D / 8)) * 8) * 2u;
+  int loff[XPT];                                   // LDS byte offsets of the thread's pieces
+#pragma unroll
+  for (int i = 0; i < XPT; ++i) {
+    const int r = (tid + NT * i) / (D / 8), c = tid % (D / 8);
+    loff[i] = r * RS + ((c ^ swz<D>(r)) * 16);
+  }
   auto load_tile = [&](uint4 (&kx)[XPT], uint4 (&vx)[XPT], int tile) {
     tile = tile < tile_end ? tile : tile_end - 1;
     const int t0 = tile * kTile;
+    const char* kt = reinterpret_cast<const char*>(kb + (size_t)t0 * rw.sn);
+    const char* vt = reinterpret_cast<const char*>(vb + (size_t)t0 * rw.sn);
+    const int last = n - 1 - t0;                  // last row of the tile that exists (>= kTile-1: all do)
+    const uint32_t last_off = (uint32_t)(last * rw.sn + (tid % (D / 8)) * 8) * 2u;
 #pragma unroll
     for (int i = 0; i < XPT; ++i) {
-      const int idx = tid + NT * i, r = idx / (D / 8), c = idx % (D / 8);
-      const int t = t0 + r < n ? t0 + r : n - 1;
-      kx[i] = ld_nt(reinterpret_cast<const uint4*>(kb + (size_t)t * rw.sn) + c);
-      vx[i] = ld_nt(reinterpret_cast<const uint4*>(vb + (size_t)t * rw.sn) + c);
+      const uint32_t off = voff[i] < last_off ? voff[i] : last_off;      // same column: offsets grow with the row
+      kx[i] = ld_nt(reinterpret_cast<const uint4*>(kt + off));
+      vx[i] = ld_nt(reinterpret_cast<const uint4*>(vt + off));
     }
   };
   auto consume = [&](uint4 (&kx)[XPT], uint4 (&vx)[XPT], int tile, bool real) {
     __syncthreads();                              // previous tile's operand reads are done
+    // the tiles stay bf16 (the products of a bf16 MFMA are exact): K through the sign test, V as it
+    // is.  Rows that do not exist hold copies of row n-1: zeroing their K is enough (phi = 0 adds
+    // nothing to S or z); only a head's last tile and padding steps pay for that.
+    const bool full = real && (tile + 1) * kTile <= n;      // uniform
 #pragma unroll
     for (int i = 0; i < XPT; ++i) {
-      const int idx = tid + NT * i, r = idx / (D / 8), c = idx % (D / 8);
-      const bool there = real && tile * kTile + r < n;
-      // the tiles stay bf16 (the products of a bf16 MFMA are exact): K through the sign test, V as it is
-      uint4 hk, hv = vx[i];
+      uint4 hk;
       hk.x = relu_bf16x2(kx[i].x); hk.y = relu_bf16x2(kx[i].y); hk.z = relu_bf16x2(kx[i].z); hk.w = relu_bf16x2(kx[i].w);
-      if (!there) { hk = make_uint4(0, 0, 0, 0); hv = hk; }
-      *reinterpret_cast<uint4*>(sK + r * RS + ((c ^ swz<D>(r)) * 16)) = hk;
-      *reinterpret_cast<uint4*>(sV + r * RS + ((c ^ swz<D>(r)) * 16)) = hv;
+      if (!full) {
+        const int r = (tid + NT * i) / (D / 8);
+        if (!(real && tile * kTile + r < n)) hk = make_uint4(0, 0, 0, 0);
+      }
+      *reinterpret_cast<uint4*>(sK + loff[i]) = hk;
+      *reinterpret_cast<uint4*>(sV + loff[i]) = vx[i];
     }
     load_tile(kx, vx, tile + DEPTH);
     __syncthreads();
