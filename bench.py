@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published peak
 # command with --calib-copy, scaled by the readings of the 1 GiB copy kernel (FETCH x2 KiB,
 # WRITE x1 KiB); keyed by (workload, stage).  The committed summary with the commands is
 # profiles/fwd_wan14b_720p_pmc.md.  None for workloads that have not been measured.
-MEASURED_TRAFFIC = {("C3", 0): 1_553_379_328 + 19_021_824, ("C3", 2): 794_359_808 + 774_176_768}
+MEASURED_TRAFFIC = {("C3", 0): 1_553_370_522 + 19_021_824, ("C3", 2): 794_324_787 + 774_176_666}
 
 
 def _hip():
