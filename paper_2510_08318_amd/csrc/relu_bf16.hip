@@ -4,7 +4,9 @@
 // in fwd_bf16.hip.
 //
 // With no projection and no softmax the map costs a sign test, so every kernel here is the plain
-// contraction of Eq. 3 (or of its chain rule) on fp16 MFMA operands with fp32 accumulation:
+// contraction of Eq. 3 (or of its chain rule) on MFMA with fp32 accumulation -- bf16 operands in
+// the state pass (K and V as stored: exact products, no conversion), fp16 where a state or a
+// gradient is an operand (the query pass and the backward):
 //   relu_state_kernel  : S_p = sum_j phi(k_j)^T v_j, z_p = sum_j phi(k_j) over the tiles of a split
 //   relu_prep_kernel   : MFMA operand images of a state (S or dS), built once per head
 //   relu_bwd_q_kernel  : den, G = dO S^T, delta, dq; split-n partials of dS, dz
