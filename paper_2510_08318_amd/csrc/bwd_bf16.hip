@@ -265,15 +265,24 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
   const int psw = swz<D>(prow);
   float gamma = 1.f;
 
+  // the lane's q rows of a tile are requested for the next tile as soon as the projection has
+  // consumed this tile's copy (never behind a branch: after the last tile it is simply read again);
+  // its dO rows are requested at the top of the tile and first needed after the projection, the
+  // softmaxes and o
+  uint4 xq[C::UK];
+  auto load_q = [&](int tile) {
+    const int t = tile * kTile + prow;
+    const uint4* row = reinterpret_cast<const uint4*>(qb + (size_t)(t < n ? t : n - 1) * rw.sn);
+#pragma unroll
+    for (int ks = 0; ks < C::UK; ++ks) xq[ks] = row[2 * ks + g];
+  };
+  load_q(p < ntile ? p : 0);
   for (int tile = p; tile < ntile; tile += P) {
     const int t = tile * kTile + prow;
     const bool valid = t < n;
     const int tc = valid ? t : (n - 1);
-    uint4 xq[C::UK], dor[D / 16];
+    uint4 dor[D / 16];
     {
-      const uint4* row = reinterpret_cast<const uint4*>(qb + (size_t)tc * rw.sn);
-#pragma unroll
-      for (int ks = 0; ks < C::UK; ++ks) xq[ks] = row[2 * ks + g];
       const uint4* drow = reinterpret_cast<const uint4*>(dob + (size_t)tc * rw.sn + g * (D / 2));
 #pragma unroll
       for (int i = 0; i < D / 16; ++i) dor[i] = drow[i];
@@ -283,6 +292,7 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
     // dout . s is taken here, while few registers are live.
     f32x16 u[C::UM];
     project<D, 3>(xq, sWA, lane, u);
+    load_q(tile + P < ntile ? tile + P : tile);
     float pp[C::LOC], pm[C::LOC];
     uint32_t pk[C::NPK];
     softmax_full<D>(u, pp, pm, pk);
