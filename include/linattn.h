@@ -127,7 +127,7 @@ size_t linattn_workspace_bytes(int B, int H, int n, int d, int kind, int dtype);
 size_t linattn_workspace_bytes_wgrads(int B, int H, int n, int d, int kind, int dtype);
 
 /*
- * Forward, Eq. 3 with phi of Eq. 5.  Three stages on `stream`: phi(K) fused with a split-n
+ * Forward, Eq. 3 with the descriptor's phi (Eq. 5, or the ReLU map).  Three stages on `stream`: phi(K) fused with a split-n
  * partial state, a fixed-order reduction of the partials, phi(Q) S / (phi(Q) . z) with the
  * store of out.  Writes out [B,H,n,d] and, if the descriptor has one, state.
  * Errors: E_PHI, E_NULL, E_SHAPE (also H or d different from the descriptor), E_ALIGN,
@@ -138,8 +138,8 @@ int linattn_fwd(const void* q, const void* k, const void* v, void* out,
 
 /*
  * Backward of linattn_fwd for L with dL/dout = dout: writes dq, dk, dv [B,H,n,d] and, if the
- * descriptor has them, dwq and dwk.  Needs the state a forward call with the same q-independent
- * inputs (k, v, wk) left in the descriptor's state buffer.
+ * descriptor has them, dwq and dwk (Eq. 5 only; the ReLU map has no weights).  Needs the state a
+ * forward call with the same q-independent inputs (k, v, wk) left in the descriptor's state buffer.
  * Errors: as linattn_fwd, plus E_STATE.
  */
 int linattn_bwd(const void* q, const void* k, const void* v, const void* dout,
