@@ -39,6 +39,50 @@ def _hip():
     return lib
 
 
+def streaming_rates(nbytes: int, stream: int, reps: int = 20):
+    """What plain streaming kernels reach on this GPU, measured now: GB/s of a read-only kernel over
+    nbytes and of a copy kernel (nbytes read + nbytes written), HIP events on `stream`.  Context for
+    `frac`, which stays relative to the published peak."""
+    import torch
+    from paper_2510_08318_amd import build as B
+    if not os.path.exists(B.PROBE_LIB):
+        raise RuntimeError(f"{B.PROBE_LIB} is missing: run `python paper_2510_08318_amd/build.py`")
+    lib = ctypes.CDLL(B.PROBE_LIB)
+    lib.membw_probe.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
+    lib.membw_probe.restype = ctypes.c_int
+    hip = _hip()
+    nbytes -= nbytes % 16
+    src = torch.ones(nbytes, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    ev = [ctypes.c_void_p() for _ in range(2)]
+    for e in ev:
+        assert hip.hipEventCreate(ctypes.byref(e)) == 0
+    hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    out = {}
+    # each rate is the best of a few launch shapes
+    for name, kind, moved in (("read_GBps", 0, nbytes), ("copy_GBps", 1, 2 * nbytes)):
+        best = 0.0
+        for groups in (256, 512, 2048, 8192):
+            def run():
+                rc = lib.membw_probe(kind, src.data_ptr(), dst.data_ptr(), nbytes, groups, stream)
+                assert rc == 0, f"membw_probe: hip error {rc}"
+            for _ in range(3):
+                run()
+            assert hip.hipEventRecord(ev[0], stream) == 0
+            for _ in range(reps):
+                run()
+            assert hip.hipEventRecord(ev[1], stream) == 0
+            torch.cuda.synchronize()
+            ms = ctypes.c_float()
+            assert hip.hipEventElapsedTime(ctypes.byref(ms), ev[0], ev[1]) == 0
+            best = max(best, moved / (ms.value / reps * 1e-3) / 1e9)
+        out[name] = round(best, 1)
+    for e in ev:
+        hip.hipEventDestroy(e)
+    del src, dst
+    return out
+
+
 def cpu_baseline(x, budget_s: float = 12.0, relu: bool = False):
     """The oracle as it stands, on a bounded sample: whole heads of the same workload."""
     from oracle import linattn_oracle as O
@@ -240,6 +284,13 @@ def main():
                 "path_frac": round(4 * x.d * esz * head_tokens / (sum(stage_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                 # one call = first to last stage event; distribution over the K event-bracketed calls
                 "call_ms_median": round(per_call[len(per_call) // 2], 4), "call_ms_min": round(per_call[0], 4)}
+
+    # the same bytes through plain streaming kernels, measured now (the state pass only reads, the
+    # query pass reads and writes the same amount)
+    rates = streaming_rates(stage_bytes[0], stream)
+    floor_ms = stage_bytes[0] / rates["read_GBps"] / 1e6 + stage_bytes[2] / rates["copy_GBps"] / 1e6
+    roofline["streaming"] = {**rates, "path_ms_at_streaming_rates": round(floor_ms, 4),
+                             "path_frac_of_streaming": round(floor_ms / sum(stage_ms), 4)}
 
     res = {
         "metric": "linear-attn fwd tokens/s (Wan-14B 720p shape)" if args.workload == "C3" and not relu

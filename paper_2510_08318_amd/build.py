@@ -8,6 +8,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblinattn.so")
+PROBE_LIB = os.path.join(HERE, "libmembw_probe.so")      # bench.py's streaming-rate probe, a library of its own
+PROBE_SOURCE = "membw_probe.hip"
 SOURCES = ["api.cpp", "fwd_f32.hip", "fwd_bf16.hip", "state_reduce.hip", "bwd_bf16.hip", "bwd_f32.hip", "relu_bf16.hip"]
 # Packed-fp32 VALU forms are switched off for every device compilation.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -25,13 +27,16 @@ def build(verbose: bool = False) -> str:
     objs = []
     procs = []
     os.makedirs(os.path.join(HERE, "_build"), exist_ok=True)
-    for src in SOURCES:
+    for src in SOURCES + [PROBE_SOURCE]:
         obj = os.path.join(HERE, "_build", src.rsplit(".", 1)[0] + ".o")
         cmd = [hipcc, *FLAGS, *EXTRA.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
         if src.endswith(".cpp"):
             cmd.insert(1, "-x"); cmd.insert(2, "hip")
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
-        objs.append(obj)
+        if src != PROBE_SOURCE:
+            objs.append(obj)
+        else:
+            probe_obj = obj
     failed = False
     for src, pr in procs:
         out, _ = pr.communicate()
@@ -45,6 +50,7 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed")
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
     subprocess.run(cmd, check=True)
+    subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", probe_obj, "-o", PROBE_LIB], check=True)
     return LIB
 
 
