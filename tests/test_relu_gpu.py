@@ -113,3 +113,22 @@ def test_full_config5_shape_sampled():
         ref = [R.relu_fwd(q, k, v)] + list(R.relu_bwd(q, k, v, do))
         for g, r in zip(got, ref):
             assert O.err_metric(g[0, h], r)[0] <= 1e-2
+
+
+def test_premapped_nonnegative_features_reduce_to_textbook_gemms():
+    """q, k that already are non-negative features pass through max(x, 0) unchanged, so the path must
+    return plain kernel attention: (q k^T) v divided by the row sums of q k^T, written here with
+    numpy matmuls only (no oracle code), fp32 and bf16."""
+    for cfg, n, d, tol in (("C1", 300, 64, 1e-5), ("C5", 1000, 128, 1e-2)):
+        x = synth.generate(cfg, n=n, d=d, H=2, B=1, with_dout=True)
+        if x.dtype == "bf16":
+            x.q = x.q & np.uint16(0x7FFF)                    # clear the sign bit: |q|, |k|
+            x.k = x.k & np.uint16(0x7FFF)
+        else:
+            x.q, x.k = np.abs(x.q), np.abs(x.k)
+        got, _ = _run(x, backward=False)
+        q, k, v = (O.to_f64(t) for t in (x.q, x.k, x.v))
+        for h in range(x.H):
+            w = q[0, h] @ k[0, h].T
+            ref = (w @ v[0, h]) / (w.sum(-1, keepdims=True) + 1e-6)
+            assert O.err_metric(got[0][0, h], ref)[0] <= tol
