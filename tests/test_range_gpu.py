@@ -50,3 +50,19 @@ def test_near_uniform_phi_is_the_known_limit(d):
     errs = _errors(_scaled(d, sq=0.01, sk=0.01))
     assert errs["out"] <= 1e-2 and errs["dv"] <= 1e-2, errs
     assert max(errs.values()) <= 0.2, errs
+
+
+@pytest.mark.parametrize("scales", [
+    dict(sq=1e4), dict(sq=1e-4), dict(sk=1e4), dict(sk=1e-4), dict(sq=1e3, sk=1e3), dict(sv=1000), dict(sdo=1e4), dict(sdo=1e-6),
+], ids=lambda s: ",".join(f"{k}={v}" for k, v in s.items()))
+def test_relu_map_rescaled_inputs_stay_within_tolerance(scales):
+    """max(x, 0) commutes with positive scaling, so the output does not depend on the scale of q or k;
+    the kernels must not depend on it through fp16 range either."""
+    from oracle import relu_oracle as R
+    from tests.test_relu_gpu import _run
+    x = _scaled(128, **scales)
+    got, _ = _run(x)
+    ref = [R.relu_fwd_bh(x.q, x.k, x.v)] + list(R.relu_bwd_bh(x.q, x.k, x.v, x.dout))
+    errs = {name: O.err_metric(g, r)[0] for name, g, r in zip(["out", "dq", "dk", "dv"], got, ref)}
+    assert all(np.isfinite(g).all() for g in got)
+    assert max(errs.values()) <= 1e-2, errs
