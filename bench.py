@@ -29,6 +29,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X published peak
 # WRITE x1 KiB); keyed by (workload, stage).  The committed summary with the commands is
 # profiles/fwd_wan14b_720p_pmc.md.  None for workloads that have not been measured.
 MEASURED_TRAFFIC = {("C3", 0): 1_553_370_522 + 19_021_824, ("C3", 2): 794_324_787 + 774_176_666}
+# The same for one linattn_bwd call (all its kernels), weight gradients on: profiles/bwd_wan1p3b_480p_pmc.md.
+MEASURED_TRAFFIC_BWD = {"C5": 816_400_000 + 446_700_000}
 
 
 def _hip():
@@ -133,6 +135,17 @@ def cpu_baseline_bwd(x, budget_s: float = 12.0, relu: bool = False):
             "sample": f"{done} of {x.H} heads of batch item 0, all {x.n} tokens, fp64 numpy backward, {dt:.1f} s"}
 
 
+def _calib_copy():
+    """One 1 GiB device-to-device copy: the reference reading for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE."""
+    import torch
+    src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    dst.copy_(src)                      # reads 1 GiB, writes 1 GiB
+    torch.cuda.synchronize()
+    del src, dst
+
+
 def bench_bwd(args):
     """linattn_bwd on one batch (state from one forward call made before the timed region)."""
     import torch
@@ -177,8 +190,12 @@ def bench_bwd(args):
                                + (", [B,n,H,d] layout" if args.layout == "bnhd" else "")
                                + (", mixed attention (Eq. 6, r = 0.5) with dL/dr" if args.blend else "")},
         "roofline": {"bound": "hbm", "kernel": "linattn_bwd (all kernels of one call)", "achieved": round(achieved, 1),
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None},
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": None if (relu or args.blend or args.no_wgrads or args.layout != "bhnd")
+                                else MEASURED_TRAFFIC_BWD.get(args.workload)},
     }
+    if args.calib_copy:
+        _calib_copy()
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline_bwd(x, relu=relu)
     lay.close()
@@ -305,12 +322,7 @@ def main():
         "roofline": roofline,
     }
     if args.calib_copy:
-        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        dst.copy_(src)                      # reads 1 GiB, writes 1 GiB
-        torch.cuda.synchronize()
-        del src, dst
+        _calib_copy()
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(x, relu=relu)
     lay.close()
