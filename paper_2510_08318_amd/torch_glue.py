@@ -79,7 +79,8 @@ class Layer:
 
     def __init__(self, wq: torch.Tensor, wk: torch.Tensor, B: int, n: int, *, keep_state: bool = True,
                  want_wgrads: bool = False, layout: str = "bhnd"):
-        """layout "bhnd": q, k, v, out are [B, H, n, d]; "bnhd": [B, n, H, d] (heads interleaved per token)."""
+        """layout "bhnd": q, k, v, out are [B, H, n, d]; "bnhd": [B, n, H, d] (heads interleaved per token).
+        want_wgrads: False, True (both dW~_q and dW~_k), or "q" / "k" for one of them."""
         assert layout in ("bhnd", "bnhd")
         self.layout = layout
         assert wq.is_cuda and wk.is_cuda and wq.dtype == wk.dtype and wq.shape == wk.shape
@@ -91,8 +92,9 @@ class Layer:
         self.B, self.n = B, n
         dev = wq.device
         self.state = torch.empty((B, self.H, self.d + 1, self.d), dtype=torch.float32, device=dev) if keep_state else None
-        self.dwq = torch.empty((self.H, self.d, half), dtype=torch.float32, device=dev) if want_wgrads else None
-        self.dwk = torch.empty((self.H, self.d, half), dtype=torch.float32, device=dev) if want_wgrads else None
+        assert want_wgrads in (False, True, "q", "k")
+        self.dwq = torch.empty((self.H, self.d, half), dtype=torch.float32, device=dev) if want_wgrads in (True, "q") else None
+        self.dwk = torch.empty((self.H, self.d, half), dtype=torch.float32, device=dev) if want_wgrads in (True, "k") else None
         size_fn = B_.linattn_workspace_bytes_wgrads if want_wgrads else B_.linattn_workspace_bytes
         self.workspace_bytes = size_fn(B, self.H, n, self.d, B_.PHI_HEDGEHOG, self.dtype)
         if self.workspace_bytes == 0:

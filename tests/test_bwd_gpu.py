@@ -90,6 +90,28 @@ def test_backward_without_weight_grads_and_small_dout():
         assert O.err_metric(u, r)[0] <= 1e-2
 
 
+@pytest.mark.parametrize("cfg,n,d", [("C5", 1000, 128), ("C5", 333, 64), ("C1", 300, 64)])
+@pytest.mark.parametrize("side", ["q", "k"])
+def test_one_weight_gradient_only(cfg, n, d, side):
+    """dwq or dwk alone may be requested: the one asked for matches the oracle, dq, dk, dv are unchanged."""
+    import torch
+    from paper_2510_08318_amd import torch_glue as G
+    x = synth.generate(cfg, n=n, d=d, H=2, B=2, with_dout=True)
+    q, k, v, wq, wk, do = [G.to_device(t) for t in (x.q, x.k, x.v, x.wq, x.wk, x.dout)]
+    lay = G.Layer(wq, wk, x.B, x.n, want_wgrads=side)
+    lay.forward(q, k, v)
+    grads = lay.backward(q, k, v, do)
+    torch.cuda.synchronize()
+    got = [G.to_host_f64(t) for t in grads] + [G.to_host_f64(lay.dwq if side == "q" else lay.dwk)]
+    assert (lay.dwk if side == "q" else lay.dwq) is None
+    lay.close()
+    ref = O.bwd_bh(x.q, x.k, x.v, x.wq, x.wk, x.dout)
+    ref = list(ref[:3]) + [ref[3] if side == "q" else ref[4]]
+    for name, g, r in zip(["dq", "dk", "dv", "dw"], got, ref):
+        tol = WTOL[x.dtype] if name == "dw" else TOL[x.dtype]
+        assert O.err_metric(g, r)[0] <= tol, (name, side)
+
+
 def test_backward_bitwise_deterministic():
     import torch
     from paper_2510_08318_amd import torch_glue as G
