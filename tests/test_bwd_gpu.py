@@ -112,6 +112,30 @@ def test_one_weight_gradient_only(cfg, n, d, side):
         assert O.err_metric(g, r)[0] <= tol, (name, side)
 
 
+def test_one_descriptor_serves_smaller_calls():
+    """A descriptor whose workspace and state were sized for (B=2, n=1000) also serves a (B=1, n=300) call,
+    between two full-size calls: every call is planned from its own arguments."""
+    import torch
+    from paper_2510_08318_amd import binding as L, torch_glue as G
+    big = synth.generate("C5", n=1000, H=2, B=2)
+    small = synth.generate("C5", n=300, H=2, B=1)
+    small.wq, small.wk = big.wq, big.wk                  # the layer's maps
+    wq, wk = G.to_device(big.wq), G.to_device(big.wk)
+    lay = G.Layer(wq, wk, big.B, big.n, want_wgrads=True)
+    stream = torch.cuda.current_stream().cuda_stream
+    for x in (big, small, big):
+        q, k, v, do = [G.to_device(t) for t in (x.q, x.k, x.v, x.dout)]
+        out, dq, dk, dv = (torch.empty_like(q) for _ in range(4))
+        L.linattn_fwd(q, k, v, out, x.B, x.H, x.n, x.d, lay.phi_id, stream)
+        L.linattn_bwd(q, k, v, do, dq, dk, dv, x.B, x.H, x.n, x.d, lay.phi_id, stream)
+        torch.cuda.synchronize()
+        got = [G.to_host_f64(t) for t in (out, dq, dk, dv, lay.dwq, lay.dwk)]
+        ref = [O.fwd_bh(x.q, x.k, x.v, x.wq, x.wk)] + list(O.bwd_bh(x.q, x.k, x.v, x.wq, x.wk, x.dout))
+        for name, g, r in zip(["out", "dq", "dk", "dv", "dwq", "dwk"], got, ref):
+            assert O.err_metric(g, r)[0] <= 1e-2, (name, x.B, x.n)
+    lay.close()
+
+
 def test_backward_bitwise_deterministic():
     import torch
     from paper_2510_08318_amd import torch_glue as G
