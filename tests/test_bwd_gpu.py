@@ -136,6 +136,34 @@ def test_one_descriptor_serves_smaller_calls():
     lay.close()
 
 
+def test_two_layers_on_two_streams():
+    """Two descriptors, each with its own workspace, driven from two streams at once (default priority):
+    calls share no state, so both results are those of the oracle."""
+    import torch
+    from paper_2510_08318_amd import binding as L, torch_glue as G
+    xs = [synth.generate("C5", n=3000, H=3, B=1), synth.generate("C5", n=2049, H=2, B=2)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    work = []
+    for x in xs:
+        q, k, v, do, wq, wk = [G.to_device(t) for t in (x.q, x.k, x.v, x.dout, x.wq, x.wk)]
+        lay = G.Layer(wq, wk, x.B, x.n, want_wgrads=True)
+        outs = [torch.empty_like(q) for _ in range(4)]
+        work.append((x, lay, (q, k, v, do), outs))
+    torch.cuda.synchronize()
+    for _ in range(4):
+        for (x, lay, (q, k, v, do), (out, dq, dk, dv)), st in zip(work, streams):
+            L.linattn_fwd(q, k, v, out, x.B, x.H, x.n, x.d, lay.phi_id, st.cuda_stream)
+            L.linattn_bwd(q, k, v, do, dq, dk, dv, x.B, x.H, x.n, x.d, lay.phi_id, st.cuda_stream)
+    for st in streams:
+        st.synchronize()
+    for x, lay, _, (out, dq, dk, dv) in work:
+        got = [G.to_host_f64(t) for t in (out, dq, dk, dv, lay.dwq, lay.dwk)]
+        ref = [O.fwd_bh(x.q, x.k, x.v, x.wq, x.wk)] + list(O.bwd_bh(x.q, x.k, x.v, x.wq, x.wk, x.dout))
+        for name, g, r in zip(["out", "dq", "dk", "dv", "dwq", "dwk"], got, ref):
+            assert O.err_metric(g, r)[0] <= 1e-2, (name, x.n)
+        lay.close()
+
+
 def test_backward_bitwise_deterministic():
     import torch
     from paper_2510_08318_amd import torch_glue as G
