@@ -175,7 +175,7 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
       }
       if (pass == 0) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) inv[r] = __builtin_amdgcn_rcpf(dn[r] + den_eps);
+        for (int r = 0; r < 16; ++r) inv[r] = __builtin_amdgcn_rcpf(KIND == kPhiRelu ? dn[r] + den_eps : dn[r]);
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
