@@ -289,7 +289,8 @@ def main():
 
     esz = 2 if x.dtype == "bf16" else 4
     head_tokens = x.B * x.H * x.n
-    stage_bytes = [2 * x.d * esz * head_tokens, 0, 2 * x.d * esz * head_tokens]   # read K,V | - | read Q, write out
+    # read K, V | - | read Q (and the softmax-branch tensor of Eq. 6 when blending), write out
+    stage_bytes = [2 * x.d * esz * head_tokens, 0, (3 if args.blend else 2) * x.d * esz * head_tokens]
     names = ["state_partials (phi(K)^T V, split-n)", "state_reduce", "apply (phi(Q) S / phi(Q).z)"]
     dom = 0 if stage_ms[0] >= stage_ms[2] else 2
     achieved = stage_bytes[dom] / (stage_ms[dom] * 1e-3) / 1e9
@@ -297,8 +298,8 @@ def main():
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": None if (relu or args.blend or args.layout != "bhnd") else MEASURED_TRAFFIC.get((args.workload, dom)),
                 "stage_ms": [round(t, 4) for t in stage_ms],
-                "path_GBps": round(4 * x.d * esz * head_tokens / (sum(stage_ms) * 1e-3) / 1e9, 1),
-                "path_frac": round(4 * x.d * esz * head_tokens / (sum(stage_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                "path_GBps": round(sum(stage_bytes) / (sum(stage_ms) * 1e-3) / 1e9, 1),
+                "path_frac": round(sum(stage_bytes) / (sum(stage_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                 # one call = first to last stage event; distribution over the K event-bracketed calls
                 "call_ms_median": round(per_call[len(per_call) // 2], 4), "call_ms_min": round(per_call[0], 4)}
 
