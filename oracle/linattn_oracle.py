@@ -202,13 +202,16 @@ def err_metric(got: np.ndarray, ref: np.ndarray):
     The outputs are heavily cancelling averages of zero-mean values, so a plain
     element-wise relative error is unbounded near zeros; each element's error is
     therefore divided by max(|ref|, rms of ref over its (b, h) slice).
-    Returns (max floored relative error, max |diff| / max |ref|).
+    Returns (max floored relative error, max |diff| / max |ref|); both are +inf if any
+    element of got (or of ref) is NaN or infinite, so that `err <= tol` can never pass on one.
     """
     got = np.asarray(got, np.float64)
     ref = np.asarray(ref, np.float64)
     lead = ref.shape[:-2]
     g2 = got.reshape((-1,) + ref.shape[-2:])
     r2 = ref.reshape((-1,) + ref.shape[-2:])
+    if not (np.isfinite(g2).all() and np.isfinite(r2).all()):
+        return float("inf"), float("inf")
     worst, worst_norm = 0.0, 0.0
     for s in range(r2.shape[0]):
         diff = np.abs(g2[s] - r2[s])

@@ -279,19 +279,105 @@ def test_planted_mistakes_are_caught_by_bruteforce_pin():
 
 
 def test_planted_gradient_mistakes_are_caught_by_fd():
+    """Three plausible slips in the chain rule of Eq. 3 + Eq. 5 -- the dz term dropped, the sign of the
+    softmax(-u) half of the Jacobian flipped, the 1/den of dL/dphi(q) left out -- each planted in a copy
+    of the oracle's arithmetic: the finite difference sides with the oracle and against the copy."""
     q, k, v, Wq, Wk = _rand(12, 8, 22, 2.0)
     dout = np.random.default_rng(23).standard_normal((12, 8))
     dq, dk, dv, dWq, dWk = O.bwd(q, k, v, Wq, Wk, dout)
-    # a dropped dz term, a wrong sign on the minus half, a missing 1/den: each moves dk or dq
     fk, fq = O.phi(k, Wk), O.phi(q, Wq)
     S, z = fk.T @ v, fk.sum(0)
     den = fq @ z
+    o = (fq @ S) / den[:, None]
+    delta = (dout * o).sum(-1)
     dS = fq.T @ (dout / den[:, None])
-    dfk_no_dz = v @ dS.T
-    dk_bad, _ = O._phi_vjp(k, Wk, dfk_no_dz)
-    idx = np.unravel_index(np.abs(dk_bad - dk).argmax(), dk.shape)
-    fd = O.finite_difference(q, k, v, Wq, Wk, dout, "k", tuple(int(i) for i in idx))
-    assert abs(fd - dk[idx]) < 1e-6 * max(1e-3, abs(dk[idx])) and abs(fd - dk_bad[idx]) > 1e-4 * abs(dk[idx])
+    dz = -(fq * (delta / den)[:, None]).sum(0)
+
+    def vjp_wrong_sign(x, W, g):
+        h = W.shape[1]
+        u = x @ W
+        pp, pm = scipy_softmax(u, axis=-1), scipy_softmax(-u, axis=-1)
+        gp, gm = g[:, :h], g[:, h:]
+        du = pp * (gp - (gp * pp).sum(-1, keepdims=True)) + pm * (gm - (gm * pm).sum(-1, keepdims=True))
+        return du @ W.T
+
+    planted = {
+        "dropped dz": ("k", dk, O._phi_vjp(k, Wk, v @ dS.T)[0]),
+        "plus sign on the minus half": ("k", dk, vjp_wrong_sign(k, Wk, v @ dS.T + dz[None, :])),
+        "missing 1/den": ("q", dq, O._phi_vjp(q, Wq, dout @ S.T - delta[:, None] * z[None, :])[0]),
+    }
+    for name, (which, good, bad) in planted.items():
+        idx = tuple(int(i) for i in np.unravel_index(np.abs(bad - good).argmax(), good.shape))
+        fd = O.finite_difference(q, k, v, Wq, Wk, dout, which, idx)
+        assert abs(fd - good[idx]) < 1e-6 * max(1e-3, abs(good[idx])), name
+        assert abs(fd - bad[idx]) > 1e-4 * abs(good[idx]), name
+
+
+# ---------------------------------------------------------------- the error metric of the parity tests
+
+def _metric_case():
+    """Two (b,h) slices [2 x 3] with very different magnitudes and three planted errors.
+    Slice 0: ref = [[3, 4, 0], [0, 0, 0]]  -> rms = sqrt(25/6) = 2.0412...
+      got differs by 0.3 at the entry 4  (|ref| > rms: 0.3/4 = 0.075)
+      and by 0.1 at an entry 0           (|ref| < rms: 0.1/rms = 0.04899)
+    Slice 1: ref = 1e-3 * [[1, 1, 1], [1, 1, 1]] -> rms = 1e-3
+      got differs by 2e-4 at one entry   (2e-4/1e-3 = 0.2)   <- the worst
+    """
+    ref = np.zeros((1, 2, 2, 3))
+    ref[0, 0] = [[3.0, 4.0, 0.0], [0.0, 0.0, 0.0]]
+    ref[0, 1] = 1e-3
+    got = ref.copy()
+    got[0, 0, 0, 1] += 0.3
+    got[0, 0, 1, 2] -= 0.1
+    got[0, 1, 1, 0] += 2e-4
+    return got, ref
+
+
+def test_err_metric_hand_values():
+    """max |got - ref| / max(|ref|, rms of ref over the element's own (b,h) slice), and the normwise
+    max |diff| / max |ref| per slice: values worked out by hand."""
+    got, ref = _metric_case()
+    rms0 = np.sqrt(25.0 / 6.0)
+    # each error alone
+    one = ref.copy(); one[0, 0, 0, 1] += 0.3
+    assert O.err_metric(one, ref) == (pytest.approx(0.3 / 4.0, rel=1e-12), pytest.approx(0.3 / 4.0, rel=1e-12))
+    one = ref.copy(); one[0, 0, 1, 2] -= 0.1
+    assert O.err_metric(one, ref) == (pytest.approx(0.1 / rms0, rel=1e-12), pytest.approx(0.1 / 4.0, rel=1e-12))
+    one = ref.copy(); one[0, 1, 1, 0] += 2e-4
+    assert O.err_metric(one, ref) == (pytest.approx(0.2, rel=1e-9), pytest.approx(0.2, rel=1e-9))
+    # all three: the small slice decides both numbers; a floor or a norm taken over the whole tensor
+    # would hide it behind the large slice
+    worst, norm = O.err_metric(got, ref)
+    assert worst == pytest.approx(0.2, rel=1e-9) and norm == pytest.approx(0.2, rel=1e-9)
+    # exact agreement, an all-zero reference (floor 1: absolute error), symmetric in sign
+    assert O.err_metric(ref, ref) == (0.0, 0.0)
+    zero = np.zeros((1, 1, 2, 2)); off = zero.copy(); off[0, 0, 1, 1] = -0.25
+    assert O.err_metric(off, zero) == (0.25, 0.25)
+    # 2-D input is one slice
+    assert O.err_metric(got[0, 0], ref[0, 0])[0] == pytest.approx(0.3 / 4.0, rel=1e-12)
+    # a non-finite value never passes
+    for poison in (np.nan, np.inf, -np.inf):
+        for where in ((0, 0, 0, 0), (0, 1, 1, 2)):
+            bad = got.copy(); bad[where] = poison
+            assert O.err_metric(bad, ref) == (np.inf, np.inf)
+
+
+def test_err_metric_lenient_variants_give_other_numbers():
+    """Plausible lenient versions of the metric -- one floor for the whole tensor, max |ref| in place of
+    the RMS, the mean in place of the max, no per-slice norm -- all disagree with the hand values."""
+    got, ref = _metric_case()
+    diff = np.abs(got - ref)
+    want = 0.2
+    global_floor = (diff / np.maximum(np.abs(ref), np.sqrt(np.mean(ref ** 2)))).max()
+    per_slice_max_floor = max((diff[0, s] / np.abs(ref[0, s]).max()).max() for s in range(2))
+    mean_not_max = max((diff[0, s] / np.maximum(np.abs(ref[0, s]), np.sqrt(np.mean(ref[0, s] ** 2)))).mean() for s in range(2))
+    global_norm = diff.max() / np.abs(ref).max()
+    for name, val in (("global floor", global_floor), ("mean instead of max", mean_not_max), ("global norm", global_norm)):
+        assert abs(val - want) > 0.05, name
+    # max|ref| as the floor agrees on the small slice (all entries equal) but not on the large one
+    got0, ref0 = got[:, :1], ref[:, :1]
+    assert abs((diff[0, 0] / np.abs(ref[0, 0]).max()).max() - O.err_metric(got0, ref0)[0]) > 0.01
+    assert per_slice_max_floor == pytest.approx(0.2, rel=1e-9)      # (that variant is caught by the line above)
 
 
 # ---- mixed attention (Eq. 6) -------------------------------------------------------------
