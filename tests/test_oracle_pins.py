@@ -374,10 +374,12 @@ def test_err_metric_lenient_variants_give_other_numbers():
     global_norm = diff.max() / np.abs(ref).max()
     for name, val in (("global floor", global_floor), ("mean instead of max", mean_not_max), ("global norm", global_norm)):
         assert abs(val - want) > 0.05, name
-    # max|ref| as the floor agrees on the small slice (all entries equal) but not on the large one
-    got0, ref0 = got[:, :1], ref[:, :1]
-    assert abs((diff[0, 0] / np.abs(ref[0, 0]).max()).max() - O.err_metric(got0, ref0)[0]) > 0.01
-    assert per_slice_max_floor == pytest.approx(0.2, rel=1e-9)      # (that variant is caught by the line above)
+    # max |ref| of the slice as the floor: the error at a zero entry of the large slice reads 0.1/4 with
+    # it, 0.1/rms = 0.049 with the RMS floor
+    one = ref.copy(); one[0, 0, 1, 2] -= 0.1
+    with_max_floor = max((np.abs(one - ref)[0, s] / np.abs(ref[0, s]).max()).max() for s in range(2))
+    assert with_max_floor == pytest.approx(0.025) and O.err_metric(one, ref)[0] == pytest.approx(0.1 / np.sqrt(25.0 / 6.0))
+    assert per_slice_max_floor == pytest.approx(0.2, rel=1e-9)      # (on the full case that variant agrees)
 
 
 # ---- mixed attention (Eq. 6) -------------------------------------------------------------
