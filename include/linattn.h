@@ -28,6 +28,17 @@
  *   - out must not alias q, k or v; dq, dk, dv must not alias any input.
  *   - calls that share a descriptor share its workspace: do not overlap them on
  *     different streams.
+ *
+ * Numeric domain of the bf16 mode (the fp32 mode computes in fp32 throughout)
+ *   - q, k enter the projection of Eq. 5 as stored; phi, v, dout and the states S, dS enter the
+ *     matrix cores as fp16 (11-bit significand) with fp32 accumulation.  phi, the states, dout and
+ *     every gradient operand are rescaled by exact powers of two first (per token, per 32-token
+ *     block, per head, or per workgroup following the running maximum), so their magnitude does
+ *     not matter: any finite bf16 q, k, dout is in the domain.
+ *   - v is widened to fp16 unscaled: |v| must be below 65504 (fp16's largest finite value).  Larger
+ *     entries become infinite inside the kernels and the call returns LINATTN_OK with Inf/NaN in
+ *     out, state and the gradients; the library does not scan for them.  Entries with
+ *     0 < |v| < 2^-14 lose their low bits (absolute error below 2^-25).
  */
 #ifndef LINATTN_H
 #define LINATTN_H
@@ -47,7 +58,7 @@ extern "C" {
 #define LINATTN_E_PHI        -5   /* unknown phi_id / unsupported kind / table full */
 #define LINATTN_E_WORKSPACE  -6   /* workspace missing or smaller than linattn_workspace_bytes() */
 #define LINATTN_E_HIP        -7   /* a HIP launch reported an error */
-#define LINATTN_E_STATE      -8   /* linattn_bwd needs the descriptor's state buffer */
+#define LINATTN_E_STATE      -8   /* linattn_bwd without a state buffer, or a state buffer too small for this B */
 #define LINATTN_E_ALIAS      -9   /* an output aliases an input */
 
 /* feature-map kinds */
@@ -82,7 +93,8 @@ typedef struct linattn_phi_desc {
                              gradient summed over batch and tokens; NULL = not computed */
   void *state;            /* optional device fp32 [B, H, d+1, d]: rows 0..d-1 = S with rows indexed by
                              the feature of phi in the order of Eq. 5 (softmax(+) half first),
-                             row d = z.  linattn_fwd writes it when non-NULL; linattn_bwd reads it. */
+                             row d = z.  linattn_fwd writes it when non-NULL; linattn_bwd reads it.
+                             Its size is state_bytes (last field). */
   void *workspace;        /* device scratch, 256-byte aligned, >= linattn_workspace_bytes(...) */
   size_t workspace_bytes;
   int layout;             /* LINATTN_LAYOUT_BHND (0) or LINATTN_LAYOUT_BNHD; the state, dW~ and the
@@ -100,11 +112,15 @@ typedef struct linattn_phi_desc {
   const void *blend_in;
   const float *blend_r;
   float *blend_dr;
+  size_t state_bytes;     /* bytes behind `state` (ignored when state is NULL).  A call with batch size B
+                             touches B * H * (d+1) * d * 4 of them: linattn_phi_create returns E_STATE if
+                             not even B = 1 fits, linattn_fwd / linattn_bwd return E_STATE for a B that
+                             does not fit. */
 } linattn_phi_desc;
 
 /* Register a descriptor; *phi_id_out receives a handle >= 16.  Host-only, no HIP call.
  * Errors: E_NULL (desc, out, wq, wk), E_PHI (kind, table full), E_DTYPE, E_SHAPE (H, d, layout),
- * E_ALIGN. */
+ * E_ALIGN, E_STATE (state given with state_bytes < H * (d+1) * d * 4). */
 int linattn_phi_create(const linattn_phi_desc* desc, int* phi_id_out);
 
 /* Forget a handle.  E_PHI if it is not live.  Buffers stay the caller's. */
@@ -131,7 +147,7 @@ size_t linattn_workspace_bytes_wgrads(int B, int H, int n, int d, int kind, int 
  * partial state, a fixed-order reduction of the partials, phi(Q) S / (phi(Q) . z) with the
  * store of out.  Writes out [B,H,n,d] and, if the descriptor has one, state.
  * Errors: E_PHI, E_NULL, E_SHAPE (also H or d different from the descriptor), E_ALIGN,
- * E_WORKSPACE, E_ALIAS, E_HIP.
+ * E_WORKSPACE, E_STATE (state buffer smaller than this B needs), E_ALIAS, E_HIP.
  */
 int linattn_fwd(const void* q, const void* k, const void* v, void* out,
                 int B, int H, int n, int d, int phi_id, void* stream);
@@ -145,16 +161,6 @@ int linattn_fwd(const void* q, const void* k, const void* v, void* out,
 int linattn_bwd(const void* q, const void* k, const void* v, const void* dout,
                 void* dq, void* dk, void* dv,
                 int B, int H, int n, int d, int phi_id, void* stream);
-
-/*
- * Optional instrumentation for benchmarks (the paper reports end-to-end latency only, Sec. 5.2;
- * per-stage times are what the roofline accounting of this library needs).  `events` points to
- * four hipEvent_t (passed as void*) created by the caller; from then on every linattn_fwd records
- * events[0] before its first stage and events[1..3] after the state pass, the reduction, and the
- * query pass, on the call's stream.  NULL switches it off (the default).  Process-wide and not
- * thread-safe; the caller keeps the events alive while they are set.  Always returns LINATTN_OK.
- */
-int linattn_set_stage_events(void* const* events);
 
 /* Static description of a status code. */
 const char* linattn_strerror(int status);

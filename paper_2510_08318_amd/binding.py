@@ -32,6 +32,7 @@ class PhiDesc(ctypes.Structure):
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
         ("layout", ctypes.c_int),
         ("blend_in", ctypes.c_void_p), ("blend_r", ctypes.c_void_p), ("blend_dr", ctypes.c_void_p),
+        ("state_bytes", ctypes.c_size_t),
     ]
 
 
@@ -97,10 +98,14 @@ def linattn_workspace_bytes_wgrads(B: int, H: int, n: int, d: int, kind: int = P
 
 def linattn_phi_create(kind, dtype, H, d, wq, wk, dwq=None, dwk=None, state=None,
                        workspace=None, workspace_bytes: int = 0, layout: int = 0,
-                       blend_in=None, blend_r=None, blend_dr=None, *, check: bool = True) -> int:
+                       blend_in=None, blend_r=None, blend_dr=None, state_bytes: Optional[int] = None,
+                       *, check: bool = True) -> int:
+    """state_bytes defaults to the size of `state` when that is a tensor."""
+    if state_bytes is None:
+        state_bytes = 0 if state is None or isinstance(state, int) else state.numel() * state.element_size()
     desc = PhiDesc(int(kind), int(dtype), int(H), int(d), _ptr(wq), _ptr(wk), _ptr(dwq), _ptr(dwk),
                    _ptr(state), _ptr(workspace), int(workspace_bytes), int(layout),
-                   _ptr(blend_in), _ptr(blend_r), _ptr(blend_dr))
+                   _ptr(blend_in), _ptr(blend_r), _ptr(blend_dr), int(state_bytes))
     out = ctypes.c_int(-1)
     st = lib().linattn_phi_create(ctypes.byref(desc), ctypes.byref(out))
     if st != OK:

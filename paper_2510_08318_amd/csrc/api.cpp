@@ -2,6 +2,7 @@
 // Every check happens before the first HIP call, so the error paths run on a machine
 // with no GPU.
 #include "../../include/linattn.h"
+#include "../../include/linattn_bench.h"
 #include "kernels.h"
 
 #include <mutex>
@@ -103,8 +104,20 @@ std::mutex g_mu;
 hipEvent_t g_stage_events[4];
 bool g_stage_events_on = false;
 
-inline void mark(int i, hipStream_t s) {
-  if (g_stage_events_on) (void)hipEventRecord(g_stage_events[i], s);
+// The four events of the call in flight, copied under the lock by the entry point (null = off).
+struct StageEvents {
+  bool on = false;
+  hipEvent_t ev[4];
+  void mark(int i, hipStream_t s) const {
+    if (on) (void)hipEventRecord(ev[i], s);
+  }
+};
+StageEvents stage_events() {
+  std::lock_guard<std::mutex> lk(g_mu);
+  StageEvents r;
+  r.on = g_stage_events_on;
+  for (int i = 0; i < 4; ++i) r.ev[i] = g_stage_events[i];
+  return r;
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -143,6 +156,7 @@ int check_call(const void* const* tensors, int n_tensors, int B, int H, int n, i
     if (!aligned16(tensors[i])) return LINATTN_E_ALIGN;
   const size_t need = (want_wgrads && (desc->dwq || desc->dwk)) ? plan->total_bytes : plan->bytes_no_wgrads;
   if (!desc->workspace || desc->workspace_bytes < need) return LINATTN_E_WORKSPACE;
+  if (desc->state && (size_t)plan->BH * plan->state_elems * sizeof(float) > desc->state_bytes) return LINATTN_E_STATE;
   return LINATTN_OK;
 }
 
@@ -163,13 +177,14 @@ const char* linattn_strerror(int status) {
     case LINATTN_E_PHI: return "unknown phi_id, unsupported feature-map kind, or descriptor table full";
     case LINATTN_E_WORKSPACE: return "workspace missing or smaller than linattn_workspace_bytes()";
     case LINATTN_E_HIP: return "a HIP launch failed";
-    case LINATTN_E_STATE: return "linattn_bwd needs the descriptor's state buffer";
+    case LINATTN_E_STATE: return "linattn_bwd needs the descriptor's state buffer, or the state buffer is too small for this batch size";
     case LINATTN_E_ALIAS: return "an output aliases an input";
     default: return "unknown status";
   }
 }
 
 int linattn_set_stage_events(void* const* events) {
+  std::lock_guard<std::mutex> lk(g_mu);
   g_stage_events_on = events != nullptr;
   if (events)
     for (int i = 0; i < 4; ++i) g_stage_events[i] = static_cast<hipEvent_t>(events[i]);
@@ -207,6 +222,7 @@ int linattn_phi_create(const linattn_phi_desc* desc, int* phi_id_out) {
     if (desc->dwk && !aligned16(desc->dwk)) return LINATTN_E_ALIGN;
   }
   if (desc->state && !aligned16(desc->state)) return LINATTN_E_ALIGN;
+  if (desc->state && desc->state_bytes < (size_t)desc->H * (desc->d + 1) * desc->d * sizeof(float)) return LINATTN_E_STATE;
   if (desc->workspace && (reinterpret_cast<uintptr_t>(desc->workspace) & 255u)) return LINATTN_E_ALIGN;
   if (int st = check_blend(desc->blend_in, desc->blend_r, desc->blend_dr)) return st;
   std::lock_guard<std::mutex> lk(g_mu);
@@ -258,6 +274,8 @@ int linattn_fwd(const void* q, const void* k, const void* v, void* out,
   float* partials = reinterpret_cast<float*>(ws + plan.off_partials);
   float* state = desc.state ? static_cast<float*>(desc.state) : reinterpret_cast<float*>(ws + plan.off_state);
   hipError_t e;
+  const StageEvents ev = stage_events();
+  auto mark = [&](int i, hipStream_t st) { ev.mark(i, st); };
   mark(0, s);
   if (desc.dtype == LINATTN_F32) {
     e = launch_state_partials_f32((const float*)k, (const float*)v, (const float*)desc.wk, partials, plan, s);

@@ -15,10 +15,12 @@
 // Precision: every 16-bit MFMA operand except the stored bf16 q, k (projection) is fp16.
 // Operands that belong to one token only (dO_i for g_i, du_i for dx_i) are scaled by a per-token
 // power of two taken from their largest magnitude, so any gradient scale is safe.  Operands of
-// the sums over tokens (dO_i/den_i, delta_i/den_i) are scaled by one power of two per workgroup,
-// taken from its first tile so that the tile's largest magnitude lands in [16, 32); later tiles
-// may exceed that by 2^11 before fp16 overflows, and values down to 2^-18 of it keep full
-// precision.  Accumulation is fp32 everywhere; partial sums are combined in a fixed order.
+// the sums over tokens (dO_i/den_i, delta_i/den_i, du for dW~) are scaled by one power of two per
+// workgroup that follows the running maximum over its tiles (largest magnitude so far in [16, 32));
+// when a tile raises the maximum the fp32 accumulators are rescaled by the exact ratio, so neither a
+// late large tile nor leading all-zero tiles can overflow or flush fp16; within a tile values down
+// to 2^-18 of the running maximum keep full precision.  Accumulation is fp32 everywhere; partial
+// sums are combined in a fixed order.
 #include "kernels.h"
 #include "mfma_common.h"
 
@@ -263,7 +265,7 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
     }
   const int prow = 32 * w + (lane % 32);
   const int psw = swz<D>(prow);
-  float gamma = 1.f;
+  float gamma = kGammaUnset;
 
   // the lane's q rows of a tile are requested for the next tile as soon as the projection has
   // consumed this tile's copy (never behind a branch: after the last tile it is simply read again);
@@ -343,15 +345,27 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
 
     // operands of the sums over tokens, parked now so that phi and dO need not stay in registers
     // through the rest of the block
-    if (tile == p) {
-      float m = valid ? dmax * inv_den * om : 0.f;
-      for (int k = 32; k >= 1; k >>= 1) m = fmaxf(m, __shfl_xor(m, k, 64));
+    {
+      // the tile's largest operand of the two sums, |dO_i| / den_i or |delta_i| / den_i
+      float m = valid ? fmaxf(dmax, fabsf(delta)) * inv_den * om : 0.f;
+      m = wave_max_paired(m);
       if (lane == 0) sRed[w] = m;
-      __syncthreads();
-      m = fmaxf(fmaxf(sRed[0], sRed[1]), fmaxf(sRed[2], sRed[3]));
-      gamma = 16.f * pow2_normaliser(m);
     }
     __syncthreads();                             // previous tile's operand reads are done
+    {
+      const float m = fmaxf(fmaxf(sRed[0], sRed[1]), fmaxf(sRed[2], sRed[3]));
+      const float ratio = gamma_step(gamma, gamma_for(m));
+      if (ratio != 1.f) {                        // this tile is larger than every earlier one
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          zacc[r] *= ratio;
+#pragma unroll
+          for (int i = 0; i < WMN; ++i)
+#pragma unroll
+            for (int j = 0; j < WMN; ++j) s[i][j][r] *= ratio;
+        }
+      }
+    }
     {
       char* rowp = sPhi + prow * RS;
       constexpr int CPH = C::LOC / 8;
@@ -655,7 +669,7 @@ __global__ __launch_bounds__(NT) void dw_mfma_kernel(DwSides sides, int H, int n
   for (int i = 0; i < RB; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j) offA[i][j] = tr_offset_g4<D>(32 * (active ? row0 + i : 0), lane, j);
-  float gamma = 1.f;
+  float gamma = kGammaUnset;
   uint4 xr[XPT], ur[2 * BPT];
   float its[BPT];
   // the next tile's rows are requested while the current one is contracted
@@ -679,11 +693,18 @@ __global__ __launch_bounds__(NT) void dw_mfma_kernel(DwSides sides, int H, int n
   };
   if (p < ntile) load_tile(p);
   for (int tile = p; tile < ntile; tile += P) {
-    if (tile == p) {
+    {
+      // the tile's largest block scale (a power of two, the same in every thread)
       float m = 0.f;
 #pragma unroll
       for (int i = 0; i < BPT; ++i) m = fmaxf(m, its[i]);
-      gamma = m > 0.f ? 16.f * __builtin_amdgcn_rcpf(m) : 1.f;      // m is a power of two
+      const float ratio = gamma_step(gamma, gamma_for(m));
+      if (ratio != 1.f) {
+#pragma unroll
+        for (int j = 0; j < RB; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[j][r] *= ratio;
+      }
     }
     __syncthreads();                              // previous tile's operand reads are done
 #pragma unroll
@@ -736,11 +757,6 @@ constexpr size_t k_smem() {
   return sizeof(uint4) * (Cfg<D>::W_IMG + ApplyLayout<D>::KS * ApplyLayout<D>::MBZ * 64 + GradLayout<D>::IMG
                           + (Cfg<D>::LOC / 8) * ApplyLayout<D>::MB * 64) + (D + 8) * sizeof(float);
 }
-template <typename K>
-hipError_t set_smem(K kernel, size_t bytes) {
-  return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-}
-
 template <int D>
 hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   hipError_t e;
@@ -750,13 +766,13 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   uint4* duk = reinterpret_cast<uint4*>(a.du_k);
   float* duq_its = reinterpret_cast<float*>(reinterpret_cast<char*>(a.du_q) + du_img_bytes);
   float* duk_its = reinterpret_cast<float*>(reinterpret_cast<char*>(a.du_k) + du_img_bytes);
-  if ((e = set_smem(bwd_prep_kernel<D, true>, prep_smem_bytes<D>())) != hipSuccess) return e;
-  if ((e = set_smem(bwd_prep_kernel<D, false>, prep_smem_bytes<D>())) != hipSuccess) return e;
+  if ((e = set_smem_once<bwd_prep_kernel<D, true>>(prep_smem_bytes<D>())) != hipSuccess) return e;
+  if ((e = set_smem_once<bwd_prep_kernel<D, false>>(prep_smem_bytes<D>())) != hipSuccess) return e;
   bwd_prep_kernel<D, true><<<dim3(p.BH, PREP_Y), PT, prep_smem_bytes<D>(), s>>>(a.state, (uint4*)a.gimg, (uint4*)a.simg, a.scales,
                                                        (const uint16_t*)a.wq, (const uint16_t*)a.wk, (uint4*)a.wimg, p.H);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (a.blend_in) {
-    if ((e = set_smem(bwd_q_kernel<D, true>, q_smem<D>())) != hipSuccess) return e;
+    if ((e = set_smem_once<bwd_q_kernel<D, true>>(q_smem<D>())) != hipSuccess) return e;
     bwd_q_kernel<D, true><<<dim3(p.P, p.BH), NT, q_smem<D>(), s>>>(
         (const uint16_t*)a.q, (const uint16_t*)a.dout, (const uint16_t*)a.wq, a.state, (const uint4*)a.gimg,
         (const uint4*)a.simg, (const uint4*)a.wimg, a.scales,
@@ -768,7 +784,7 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
       if ((e = launch_dr_reduce(a.dr_part, p.BH * p.P + kDotParts, a.blend_r, a.blend_dr, s)) != hipSuccess) return e;
     }
   } else {
-    if ((e = set_smem(bwd_q_kernel<D, false>, q_smem<D>())) != hipSuccess) return e;
+    if ((e = set_smem_once<bwd_q_kernel<D, false>>(q_smem<D>())) != hipSuccess) return e;
     bwd_q_kernel<D, false><<<dim3(p.P, p.BH), NT, q_smem<D>(), s>>>(
         (const uint16_t*)a.q, (const uint16_t*)a.dout, (const uint16_t*)a.wq, a.state, (const uint4*)a.gimg,
         (const uint4*)a.simg, (const uint4*)a.wimg, a.scales,
@@ -780,7 +796,7 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   bwd_prep_kernel<D, false><<<dim3(p.BH, PREP_Y), PT, prep_smem_bytes<D>(), s>>>(a.dstate, (uint4*)a.dgimg, (uint4*)a.dsimg, a.scales + 1,
                                                         nullptr, nullptr, nullptr, p.H);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  if ((e = set_smem(bwd_k_kernel<D>, k_smem<D>())) != hipSuccess) return e;
+  if ((e = set_smem_once<bwd_k_kernel<D>>(k_smem<D>())) != hipSuccess) return e;
   bwd_k_kernel<D><<<dim3(p.KP, p.BH), NTK, k_smem<D>(), s>>>(
       (const uint16_t*)a.k, (const uint16_t*)a.v, (const uint16_t*)a.wk, a.dstate,
       (const uint4*)a.dsimg, (const uint4*)a.dgimg, (const uint4*)a.wimg, a.scales,

@@ -286,7 +286,7 @@ template <int D, int KIND>
 hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   hipError_t e;
   const dim3 grid(p.P, p.BH);
-  if ((e = hipFuncSetAttribute((const void*)bwd_q_f32_kernel<D, KIND>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)q_smem<D>())) != hipSuccess) return e;
+  if ((e = set_smem_once<bwd_q_f32_kernel<D, KIND>>(q_smem<D>())) != hipSuccess) return e;
   bwd_q_f32_kernel<D, KIND><<<grid, NT, q_smem<D>(), s>>>((const float*)a.q, (const float*)a.dout, (const float*)a.wq, a.state,
                                                     (float*)a.dq, a.partials, a.dwq ? a.du_q : nullptr,
                                                     (const float*)a.blend_in, a.blend_r, a.dr_part, p.H, p.n, p.P, p.chunk, p.rows);
@@ -294,7 +294,7 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   if (a.blend_in && a.blend_dr && (e = launch_dr_reduce(a.dr_part, p.BH * p.P, a.blend_r, a.blend_dr, s)) != hipSuccess) return e;
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if ((e = launch_state_reduce(a.partials, a.dstate, p, s)) != hipSuccess) return e;
-  if ((e = hipFuncSetAttribute((const void*)bwd_k_f32_kernel<D, KIND>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)k_smem<D>())) != hipSuccess) return e;
+  if ((e = set_smem_once<bwd_k_f32_kernel<D, KIND>>(k_smem<D>())) != hipSuccess) return e;
   bwd_k_f32_kernel<D, KIND><<<grid, NT, k_smem<D>(), s>>>((const float*)a.k, (const float*)a.v, (const float*)a.wk, a.dstate,
                                                     (float*)a.dk, (float*)a.dv, a.dwk ? a.du_k : nullptr, p.H, p.n, p.chunk, p.rows);
   if ((e = hipGetLastError()) != hipSuccess) return e;

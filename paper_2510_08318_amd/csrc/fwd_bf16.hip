@@ -473,11 +473,6 @@ constexpr size_t apply_smem() {
        + (size_t)(D + 1) * D * sizeof(float) + (size_t)D * (D / 2) * 2 + 64 * sizeof(float);
 }
 
-template <typename K>
-hipError_t set_smem(K kernel, size_t bytes) {
-  return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-}
-
 }  // namespace
 
 hipError_t launch_state_partials_bf16(const void* k, const void* v, const void* wk, float* partials,
@@ -485,11 +480,11 @@ hipError_t launch_state_partials_bf16(const void* k, const void* v, const void* 
   dim3 grid(p.split.G), block(NT1);
   hipError_t e;
   if (p.d == 128) {
-    if ((e = set_smem(state_partials_ws_kernel<128>, state_ws_smem<128>())) != hipSuccess) return e;
+    if ((e = set_smem_once<state_partials_ws_kernel<128>>(state_ws_smem<128>())) != hipSuccess) return e;
     state_partials_ws_kernel<128><<<grid, block, state_ws_smem<128>(), s>>>(
         (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)wk, partials, p.H, p.n, p.split, p.rows);
   } else {
-    if ((e = set_smem(state_partials_ws_kernel<64>, state_ws_smem<64>())) != hipSuccess) return e;
+    if ((e = set_smem_once<state_partials_ws_kernel<64>>(state_ws_smem<64>())) != hipSuccess) return e;
     state_partials_ws_kernel<64><<<grid, block, state_ws_smem<64>(), s>>>(
         (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)wk, partials, p.H, p.n, p.split, p.rows);
   }
@@ -502,7 +497,7 @@ template <int D, bool BLEND, int KIND>
 hipError_t run_apply(const void* q, const void* wq, const float* state, void* out, const void* blend_in,
                      const float* blend_r, const Plan& p, hipStream_t s) {
   hipError_t e;
-  if ((e = set_smem(apply_bf16_kernel<D, BLEND, KIND>, apply_smem<D>())) != hipSuccess) return e;
+  if ((e = set_smem_once<apply_bf16_kernel<D, BLEND, KIND>>(apply_smem<D>())) != hipSuccess) return e;
   apply_bf16_kernel<D, BLEND, KIND><<<dim3(p.QP, p.BH), NT3, apply_smem<D>(), s>>>(
       (const uint16_t*)q, (const uint16_t*)wq, state, (uint16_t*)out, (const uint16_t*)blend_in, blend_r, p.H, p.n, p.rows);
   return hipGetLastError();

@@ -141,7 +141,7 @@ constexpr size_t apply_smem() { return sizeof(float) * (D * (D / 2) + (D + 1) * 
 
 template <int D, int KIND>
 hipError_t run_state(const float* k, const float* v, const float* wk, float* partials, const Plan& p, hipStream_t s) {
-  hipError_t e = hipFuncSetAttribute((const void*)state_partials_f32_kernel<D, KIND>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)state_smem<D>());
+  hipError_t e = set_smem_once<state_partials_f32_kernel<D, KIND>>(state_smem<D>());
   if (e != hipSuccess) return e;
   state_partials_f32_kernel<D, KIND><<<dim3(p.P, p.BH), NT, state_smem<D>(), s>>>(k, v, wk, partials, p.H, p.n, p.P, p.chunk, p.rows);
   return hipGetLastError();
@@ -149,7 +149,7 @@ hipError_t run_state(const float* k, const float* v, const float* wk, float* par
 template <int D, int KIND>
 hipError_t run_apply(const float* q, const float* wq, const float* state, float* out,
                      const float* blend_in, const float* blend_r, const Plan& p, hipStream_t s) {
-  hipError_t e = hipFuncSetAttribute((const void*)apply_f32_kernel<D, KIND>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)apply_smem<D>());
+  hipError_t e = set_smem_once<apply_f32_kernel<D, KIND>>(apply_smem<D>());
   if (e != hipSuccess) return e;
   apply_f32_kernel<D, KIND><<<dim3(p.QP, p.BH), NT, apply_smem<D>(), s>>>(q, wq, state, out, blend_in, blend_r, p.H, p.n, p.qchunk, p.rows);
   return hipGetLastError();

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <atomic>
 
 namespace linattn {
 
@@ -108,6 +109,19 @@ struct BwdArgs {
   float* blend_dr;
   float* dr_part;
 };
+
+// Raises a kernel's dynamic-LDS limit to `bytes`, once per kernel instantiation and device: the
+// attribute call is a driver call, and the launchers sit on the enqueue path of every step.
+template <auto Kernel>
+hipError_t set_smem_once(size_t bytes) {
+  static std::atomic<uint64_t> done{0};
+  int dev = -1;
+  const bool tracked = hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64;
+  if (tracked && (done.load(std::memory_order_acquire) >> dev & 1)) return hipSuccess;
+  const hipError_t e = hipFuncSetAttribute((const void*)Kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess && tracked) done.fetch_or(uint64_t(1) << dev, std::memory_order_release);
+  return e;
+}
 
 // ---- forward launchers (enqueue only) ---------------------------------------------------
 // phi(K) fused with the split-n partial state (Eq. 5 + the two sums of Eq. 3).

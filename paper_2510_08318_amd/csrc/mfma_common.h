@@ -405,6 +405,24 @@ __device__ __forceinline__ float pow2_normaliser(float m) {
   return (m > 0.f && m < 3.0e38f) ? ldexpf(1.0f, -ilogbf(m)) : 1.0f;
 }
 
+// Running power-of-two scale of a workgroup's sums over tokens (fp16 MFMA operands, fp32
+// accumulators).  A tile whose largest operand magnitude is m wants the scale gamma_for(m), which
+// puts m into [16, 32).  The workgroup keeps the smallest scale any of its tiles has asked for and,
+// when a tile lowers it, multiplies its accumulators by the exact ratio (gamma_step), so a tile far
+// larger than every earlier one cannot overflow fp16, and tiles that are all zero (kGammaUnset) leave
+// the choice to the first tile that is not.
+constexpr float kGammaUnset = 0x1p60f;
+__device__ __forceinline__ float gamma_for(float m) {
+  return m >= 0x1p-56f && m < 3.0e38f ? 16.f * pow2_normaliser(m) : kGammaUnset;
+}
+// Returns the factor (a power of two <= 1) the accumulators must be multiplied by; updates gamma.
+__device__ __forceinline__ float gamma_step(float& gamma, float wanted) {
+  const float next = fminf(gamma, wanted);
+  const float ratio = next * __builtin_amdgcn_rcpf(gamma);      // exact: both are powers of two
+  gamma = next;
+  return ratio;
+}
+
 __device__ __forceinline__ void unpack_bf16x8(uint4 v, float* f) {
   f[0] = __builtin_bit_cast(float, v.x << 16); f[1] = __builtin_bit_cast(float, v.x & 0xffff0000u);
   f[2] = __builtin_bit_cast(float, v.y << 16); f[3] = __builtin_bit_cast(float, v.y & 0xffff0000u);

@@ -320,7 +320,7 @@ __global__ __launch_bounds__(NT) void relu_bwd_q_kernel(const uint16_t* __restri
   const int prow = 32 * w + (lane % 32);
   const int psw = swz<D>(prow);
   float* myRow = sRow + w * 64;
-  float gamma = 1.f;
+  float gamma = kGammaUnset;
 
   for (int tile = p; tile < ntile; tile += P) {
     const int t0 = tile * kTile + 32 * w;
@@ -429,15 +429,27 @@ __global__ __launch_bounds__(NT) void relu_bwd_q_kernel(const uint16_t* __restri
     }
 
     // operands of the sums over tokens
-    if (tile == p) {
-      float m = live ? dmax * inv_den : 0.f;
-      for (int k2 = 32; k2 >= 1; k2 >>= 1) m = fmaxf(m, __shfl_xor(m, k2, 64));
+    {
+      float m = live ? fmaxf(dmax, fabsf(delta_t)) * inv_den : 0.f;
+      m = wave_max_paired(m);
       if (lane == 0) sRed[w] = m;
-      __syncthreads();
-      m = fmaxf(fmaxf(sRed[0], sRed[1]), fmaxf(sRed[2], sRed[3]));
-      gamma = 16.f * pow2_normaliser(m);
     }
     __syncthreads();                             // previous tile's operand reads are done
+    {
+      // running power-of-two scale of the two sums over tokens (see gamma_for)
+      const float m = fmaxf(fmaxf(sRed[0], sRed[1]), fmaxf(sRed[2], sRed[3]));
+      const float ratio = gamma_step(gamma, gamma_for(m));
+      if (ratio != 1.f) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          zacc[r] *= ratio;
+#pragma unroll
+          for (int i = 0; i < WMN; ++i)
+#pragma unroll
+            for (int j = 0; j < WMN; ++j) s[i][j][r] *= ratio;
+        }
+      }
+    }
     {
       char* rowp = sPhi + prow * RS;
       char* drowp = sDO + prow * RS;
@@ -573,10 +585,6 @@ __global__ __launch_bounds__(NTK) void relu_bwd_k_kernel(const uint16_t* __restr
   }
 }
 
-template <typename K>
-hipError_t set_smem(K kernel, size_t bytes) {
-  return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-}
 template <int D>
 constexpr size_t state_smem() { return 2 * (size_t)kTile * D * 2; }
 template <int D>
@@ -594,7 +602,7 @@ constexpr size_t k_smem() {
 template <int D>
 hipError_t run_state(const void* k, const void* v, float* partials, const Plan& p, hipStream_t s) {
   hipError_t e;
-  if ((e = set_smem(relu_state_kernel<D>, state_smem<D>())) != hipSuccess) return e;
+  if ((e = set_smem_once<relu_state_kernel<D>>(state_smem<D>())) != hipSuccess) return e;
   relu_state_kernel<D><<<dim3(p.split.G), NT, state_smem<D>(), s>>>((const uint16_t*)k, (const uint16_t*)v, partials,
                                                                    p.H, p.n, p.split, p.rows);
   return hipGetLastError();
@@ -603,10 +611,10 @@ hipError_t run_state(const void* k, const void* v, float* partials, const Plan& 
 template <int D>
 hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   hipError_t e;
-  if ((e = set_smem(relu_prep_kernel<D>, prep_smem<D>())) != hipSuccess) return e;
+  if ((e = set_smem_once<relu_prep_kernel<D>>(prep_smem<D>())) != hipSuccess) return e;
   relu_prep_kernel<D><<<dim3(p.BH, 8), PT, prep_smem<D>(), s>>>(a.state, (uint4*)a.simg, (uint4*)a.gimg, a.scales);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  if ((e = set_smem(relu_bwd_q_kernel<D>, q_smem<D>())) != hipSuccess) return e;
+  if ((e = set_smem_once<relu_bwd_q_kernel<D>>(q_smem<D>())) != hipSuccess) return e;
   relu_bwd_q_kernel<D><<<dim3(p.P, p.BH), NT, q_smem<D>(), s>>>(
       (const uint16_t*)a.q, (const uint16_t*)a.dout, a.state, (const uint4*)a.simg, (const uint4*)a.gimg, a.scales,
       (uint16_t*)a.dq, a.partials, p.H, p.n, p.P, p.rows);
@@ -614,7 +622,7 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   if ((e = launch_state_reduce(a.partials, a.dstate, p, s)) != hipSuccess) return e;
   relu_prep_kernel<D><<<dim3(p.BH, 8), PT, prep_smem<D>(), s>>>(a.dstate, (uint4*)a.dsimg, (uint4*)a.dgimg, a.scales + 1);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  if ((e = set_smem(relu_bwd_k_kernel<D>, k_smem<D>())) != hipSuccess) return e;
+  if ((e = set_smem_once<relu_bwd_k_kernel<D>>(k_smem<D>())) != hipSuccess) return e;
   relu_bwd_k_kernel<D><<<dim3(p.KP, p.BH), NTK, k_smem<D>(), s>>>(
       (const uint16_t*)a.k, (const uint16_t*)a.v, a.dstate, (const uint4*)a.dsimg, (const uint4*)a.dgimg, a.scales + 1,
       (uint16_t*)a.dk, (uint16_t*)a.dv, p.H, p.n, p.rows);

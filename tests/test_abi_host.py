@@ -15,8 +15,12 @@ P = 0x10000000
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "linattn.h")).read()
-    declared = set(re.findall(r"\b(linattn_[a-z_]+)\s*\(", header))
+    inc = os.path.join(ROOT, "include")
+    headers = sorted(f for f in os.listdir(inc) if f.endswith(".h"))
+    assert headers == ["linattn.h", "linattn_bench.h"]
+    declared = set()
+    for f in headers:
+        declared |= set(re.findall(r"\b(linattn_[a-z_]+)\s*\(", open(os.path.join(inc, f)).read()))
     assert declared == set(L.EXPORTS)
     lib = L.lib()
     for name in declared:
@@ -61,7 +65,12 @@ def test_phi_create_rejects_bad_descriptors():
     assert mk(wq=None) == L.E_NULL
     assert mk(wk=None) == L.E_NULL
     assert mk(wq=P + 2) == L.E_ALIGN
-    assert mk(state=P + 8) == L.E_ALIGN
+    assert mk(state=P + 8, state_bytes=1 << 20) == L.E_ALIGN
+    one = 2 * 65 * 64 * 4                                           # H * (d+1) * d fp32: the state of one batch item
+    assert mk(state=P + 4096) == L.E_STATE                          # a state buffer of unknown size
+    assert mk(state=P + 4096, state_bytes=one - 4) == L.E_STATE
+    pid = mk(state=P + 4096, state_bytes=one)
+    assert pid >= 16 and L.linattn_phi_destroy(pid) == L.OK
     assert mk(workspace=P + 128, workspace_bytes=1 << 20) == L.E_ALIGN
     out = ctypes.c_int(0)
     assert L.lib().linattn_phi_create(None, ctypes.byref(out)) == L.E_NULL
@@ -104,6 +113,16 @@ def test_fwd_rejects_bad_calls_before_touching_the_gpu():
         assert f(q, k, v, o, B, H, n, d, pid2) == L.E_WORKSPACE
     finally:
         L.linattn_phi_destroy(pid2)
+    # a state buffer sized for B = 1 serves B = 1 but refuses B = 2 (forward and backward alike)
+    ws2 = L.linattn_workspace_bytes(2, H, n, d, L.PHI_HEDGEHOG, L.BF16)
+    pid3 = L.linattn_phi_create(L.PHI_HEDGEHOG, L.BF16, H, d, P, P + 8192, state=P + 16384, state_bytes=H * (d + 1) * d * 4,
+                                workspace=P + (1 << 20), workspace_bytes=ws2)
+    try:
+        assert f(q, k, v, o, 2, H, n, d, pid3) == L.E_STATE
+        t = [P + (i + 2) * big for i in range(7)]
+        assert L.linattn_bwd(*t, 2, H, n, d, pid3, check=False) == L.E_STATE
+    finally:
+        L.linattn_phi_destroy(pid3)
 
 
 def test_bwd_rejects_bad_calls():

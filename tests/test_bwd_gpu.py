@@ -197,24 +197,3 @@ def test_backward_closed_forms_on_device():
     dq0, dk0, _ = _gpu_fwd_bwd(c, want_wgrads=False)
     assert np.abs(dq0).max() <= 2e-2 * np.abs(dq).max()
     assert np.abs(dk0).max() <= 2e-2 * np.abs(dk).max()
-
-
-def test_config5_post_training_step_full_size():
-    """Config 5 at full size (B=1, H=12, n=32760, d=128), forward then backward in the launch
-    configuration the library uses; three heads are compared in full with the oracle."""
-    import torch
-    from paper_2510_08318_amd import torch_glue as G
-    x = synth.generate("C5")
-    q, k, v, wq, wk, do = [G.to_device(t) for t in (x.q, x.k, x.v, x.wq, x.wk, x.dout)]
-    lay = G.Layer(wq, wk, x.B, x.n, want_wgrads=True)
-    lay.forward(q, k, v)
-    dq, dk, dv = lay.backward(q, k, v, do)
-    torch.cuda.synchronize()
-    for t in (dq, dk, dv):
-        assert torch.isfinite(t.float()).all()
-    for h in (0, 6, 11):
-        ref = O.bwd(*[O.to_f64(t) for t in (x.q[0, h], x.k[0, h], x.v[0, h], x.wq[h], x.wk[h], x.dout[0, h])])
-        got = [G.to_host_f64(t[0, h]) for t in (dq, dk, dv)] + [G.to_host_f64(lay.dwq[h]), G.to_host_f64(lay.dwk[h])]
-        errs = [O.err_metric(g, r)[0] for g, r in zip(got, ref)]
-        assert max(errs[:3]) <= TOL["bf16"] and max(errs[3:]) <= WTOL["bf16"], (h, errs)
-    lay.close()

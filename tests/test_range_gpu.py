@@ -66,3 +66,73 @@ def test_relu_map_rescaled_inputs_stay_within_tolerance(scales):
     errs = {name: O.err_metric(g, r)[0] for name, g, r in zip(["out", "dq", "dk", "dv"], got, ref)}
     assert all(np.isfinite(g).all() for g in got)
     assert max(errs.values()) <= 1e-2, errs
+
+
+# ---- operands of the sums over tokens: one power-of-two scale per workgroup that follows the running maximum
+
+def _stepped(d, H=16, n=6161, **steps):
+    """Config-5 recipe with B*H = 16, so that the backward's token sums run in 16 workgroups per head, each
+    striding over the head's 128-token tiles: tokens below `edge` = 16 * 128 are every workgroup's first tile."""
+    x = synth.generate("C5", n=n, H=H, d=d)
+    edge = 16 * 128
+    for name, (lo_mul, hi_mul) in steps.items():
+        a = O.to_f64(getattr(x, name))
+        a[:, :, :edge] *= lo_mul
+        a[:, :, edge:] *= hi_mul
+        setattr(x, name, synth._pack(a.astype(np.float32), x.dtype))
+    return x
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("steps", [
+    dict(dout=(0.0, 1e-6)),            # every workgroup starts on all-zero gradients, tiny ones follow
+    dict(dout=(0.0, 1.0)),
+    dict(dout=(1.0, 2.0 ** 13)),       # the gradient steps up by 2^13 after the first tile
+    dict(dout=(2.0 ** -14, 2.0 ** 4)),
+    dict(dout=(2.0 ** 13, 1.0)),       # and down
+    dict(q=(1.0, 2.0 ** 12)), dict(k=(1.0, 2.0 ** 12)), dict(v=(1.0, 2.0 ** 12)),
+    dict(q=(2.0 ** -6, 64.0), k=(64.0, 2.0 ** -6)),
+], ids=lambda s: ",".join(f"{k}={v[0]:g}->{v[1]:g}" for k, v in s.items()))
+def test_magnitude_steps_between_tiles_of_a_workgroup(d, steps):
+    x = _stepped(d, **steps)
+    if "dout" not in steps:
+        errs = _errors(x)
+    else:
+        # dq_i is proportional to dO_i, so with a stepped dO the two token ranges hold gradients of different
+        # magnitude: each range is measured against its own RMS floor (one floor for both would only see the
+        # larger range).  Tokens without an upstream gradient have dq = 0 exactly.
+        edge = 16 * 128
+        got = _gpu_fwd_bwd(x)
+        ref = O.bwd_bh(x.q, x.k, x.v, x.wq, x.wk, x.dout)
+        errs = {"dq hi": O.err_metric(got[0][:, :, edge:], ref[0][:, :, edge:])[0]}
+        if steps["dout"][0] == 0.0:
+            assert not got[0][:, :, :edge].any() and not ref[0][:, :, :edge].any()
+        else:
+            errs["dq lo"] = O.err_metric(got[0][:, :, :edge], ref[0][:, :, :edge])[0]
+        for name, g, r in list(zip(NAMES, got, ref))[1:]:
+            assert np.isfinite(g).all(), name
+            errs[name] = O.err_metric(g, r)[0]
+    assert max(errs.values()) <= 1e-2, errs
+
+
+def test_relu_map_magnitude_steps_between_tiles():
+    from oracle import relu_oracle as R
+    from tests.test_relu_gpu import _run
+    for steps in (dict(dout=(0.0, 1e-6)), dict(dout=(1.0, 2.0 ** 13)), dict(q=(1.0, 2.0 ** 12)), dict(v=(1.0, 2.0 ** 12))):
+        x = _stepped(128, **steps)
+        got, _ = _run(x)
+        ref = [R.relu_fwd_bh(x.q, x.k, x.v)] + list(R.relu_bwd_bh(x.q, x.k, x.v, x.dout))
+        errs = {name: O.err_metric(g, r)[0] for name, g, r in zip(["out", "dq", "dk", "dv"], got, ref)}
+        assert max(errs.values()) <= 1e-2, (steps, errs)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_values_up_to_the_documented_limit(d):
+    """bf16 mode widens v to fp16 on its way into the matrix cores: the documented domain is |v| < 65504.
+    Values right below that limit (largest |v| = 6.1e4) keep the 1e-2 contract, forward and backward."""
+    x = synth.generate("C5", n=700, H=2, d=d)
+    v = O.to_f64(x.v)
+    x.v = synth._pack((v * (6.1e4 / np.abs(v).max())).astype(np.float32), x.dtype)
+    assert 6.0e4 < np.abs(O.to_f64(x.v)).max() < 65504
+    errs = _errors(x)
+    assert max(errs.values()) <= 1e-2, errs
