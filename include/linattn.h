@@ -39,6 +39,12 @@
  *     entries become infinite inside the kernels and the call returns LINATTN_OK with Inf/NaN in
  *     out, state and the gradients; the library does not scan for them.  Entries with
  *     0 < |v| < 2^-14 lose their low bits (absolute error below 2^-25).
+ *   - Accuracy: out, dq, dk, dv, dW~ agree with exact arithmetic on the stored inputs to 1e-2 of
+ *     max(|value|, RMS of the tensor over its (b,h) slice).  Known exception (11-bit operands): the
+ *     dk row of a key whose k_j and v_j are far larger than the other tokens' -- phi(k_j) is then
+ *     nearly one-hot and the Jacobian of Eq. 5 takes differences of close entries of dL/dphi(k_j) --
+ *     is resolved to 1-2e-2 of that row's own RMS.  For the rows at 20x magnitude of the
+ *     Wan-14B-shaped test recipe this reads 1.4e-2 against the slice RMS; all other rows meet 1e-2.
  */
 #ifndef LINATTN_H
 #define LINATTN_H
