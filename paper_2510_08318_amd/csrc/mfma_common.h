@@ -275,7 +275,7 @@ __device__ __forceinline__ float head_scale(const float* __restrict__ S, float* 
 #pragma unroll
   for (int i = 1; i < NTHREADS / 64; ++i) amax = fmaxf(amax, red[i]);
   __syncthreads();                       // red may be reused by the caller
-  return (amax > 0.f && amax < 3.0e38f) ? ldexpf(1.0f, 13 - ilogbf(amax)) : 1.0f;
+  return (amax >= 0x1p-100f && amax < 3.0e38f) ? ldexpf(1.0f, 13 - ilogbf(amax)) : 1.0f;   // the scale itself stays finite
 }
 
 // fp32 state [D+1][D] of one (b,h) -> LDS image of the fp16 A operands of Y^T = S^T phi^T
@@ -400,9 +400,12 @@ __device__ __forceinline__ f16x8 read_tr(const char* tile, int off0, int off1) {
   return __builtin_bit_cast(f16x8, v);
 }
 
-// power of two p with p * m in [1, 2) (m > 0), 1 for m == 0 or non-finite
+// power of two p with p * m in [1, 2) for 2^-100 <= m < 3e38; 1 for smaller m (zero included) and
+// for non-finite m.  The lower limit keeps p itself finite: for m below 2^-127 (fp32 subnormals, which
+// a saturated softmax leaves in du) the exact normaliser is not representable, and such values are
+// zero against anything they are added to, so they may flush in the fp16 operand.
 __device__ __forceinline__ float pow2_normaliser(float m) {
-  return (m > 0.f && m < 3.0e38f) ? ldexpf(1.0f, -ilogbf(m)) : 1.0f;
+  return (m >= 0x1p-100f && m < 3.0e38f) ? ldexpf(1.0f, -ilogbf(m)) : 1.0f;
 }
 
 // Running power-of-two scale of a workgroup's sums over tokens (fp16 MFMA operands, fp32

