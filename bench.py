@@ -24,6 +24,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published peak
+MFMA_PEAK_TFLOPS = 2500.0      # dense bf16 / fp16 matrix-core peak
+CONFIG_HEADS = {"C2": 12}
+PREWARM_SECONDS = 0.25         # forward calls before --warmup, so that short runs do not time the clock ramp
 # HBM bytes per launch (read + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # command with --calib-copy, scaled by the readings of the 1 GiB copy kernel (FETCH x2 KiB,
 # WRITE x1 KiB); keyed by (workload, stage).  The committed summary with the commands is
@@ -106,8 +109,27 @@ def cpu_baseline(x, budget_s: float = 12.0, relu: bool = False):
             break
     dt = time.perf_counter() - t0
     head_tokens_per_s = done * x.n / dt
-    return {"value": head_tokens_per_s / x.H, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{done} of {x.H} heads of batch item 0, all {x.n} tokens, fp64 numpy, {dt:.1f} s"}
+    res = {"value": head_tokens_per_s / x.H, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+           "sample": f"{done} of {x.H} heads of batch item 0, all {x.n} tokens, fp64 numpy, {dt:.1f} s"}
+    if not relu:
+        res["single_thread"] = cpu_single_thread()
+    return res
+
+
+def cpu_single_thread():
+    """Per-core figure: the oracle on one head of the Wan-1.3B 480p shape (config 2) with one BLAS thread."""
+    from oracle import linattn_oracle as O
+    from paper_2510_08318_amd import synth
+    from threadpoolctl import threadpool_limits
+    y = synth.generate("C2", H=1)
+    args = [O.to_f64(t) for t in (y.q[0, 0], y.k[0, 0], y.v[0, 0], y.wq[0], y.wk[0])]
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        O.fwd(*args)
+        dt = time.perf_counter() - t0
+    heads = CONFIG_HEADS["C2"]
+    return {"value": round(y.n / dt / heads, 1), "unit": "tokens/s", "cores": 1,
+            "sample": f"1 of {heads} heads of config 2 (n={y.n}, d={y.d}), {dt:.2f} s; tokens/s = n / (time x {heads} heads)"}
 
 
 def cpu_baseline_bwd(x, budget_s: float = 12.0, relu: bool = False):
@@ -133,6 +155,43 @@ def cpu_baseline_bwd(x, budget_s: float = 12.0, relu: bool = False):
     dt = time.perf_counter() - t0
     return {"value": done * x.n / dt / x.H, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
             "sample": f"{done} of {x.H} heads of batch item 0, all {x.n} tokens, fp64 numpy backward, {dt:.1f} s"}
+
+
+def check_timed_output(x, sets, calls, lay, relu, args, blend_s):
+    """Sampled rows of the buffer the last timed step wrote, against the oracle (Eq. 3 from the fp64
+    state of the head): four heads, 1024 rows each plus the first and last 64.  Not part of the timing."""
+    import numpy as np
+    import torch
+    from oracle import linattn_oracle as O
+    from paper_2510_08318_amd import torch_glue as G
+    out = sets[(calls - 1) % len(sets)][3]
+    if args.layout == "bnhd":
+        out = out.permute(0, 2, 1, 3)
+    rng = np.random.default_rng(0)
+    heads = sorted(set([(0, 0), (x.B - 1, x.H - 1), (0, x.H // 2), (x.B - 1, x.H // 3)]))
+    worst = 0.0
+    for b, h in heads:
+        rows = np.unique(np.concatenate([rng.choice(x.n, min(1024, x.n), replace=False), np.arange(min(64, x.n)),
+                                         np.arange(max(0, x.n - 64), x.n)])).astype(np.int64)
+        kk, vv, qq = O.to_f64(x.k[b, h]), O.to_f64(x.v[b, h]), O.to_f64(x.q[b, h][rows])
+        if relu:
+            from oracle import relu_oracle as R
+            S, z = R.relu_state(kk, vv)
+            fq = R.phi_relu(qq)
+            ref = (fq @ S) / ((fq @ z) + R.RELU_EPS)[:, None]
+        else:
+            S, z = O.state(kk, vv, O.to_f64(x.wk[h]))
+            fq = O.phi(qq, O.to_f64(x.wq[h]))
+            ref = (fq @ S) / (fq @ z)[:, None]
+        idx = torch.from_numpy(rows).cuda()
+        if blend_s is not None:
+            sb = blend_s.permute(0, 2, 1, 3) if args.layout == "bnhd" else blend_s
+            ref = 0.5 * G.to_host_f64(sb[b, h][idx]) + 0.5 * ref
+        worst = max(worst, O.err_metric(G.to_host_f64(out[b, h][idx]), ref)[0])
+    tol = 1e-2 if x.dtype == "bf16" else 1e-5
+    return {"value": float(f"{worst:.3e}"), "tolerance": tol, "ok": bool(worst <= tol),
+            "sample": f"{len(heads)} heads x ~1150 sampled rows of the last timed step's output vs the fp64 oracle, "
+                      "max |diff| / max(|ref|, rms of the sampled rows of the head)"}
 
 
 def _calib_copy():
@@ -168,6 +227,14 @@ def bench_bwd(args):
     def step():
         lay.backward(q, k, v, dout, dq, dk, dv)
 
+    t0 = time.perf_counter()
+    prewarm_calls = 0
+    while time.perf_counter() - t0 < PREWARM_SECONDS:      # as in the forward benchmark
+        for _ in range(8):
+            step()
+        torch.cuda.synchronize()
+        prewarm_calls += 8
+    prewarm_s = time.perf_counter() - t0
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -193,6 +260,7 @@ def bench_bwd(args):
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": None if (relu or args.blend or args.no_wgrads or args.layout != "bhnd")
                                 else MEASURED_TRAFFIC_BWD.get(args.workload)},
+        "prewarm": {"seconds": round(prewarm_s, 3), "calls": prewarm_calls},
     }
     if args.calib_copy:
         _calib_copy()
@@ -238,14 +306,34 @@ def main():
         q, k, v = [t.permute(0, 2, 1, 3).contiguous() for t in (q, k, v)]
     relu = args.phi == "relu"
     lay = G.ReluLayer(x.H, x.d, x.B, x.n, q.dtype, layout=args.layout) if relu else G.Layer(wq, wk, x.B, x.n, layout=args.layout)
+    blend_s = None
     if args.blend:
-        lay.set_blend((torch.randn(q.shape, device="cuda") * 0.1).to(q.dtype), torch.tensor([0.5], device="cuda"))
+        blend_s = (torch.randn(q.shape, device="cuda") * 0.1).to(q.dtype)
+        lay.set_blend(blend_s, torch.tensor([0.5], device="cuda"))
     out = torch.empty_like(q)
     stream = torch.cuda.current_stream().cuda_stream
+    # A buffer set below the last-level cache scale (256 MB) would be served from cache on the next
+    # step: such workloads rotate over several distinct sets (copies of the same values), so that a
+    # step never re-reads what the previous steps left behind.  Set 0 is the one that is checked.
+    set_bytes = 4 * q.numel() * q.element_size()
+    nsets = 1 if set_bytes >= 1_000_000_000 else min(16, max(3, -(-1_500_000_000 // set_bytes)))
+    sets = [(q, k, v, out)] + [tuple(t.clone() for t in (q, k, v, out)) for _ in range(nsets - 1)]
+    calls = [0]
 
     def step():
-        L.linattn_fwd(q, k, v, out, x.B, x.H, x.n, x.d, lay.phi_id, stream)
+        a, b_, c, o = sets[calls[0] % nsets]
+        calls[0] += 1
+        L.linattn_fwd(a, b_, c, o, x.B, x.H, x.n, x.d, lay.phi_id, stream)
 
+    # pre-warm: a fixed, reported phase of forward calls (clocks ramp over the first ~0.2 s)
+    t0 = time.perf_counter()
+    prewarm_calls = 0
+    while time.perf_counter() - t0 < PREWARM_SECONDS:
+        for _ in range(8):
+            step()
+        torch.cuda.synchronize()
+        prewarm_calls += 8
+    prewarm_s = time.perf_counter() - t0
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -257,7 +345,8 @@ def main():
     ms_per_step = dt / args.steps * 1e3
     tokens_per_s = x.B * x.n / (dt / args.steps)
 
-    # per-stage durations: the same K steps again with HIP events between the stages
+    # per-stage durations: the same K steps again, right away (the clocks are still up), with HIP events
+    # between the stages
     hip = _hip()
     evs = []
     for _ in range(args.steps):
@@ -286,6 +375,9 @@ def main():
     for four in evs:
         for e in four:
             hip.hipEventDestroy(e)
+    # every step writes the same values (the path is deterministic), so the buffer the last call wrote is
+    # what the timed steps wrote
+    max_err = None if args.no_cpu_baseline else check_timed_output(x, sets, calls[0], lay, relu, args, blend_s)
 
     esz = 2 if x.dtype == "bf16" else 4
     head_tokens = x.B * x.H * x.n
@@ -302,6 +394,18 @@ def main():
                 "path_frac": round(sum(stage_bytes) / (sum(stage_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                 # one call = first to last stage event; distribution over the K event-bracketed calls
                 "call_ms_median": round(per_call[len(per_call) // 2], 4), "call_ms_min": round(per_call[0], 4)}
+    if x.dtype == "bf16":
+        # matrix-core use, reported beside the HBM bound: each pass issues 56 v_mfma_f32_32x32x16 (32768 FLOP
+        # each) per 32 head-tokens -- state pass 16 projection + 8 turning + 32 contraction, query pass
+        # 16 + 40; the ReLU map 32 + 8 and 40 -- which SQ_INSTS_MFMA confirms (profiles/fwd_wan14b_720p_pmc.md)
+        blocks = x.B * x.H * -(-x.n // 32)
+        per_block = ([40, 0, 40] if relu else [56, 0, 56]) if x.d == 128 else (None if relu else [16, 0, 16])
+        if per_block:
+            tf = [per_block[i] * blocks * 32768 / (stage_ms[i] * 1e-3) / 1e12 if stage_ms[i] > 0 else 0.0 for i in (0, 2)]
+            roofline["mfma"] = {"state_pass_TFLOPs": round(tf[0], 1), "query_pass_TFLOPs": round(tf[1], 1),
+                                "peak_TFLOPs": MFMA_PEAK_TFLOPS, "state_pass_frac": round(tf[0] / MFMA_PEAK_TFLOPS, 4),
+                                "query_pass_frac": round(tf[1] / MFMA_PEAK_TFLOPS, 4),
+                                "source": "MFMA instructions per 32-token block x blocks x 32768 FLOP / stage duration (HIP events)"}
 
     # the same bytes through plain streaming kernels, measured now (the state pass only reads, the
     # query pass reads and writes the same amount)
@@ -325,6 +429,10 @@ def main():
                                + (", mixed with a softmax-branch input (Eq. 6, r = 0.5)" if args.blend else ""),
                    "head_tokens_per_s": round(tokens_per_s * x.H, 1)},
         "roofline": roofline,
+        "prewarm": {"seconds": round(prewarm_s, 3), "calls": prewarm_calls,
+                    "note": "untimed forward calls before --warmup; steps and warmup echo the arguments"},
+        "buffer_sets": nsets,
+        "max_err": max_err,
     }
     if args.calib_copy:
         _calib_copy()
