@@ -161,6 +161,27 @@ int linattn_fwd(const void* q, const void* k, const void* v, void* out,
                 int B, int H, int n, int d, int phi_id, void* stream);
 
 /*
+ * linattn_fwd for callers that cannot allocate device memory or size a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and bit-identical results, but the split-n partials (and the state, when the descriptor
+ * has no state buffer) live in a static device array of LINATTN_NOALLOC_SCRATCH_BYTES that is part
+ * of the library's code object on each GPU; the descriptor's workspace is ignored and may be NULL.
+ * The call allocates nothing and frees nothing.
+ *   - Limit: the forward scratch of the problem (what linattn_workspace_bytes counts up to the
+ *     state region: partials of at most 256 workgroups plus B*H states) must fit the array;
+ *     E_WORKSPACE otherwise.  All five task configurations fit (config 4 needs 31.7 MB).
+ *   - Every call on one GPU shares that GPU's array: calls that overlap in time on one GPU (two
+ *     streams, two threads) race.  Nothing needs clearing between calls: a call overwrites every
+ *     scratch word before reading it.
+ *   - The first call on a device looks the array's address up (hipGetSymbolAddress); make that
+ *     call outside stream capture.
+ * Errors: as linattn_fwd; E_HIP also if the array's address cannot be found.
+ */
+#define LINATTN_NOALLOC_SCRATCH_BYTES (32u << 20)
+int linattn_fwd_noalloc(const void* q, const void* k, const void* v, void* out,
+                        int B, int H, int n, int d, int phi_id, void* stream);
+
+/*
  * Backward of linattn_fwd for L with dL/dout = dout: writes dq, dk, dv [B,H,n,d] and, if the
  * descriptor has them, dwq and dwk (Eq. 5 only; the ReLU map has no weights).  Needs the state a
  * forward call with the same q-independent inputs (k, v, wk) left in the descriptor's state buffer.

@@ -20,7 +20,7 @@ BF16, F32 = 1, 2
 LAYOUT_BHND, LAYOUT_BNHD = 0, 1
 
 EXPORTS = ("linattn_phi_create", "linattn_phi_destroy", "linattn_workspace_bytes", "linattn_workspace_bytes_wgrads",
-           "linattn_fwd", "linattn_bwd", "linattn_strerror", "linattn_set_stage_events", "linattn_phi_set_blend")
+           "linattn_fwd", "linattn_fwd_noalloc", "linattn_bwd", "linattn_strerror", "linattn_set_stage_events", "linattn_phi_set_blend")
 
 
 class PhiDesc(ctypes.Structure):
@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
         L.linattn_workspace_bytes_wgrads.restype = ctypes.c_size_t
         L.linattn_fwd.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, vp]
         L.linattn_fwd.restype = ci
+        L.linattn_fwd_noalloc.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, vp]
+        L.linattn_fwd_noalloc.restype = ci
         L.linattn_bwd.argtypes = [vp] * 7 + [ci] * 5 + [vp]
         L.linattn_bwd.restype = ci
         L.linattn_set_stage_events.argtypes = [ctypes.POINTER(vp)]
@@ -133,6 +135,13 @@ def linattn_fwd(q, k, v, out, B, H, n, d, phi_id, stream=None, *, check: bool = 
     st = lib().linattn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, H, n, d, phi_id, _ptr(stream))
     if st != OK and check:
         raise LinattnError(st, "linattn_fwd")
+    return st
+
+
+def linattn_fwd_noalloc(q, k, v, out, B, H, n, d, phi_id, stream=None, *, check: bool = True) -> int:
+    st = lib().linattn_fwd_noalloc(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, H, n, d, phi_id, _ptr(stream))
+    if st != OK and check:
+        raise LinattnError(st, "linattn_fwd_noalloc")
     return st
 
 

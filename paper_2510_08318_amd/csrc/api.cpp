@@ -57,6 +57,7 @@ bool make_plan(int B, int H, int n, int d, int dtype, int layout, Plan* p) {
   const int slots = r.P > r.split.PS ? r.P : r.split.PS;
   r.off_partials = off; off = up(off + (size_t)BH * slots * r.state_elems * sizeof(float));
   r.off_state = off;    off = up(off + (size_t)BH * r.state_elems * sizeof(float));
+  r.fwd_bytes = off;
   {
     const int nblk = (n + 31) / 32;
     int KP = kCUs / (int)BH;
@@ -142,9 +143,10 @@ int fetch(int phi_id, linattn_phi_desc* out) {
   return LINATTN_OK;
 }
 
-// Checks common to forward and backward.  Fills desc and plan.
+// Checks common to forward and backward.  Fills desc and plan.  own_scratch: the call brings its own
+// scratch memory, so the descriptor's workspace is neither needed nor looked at.
 int check_call(const void* const* tensors, int n_tensors, int B, int H, int n, int d, int phi_id,
-               bool want_wgrads, linattn_phi_desc* desc, Plan* plan) {
+               bool want_wgrads, linattn_phi_desc* desc, Plan* plan, bool own_scratch = false) {
   int st = fetch(phi_id, desc);
   if (st != LINATTN_OK) return st;
   for (int i = 0; i < n_tensors; ++i)
@@ -155,8 +157,76 @@ int check_call(const void* const* tensors, int n_tensors, int B, int H, int n, i
   for (int i = 0; i < n_tensors; ++i)
     if (!aligned16(tensors[i])) return LINATTN_E_ALIGN;
   const size_t need = (want_wgrads && (desc->dwq || desc->dwk)) ? plan->total_bytes : plan->bytes_no_wgrads;
-  if (!desc->workspace || desc->workspace_bytes < need) return LINATTN_E_WORKSPACE;
+  if (!own_scratch && (!desc->workspace || desc->workspace_bytes < need)) return LINATTN_E_WORKSPACE;
   if (desc->state && (size_t)plan->BH * plan->state_elems * sizeof(float) > desc->state_bytes) return LINATTN_E_STATE;
+  return LINATTN_OK;
+}
+
+// ---- scratch of linattn_fwd_noalloc ---------------------------------------------------------
+// One array per GPU, part of the loaded code object, alive until the process ends.  Its name is a
+// host-side handle only: device code is given the address hipGetSymbolAddress returns for the
+// current device, looked up once per device.
+constexpr size_t kStaticScratchBytes = LINATTN_NOALLOC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+char* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(char** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LINATTN_E_HIP;
+  std::lock_guard<std::mutex> lk(g_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return LINATTN_E_HIP;
+    g_scratch_ptr[dev] = static_cast<char*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return LINATTN_OK;
+}
+
+// The forward path on scratch memory `ws` (the descriptor's workspace, or the static array).
+int run_fwd(const linattn_phi_desc& desc, const Plan& plan, const void* q, const void* k, const void* v, void* out,
+            char* ws, hipStream_t s) {
+  float* partials = reinterpret_cast<float*>(ws + plan.off_partials);
+  float* state = desc.state ? static_cast<float*>(desc.state) : reinterpret_cast<float*>(ws + plan.off_state);
+  hipError_t e;
+  const StageEvents ev = stage_events();
+  ev.mark(0, s);
+  if (desc.dtype == LINATTN_F32) {
+    e = launch_state_partials_f32((const float*)k, (const float*)v, (const float*)desc.wk, partials, plan, s);
+    if (e != hipSuccess) return LINATTN_E_HIP;
+    ev.mark(1, s);
+    e = launch_state_reduce(partials, state, plan, s);
+    if (e != hipSuccess) return LINATTN_E_HIP;
+    ev.mark(2, s);
+    e = launch_apply_f32((const float*)q, (const float*)desc.wq, state, (float*)out,
+                         (const float*)desc.blend_in, desc.blend_r, plan, s);
+    if (e != hipSuccess) return LINATTN_E_HIP;
+  } else {
+    const bool relu = desc.kind == LINATTN_PHI_RELU;
+    e = relu ? launch_relu_state_bf16(k, v, partials, plan, s) : launch_state_partials_bf16(k, v, desc.wk, partials, plan, s);
+    if (e != hipSuccess) return LINATTN_E_HIP;
+    ev.mark(1, s);
+    e = launch_state_reduce_split(partials, state, plan, s);
+    if (e != hipSuccess) return LINATTN_E_HIP;
+    ev.mark(2, s);
+    e = launch_apply_bf16(q, desc.wq, state, out, desc.blend_in, desc.blend_r, plan, s);
+    if (e != hipSuccess) return LINATTN_E_HIP;
+  }
+  ev.mark(3, s);
+  return LINATTN_OK;
+}
+
+// Argument checks of a forward call (everything but the scratch memory).
+int check_fwd(const void* q, const void* k, const void* v, void* out, int B, int H, int n, int d, int phi_id,
+              bool own_scratch, linattn_phi_desc* desc, Plan* plan) {
+  const void* tensors[4] = {q, k, v, out};
+  int st = check_call(tensors, 4, B, H, n, d, phi_id, false, desc, plan, own_scratch);
+  if (st != LINATTN_OK) return st;
+  const size_t esz = desc->dtype == LINATTN_BF16 ? 2 : 4;
+  const size_t bytes = (size_t)plan->BH * n * d * esz;
+  if (overlaps(out, q, bytes) || overlaps(out, k, bytes) || overlaps(out, v, bytes)) return LINATTN_E_ALIAS;
+  if (desc->blend_in && overlaps(out, desc->blend_in, bytes)) return LINATTN_E_ALIAS;
   return LINATTN_OK;
 }
 
@@ -261,45 +331,21 @@ int linattn_fwd(const void* q, const void* k, const void* v, void* out,
                 int B, int H, int n, int d, int phi_id, void* stream) {
   linattn_phi_desc desc;
   Plan plan;
-  const void* tensors[4] = {q, k, v, out};
-  int st = check_call(tensors, 4, B, H, n, d, phi_id, false, &desc, &plan);
+  const int st = check_fwd(q, k, v, out, B, H, n, d, phi_id, false, &desc, &plan);
   if (st != LINATTN_OK) return st;
-  const size_t esz = desc.dtype == LINATTN_BF16 ? 2 : 4;
-  const size_t bytes = (size_t)plan.BH * n * d * esz;
-  if (overlaps(out, q, bytes) || overlaps(out, k, bytes) || overlaps(out, v, bytes)) return LINATTN_E_ALIAS;
-  if (desc.blend_in && overlaps(out, desc.blend_in, bytes)) return LINATTN_E_ALIAS;
+  return run_fwd(desc, plan, q, k, v, out, static_cast<char*>(desc.workspace), static_cast<hipStream_t>(stream));
+}
 
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  char* ws = static_cast<char*>(desc.workspace);
-  float* partials = reinterpret_cast<float*>(ws + plan.off_partials);
-  float* state = desc.state ? static_cast<float*>(desc.state) : reinterpret_cast<float*>(ws + plan.off_state);
-  hipError_t e;
-  const StageEvents ev = stage_events();
-  auto mark = [&](int i, hipStream_t st) { ev.mark(i, st); };
-  mark(0, s);
-  if (desc.dtype == LINATTN_F32) {
-    e = launch_state_partials_f32((const float*)k, (const float*)v, (const float*)desc.wk, partials, plan, s);
-    if (e != hipSuccess) return LINATTN_E_HIP;
-    mark(1, s);
-    e = launch_state_reduce(partials, state, plan, s);
-    if (e != hipSuccess) return LINATTN_E_HIP;
-    mark(2, s);
-    e = launch_apply_f32((const float*)q, (const float*)desc.wq, state, (float*)out,
-                         (const float*)desc.blend_in, desc.blend_r, plan, s);
-    if (e != hipSuccess) return LINATTN_E_HIP;
-  } else {
-    const bool relu = desc.kind == LINATTN_PHI_RELU;
-    e = relu ? launch_relu_state_bf16(k, v, partials, plan, s) : launch_state_partials_bf16(k, v, desc.wk, partials, plan, s);
-    if (e != hipSuccess) return LINATTN_E_HIP;
-    mark(1, s);
-    e = launch_state_reduce_split(partials, state, plan, s);
-    if (e != hipSuccess) return LINATTN_E_HIP;
-    mark(2, s);
-    e = launch_apply_bf16(q, desc.wq, state, out, desc.blend_in, desc.blend_r, plan, s);
-    if (e != hipSuccess) return LINATTN_E_HIP;
-  }
-  mark(3, s);
-  return LINATTN_OK;
+int linattn_fwd_noalloc(const void* q, const void* k, const void* v, void* out,
+                        int B, int H, int n, int d, int phi_id, void* stream) {
+  linattn_phi_desc desc;
+  Plan plan;
+  int st = check_fwd(q, k, v, out, B, H, n, d, phi_id, true, &desc, &plan);
+  if (st != LINATTN_OK) return st;
+  if (plan.fwd_bytes > kStaticScratchBytes) return LINATTN_E_WORKSPACE;
+  char* ws = nullptr;
+  if ((st = static_scratch(&ws)) != LINATTN_OK) return st;
+  return run_fwd(desc, plan, q, k, v, out, ws, static_cast<hipStream_t>(stream));
 }
 
 int linattn_bwd(const void* q, const void* k, const void* v, const void* dout,

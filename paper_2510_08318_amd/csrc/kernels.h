@@ -67,6 +67,7 @@ struct Plan {
   size_t state_elems;     // (d+1)*d
   size_t off_partials;    // fp32 [BH][max(P, split.PS)][(d+1)*d]
   size_t off_state;       // fp32 [BH][(d+1)*d]   (used when the caller gave no state buffer)
+  size_t fwd_bytes;       // end of the two regions above: all the scratch a forward call touches
   // backward only
   int KP;                 // workgroups per (b,h) of the key-side backward pass
   size_t off_dstate;      // fp32 [BH][(d+1)*d]   dS, dz

@@ -191,3 +191,30 @@ def test_relu_descriptors_take_no_weights_and_no_blend():
     # a call without workspace is refused on the host
     assert L.linattn_fwd(P, P + (1 << 20), P + (2 << 20), P + (3 << 20), 1, 2, 100, 64, pid, None, check=False) == L.E_WORKSPACE
     assert L.linattn_phi_destroy(pid) == L.OK
+
+
+def test_noalloc_forward_checks_arguments_and_its_limit_on_the_host():
+    """linattn_fwd_noalloc needs no workspace in the descriptor, rejects what linattn_fwd rejects, and refuses
+    problems whose forward scratch exceeds its static array -- all before any HIP call."""
+    header = open(os.path.join(ROOT, "include", "linattn.h")).read()
+    limit = re.search(r"#define\s+LINATTN_NOALLOC_SCRATCH_BYTES\s+\((\d+)u\s*<<\s*(\d+)\)", header)
+    limit = int(limit.group(1)) << int(limit.group(2))
+    assert limit == 32 << 20
+    H, d = 2, 128
+    pid = L.linattn_phi_create(L.PHI_HEDGEHOG, L.BF16, H, d, P, P + 65536)          # no workspace
+    big = 1 << 30
+    q, k, v, o = P + big, P + 2 * big, P + 3 * big, P + 4 * big
+    f = lambda *a: L.linattn_fwd_noalloc(*a, check=False)
+    try:
+        assert f(None, k, v, o, 1, H, 64, d, pid, None) == L.E_NULL
+        assert f(q, k, v, o, 1, H + 1, 64, d, pid, None) == L.E_SHAPE
+        assert f(q, k, v, o + 2, 1, H, 64, d, pid, None) == L.E_ALIGN
+        assert f(q, k, v, q, 1, H, 64, d, pid, None) == L.E_ALIAS
+        assert f(q, k, v, o, 1, H, 64, d, 3, None) == L.E_PHI
+        # 600 (b,h) pairs: one partial and one state each = 600 * 2 * 66048 bytes > 32 MiB
+        assert 600 * 2 * (d + 1) * d * 4 > limit
+        assert f(q, k, v, o, 300, H, 64, d, pid, None) == L.E_WORKSPACE
+    finally:
+        L.linattn_phi_destroy(pid)
+    # the task's largest configuration fits: partials + states of config 4 (B=2, H=40, n=75600, d=128)
+    assert L.linattn_workspace_bytes(2, 40, 75600, 128, L.PHI_HEDGEHOG, L.BF16) > 0
