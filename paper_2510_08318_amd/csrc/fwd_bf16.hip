@@ -71,6 +71,23 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
   const uint16_t* bb = BLEND ? blend + head_base(rw, bh, H) : nullptr;
   const float rb = BLEND ? fminf(fmaxf(*rptr, 0.f), 1.f) : 0.f;
 
+  const int nblk = (n + 31) / 32;
+  const int stride = gridDim.x * NW;
+  const int c = lane % 32;
+  const uint32_t lane_off = ((uint32_t)(4 * g) * (uint32_t)rw.sn + (uint32_t)(L::MB * c)) * 2u;   // bytes
+
+  uint4 x[C::UK];
+  auto load_block = [&](int b) {
+    const int t = b * 32 + (lane % 32);
+    const int tc = t < n ? t : (n - 1);
+    const uint4* row = reinterpret_cast<const uint4*>(qb + (size_t)tc * rw.sn);
+#pragma unroll
+    for (int ks = 0; ks < C::UK; ++ks) x[ks] = row[2 * ks + g];
+  };
+  // the first block's rows are requested before the prologue, so that they arrive under it
+  int b = blockIdx.x * NW + w;
+  if (b < nblk) load_block(b);
+
   float scale;
   {
     // The state and W~ of this (b,h) are first copied into LDS with coalesced 16-byte loads,
@@ -91,22 +108,6 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
   __syncthreads();
   const float den_eps = KIND == kPhiRelu ? scale * kReluEps : 0.f;    // the image carries scale * z
 
-  const int nblk = (n + 31) / 32;
-  const int stride = gridDim.x * NW;
-  const int c = lane % 32;
-  const uint32_t lane_off = ((uint32_t)(4 * g) * (uint32_t)rw.sn + (uint32_t)(L::MB * c)) * 2u;   // bytes
-
-  uint4 x[C::UK];
-  auto load_block = [&](int b) {
-    const int t = b * 32 + (lane % 32);
-    const int tc = t < n ? t : (n - 1);
-    const uint4* row = reinterpret_cast<const uint4*>(qb + (size_t)tc * rw.sn);
-#pragma unroll
-    for (int ks = 0; ks < C::UK; ++ks) x[ks] = row[2 * ks + g];
-  };
-
-  int b = blockIdx.x * NW + w;
-  if (b < nblk) load_block(b);
   for (; b < nblk; b += stride) {
     uint32_t pk[C::NPK];
     if constexpr (KIND == kPhiRelu) {

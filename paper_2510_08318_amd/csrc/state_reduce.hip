@@ -60,6 +60,44 @@ __global__ __launch_bounds__(256) void state_reduce_split_kernel(const float* __
   state[(size_t)bh * elems + e] = acc;
 }
 
+// The same, four adjacent elements per thread (elems % 4 == 0, both pointers 16-byte aligned): a quarter
+// of the load instructions for the same bytes.  Each element is still the sum of its slots in
+// ascending order, so the result is bitwise that of state_reduce_split_kernel.
+__global__ __launch_bounds__(256) void state_reduce_split4_kernel(const float4* __restrict__ partials, float4* __restrict__ state,
+                                                                  Split sp, int elems4) {
+  __shared__ int s_cnt;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  const int bh = blockIdx.y;
+  if (threadIdx.x == 0)
+    s_cnt = split_owner(sp, (long long)(bh + 1) * sp.ntile - 1) - split_owner(sp, (long long)bh * sp.ntile) + 1;
+  __syncthreads();
+  if (e >= elems4) return;
+  const int cnt = s_cnt;
+  const float4* src = partials + (size_t)bh * sp.PS * elems4 + e;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  int p = 0;
+  for (; p + 8 <= cnt; p += 8) {
+    float4 t[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) t[i] = src[(size_t)(p + i) * elems4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { acc.x += t[i].x; acc.y += t[i].y; acc.z += t[i].z; acc.w += t[i].w; }
+  }
+  if (p + 4 <= cnt) {
+    float4 t[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) t[i] = src[(size_t)(p + i) * elems4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { acc.x += t[i].x; acc.y += t[i].y; acc.z += t[i].z; acc.w += t[i].w; }
+    p += 4;
+  }
+  for (; p < cnt; ++p) {
+    const float4 t = src[(size_t)p * elems4];
+    acc.x += t.x; acc.y += t.y; acc.z += t.z; acc.w += t.w;
+  }
+  state[(size_t)bh * elems4 + e] = acc;
+}
+
 // ---- dW~ = sum_{b, i} x_i^T du_i ------------------------------------------------------------
 // Partial sums per (b,h) and token split (fp32 FMA, LDS tiles), then a fixed-order reduction over
 // splits and batch items.
@@ -208,7 +246,13 @@ hipError_t launch_state_reduce(const float* partials, float* state, const Plan& 
 
 hipError_t launch_state_reduce_split(const float* partials, float* state, const Plan& p, hipStream_t s) {
   const int elems = (int)p.state_elems;
-  state_reduce_split_kernel<<<dim3((elems + 255) / 256, p.BH), 256, 0, s>>>(partials, state, p.split, elems);
+  if (elems % 4 == 0 && ((reinterpret_cast<uintptr_t>(partials) | reinterpret_cast<uintptr_t>(state)) & 15u) == 0) {
+    const int elems4 = elems / 4;
+    state_reduce_split4_kernel<<<dim3((elems4 + 255) / 256, p.BH), 256, 0, s>>>(
+        reinterpret_cast<const float4*>(partials), reinterpret_cast<float4*>(state), p.split, elems4);
+  } else {
+    state_reduce_split_kernel<<<dim3((elems + 255) / 256, p.BH), 256, 0, s>>>(partials, state, p.split, elems);
+  }
   return hipGetLastError();
 }
 
