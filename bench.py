@@ -194,6 +194,93 @@ def check_timed_output(x, sets, calls, lay, relu, args, blend_s):
                       "max |diff| / max(|ref|, rms of the sampled rows of the head)"}
 
 
+SECONDARY = (
+    # label, workload, pass, options
+    ("fwd C2 (Wan-1.3B 480p)", "C2", "fwd", {}),
+    ("fwd C4 (CFG batch, B=2)", "C4", "fwd", {}),
+    ("fwd C6 (CogVideoX-2B shape)", "C6", "fwd", {}),
+    ("fwd C3 [B,n,H,d] layout", "C3", "fwd", {"layout": "bnhd"}),
+    ("fwd C3 mixed attention (Eq. 6)", "C3", "fwd", {"blend": True}),
+    ("fwd C3 ReLU map", "C3", "fwd", {"relu": True}),
+    ("bwd C5 with weight gradients", "C5", "bwd", {}),
+    ("bwd C5 without weight gradients", "C5", "bwd", {"wgrads": False}),
+    ("bwd C5 ReLU map", "C5", "bwd", {"relu": True}),
+    ("bwd C3 shape with weight gradients", "C3", "bwd", {}),
+)
+
+
+def quick_time(workload, which, *, layout="bhnd", blend=False, relu=False, wgrads=True, steps=200):
+    """One secondary workload, timed like the headline one (pre-warm, then `steps` calls by the wall
+    clock, inputs resident in HBM, buffer sets rotated below the cache scale)."""
+    import torch
+    from paper_2510_08318_amd import binding as L, synth, torch_glue as G
+    x = synth.generate(workload, with_dout=(which == "bwd"))
+    names = ("q", "k", "v") + (("dout",) if which == "bwd" else ())
+    t = {nm: G.to_device(getattr(x, nm)) for nm in names}
+    if layout == "bnhd":
+        t = {nm: a.permute(0, 2, 1, 3).contiguous() for nm, a in t.items()}
+    wq, wk = G.to_device(x.wq), G.to_device(x.wk)
+    if relu:
+        lay = G.ReluLayer(x.H, x.d, x.B, x.n, t["q"].dtype, layout=layout)
+    else:
+        lay = G.Layer(wq, wk, x.B, x.n, want_wgrads=(which == "bwd" and wgrads), layout=layout)
+    if blend:
+        lay.set_blend((torch.randn(t["q"].shape, device="cuda") * 0.1).to(t["q"].dtype), torch.tensor([0.5], device="cuda"))
+    outs = ("out",) if which == "fwd" else ("dq", "dk", "dv")
+    ntens = len(names) + len(outs) + (1 if blend else 0)
+    set_bytes = ntens * t["q"].numel() * t["q"].element_size()
+    nsets = 1 if set_bytes >= 1_000_000_000 or which == "bwd" else min(16, max(3, -(-1_500_000_000 // set_bytes)))
+    sets = []
+    for i in range(nsets):
+        ins = [t[nm] if i == 0 else t[nm].clone() for nm in names]
+        sets.append(ins + [torch.empty_like(t["q"]) for _ in outs])
+    stream = torch.cuda.current_stream().cuda_stream
+    calls = [0]
+    if which == "bwd":
+        lay.forward(t["q"], t["k"], t["v"])          # the state the backward needs
+
+    def step():
+        a = sets[calls[0] % nsets]
+        calls[0] += 1
+        if which == "fwd":
+            L.linattn_fwd(a[0], a[1], a[2], a[3], x.B, x.H, x.n, x.d, lay.phi_id, stream)
+        else:
+            L.linattn_bwd(a[0], a[1], a[2], a[3], a[4], a[5], a[6], x.B, x.H, x.n, x.d, lay.phi_id, stream)
+
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < PREWARM_SECONDS:
+        for _ in range(8):
+            step()
+        torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    lay.close()
+    esz = 2 if x.dtype == "bf16" else 4
+    # forward: read K, V, Q (and the softmax-branch tensor when blending), write out; backward: read q, k, v, dO, write dq, dk, dv
+    algo = ((5 if blend else 4) if which == "fwd" else 7) * x.d * esz * x.B * x.H * x.n
+    return {"ms_per_step": round(dt * 1e3, 4), "tokens_per_s": round(x.B * x.n / dt, 1),
+            "path_frac": round(algo / dt / 1e9 / HBM_PEAK_GBS, 4), "buffer_sets": nsets, "steps": steps}
+
+
+def secondary_measurements():
+    """The other workloads of the benchmark spec, timed in this same process after the headline measurement
+    (context for the one JSON line; none of them is `value`)."""
+    import gc
+    import torch
+    res = {}
+    for label, workload, which, opt in SECONDARY:
+        try:
+            res[label] = quick_time(workload, which, **opt)
+        except Exception as exc:                     # context only: report and go on
+            res[label] = {"error": f"{type(exc).__name__}: {exc}"}
+        gc.collect()
+        torch.cuda.empty_cache()
+    return res
+
+
 def _calib_copy():
     """One 1 GiB device-to-device copy: the reference reading for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE."""
     import torch
@@ -285,6 +372,8 @@ def main():
     ap.add_argument("--phi", choices=("hedgehog", "relu"), default="hedgehog",
                     help="feature map: Eq. 5 (default, the headline configuration) or the weight-free max(x, 0) of the kernel-function ablation")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true",
+                    help="skip the secondary workloads (other configurations, layouts, maps and the backward) timed after the headline one; --no-cpu-baseline and --calib-copy skip them as well")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy kernel (reference reading for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -439,6 +528,11 @@ def main():
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(x, relu=relu)
     lay.close()
+    headline = args.workload == "C3" and not relu and not args.blend and args.layout == "bhnd"
+    if headline and not (args.no_secondary or args.no_cpu_baseline or args.calib_copy):
+        del sets, q, k, v, out
+        torch.cuda.empty_cache()
+        res["secondary"] = secondary_measurements()
     print(json.dumps(res), flush=True)
 
 
