@@ -17,8 +17,9 @@
  *     which a transformer block's projection q = x W_q (Sec. 3) leaves them, so no transpose
  *     copy is needed around the operator).  d in {64, 128}, n >= 1 arbitrary, B, H >= 1,
  *     64-bit indexing inside.
- *   - element type of those tensors and of W~ is the descriptor's dtype (bf16 or fp32).
- *     All accumulation is fp32.  The fp32 mode never rounds through bf16.
+ *   - element type of those tensors and of W~ is the descriptor's dtype: bf16 (LINATTN_BF16 and
+ *     LINATTN_BF16_F32MATH) or fp32 (LINATTN_F32).  All accumulation is fp32.  The fp32 mode never
+ *     rounds through bf16.
  *   - all pointers are borrowed: the caller keeps them alive until the stream work is done.
  *   - calls only enqueue work on `stream` (a hipStream_t passed as void*, NULL = default
  *     stream).  They never synchronise and never allocate.
@@ -46,7 +47,14 @@
  *     tokens' carries |v_j| / rms|v| times the error of an ordinary row.  For the rows at 20x
  *     magnitude of the Wan-14B-shaped test recipe (0.1 % of the tokens) this reads up to 1e-1 of the
  *     slice RMS, and dW~_k, which weights those rows by |k_j| once more, up to 2e-2; all other rows of
- *     dk, and dq, dv, dW~_q everywhere, meet 1e-2.
+ *     dk, and dq, dv, dW~_q everywhere, meet 1e-2.  Second exception: where phi is within a few per
+ *     cent of uniform (the spread of x W~ over the features far below 1), dq, dk and dW~ are
+ *     differences of nearly equal rows of S and dS and come out up to 0.2 off; out and dv keep 1e-2.
+ *   - LINATTN_BF16_F32MATH reads and writes the same bf16 tensors but does all arithmetic in fp32
+ *     (the kernels of the fp32 mode, no matrix cores, no fp16 operands): none of the limits above
+ *     applies, |v| may be any finite bf16 value, and the only rounding that matters is the bf16
+ *     store of the results.  It is 15-25x slower than LINATTN_BF16: a device-side reference and a
+ *     mode for numerically delicate inputs, not the fast path.
  */
 #ifndef LINATTN_H
 #define LINATTN_H
@@ -80,8 +88,9 @@ extern "C" {
                                      must be NULL (E_PHI otherwise); state rows are the d channels of k. */
 
 /* dtypes */
-#define LINATTN_BF16  1
-#define LINATTN_F32   2
+#define LINATTN_BF16  1          /* bf16 tensors, matrix-core kernels (bf16 / fp16 operands, fp32 accumulation) */
+#define LINATTN_F32   2          /* fp32 tensors, fp32 arithmetic */
+#define LINATTN_BF16_F32MATH 3   /* bf16 tensors, fp32 arithmetic (see "Numeric domain" above) */
 
 /* memory layouts of q, k, v, out, dout, dq, dk, dv */
 #define LINATTN_LAYOUT_BHND  0   /* element (b,h,t,c) at ((b*H + h)*n + t)*d + c */
@@ -94,7 +103,7 @@ extern "C" {
  */
 typedef struct linattn_phi_desc {
   int kind;               /* LINATTN_PHI_HEDGEHOG or LINATTN_PHI_RELU */
-  int dtype;              /* LINATTN_BF16 or LINATTN_F32: type of q,k,v,out,dout,dq,dk,dv,wq,wk */
+  int dtype;              /* LINATTN_BF16, LINATTN_F32 or LINATTN_BF16_F32MATH: type of q,k,v,out,dout,dq,dk,dv,wq,wk */
   int H, d;               /* wq, wk: device, [H, d, d/2] contiguous, one map per head (Eq. 5) */
   const void *wq, *wk;
   void *dwq, *dwk;        /* optional device fp32 [H, d, d/2]: linattn_bwd OVERWRITES them with the

@@ -16,7 +16,7 @@ OK = 0
 E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_PHI, E_WORKSPACE, E_HIP, E_STATE, E_ALIAS = range(-1, -10, -1)
 PHI_HEDGEHOG = 1
 PHI_RELU = 2
-BF16, F32 = 1, 2
+BF16, F32, BF16_F32MATH = 1, 2, 3
 LAYOUT_BHND, LAYOUT_BNHD = 0, 1
 
 EXPORTS = ("linattn_phi_create", "linattn_phi_destroy", "linattn_workspace_bytes", "linattn_workspace_bytes_wgrads",

@@ -13,13 +13,14 @@ namespace linattn {
 bool make_plan(int B, int H, int n, int d, int dtype, int layout, Plan* p) {
   if (B <= 0 || H <= 0 || n <= 0) return false;
   if (d != 64 && d != 128) return false;
-  if (dtype != LINATTN_BF16 && dtype != LINATTN_F32) return false;
+  if (dtype != LINATTN_BF16 && dtype != LINATTN_F32 && dtype != LINATTN_BF16_F32MATH) return false;
   if (layout != LINATTN_LAYOUT_BHND && layout != LINATTN_LAYOUT_BNHD) return false;
   const long long BH = (long long)B * H;
   if (BH > 65535) return false;                       // grid.y
   if ((long long)n > (1LL << 30)) return false;
   Plan r{};
   r.B = B; r.H = H; r.n = n; r.d = d; r.BH = (int)BH;
+  r.bf16_storage = dtype == LINATTN_BF16_F32MATH;
   if (layout == LINATTN_LAYOUT_BHND) r.rows = Rows{(size_t)H * n * d, (size_t)n * d, (size_t)d};
   else r.rows = Rows{(size_t)n * H * d, (size_t)d, (size_t)H * d};
   const int tiles = (n + kTile - 1) / kTile;
@@ -192,15 +193,14 @@ int run_fwd(const linattn_phi_desc& desc, const Plan& plan, const void* q, const
   hipError_t e;
   const StageEvents ev = stage_events();
   ev.mark(0, s);
-  if (desc.dtype == LINATTN_F32) {
-    e = launch_state_partials_f32((const float*)k, (const float*)v, (const float*)desc.wk, partials, plan, s);
+  if (desc.dtype != LINATTN_BF16) {
+    e = launch_state_partials_f32(k, v, desc.wk, partials, plan, s);
     if (e != hipSuccess) return LINATTN_E_HIP;
     ev.mark(1, s);
     e = launch_state_reduce(partials, state, plan, s);
     if (e != hipSuccess) return LINATTN_E_HIP;
     ev.mark(2, s);
-    e = launch_apply_f32((const float*)q, (const float*)desc.wq, state, (float*)out,
-                         (const float*)desc.blend_in, desc.blend_r, plan, s);
+    e = launch_apply_f32(q, desc.wq, state, out, desc.blend_in, desc.blend_r, plan, s);
     if (e != hipSuccess) return LINATTN_E_HIP;
   } else {
     const bool relu = desc.kind == LINATTN_PHI_RELU;
@@ -223,7 +223,7 @@ int check_fwd(const void* q, const void* k, const void* v, void* out, int B, int
   const void* tensors[4] = {q, k, v, out};
   int st = check_call(tensors, 4, B, H, n, d, phi_id, false, desc, plan, own_scratch);
   if (st != LINATTN_OK) return st;
-  const size_t esz = desc->dtype == LINATTN_BF16 ? 2 : 4;
+  const size_t esz = desc->dtype == LINATTN_F32 ? 4 : 2;
   const size_t bytes = (size_t)plan->BH * n * d * esz;
   if (overlaps(out, q, bytes) || overlaps(out, k, bytes) || overlaps(out, v, bytes)) return LINATTN_E_ALIAS;
   if (desc->blend_in && overlaps(out, desc->blend_in, bytes)) return LINATTN_E_ALIAS;
@@ -279,7 +279,7 @@ size_t linattn_workspace_bytes_wgrads(int B, int H, int n, int d, int kind, int 
 int linattn_phi_create(const linattn_phi_desc* desc, int* phi_id_out) {
   if (!desc || !phi_id_out) return LINATTN_E_NULL;
   if (desc->kind != LINATTN_PHI_HEDGEHOG && desc->kind != LINATTN_PHI_RELU) return LINATTN_E_PHI;
-  if (desc->dtype != LINATTN_BF16 && desc->dtype != LINATTN_F32) return LINATTN_E_DTYPE;
+  if (desc->dtype != LINATTN_BF16 && desc->dtype != LINATTN_F32 && desc->dtype != LINATTN_BF16_F32MATH) return LINATTN_E_DTYPE;
   if (desc->H <= 0 || (desc->d != 64 && desc->d != 128)) return LINATTN_E_SHAPE;
   if (desc->layout != LINATTN_LAYOUT_BHND && desc->layout != LINATTN_LAYOUT_BNHD) return LINATTN_E_SHAPE;
   if (desc->kind == LINATTN_PHI_RELU) {
@@ -357,7 +357,7 @@ int linattn_bwd(const void* q, const void* k, const void* v, const void* dout,
   int st = check_call(tensors, 7, B, H, n, d, phi_id, true, &desc, &plan);
   if (st != LINATTN_OK) return st;
   if (!desc.state) return LINATTN_E_STATE;
-  const size_t esz = desc.dtype == LINATTN_BF16 ? 2 : 4;
+  const size_t esz = desc.dtype == LINATTN_F32 ? 4 : 2;
   const size_t bytes = (size_t)plan.BH * n * d * esz;
   const void* ins[4] = {q, k, v, dout};
   void* outs[3] = {dq, dk, dv};
@@ -390,7 +390,7 @@ int linattn_bwd(const void* q, const void* k, const void* v, const void* dout,
   a.du_k = reinterpret_cast<float*>(ws + plan.off_du_k);
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (desc.kind == LINATTN_PHI_RELU) { a.dwq = nullptr; a.dwk = nullptr; }
-  const hipError_t e = desc.dtype == LINATTN_F32 ? launch_bwd_f32(a, plan, s)
+  const hipError_t e = desc.dtype != LINATTN_BF16 ? launch_bwd_f32(a, plan, s)
                      : desc.kind == LINATTN_PHI_RELU ? launch_relu_bwd_bf16(a, plan, s) : launch_bwd_bf16(a, plan, s);
   return e == hipSuccess ? LINATTN_OK : LINATTN_E_HIP;
 }

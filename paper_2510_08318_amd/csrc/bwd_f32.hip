@@ -1,6 +1,7 @@
-// fp32 backward path (no bf16/fp16 anywhere): plain FMA on LDS tiles of 16 tokens.
-// Same mathematics as bwd_bf16.hip (chain rule through Eq. 3 and Eq. 5); this mode exists for the
-// 1e-5 accuracy contract on fp32 tensors, not for bandwidth.
+// fp32-arithmetic backward path: plain FMA on LDS tiles of 16 tokens, on fp32 tensors (no bf16/fp16
+// anywhere: the 1e-5 accuracy contract) or on bf16 tensors widened on load and rounded on store
+// (LINATTN_BF16_F32MATH).  Same mathematics as bwd_bf16.hip (chain rule through Eq. 3 and Eq. 5); not
+// tuned for bandwidth.
 #include "kernels.h"
 #include "f32_common.h"
 
@@ -32,8 +33,8 @@ __device__ __forceinline__ void jacobian_tile(const float* sG, const float* sPhi
 }
 
 // dx[tt][c] = sum_a du[tt][a] W[c][a], stored for valid tokens; optional copy of du to the workspace.
-template <int D>
-__device__ __forceinline__ void dx_tile(const float* sDU, const float* sW, float* xout, size_t sn, float* du_ws,
+template <int D, typename T>
+__device__ __forceinline__ void dx_tile(const float* sDU, const float* sW, T* xout, size_t sn, float* du_ws,
                                         int t0, int n_valid, int tid) {
   constexpr int HALF = D / 2;
   const int tt = tid / TPT, cb = tid % TPT;
@@ -43,19 +44,19 @@ __device__ __forceinline__ void dx_tile(const float* sDU, const float* sW, float
       const int c = cb + TPT * j;
       float acc = 0.f;
       for (int a = 0; a < HALF; ++a) acc = fmaf(sDU[tt * HALF + a], sW[c * HALF + a], acc);
-      xout[(size_t)(t0 + tt) * sn + c] = acc;
+      stf(xout, (size_t)(t0 + tt) * sn + c, acc);
     }
     if (du_ws)
       for (int a = cb; a < HALF; a += TPT) du_ws[(size_t)(t0 + tt) * HALF + a] = sDU[tt * HALF + a];
   }
 }
 
-template <int D, int KIND>
-__global__ __launch_bounds__(NT) void bwd_q_f32_kernel(const float* __restrict__ q, const float* __restrict__ dout,
-                                                       const float* __restrict__ wq, const float* __restrict__ state,
-                                                       float* __restrict__ dq, float* __restrict__ partials,
+template <int D, int KIND, typename T>
+__global__ __launch_bounds__(NT) void bwd_q_f32_kernel(const T* __restrict__ q, const T* __restrict__ dout,
+                                                       const T* __restrict__ wq, const float* __restrict__ state,
+                                                       T* __restrict__ dq, float* __restrict__ partials,
                                                        float* __restrict__ du_ws,
-                                                       const float* __restrict__ blend, const float* __restrict__ rptr,
+                                                       const T* __restrict__ blend, const float* __restrict__ rptr,
                                                        float* __restrict__ dr_part,
                                                        int H, int n, int P, int chunk, Rows rw) {
   constexpr int HALF = D / 2;
@@ -76,17 +77,17 @@ __global__ __launch_bounds__(NT) void bwd_q_f32_kernel(const float* __restrict__
   const int tid = threadIdx.x;
   const int bh = blockIdx.y, p = blockIdx.x, h = bh % H;
   const int t_begin = p * chunk, t_end = min(n, t_begin + chunk);
-  const float* qb = q + head_base(rw, bh, H);
-  const float* dob = dout + head_base(rw, bh, H);
-  float* dqb = dq + head_base(rw, bh, H);
+  const T* qb = q + head_base(rw, bh, H);
+  const T* dob = dout + head_base(rw, bh, H);
+  T* dqb = dq + head_base(rw, bh, H);
   // mixed attention (Eq. 6), off when blend is null: dout is the gradient of the mixed output
-  const float* bb = blend ? blend + head_base(rw, bh, H) : nullptr;
+  const T* bb = blend ? blend + head_base(rw, bh, H) : nullptr;
   const float om = blend ? 1.f - fminf(fmaxf(*rptr, 0.f), 1.f) : 1.f;
   float dr_acc = 0.f;
-  const float* wb = wq + (size_t)h * D * HALF;
+  const T* wb = wq + (size_t)h * D * HALF;
   const float* sb = state + (size_t)bh * (D + 1) * D;
   if constexpr (KIND == kPhiHedgehog)
-    for (int i = tid; i < D * HALF; i += NT) sW[i] = wb[i];
+    for (int i = tid; i < D * HALF; i += NT) sW[i] = ldf(wb, i);
   for (int i = tid; i < (D + 1) * D; i += NT) sS[(i / D) * SS + (i % D)] = sb[i];
 
   float acc[BLK][BLK];
@@ -104,8 +105,8 @@ __global__ __launch_bounds__(NT) void bwd_q_f32_kernel(const float* __restrict__
     for (int i = tid; i < TB * D; i += NT) {
       const int r = i / D, c = i % D;
       const bool valid = r < n_valid;
-      sX[r * (D + 1) + c] = valid ? qb[(size_t)(t0 + r) * rw.sn + c] : 0.f;
-      sDO[r * D + c] = valid ? dob[(size_t)(t0 + r) * rw.sn + c] : 0.f;
+      sX[r * (D + 1) + c] = valid ? ldf(qb, (size_t)(t0 + r) * rw.sn + c) : 0.f;
+      sDO[r * D + c] = valid ? ldf(dob, (size_t)(t0 + r) * rw.sn + c) : 0.f;
     }
     __syncthreads();
     phi_tile<D, TB, KIND>(sX, sW, sPhi, tid, n_valid);     // rows >= n_valid are zero
@@ -131,7 +132,7 @@ __global__ __launch_bounds__(NT) void bwd_q_f32_kernel(const float* __restrict__
       if (bb) {
         if (tid < n_valid) {
           float ds = 0.f;
-          for (int c = 0; c < D; ++c) ds = fmaf(sDO[tid * D + c], bb[(size_t)(t0 + tid) * rw.sn + c], ds);
+          for (int c = 0; c < D; ++c) ds = fmaf(sDO[tid * D + c], ldf(bb, (size_t)(t0 + tid) * rw.sn + c), ds);
           dr_acc += ds - dl;
         }
         for (int c = 0; c < D; ++c) sDO[tid * D + c] *= om;
@@ -166,11 +167,11 @@ __global__ __launch_bounds__(NT) void bwd_q_f32_kernel(const float* __restrict__
       if (tt < n_valid)
         for (int j = 0; j < D / TPT; ++j) {
           const int c = cb + TPT * j;
-          dqb[(size_t)(t0 + tt) * rw.sn + c] = sX[tt * (D + 1) + c] > 0.f ? sG[tt * D + c] : 0.f;
+          stf(dqb, (size_t)(t0 + tt) * rw.sn + c, sX[tt * (D + 1) + c] > 0.f ? sG[tt * D + c] : 0.f);
         }
     } else {
       jacobian_tile<D>(sG, sPhi, sDU, sC, tid);
-      dx_tile<D>(sDU, sW, dqb, rw.sn, du_ws ? du_ws + (size_t)bh * n * HALF : nullptr, t0, n_valid, tid);
+      dx_tile<D, T>(sDU, sW, dqb, rw.sn, du_ws ? du_ws + (size_t)bh * n * HALF : nullptr, t0, n_valid, tid);
     }
     // dS += phi^T (dO / den), dz -= phi * (delta / den)
     for (int r = 0; r < TB; ++r) {
@@ -206,10 +207,10 @@ __global__ __launch_bounds__(NT) void bwd_q_f32_kernel(const float* __restrict__
   }
 }
 
-template <int D, int KIND>
-__global__ __launch_bounds__(NT) void bwd_k_f32_kernel(const float* __restrict__ k, const float* __restrict__ v,
-                                                       const float* __restrict__ wk, const float* __restrict__ dstate,
-                                                       float* __restrict__ dk, float* __restrict__ dv,
+template <int D, int KIND, typename T>
+__global__ __launch_bounds__(NT) void bwd_k_f32_kernel(const T* __restrict__ k, const T* __restrict__ v,
+                                                       const T* __restrict__ wk, const float* __restrict__ dstate,
+                                                       T* __restrict__ dk, T* __restrict__ dv,
                                                        float* __restrict__ du_ws, int H, int n, int chunk, Rows rw) {
   constexpr int HALF = D / 2;
   constexpr int SS = D + 1;
@@ -226,14 +227,14 @@ __global__ __launch_bounds__(NT) void bwd_k_f32_kernel(const float* __restrict__
   const int tid = threadIdx.x;
   const int bh = blockIdx.y, p = blockIdx.x, h = bh % H;
   const int t_begin = p * chunk, t_end = min(n, t_begin + chunk);
-  const float* kb = k + head_base(rw, bh, H);
-  const float* vb = v + head_base(rw, bh, H);
-  float* dkb = dk + head_base(rw, bh, H);
-  float* dvb = dv + head_base(rw, bh, H);
-  const float* wb = wk + (size_t)h * D * HALF;
+  const T* kb = k + head_base(rw, bh, H);
+  const T* vb = v + head_base(rw, bh, H);
+  T* dkb = dk + head_base(rw, bh, H);
+  T* dvb = dv + head_base(rw, bh, H);
+  const T* wb = wk + (size_t)h * D * HALF;
   const float* sb = dstate + (size_t)bh * (D + 1) * D;
   if constexpr (KIND == kPhiHedgehog)
-    for (int i = tid; i < D * HALF; i += NT) sW[i] = wb[i];
+    for (int i = tid; i < D * HALF; i += NT) sW[i] = ldf(wb, i);
   for (int i = tid; i < (D + 1) * D; i += NT) sS[(i / D) * SS + (i % D)] = sb[i];
   const int tt = tid / TPT, cb = tid % TPT;
 
@@ -243,8 +244,8 @@ __global__ __launch_bounds__(NT) void bwd_k_f32_kernel(const float* __restrict__
     for (int i = tid; i < TB * D; i += NT) {
       const int r = i / D, c = i % D;
       const bool valid = r < n_valid;
-      sX[r * (D + 1) + c] = valid ? kb[(size_t)(t0 + r) * rw.sn + c] : 0.f;
-      sV[r * D + c] = valid ? vb[(size_t)(t0 + r) * rw.sn + c] : 0.f;
+      sX[r * (D + 1) + c] = valid ? ldf(kb, (size_t)(t0 + r) * rw.sn + c) : 0.f;
+      sV[r * D + c] = valid ? ldf(vb, (size_t)(t0 + r) * rw.sn + c) : 0.f;
     }
     __syncthreads();
     phi_tile<D, TB, KIND>(sX, sW, sPhi, tid, n_valid);
@@ -254,7 +255,7 @@ __global__ __launch_bounds__(NT) void bwd_k_f32_kernel(const float* __restrict__
       const int c = cb + TPT * j;
       float a = 0.f, gsum = 0.f;
       for (int f = 0; f < D; ++f) a = fmaf(sPhi[tt * D + f], sS[f * SS + c], a);
-      if (tt < n_valid) dvb[(size_t)(t0 + tt) * rw.sn + c] = a;
+      if (tt < n_valid) stf(dvb, (size_t)(t0 + tt) * rw.sn + c, a);
       const int f = c;
       for (int cc = 0; cc < D; ++cc) gsum = fmaf(sV[tt * D + cc], sS[f * SS + cc], gsum);
       sG[tt * D + f] = gsum + sS[D * SS + f];
@@ -264,11 +265,11 @@ __global__ __launch_bounds__(NT) void bwd_k_f32_kernel(const float* __restrict__
       if (tt < n_valid)
         for (int j = 0; j < D / TPT; ++j) {
           const int c = cb + TPT * j;
-          dkb[(size_t)(t0 + tt) * rw.sn + c] = sX[tt * (D + 1) + c] > 0.f ? sG[tt * D + c] : 0.f;
+          stf(dkb, (size_t)(t0 + tt) * rw.sn + c, sX[tt * (D + 1) + c] > 0.f ? sG[tt * D + c] : 0.f);
         }
     } else {
       jacobian_tile<D>(sG, sPhi, sDU, sC, tid);
-      dx_tile<D>(sDU, sW, dkb, rw.sn, du_ws ? du_ws + (size_t)bh * n * HALF : nullptr, t0, n_valid, tid);
+      dx_tile<D, T>(sDU, sW, dkb, rw.sn, du_ws ? du_ws + (size_t)bh * n * HALF : nullptr, t0, n_valid, tid);
     }
   }
 }
@@ -282,34 +283,40 @@ constexpr size_t k_smem() {
   return sizeof(float) * (D * (D / 2) + (D + 1) * (D + 1) + TB * (D + 1) + 3 * TB * D + TB * (D / 2) + 2 * TB);
 }
 
-template <int D, int KIND>
+template <int D, int KIND, typename T>
 hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   hipError_t e;
   const dim3 grid(p.P, p.BH);
-  if ((e = set_smem_once<bwd_q_f32_kernel<D, KIND>>(q_smem<D>())) != hipSuccess) return e;
-  bwd_q_f32_kernel<D, KIND><<<grid, NT, q_smem<D>(), s>>>((const float*)a.q, (const float*)a.dout, (const float*)a.wq, a.state,
-                                                    (float*)a.dq, a.partials, a.dwq ? a.du_q : nullptr,
-                                                    (const float*)a.blend_in, a.blend_r, a.dr_part, p.H, p.n, p.P, p.chunk, p.rows);
+  constexpr bool kBf16 = sizeof(T) == 2;
+  if ((e = set_smem_once<bwd_q_f32_kernel<D, KIND, T>>(q_smem<D>())) != hipSuccess) return e;
+  bwd_q_f32_kernel<D, KIND, T><<<grid, NT, q_smem<D>(), s>>>((const T*)a.q, (const T*)a.dout, (const T*)a.wq, a.state,
+                                                    (T*)a.dq, a.partials, a.dwq ? a.du_q : nullptr,
+                                                    (const T*)a.blend_in, a.blend_r, a.dr_part, p.H, p.n, p.P, p.chunk, p.rows);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (a.blend_in && a.blend_dr && (e = launch_dr_reduce(a.dr_part, p.BH * p.P, a.blend_r, a.blend_dr, s)) != hipSuccess) return e;
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if ((e = launch_state_reduce(a.partials, a.dstate, p, s)) != hipSuccess) return e;
-  if ((e = set_smem_once<bwd_k_f32_kernel<D, KIND>>(k_smem<D>())) != hipSuccess) return e;
-  bwd_k_f32_kernel<D, KIND><<<grid, NT, k_smem<D>(), s>>>((const float*)a.k, (const float*)a.v, (const float*)a.wk, a.dstate,
-                                                    (float*)a.dk, (float*)a.dv, a.dwk ? a.du_k : nullptr, p.H, p.n, p.chunk, p.rows);
+  if ((e = set_smem_once<bwd_k_f32_kernel<D, KIND, T>>(k_smem<D>())) != hipSuccess) return e;
+  bwd_k_f32_kernel<D, KIND, T><<<grid, NT, k_smem<D>(), s>>>((const T*)a.k, (const T*)a.v, (const T*)a.wk, a.dstate,
+                                                    (T*)a.dk, (T*)a.dv, a.dwk ? a.du_k : nullptr, p.H, p.n, p.chunk, p.rows);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if constexpr (KIND == kPhiHedgehog) {
-    if (a.dwq && (e = launch_dw(a.q, false, a.du_q, a.dw_part, a.dwq, p, s)) != hipSuccess) return e;
-    if (a.dwk && (e = launch_dw(a.k, false, a.du_k, a.dw_part, a.dwk, p, s)) != hipSuccess) return e;
+    if (a.dwq && (e = launch_dw(a.q, kBf16, a.du_q, a.dw_part, a.dwq, p, s)) != hipSuccess) return e;
+    if (a.dwk && (e = launch_dw(a.k, kBf16, a.du_k, a.dw_part, a.dwk, p, s)) != hipSuccess) return e;
   }
   return hipSuccess;
+}
+
+template <typename T>
+hipError_t bwd_any(const BwdArgs& a, const Plan& p, hipStream_t s) {
+  if (p.kind == kPhiRelu) return p.d == 128 ? run_bwd<128, kPhiRelu, T>(a, p, s) : run_bwd<64, kPhiRelu, T>(a, p, s);
+  return p.d == 128 ? run_bwd<128, kPhiHedgehog, T>(a, p, s) : run_bwd<64, kPhiHedgehog, T>(a, p, s);
 }
 
 }  // namespace
 
 hipError_t launch_bwd_f32(const BwdArgs& a, const Plan& p, hipStream_t s) {
-  if (p.kind == kPhiRelu) return p.d == 128 ? run_bwd<128, kPhiRelu>(a, p, s) : run_bwd<64, kPhiRelu>(a, p, s);
-  return p.d == 128 ? run_bwd<128, kPhiHedgehog>(a, p, s) : run_bwd<64, kPhiHedgehog>(a, p, s);
+  return p.bf16_storage ? bwd_any<uint16_t>(a, p, s) : bwd_any<float>(a, p, s);
 }
 
 }  // namespace linattn

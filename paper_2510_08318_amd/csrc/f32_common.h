@@ -1,4 +1,6 @@
-// Building blocks of the fp32 (no bf16/fp16 anywhere) kernels: plain FMA on LDS tiles.
+// Building blocks of the fp32-arithmetic kernels: plain FMA on LDS tiles.  The tensors they read and write
+// are fp32 (no bf16/fp16 anywhere: the fp32 mode) or bf16 bit patterns widened exactly on load and rounded
+// to nearest even on store (the bf16-storage, fp32-arithmetic mode); the arithmetic is the same.
 #pragma once
 #include <hip/hip_runtime.h>
 #include "kernels.h"
@@ -7,6 +9,12 @@ namespace linattn {
 namespace f32 {
 
 constexpr int NT = 256;       // threads per workgroup
+
+// Element i of a stored tensor as fp32, and the store of an fp32 value: T = float or uint16_t (bf16 bits).
+__device__ __forceinline__ float ldf(const float* p, size_t i) { return p[i]; }
+__device__ __forceinline__ float ldf(const uint16_t* p, size_t i) { return __builtin_bit_cast(float, (uint32_t)p[i] << 16); }
+__device__ __forceinline__ void stf(float* p, size_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void stf(uint16_t* p, size_t i, float v) { p[i] = __builtin_bit_cast(uint16_t, (__bf16)v); }
 
 __device__ __forceinline__ float wave_max(float x) {
   for (int m = 32; m >= 1; m >>= 1) x = fmaxf(x, __shfl_xor(x, m, 64));

@@ -1,6 +1,6 @@
-// fp32 forward path (no bf16 anywhere): plain-FMA, LDS-tiled kernels.
-// This mode exists for the 1e-5 accuracy contract on fp32 tensors; the bandwidth-tuned
-// path is the bf16 one in fwd_bf16.hip.
+// fp32-arithmetic forward path: plain-FMA, LDS-tiled kernels, on fp32 tensors (no bf16 anywhere; the 1e-5
+// accuracy contract) or on bf16 tensors widened on load (LINATTN_BF16_F32MATH: bf16 storage with none of
+// the fp16 operands of the MFMA path).  The bandwidth-tuned path is the bf16 one in fwd_bf16.hip.
 #include "kernels.h"
 #include "f32_common.h"
 
@@ -10,9 +10,9 @@ namespace {
 using namespace f32;
 constexpr int TT = 32;        // tokens per tile
 
-template <int D, int KIND>
-__global__ __launch_bounds__(NT) void state_partials_f32_kernel(const float* __restrict__ k, const float* __restrict__ v,
-                                                                const float* __restrict__ wk, float* __restrict__ partials,
+template <int D, int KIND, typename T>
+__global__ __launch_bounds__(NT) void state_partials_f32_kernel(const T* __restrict__ k, const T* __restrict__ v,
+                                                                const T* __restrict__ wk, float* __restrict__ partials,
                                                                 int H, int n, int P, int chunk, Rows rw) {
   constexpr int HALF = D / 2;
   constexpr int BLK = D / 16;
@@ -26,11 +26,11 @@ __global__ __launch_bounds__(NT) void state_partials_f32_kernel(const float* __r
   const int bh = blockIdx.y, p = blockIdx.x, h = bh % H;
   const int t_begin = p * chunk;
   const int t_end = min(n, t_begin + chunk);
-  const float* kb = k + head_base(rw, bh, H);
-  const float* vb = v + head_base(rw, bh, H);
-  const float* wb = wk + (size_t)h * D * HALF;
+  const T* kb = k + head_base(rw, bh, H);
+  const T* vb = v + head_base(rw, bh, H);
+  const T* wb = wk + (size_t)h * D * HALF;
   if constexpr (KIND == kPhiHedgehog)
-    for (int i = tid; i < D * HALF; i += NT) sW[i] = wb[i];
+    for (int i = tid; i < D * HALF; i += NT) sW[i] = ldf(wb, i);
 
   float acc[BLK][BLK];
 #pragma unroll
@@ -46,8 +46,8 @@ __global__ __launch_bounds__(NT) void state_partials_f32_kernel(const float* __r
       const int tt = i / D, c = i % D;
       const int t = t0 + tt;
       const bool valid = t < t_end;
-      sX[tt * (D + 1) + c] = valid ? kb[(size_t)t * rw.sn + c] : 0.f;
-      sV[tt * D + c] = valid ? vb[(size_t)t * rw.sn + c] : 0.f;
+      sX[tt * (D + 1) + c] = valid ? ldf(kb, (size_t)t * rw.sn + c) : 0.f;
+      sV[tt * D + c] = valid ? ldf(vb, (size_t)t * rw.sn + c) : 0.f;
     }
     __syncthreads();
     phi_tile<D, TT, KIND>(sX, sW, sPhi, tid, t_end - t0);
@@ -74,10 +74,10 @@ __global__ __launch_bounds__(NT) void state_partials_f32_kernel(const float* __r
   if (tid < D) dst[D * D + tid] = zacc;
 }
 
-template <int D, int KIND>
-__global__ __launch_bounds__(NT) void apply_f32_kernel(const float* __restrict__ q, const float* __restrict__ wq,
-                                                       const float* __restrict__ state, float* __restrict__ out,
-                                                       const float* __restrict__ blend, const float* __restrict__ rptr,
+template <int D, int KIND, typename T>
+__global__ __launch_bounds__(NT) void apply_f32_kernel(const T* __restrict__ q, const T* __restrict__ wq,
+                                                       const float* __restrict__ state, T* __restrict__ out,
+                                                       const T* __restrict__ blend, const float* __restrict__ rptr,
                                                        int H, int n, int chunk, Rows rw) {
   constexpr int HALF = D / 2;
   extern __shared__ float smem[];
@@ -90,15 +90,15 @@ __global__ __launch_bounds__(NT) void apply_f32_kernel(const float* __restrict__
   const int bh = blockIdx.y, p = blockIdx.x, h = bh % H;
   const int t_begin = p * chunk;
   const int t_end = min(n, t_begin + chunk);
-  const float* qb = q + head_base(rw, bh, H);
-  float* ob = out + head_base(rw, bh, H);
+  const T* qb = q + head_base(rw, bh, H);
+  T* ob = out + head_base(rw, bh, H);
   // mixed attention (Eq. 6): out = r' s + (1 - r') o with r' = clip(r, 0, 1); off when blend is null
-  const float* bb = blend ? blend + head_base(rw, bh, H) : nullptr;
+  const T* bb = blend ? blend + head_base(rw, bh, H) : nullptr;
   const float rb = blend ? fminf(fmaxf(*rptr, 0.f), 1.f) : 0.f;
-  const float* wb = wq + (size_t)h * D * HALF;
+  const T* wb = wq + (size_t)h * D * HALF;
   const float* sb = state + (size_t)bh * (D + 1) * D;
   if constexpr (KIND == kPhiHedgehog)
-    for (int i = tid; i < D * HALF; i += NT) sW[i] = wb[i];
+    for (int i = tid; i < D * HALF; i += NT) sW[i] = ldf(wb, i);
   for (int i = tid; i < (D + 1) * D; i += NT) sS[i] = sb[i];
 
   const int tt = tid / 8, cb = tid % 8;
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(NT) void apply_f32_kernel(const float* __restrict__
     for (int i = tid; i < TT * D; i += NT) {
       const int r = i / D, c = i % D;
       const int t = t0 + r;
-      sX[r * (D + 1) + c] = (t < t_end) ? qb[(size_t)t * rw.sn + c] : 0.f;
+      sX[r * (D + 1) + c] = (t < t_end) ? ldf(qb, (size_t)t * rw.sn + c) : 0.f;
     }
     __syncthreads();
     phi_tile<D, TT, KIND>(sX, sW, sPhi, tid, t_end - t0);
@@ -127,8 +127,8 @@ __global__ __launch_bounds__(NT) void apply_f32_kernel(const float* __restrict__
 #pragma unroll
       for (int j = 0; j < D / 8; ++j) {
         float val = acc[j] * inv;
-        if (bb) val = fmaf(rb, bb[(size_t)t * rw.sn + cb + 8 * j] - val, val);
-        ob[(size_t)t * rw.sn + cb + 8 * j] = val;
+        if (bb) val = fmaf(rb, ldf(bb, (size_t)t * rw.sn + cb + 8 * j) - val, val);
+        stf(ob, (size_t)t * rw.sn + cb + 8 * j, val);
       }
     }
   }
@@ -139,38 +139,51 @@ constexpr size_t state_smem() { return sizeof(float) * (D * (D / 2) + TT * (D + 
 template <int D>
 constexpr size_t apply_smem() { return sizeof(float) * (D * (D / 2) + (D + 1) * D + TT * (D + 1) + TT * D); }
 
-template <int D, int KIND>
-hipError_t run_state(const float* k, const float* v, const float* wk, float* partials, const Plan& p, hipStream_t s) {
-  hipError_t e = set_smem_once<state_partials_f32_kernel<D, KIND>>(state_smem<D>());
+template <int D, int KIND, typename T>
+hipError_t run_state(const void* k, const void* v, const void* wk, float* partials, const Plan& p, hipStream_t s) {
+  hipError_t e = set_smem_once<state_partials_f32_kernel<D, KIND, T>>(state_smem<D>());
   if (e != hipSuccess) return e;
-  state_partials_f32_kernel<D, KIND><<<dim3(p.P, p.BH), NT, state_smem<D>(), s>>>(k, v, wk, partials, p.H, p.n, p.P, p.chunk, p.rows);
+  state_partials_f32_kernel<D, KIND, T><<<dim3(p.P, p.BH), NT, state_smem<D>(), s>>>(
+      (const T*)k, (const T*)v, (const T*)wk, partials, p.H, p.n, p.P, p.chunk, p.rows);
   return hipGetLastError();
 }
-template <int D, int KIND>
-hipError_t run_apply(const float* q, const float* wq, const float* state, float* out,
-                     const float* blend_in, const float* blend_r, const Plan& p, hipStream_t s) {
-  hipError_t e = set_smem_once<apply_f32_kernel<D, KIND>>(apply_smem<D>());
+template <int D, int KIND, typename T>
+hipError_t run_apply(const void* q, const void* wq, const float* state, void* out,
+                     const void* blend_in, const float* blend_r, const Plan& p, hipStream_t s) {
+  hipError_t e = set_smem_once<apply_f32_kernel<D, KIND, T>>(apply_smem<D>());
   if (e != hipSuccess) return e;
-  apply_f32_kernel<D, KIND><<<dim3(p.QP, p.BH), NT, apply_smem<D>(), s>>>(q, wq, state, out, blend_in, blend_r, p.H, p.n, p.qchunk, p.rows);
+  apply_f32_kernel<D, KIND, T><<<dim3(p.QP, p.BH), NT, apply_smem<D>(), s>>>(
+      (const T*)q, (const T*)wq, state, (T*)out, (const T*)blend_in, blend_r, p.H, p.n, p.qchunk, p.rows);
   return hipGetLastError();
+}
+
+template <typename T>
+hipError_t state_any(const void* k, const void* v, const void* wk, float* partials, const Plan& p, hipStream_t s) {
+  if (p.kind == kPhiRelu)
+    return p.d == 128 ? run_state<128, kPhiRelu, T>(k, v, wk, partials, p, s) : run_state<64, kPhiRelu, T>(k, v, wk, partials, p, s);
+  return p.d == 128 ? run_state<128, kPhiHedgehog, T>(k, v, wk, partials, p, s) : run_state<64, kPhiHedgehog, T>(k, v, wk, partials, p, s);
+}
+template <typename T>
+hipError_t apply_any(const void* q, const void* wq, const float* state, void* out,
+                     const void* blend_in, const float* blend_r, const Plan& p, hipStream_t s) {
+  if (p.kind == kPhiRelu)
+    return p.d == 128 ? run_apply<128, kPhiRelu, T>(q, wq, state, out, blend_in, blend_r, p, s)
+                      : run_apply<64, kPhiRelu, T>(q, wq, state, out, blend_in, blend_r, p, s);
+  return p.d == 128 ? run_apply<128, kPhiHedgehog, T>(q, wq, state, out, blend_in, blend_r, p, s)
+                    : run_apply<64, kPhiHedgehog, T>(q, wq, state, out, blend_in, blend_r, p, s);
 }
 
 }  // namespace
 
-hipError_t launch_state_partials_f32(const float* k, const float* v, const float* wk, float* partials,
+hipError_t launch_state_partials_f32(const void* k, const void* v, const void* wk, float* partials,
                                      const Plan& p, hipStream_t s) {
-  if (p.kind == kPhiRelu)
-    return p.d == 128 ? run_state<128, kPhiRelu>(k, v, wk, partials, p, s) : run_state<64, kPhiRelu>(k, v, wk, partials, p, s);
-  return p.d == 128 ? run_state<128, kPhiHedgehog>(k, v, wk, partials, p, s) : run_state<64, kPhiHedgehog>(k, v, wk, partials, p, s);
+  return p.bf16_storage ? state_any<uint16_t>(k, v, wk, partials, p, s) : state_any<float>(k, v, wk, partials, p, s);
 }
 
-hipError_t launch_apply_f32(const float* q, const float* wq, const float* state, float* out,
-                            const float* blend_in, const float* blend_r, const Plan& p, hipStream_t s) {
-  if (p.kind == kPhiRelu)
-    return p.d == 128 ? run_apply<128, kPhiRelu>(q, wq, state, out, blend_in, blend_r, p, s)
-                      : run_apply<64, kPhiRelu>(q, wq, state, out, blend_in, blend_r, p, s);
-  return p.d == 128 ? run_apply<128, kPhiHedgehog>(q, wq, state, out, blend_in, blend_r, p, s)
-                    : run_apply<64, kPhiHedgehog>(q, wq, state, out, blend_in, blend_r, p, s);
+hipError_t launch_apply_f32(const void* q, const void* wq, const float* state, void* out,
+                            const void* blend_in, const float* blend_r, const Plan& p, hipStream_t s) {
+  return p.bf16_storage ? apply_any<uint16_t>(q, wq, state, out, blend_in, blend_r, p, s)
+                        : apply_any<float>(q, wq, state, out, blend_in, blend_r, p, s);
 }
 
 }  // namespace linattn

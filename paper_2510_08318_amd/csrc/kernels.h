@@ -57,6 +57,7 @@ __host__ __device__ inline int split_owner(const Split& s, long long x) {
 struct Plan {
   int B, H, n, d;
   int kind;         // kPhiHedgehog or kPhiRelu (set by the dispatch, not by make_plan)
+  bool bf16_storage; // the fp32-arithmetic kernels read and write bf16 tensors (LINATTN_BF16_F32MATH)
   int BH;
   Rows rows;        // memory layout of the token tensors
   Split split;      // bf16 forward state pass
@@ -126,7 +127,7 @@ hipError_t set_smem_once(size_t bytes) {
 
 // ---- forward launchers (enqueue only) ---------------------------------------------------
 // phi(K) fused with the split-n partial state (Eq. 5 + the two sums of Eq. 3).
-hipError_t launch_state_partials_f32(const float* k, const float* v, const float* wk, float* partials,
+hipError_t launch_state_partials_f32(const void* k, const void* v, const void* wk, float* partials,
                                      const Plan& p, hipStream_t s);
 hipError_t launch_state_partials_bf16(const void* k, const void* v, const void* wk, float* partials,
                                       const Plan& p, hipStream_t s);
@@ -137,8 +138,8 @@ hipError_t launch_state_reduce(const float* partials, float* state, const Plan& 
 // The same for the partials of the bf16 forward state pass (slots per head follow Plan::split).
 hipError_t launch_state_reduce_split(const float* partials, float* state, const Plan& p, hipStream_t s);
 // phi(Q) S / (phi(Q) . z) and the store of out (Eq. 3, right-hand side).
-hipError_t launch_apply_f32(const float* q, const float* wq, const float* state, float* out,
-                            const float* blend_in, const float* blend_r, const Plan& p, hipStream_t s);
+hipError_t launch_apply_f32(const void* q, const void* wq, const float* state, void* out,
+                            const void* blend_in, const float* blend_r, const Plan& p, hipStream_t s);
 hipError_t launch_apply_bf16(const void* q, const void* wq, const float* state, void* out,
                              const void* blend_in, const float* blend_r, const Plan& p, hipStream_t s);
 

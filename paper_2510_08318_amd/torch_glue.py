@@ -28,10 +28,11 @@ class ReluLayer:
     """Buffers + descriptor of one linear-attention layer with the weight-free map phi(x) = max(x, 0)
     (the "ReLU" row of the paper's ablation of kernel functions)."""
 
-    def __init__(self, H: int, d: int, B: int, n: int, dtype: torch.dtype, *, layout: str = "bhnd", device="cuda"):
+    def __init__(self, H: int, d: int, B: int, n: int, dtype: torch.dtype, *, layout: str = "bhnd", device="cuda",
+                 f32_math: bool = False):
         assert layout in ("bhnd", "bnhd") and dtype in (torch.bfloat16, torch.float32)
         self.layout, self.H, self.d, self.B, self.n, self.tdtype = layout, H, d, B, n, dtype
-        self.dtype = B_.BF16 if dtype == torch.bfloat16 else B_.F32
+        self.dtype = (B_.BF16_F32MATH if f32_math else B_.BF16) if dtype == torch.bfloat16 else B_.F32
         self.state = torch.empty((B, H, d + 1, d), dtype=torch.float32, device=device)
         self.workspace_bytes = B_.linattn_workspace_bytes(B, H, n, d, B_.PHI_RELU, self.dtype)
         if self.workspace_bytes == 0:
@@ -78,15 +79,16 @@ class Layer:
     """Buffers + descriptor of one linear-attention layer (Eq. 3 with the map of Eq. 5)."""
 
     def __init__(self, wq: torch.Tensor, wk: torch.Tensor, B: int, n: int, *, keep_state: bool = True,
-                 want_wgrads: bool = False, layout: str = "bhnd"):
+                 want_wgrads: bool = False, layout: str = "bhnd", f32_math: bool = False):
         """layout "bhnd": q, k, v, out are [B, H, n, d]; "bnhd": [B, n, H, d] (heads interleaved per token).
-        want_wgrads: False, True (both dW~_q and dW~_k), or "q" / "k" for one of them."""
+        want_wgrads: False, True (both dW~_q and dW~_k), or "q" / "k" for one of them.
+        f32_math (bf16 tensors only): fp32 arithmetic on the bf16 tensors (LINATTN_BF16_F32MATH)."""
         assert layout in ("bhnd", "bnhd")
         self.layout = layout
         assert wq.is_cuda and wk.is_cuda and wq.dtype == wk.dtype and wq.shape == wk.shape
         self.H, self.d, half = wq.shape
         assert half * 2 == self.d
-        self.dtype = B_.BF16 if wq.dtype == torch.bfloat16 else B_.F32
+        self.dtype = (B_.BF16_F32MATH if f32_math else B_.BF16) if wq.dtype == torch.bfloat16 else B_.F32
         assert wq.dtype in (torch.bfloat16, torch.float32)
         self.wq, self.wk = wq.contiguous(), wk.contiguous()
         self.B, self.n = B, n

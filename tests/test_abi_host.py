@@ -218,3 +218,24 @@ def test_noalloc_forward_checks_arguments_and_its_limit_on_the_host():
         L.linattn_phi_destroy(pid)
     # the task's largest configuration fits: partials + states of config 4 (B=2, H=40, n=75600, d=128)
     assert L.linattn_workspace_bytes(2, 40, 75600, 128, L.PHI_HEDGEHOG, L.BF16) > 0
+
+
+def test_bf16_storage_fp32_arithmetic_dtype_is_accepted_on_the_host():
+    """LINATTN_BF16_F32MATH: sized like the fp32 mode's plan (no operand images), tensors of 2 bytes per element."""
+    header = open(os.path.join(ROOT, "include", "linattn.h")).read()
+    assert re.search(r"#define\s+LINATTN_BF16_F32MATH\s+3\b", header) and L.BF16_F32MATH == 3
+    assert L.linattn_workspace_bytes(1, 2, 1000, 128, L.PHI_HEDGEHOG, L.BF16_F32MATH) > 0
+    assert L.linattn_workspace_bytes(1, 2, 1000, 128, L.PHI_HEDGEHOG, 4) == 0
+    H, d = 2, 128
+    ws = L.linattn_workspace_bytes(1, H, 500, d, L.PHI_HEDGEHOG, L.BF16_F32MATH)
+    pid = L.linattn_phi_create(L.PHI_HEDGEHOG, L.BF16_F32MATH, H, d, P, P + 65536, workspace=P + (1 << 20), workspace_bytes=ws)
+    big = 1 << 30
+    q, k, v, o = P + big, P + 2 * big, P + 3 * big, P + 4 * big
+    try:
+        # tensors are 2 bytes per element: out right behind q (B*H*n*d*2 bytes further) does not alias it
+        nbytes = 1 * H * 500 * d * 2
+        assert L.linattn_fwd(q, k, v, q + nbytes - 16, 1, H, 500, d, pid, None, check=False) == L.E_ALIAS
+        assert L.linattn_fwd(None, k, v, o, 1, H, 500, d, pid, None, check=False) == L.E_NULL
+    finally:
+        L.linattn_phi_destroy(pid)
+    assert L.linattn_phi_create(L.PHI_HEDGEHOG, 4, H, d, P, P + 65536, check=False) == L.E_DTYPE
