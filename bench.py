@@ -206,12 +206,14 @@ SECONDARY = (
     ("bwd C5 without weight gradients", "C5", "bwd", {"wgrads": False}),
     ("bwd C5 ReLU map", "C5", "bwd", {"relu": True}),
     ("bwd C3 shape with weight gradients", "C3", "bwd", {}),
+    ("fwd C3 with LINATTN_FLAG_CENTRED", "C3", "fwd", {"centred": True}),
+    ("bwd C5 with weight gradients and LINATTN_FLAG_CENTRED", "C5", "bwd", {"centred": True}),
     ("fwd C2, bf16 tensors with fp32 arithmetic (LINATTN_BF16_F32MATH)", "C2", "fwd", {"f32math": True, "steps": 20}),
     ("bwd C5, bf16 tensors with fp32 arithmetic (LINATTN_BF16_F32MATH)", "C5", "bwd", {"f32math": True, "steps": 10}),
 )
 
 
-def quick_time(workload, which, *, layout="bhnd", blend=False, relu=False, wgrads=True, f32math=False, steps=200):
+def quick_time(workload, which, *, layout="bhnd", blend=False, relu=False, wgrads=True, f32math=False, centred=False, steps=200):
     """One secondary workload, timed like the headline one (pre-warm, then `steps` calls by the wall
     clock, inputs resident in HBM, buffer sets rotated below the cache scale)."""
     import torch
@@ -225,7 +227,7 @@ def quick_time(workload, which, *, layout="bhnd", blend=False, relu=False, wgrad
     if relu:
         lay = G.ReluLayer(x.H, x.d, x.B, x.n, t["q"].dtype, layout=layout, f32_math=f32math)
     else:
-        lay = G.Layer(wq, wk, x.B, x.n, want_wgrads=(which == "bwd" and wgrads), layout=layout, f32_math=f32math)
+        lay = G.Layer(wq, wk, x.B, x.n, want_wgrads=(which == "bwd" and wgrads), layout=layout, f32_math=f32math, centred=centred)
     if blend:
         lay.set_blend((torch.randn(t["q"].shape, device="cuda") * 0.1).to(t["q"].dtype), torch.tensor([0.5], device="cuda"))
     outs = ("out",) if which == "fwd" else ("dq", "dk", "dv")

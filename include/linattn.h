@@ -50,6 +50,7 @@
  *     dk, and dq, dv, dW~_q everywhere, meet 1e-2.  Second exception: where phi is within a few per
  *     cent of uniform (the spread of x W~ over the features far below 1), dq, dk and dW~ are
  *     differences of nearly equal rows of S and dS and come out up to 0.2 off; out and dv keep 1e-2.
+ *     LINATTN_FLAG_CENTRED removes this exception (not the first) at a cost of 3-4 %.
  *   - LINATTN_BF16_F32MATH reads and writes the same bf16 tensors but does all arithmetic in fp32
  *     (the kernels of the fp32 mode, no matrix cores, no fp16 operands): none of the limits above
  *     applies, |v| may be any finite bf16 value, and the only rounding that matters is the bf16
@@ -93,6 +94,18 @@ extern "C" {
 #define LINATTN_F32   2          /* fp32 tensors, fp32 arithmetic */
 #define LINATTN_BF16_F32MATH 3   /* bf16 tensors, fp32 arithmetic (see "Numeric domain" above) */
 
+/* descriptor flags */
+#define LINATTN_FLAG_CENTRED 1u  /* LINATTN_BF16 with the map of Eq. 5: every fp16 operand that carries phi or a state is
+                                    rounded after its mean has been taken out -- phi - 2/d in the two sums over tokens
+                                    (state pass: S, z; query-side backward: dS, dz), with (2/d) x the column sums of v
+                                    resp. of dout/den added back in fp32; operand images of S - z vbar^T (vbar the
+                                    head's mean value row) and of dS, dz minus their means over each half's features,
+                                    which the softmax Jacobian drops (dv gets the constant row back).  Exact in real
+                                    arithmetic; the roundings then act on the deviation of phi from the uniform map, so
+                                    the regime where phi is within a few per cent of uniform meets the 1e-2 contract
+                                    for all five gradients.  Costs about 3 % of the forward (8 % of its state pass) and
+                                    4 % of the backward.  A layer uses one setting for its forward and backward calls. */
+
 /* memory layouts of q, k, v, out, dout, dq, dk, dv */
 #define LINATTN_LAYOUT_BHND  0   /* element (b,h,t,c) at ((b*H + h)*n + t)*d + c */
 #define LINATTN_LAYOUT_BNHD  1   /* element (b,h,t,c) at ((b*n + t)*H + h)*d + c */
@@ -134,10 +147,11 @@ typedef struct linattn_phi_desc {
                              touches B * H * (d+1) * d * 4 of them: linattn_phi_create returns E_STATE if
                              not even B = 1 fits, linattn_fwd / linattn_bwd return E_STATE for a B that
                              does not fit. */
+  unsigned flags;         /* 0, or LINATTN_FLAG_CENTRED (Eq. 5 map with LINATTN_BF16 only: E_PHI otherwise) */
 } linattn_phi_desc;
 
 /* Register a descriptor; *phi_id_out receives a handle >= 16.  Host-only, no HIP call.
- * Errors: E_NULL (desc, out, wq, wk), E_PHI (kind, table full), E_DTYPE, E_SHAPE (H, d, layout),
+ * Errors: E_NULL (desc, out, wq, wk), E_PHI (kind, table full, flags that do not fit kind or dtype), E_DTYPE, E_SHAPE (H, d, layout),
  * E_ALIGN, E_STATE (state given with state_bytes < H * (d+1) * d * 4). */
 int linattn_phi_create(const linattn_phi_desc* desc, int* phi_id_out);
 

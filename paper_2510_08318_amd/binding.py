@@ -18,6 +18,7 @@ PHI_HEDGEHOG = 1
 PHI_RELU = 2
 BF16, F32, BF16_F32MATH = 1, 2, 3
 LAYOUT_BHND, LAYOUT_BNHD = 0, 1
+FLAG_CENTRED = 1
 
 EXPORTS = ("linattn_phi_create", "linattn_phi_destroy", "linattn_workspace_bytes", "linattn_workspace_bytes_wgrads",
            "linattn_fwd", "linattn_fwd_noalloc", "linattn_bwd", "linattn_strerror", "linattn_set_stage_events", "linattn_phi_set_blend")
@@ -33,6 +34,7 @@ class PhiDesc(ctypes.Structure):
         ("layout", ctypes.c_int),
         ("blend_in", ctypes.c_void_p), ("blend_r", ctypes.c_void_p), ("blend_dr", ctypes.c_void_p),
         ("state_bytes", ctypes.c_size_t),
+        ("flags", ctypes.c_uint),
     ]
 
 
@@ -101,13 +103,13 @@ def linattn_workspace_bytes_wgrads(B: int, H: int, n: int, d: int, kind: int = P
 def linattn_phi_create(kind, dtype, H, d, wq, wk, dwq=None, dwk=None, state=None,
                        workspace=None, workspace_bytes: int = 0, layout: int = 0,
                        blend_in=None, blend_r=None, blend_dr=None, state_bytes: Optional[int] = None,
-                       *, check: bool = True) -> int:
+                       *, flags: int = 0, check: bool = True) -> int:
     """state_bytes defaults to the size of `state` when that is a tensor."""
     if state_bytes is None:
         state_bytes = 0 if state is None or isinstance(state, int) else state.numel() * state.element_size()
     desc = PhiDesc(int(kind), int(dtype), int(H), int(d), _ptr(wq), _ptr(wk), _ptr(dwq), _ptr(dwk),
                    _ptr(state), _ptr(workspace), int(workspace_bytes), int(layout),
-                   _ptr(blend_in), _ptr(blend_r), _ptr(blend_dr), int(state_bytes))
+                   _ptr(blend_in), _ptr(blend_r), _ptr(blend_dr), int(state_bytes), int(flags))
     out = ctypes.c_int(-1)
     st = lib().linattn_phi_create(ctypes.byref(desc), ctypes.byref(out))
     if st != OK:

@@ -74,6 +74,7 @@ bool make_plan(int B, int H, int n, int d, int dtype, int layout, Plan* p) {
   r.off_dgimg = off;    off = up(off + (size_t)BH * d * d * 2);
   r.off_wimg = off;     off = up(off + (size_t)H * 4 * d * d);
   r.off_scales = off;   off = up(off + (size_t)BH * 2 * sizeof(float));
+  r.off_centre = off;   off = up(off + ((size_t)BH * 3 * d + (size_t)BH * r.P * (d + 8)) * sizeof(float));
   r.off_drpart = off;   off = up(off + ((size_t)BH * r.P + kDotParts) * sizeof(float));
   r.bytes_no_wgrads = off;
   r.off_dwpart = off;   off = up(off + 2 * (size_t)BH * r.P * d * (d / 2) * sizeof(float));
@@ -155,6 +156,7 @@ int check_call(const void* const* tensors, int n_tensors, int B, int H, int n, i
   if (H != desc->H || d != desc->d) return LINATTN_E_SHAPE;
   if (!make_plan(B, H, n, d, desc->dtype, desc->layout, plan)) return LINATTN_E_SHAPE;
   plan->kind = desc->kind;
+  plan->centred = (desc->flags & LINATTN_FLAG_CENTRED) != 0;
   for (int i = 0; i < n_tensors; ++i)
     if (!aligned16(tensors[i])) return LINATTN_E_ALIGN;
   const size_t need = (want_wgrads && (desc->dwq || desc->dwk)) ? plan->total_bytes : plan->bytes_no_wgrads;
@@ -291,6 +293,8 @@ int linattn_phi_create(const linattn_phi_desc* desc, int* phi_id_out) {
     if (desc->dwq && !aligned16(desc->dwq)) return LINATTN_E_ALIGN;
     if (desc->dwk && !aligned16(desc->dwk)) return LINATTN_E_ALIGN;
   }
+  if (desc->flags & ~LINATTN_FLAG_CENTRED) return LINATTN_E_PHI;
+  if ((desc->flags & LINATTN_FLAG_CENTRED) && (desc->kind != LINATTN_PHI_HEDGEHOG || desc->dtype != LINATTN_BF16)) return LINATTN_E_PHI;
   if (desc->state && !aligned16(desc->state)) return LINATTN_E_ALIGN;
   if (desc->state && desc->state_bytes < (size_t)desc->H * (desc->d + 1) * desc->d * sizeof(float)) return LINATTN_E_STATE;
   if (desc->workspace && (reinterpret_cast<uintptr_t>(desc->workspace) & 255u)) return LINATTN_E_ALIGN;
@@ -383,6 +387,10 @@ int linattn_bwd(const void* q, const void* k, const void* v, const void* dout,
   a.dgimg = ws + plan.off_dgimg;
   a.wimg = ws + plan.off_wimg;
   a.scales = reinterpret_cast<float*>(ws + plan.off_scales);
+  a.vbar = reinterpret_cast<float*>(ws + plan.off_centre);
+  a.dv_row = a.vbar + (size_t)plan.BH * d;
+  a.dzc = a.dv_row + (size_t)plan.BH * d;
+  a.cs_part = a.dzc + (size_t)plan.BH * d;
   a.blend_in = desc.blend_in; a.blend_r = desc.blend_r; a.blend_dr = desc.blend_dr;
   a.dr_part = reinterpret_cast<float*>(ws + plan.off_drpart);
   a.dw_part = reinterpret_cast<float*>(ws + plan.off_dwpart);

@@ -40,11 +40,28 @@ namespace {
 // 512 threads: staging the state is latency, not bandwidth (256 threads: 16.8 + 10.8 us for the two
 // passes at config 5, 512: 11.9 + 8.3 us, 1024 the same; more slices per head change nothing).
 constexpr int PT = 512, PREP_Y = 8;
-template <int D, bool WQK>
+// Both passes centre the state before it is rounded to fp16 operands (exact in real arithmetic; the roundings
+// then act on what the gradients are made of instead of on a common part that cancels):
+//   pass over S:  S^c = S - z vbar^T with vbar = sum_j v_j / n (the + half of S sums to sum_j v_j, the + half
+//                 of z to n).  The query-side kernel then works with o - vbar and delta^c = delta - dO . vbar, g is
+//                 unchanged, and its dz comes out as dz^c = dz + dS vbar.
+//   pass over dS: the key-side dz is completed against the ROUNDED image: dzc[f] = dz^c[f] - vbar . r(dS[f]), so
+//                 that v_j . r(dS[f]) + dzc[f] = (v_j - vbar) . r(dS[f]) + dz^c[f] holds exactly and the rounding
+//                 of the image acts on v_j - vbar, not on v_j (values with a common offset cost nothing).
+//   CENTRE (LINATTN_FLAG_CENTRED): the query-side kernel accumulated dS' = sum (phi - 2/D)^T dO/den and dz' likewise;
+//                 (2/D) x its column sums (cs_part) complete them: dS = dS' + (2/D) 1 colsum^T (constant over the
+//                 features: it only enters the row that dv gets back), dz^c = dz' + (2/D) wsum.  In addition the
+//                 mean over each half's features is taken out of dS' and of dz^c: the softmax Jacobian drops what
+//                 is constant over a half, and dv gets the constant row mean_+ + mean_- back.  (Without the flag
+//                 this last step is left out: where phi is spiky the rows of dS differ by orders of magnitude and
+//                 a common shift only adds rounding error to the small ones.)
+template <int D, bool WQK, bool CENTRE>
 __global__ __launch_bounds__(PT) void bwd_prep_kernel(const float* __restrict__ state, uint4* __restrict__ gimg,
                                                        uint4* __restrict__ simg, float* __restrict__ scale_out,
                                                        const uint16_t* __restrict__ wq, const uint16_t* __restrict__ wk,
-                                                       uint4* __restrict__ wimg, int H) {
+                                                       uint4* __restrict__ wimg, int H,
+                                                       float* __restrict__ vbar, float* __restrict__ dv_row, float* __restrict__ dzc,
+                                                       const float* __restrict__ cs_part, int P) {
   using C = Cfg<D>;
   using L = ApplyLayout<D>;
   using G = GradLayout<D>;
@@ -73,8 +90,73 @@ __global__ __launch_bounds__(PT) void bwd_prep_kernel(const float* __restrict__ 
     }
   }
   __syncthreads();
+  __shared__ float cA[D], cB[D], cC[D];
+  constexpr int HF = D / 2;
+  if constexpr (WQK) {
+    if (tid < D) {
+      float sv = 0.f, nt = 0.f;
+      for (int f = 0; f < HF; ++f) { sv += S[f * D + tid]; nt += S[D * D + f]; }
+      const float vb = sv / nt;
+      cA[tid] = vb;
+      if (blockIdx.y == 0) vbar[(size_t)bh * D + tid] = vb;
+    }
+    __syncthreads();
+    for (int i = tid; i < D * D; i += PT) S[i] -= S[D * D + i / D] * cA[i % D];
+    __syncthreads();
+  } else {
+    // colsum (cA) and wsum of the query-side workgroups, in a fixed order (CENTRE only); vbar (cC)
+    if (tid < D) {
+      float t = 0.f;
+      if constexpr (CENTRE)
+        for (int p = 0; p < P; ++p) t += cs_part[((size_t)bh * P + p) * (D + 8) + tid];
+      cA[tid] = t;
+      cC[tid] = vbar[(size_t)bh * D + tid];
+    } else if (tid == D) {
+      float t = 0.f;
+      if constexpr (CENTRE)
+        for (int p = 0; p < P; ++p) t += cs_part[((size_t)bh * P + p) * (D + 8) + D];
+      red[0] = t;
+    }
+    __syncthreads();
+    const float wsum = red[0];
+    // means over each half: of dS per channel (thread = channel); dz^c (cB)
+    float m0 = 0.f, m1 = 0.f;
+    if (tid < D) {
+      for (int f = 0; f < HF; ++f) { m0 += S[f * D + tid]; m1 += S[(HF + f) * D + tid]; }
+      m0 *= 1.0f / HF; m1 *= 1.0f / HF;
+      if constexpr (!CENTRE) { m0 = 0.f; m1 = 0.f; }
+      if (blockIdx.y == 0) dv_row[(size_t)bh * D + tid] = (m0 + m1) + (4.0f / D) * cA[tid];
+      cB[tid] = S[D * D + tid] + (2.0f / D) * wsum;
+    }
+    __syncthreads();
+    if (tid < D) cA[tid] = m0;
+    __syncthreads();
+    for (int i = tid; i < HF * D; i += PT) S[i] -= cA[i % D];
+    __syncthreads();
+    if (tid < D) cA[tid] = m1;
+    if (tid == D) {
+      float a = 0.f, b = 0.f;
+      for (int f = 0; f < HF; ++f) { a += cB[f]; b += cB[HF + f]; }
+      red[0] = CENTRE ? a * (1.0f / HF) : 0.f; red[1] = CENTRE ? b * (1.0f / HF) : 0.f;
+    }
+    __syncthreads();
+    for (int i = HF * D + tid; i < D * D; i += PT) S[i] -= cA[i % D];
+    if (tid < D) {
+      cB[tid] -= tid < HF ? red[0] : red[1];
+      S[D * D + tid] = 0.f;            // the image's z block is not used on the key side and stays out of the scale
+    }
+    __syncthreads();
+  }
   const float scale = head_scale<D, PT>(S, red, tid);      // every block of a head computes the same value
   if (blockIdx.y == 0 && tid == 0) scale_out[2 * bh] = scale;
+  if constexpr (!WQK) {
+    if (blockIdx.y == 0 && tid < D) {
+      const float inv = __builtin_amdgcn_rcpf(scale);       // exact: a power of two
+      float dot = 0.f;
+      for (int ch = 0; ch < D; ++ch) dot = fmaf((float)(_Float16)(scale * S[tid * D + ch]), cC[ch], dot);
+      dzc[(size_t)bh * D + tid] = cB[tid] - dot * inv;
+    }
+  }
   const int first = blockIdx.y * PT + tid, step = PT * gridDim.y;
   for (int idx = first; idx < G::IMG; idx += step) gimg[(size_t)bh * G::IMG + idx] = grad_image_entry<D>(S, scale, idx);
   for (int idx = first; idx < SIMG; idx += step) simg[(size_t)bh * SIMG + idx] = state_image_entry<D, !WQK>(S, scale, idx);
@@ -194,7 +276,7 @@ __device__ __forceinline__ void du_to_dx(const float (&du)[Cfg<D>::LOC], const u
 // BLEND: dout is the gradient of the mixed output of Eq. 6; the linear branch receives
 // (1 - r') dout, and the workgroup's part of -sum dout . o goes to dr_part (dL/dr = sum dout . (s - o);
 // the sum dout . s is a separate streaming dot product, taken only when dL/dr is asked for).
-template <int D, bool BLEND>
+template <int D, bool BLEND, bool CENTRE>
 __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ dout,
                                                    const uint16_t* __restrict__ wq, const float* __restrict__ state,
                                                    const uint4* __restrict__ gimg, const uint4* __restrict__ simg,
@@ -203,6 +285,7 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
                                                    float* __restrict__ partials, uint4* __restrict__ du_img, float* __restrict__ du_its,
                                                    const uint16_t* __restrict__ blend, const float* __restrict__ rptr,
                                                    float* __restrict__ dr_part,
+                                                   float* __restrict__ cs_part,
                                                    int H, int n, int P, Rows rw) {
   using C = Cfg<D>;
   using L = ApplyLayout<D>;
@@ -212,11 +295,12 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
   constexpr int SA_IMG = L::KS * L::MBZ * 64;
   constexpr int WB_IMG = (C::LOC / 8) * L::MB * 64;
   constexpr int DU_BLK = 2 * (C::HALF / 32) * 64;          // 16-byte entries of one block's du image
+  constexpr float kMean = 2.0f / D;                        // mean of phi over its features
   extern __shared__ uint4 smem[];
   uint4* sWA = smem;
   uint4* sSA = sWA + C::W_IMG;
   uint4* sWB = sSA + SA_IMG;
-  char* sPhi = reinterpret_cast<char*>(sWB + WB_IMG);      // [kTile][D] fp16: phi(q)
+  char* sPhi = reinterpret_cast<char*>(sWB + WB_IMG);      // [kTile][D] fp16: phi(q) (CENTRE: phi(q) - 2/D)
   char* sDO = sPhi + kTile * RS;                           // [kTile][D] fp16: gamma * dO / den
   uint16_t* sW16 = reinterpret_cast<uint16_t*>(sDO + kTile * RS);   // [kTile] fp16: -gamma * delta / den
   float* sZ = reinterpret_cast<float*>(sW16 + kTile);      // [D] z, unscaled
@@ -244,6 +328,9 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
   for (int i = tid; i < D; i += NT) sZ[i] = sb[D * D + i];
   __syncthreads();
 
+  float csum[WMN], wsum = 0.f;                     // column sums of the dO/den operand, sum of the -delta/den operand
+#pragma unroll
+  for (int j = 0; j < WMN; ++j) csum[j] = 0.f;
   f32x16 s[WMN][WMN], zacc;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
@@ -336,7 +423,9 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
 #pragma unroll
     for (int c = 0; c < D / 2; ++c) { delta = fmaf(dof[c], o[c], delta); dmax = fmaxf(dmax, fabsf(dof[c])); }
     if constexpr (BLEND) {
-      if (valid) dr_acc -= delta;      // the -dout . o part of dout . (s - o), on this lane's channels
+      // the -dout . o part of dout . (s - o), on this lane's channels; the images are centred, so o here is
+      // o - vbar: the other part of the sum is taken as dout . (s - vbar) to match
+      if (valid) dr_acc -= delta;
     }
     float lo, hi;
     pair32(delta, lo, hi); delta = lo + hi;
@@ -356,6 +445,11 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
       const float m = fmaxf(fmaxf(sRed[0], sRed[1]), fmaxf(sRed[2], sRed[3]));
       const float ratio = gamma_step(gamma, gamma_for(m));
       if (ratio != 1.f) {                        // this tile is larger than every earlier one
+        if constexpr (CENTRE) {
+          wsum *= ratio;
+#pragma unroll
+          for (int j = 0; j < WMN; ++j) csum[j] *= ratio;
+        }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           zacc[r] *= ratio;
@@ -371,10 +465,19 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
       constexpr int CPH = C::LOC / 8;
 #pragma unroll
       for (int c = 0; c < CPH; ++c) {
+        // CENTRE: phi minus its mean over the features, rounded after the subtraction: the fp16 rounding then acts
+        // on the deviation from the uniform map; (2/D) x the column sums are added back by the prep kernel
         uint4 a, b;
-        a.x = pk[4 * c]; a.y = pk[4 * c + 1]; a.z = pk[4 * c + 2]; a.w = pk[4 * c + 3];
-        b.x = pk[C::LOC / 2 + 4 * c]; b.y = pk[C::LOC / 2 + 4 * c + 1];
-        b.z = pk[C::LOC / 2 + 4 * c + 2]; b.w = pk[C::LOC / 2 + 4 * c + 3];
+        if constexpr (CENTRE) {
+          a.x = pack_f16x2(pp[8 * c] - kMean, pp[8 * c + 1] - kMean);     a.y = pack_f16x2(pp[8 * c + 2] - kMean, pp[8 * c + 3] - kMean);
+          a.z = pack_f16x2(pp[8 * c + 4] - kMean, pp[8 * c + 5] - kMean); a.w = pack_f16x2(pp[8 * c + 6] - kMean, pp[8 * c + 7] - kMean);
+          b.x = pack_f16x2(pm[8 * c] - kMean, pm[8 * c + 1] - kMean);     b.y = pack_f16x2(pm[8 * c + 2] - kMean, pm[8 * c + 3] - kMean);
+          b.z = pack_f16x2(pm[8 * c + 4] - kMean, pm[8 * c + 5] - kMean); b.w = pack_f16x2(pm[8 * c + 6] - kMean, pm[8 * c + 7] - kMean);
+        } else {
+          a.x = pk[4 * c]; a.y = pk[4 * c + 1]; a.z = pk[4 * c + 2]; a.w = pk[4 * c + 3];
+          b.x = pk[C::LOC / 2 + 4 * c]; b.y = pk[C::LOC / 2 + 4 * c + 1];
+          b.z = pk[C::LOC / 2 + 4 * c + 2]; b.w = pk[C::LOC / 2 + 4 * c + 3];
+        }
         if (!valid) { a = make_uint4(0, 0, 0, 0); b = a; }
         *reinterpret_cast<uint4*>(rowp + (((g * CPH + c) ^ psw) * 16)) = a;
         *reinterpret_cast<uint4*>(rowp + (((C::CH / 2 + g * CPH + c) ^ psw) * 16)) = b;
@@ -449,11 +552,24 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
     }
 
     __syncthreads();
-    contract_tile<D>(sPhi, sDO, offA, offB, s, zacc, ni != 0, do_z,
-                     [&](int ks) { return as_f16x8(*reinterpret_cast<const uint4*>(sW16 + 16 * ks + 8 * g)); });
+    contract_tile<D, false, CENTRE>(sPhi, sDO, offA, offB, s, zacc, ni != 0, do_z,
+                     [&](int ks) { return as_f16x8(*reinterpret_cast<const uint4*>(sW16 + 16 * ks + 8 * g)); }, csum, &wsum);
   }
 
   const float ig = __builtin_amdgcn_rcpf(gamma);    // exact: gamma is a power of two
+  if constexpr (CENTRE) {
+    // column sums of dO/den (the wavefronts mi = 0 hold every channel block once) and the sum of -delta/den
+    float* cs = cs_part + ((size_t)bh * P + p) * (D + 8);
+#pragma unroll
+    for (int j = 0; j < WMN; ++j) {
+      float lo, hi;
+      pair32(csum[j], lo, hi);
+      if (mi == 0 && g == 0) cs[32 * (ni * WMN + j) + (lane % 32)] = (lo + hi) * ig;
+    }
+    float lo, hi;
+    pair32(wsum, lo, hi);
+    if (w == 0 && lane == 0) cs[D] = (lo + hi) * ig;
+  }
   float* dst = partials + ((size_t)bh * P + p) * (size_t)(D + 1) * D;
   const int c = lane % 32;
 #pragma unroll
@@ -491,7 +607,9 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
                                                     const uint4* __restrict__ dsimg, const uint4* __restrict__ dgimg,
                                                     const uint4* __restrict__ wimg, const float* __restrict__ scales,
                                                     uint16_t* __restrict__ dk, uint16_t* __restrict__ dv,
-                                                    uint4* __restrict__ du_img, float* __restrict__ du_its, int H, int n, Rows rw) {
+                                                    uint4* __restrict__ du_img, float* __restrict__ du_its,
+                                                    const float* __restrict__ dzc, const float* __restrict__ dv_row,
+                                                    int H, int n, Rows rw) {
   using C = Cfg<D>;
   using L = ApplyLayout<D>;
   using G = GradLayout<D>;
@@ -522,9 +640,14 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
   copy_image<NTK>(dsimg + (size_t)bh * SA_IMG, sVA, SA_IMG, tid);
   copy_image<NTK>(dgimg + (size_t)bh * G::IMG, sGA, G::IMG, tid);
   const float scale = scales[2 * bh + 1];
-  for (int i = tid; i < D; i += NTK) sZ[i] = ds[D * D + i];
+  // dzc is dz matched to the rounded image of dS (and, with LINATTN_FLAG_CENTRED, to its centring over the
+  // features, for which dv gets a constant row back): see bwd_prep_kernel
+  for (int i = tid; i < D; i += NTK) sZ[i] = dzc[(size_t)bh * D + i];
   __syncthreads();
   const float inv_scale = __builtin_amdgcn_rcpf(scale);    // exact: power of two
+  float dv_add[L::MB];
+#pragma unroll
+  for (int mb = 0; mb < L::MB; ++mb) dv_add[mb] = dv_row[(size_t)bh * D + L::MB * (lane % 32) + mb];
 
   const int nblk = (n + 31) / 32;
   const int stride = gridDim.x * NW;
@@ -571,7 +694,7 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
             uint4 aq; aq.x = pk[4 * ks]; aq.y = pk[4 * ks + 1]; aq.z = pk[4 * ks + 2]; aq.w = pk[4 * ks + 3];
             va[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(aq), as_f16x8(b), va[mb], 0, 0, 0);
           });
-      store_token_rows<D>(dvb, rw.sn, b * 32, n, lane, va, inv_scale);
+      store_token_rows<D>(dvb, rw.sn, b * 32, n, lane, va, inv_scale, dv_add);
     }
 
     // g = v dS^T + dz, rows laid out like phi
@@ -757,7 +880,7 @@ constexpr size_t k_smem() {
   return sizeof(uint4) * (Cfg<D>::W_IMG + ApplyLayout<D>::KS * ApplyLayout<D>::MBZ * 64 + GradLayout<D>::IMG
                           + (Cfg<D>::LOC / 8) * ApplyLayout<D>::MB * 64) + (D + 8) * sizeof(float);
 }
-template <int D>
+template <int D, bool CENTRE>
 hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   hipError_t e;
   // a dL/du region: the blocks' operand images, then (256-byte aligned) one inverse scale per block
@@ -766,41 +889,42 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   uint4* duk = reinterpret_cast<uint4*>(a.du_k);
   float* duq_its = reinterpret_cast<float*>(reinterpret_cast<char*>(a.du_q) + du_img_bytes);
   float* duk_its = reinterpret_cast<float*>(reinterpret_cast<char*>(a.du_k) + du_img_bytes);
-  if ((e = set_smem_once<bwd_prep_kernel<D, true>>(prep_smem_bytes<D>())) != hipSuccess) return e;
-  if ((e = set_smem_once<bwd_prep_kernel<D, false>>(prep_smem_bytes<D>())) != hipSuccess) return e;
-  bwd_prep_kernel<D, true><<<dim3(p.BH, PREP_Y), PT, prep_smem_bytes<D>(), s>>>(a.state, (uint4*)a.gimg, (uint4*)a.simg, a.scales,
-                                                       (const uint16_t*)a.wq, (const uint16_t*)a.wk, (uint4*)a.wimg, p.H);
+  if ((e = set_smem_once<bwd_prep_kernel<D, true, CENTRE>>(prep_smem_bytes<D>())) != hipSuccess) return e;
+  if ((e = set_smem_once<bwd_prep_kernel<D, false, CENTRE>>(prep_smem_bytes<D>())) != hipSuccess) return e;
+  bwd_prep_kernel<D, true, CENTRE><<<dim3(p.BH, PREP_Y), PT, prep_smem_bytes<D>(), s>>>(a.state, (uint4*)a.gimg, (uint4*)a.simg, a.scales,
+                                                       (const uint16_t*)a.wq, (const uint16_t*)a.wk, (uint4*)a.wimg, p.H,
+                                                       a.vbar, nullptr, nullptr, nullptr, p.P);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (a.blend_in) {
-    if ((e = set_smem_once<bwd_q_kernel<D, true>>(q_smem<D>())) != hipSuccess) return e;
-    bwd_q_kernel<D, true><<<dim3(p.P, p.BH), NT, q_smem<D>(), s>>>(
+    if ((e = set_smem_once<bwd_q_kernel<D, true, CENTRE>>(q_smem<D>())) != hipSuccess) return e;
+    bwd_q_kernel<D, true, CENTRE><<<dim3(p.P, p.BH), NT, q_smem<D>(), s>>>(
         (const uint16_t*)a.q, (const uint16_t*)a.dout, (const uint16_t*)a.wq, a.state, (const uint4*)a.gimg,
         (const uint4*)a.simg, (const uint4*)a.wimg, a.scales,
         (uint16_t*)a.dq, a.partials, a.dwq ? duq : nullptr, duq_its,
-        (const uint16_t*)a.blend_in, a.blend_r, a.dr_part, p.H, p.n, p.P, p.rows);
+        (const uint16_t*)a.blend_in, a.blend_r, a.dr_part, a.cs_part, p.H, p.n, p.P, p.rows);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (a.blend_dr) {
-      if ((e = launch_dot_bf16(a.dout, a.blend_in, (size_t)p.BH * p.n * D, a.dr_part + (size_t)p.BH * p.P, s)) != hipSuccess) return e;
+      if ((e = launch_dot_centred_bf16(a.dout, a.blend_in, a.vbar, a.dr_part + (size_t)p.BH * p.P, p, s)) != hipSuccess) return e;
       if ((e = launch_dr_reduce(a.dr_part, p.BH * p.P + kDotParts, a.blend_r, a.blend_dr, s)) != hipSuccess) return e;
     }
   } else {
-    if ((e = set_smem_once<bwd_q_kernel<D, false>>(q_smem<D>())) != hipSuccess) return e;
-    bwd_q_kernel<D, false><<<dim3(p.P, p.BH), NT, q_smem<D>(), s>>>(
+    if ((e = set_smem_once<bwd_q_kernel<D, false, CENTRE>>(q_smem<D>())) != hipSuccess) return e;
+    bwd_q_kernel<D, false, CENTRE><<<dim3(p.P, p.BH), NT, q_smem<D>(), s>>>(
         (const uint16_t*)a.q, (const uint16_t*)a.dout, (const uint16_t*)a.wq, a.state, (const uint4*)a.gimg,
         (const uint4*)a.simg, (const uint4*)a.wimg, a.scales,
-        (uint16_t*)a.dq, a.partials, a.dwq ? duq : nullptr, duq_its, nullptr, nullptr, nullptr, p.H, p.n, p.P, p.rows);
+        (uint16_t*)a.dq, a.partials, a.dwq ? duq : nullptr, duq_its, nullptr, nullptr, nullptr, a.cs_part, p.H, p.n, p.P, p.rows);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if ((e = launch_state_reduce(a.partials, a.dstate, p, s)) != hipSuccess) return e;
   // images of dS: the second half of the scales array, no W~ images
-  bwd_prep_kernel<D, false><<<dim3(p.BH, PREP_Y), PT, prep_smem_bytes<D>(), s>>>(a.dstate, (uint4*)a.dgimg, (uint4*)a.dsimg, a.scales + 1,
-                                                        nullptr, nullptr, nullptr, p.H);
+  bwd_prep_kernel<D, false, CENTRE><<<dim3(p.BH, PREP_Y), PT, prep_smem_bytes<D>(), s>>>(a.dstate, (uint4*)a.dgimg, (uint4*)a.dsimg, a.scales + 1,
+                                                        nullptr, nullptr, nullptr, p.H, a.vbar, a.dv_row, a.dzc, a.cs_part, p.P);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if ((e = set_smem_once<bwd_k_kernel<D>>(k_smem<D>())) != hipSuccess) return e;
   bwd_k_kernel<D><<<dim3(p.KP, p.BH), NTK, k_smem<D>(), s>>>(
       (const uint16_t*)a.k, (const uint16_t*)a.v, (const uint16_t*)a.wk, a.dstate,
       (const uint4*)a.dsimg, (const uint4*)a.dgimg, (const uint4*)a.wimg, a.scales,
-      (uint16_t*)a.dk, (uint16_t*)a.dv, a.dwk ? duk : nullptr, duk_its, p.H, p.n, p.rows);
+      (uint16_t*)a.dk, (uint16_t*)a.dv, a.dwk ? duk : nullptr, duk_its, a.dzc, a.dv_row, p.H, p.n, p.rows);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (a.dwq || a.dwk) {
     // partial sums of the two sides sit one behind the other in the dW~ partial region
@@ -820,7 +944,8 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
 }  // namespace
 
 hipError_t launch_bwd_bf16(const BwdArgs& a, const Plan& p, hipStream_t s) {
-  return p.d == 128 ? run_bwd<128>(a, p, s) : run_bwd<64>(a, p, s);
+  if (p.centred) return p.d == 128 ? run_bwd<128, true>(a, p, s) : run_bwd<64, true>(a, p, s);
+  return p.d == 128 ? run_bwd<128, false>(a, p, s) : run_bwd<64, false>(a, p, s);
 }
 
 }  // namespace linattn

@@ -240,7 +240,11 @@ __device__ __forceinline__ int turned_feature(int fb, int n) {
 // One segment of a workgroup's tile range: tiles tile0 .. tile0+nt-1 of one (b,h), whose K and V
 // rows start at kb, vb and whose W~_k is wkh; the partial state goes to dst.  Every thread of the
 // workgroup calls it (it contains workgroup barriers).
-template <int D>
+// CENTRE (LINATTN_FLAG_CENTRED): the phi wavefronts produce phi - 2/D, so that the fp16 rounding acts on the
+// deviation from the uniform map; the accumulate wavefronts sum the columns of V from the operands they read
+// anyway (a lane of a transposed V operand holds 8 tokens of one channel) and the segment's partial state is
+// completed in fp32: S += (2/D) 1 (sum v)^T, z += (2/D) x the number of tokens.
+template <int D, bool CENTRE>
 __device__ __forceinline__ void state_segment(const uint16_t* __restrict__ kb, const uint16_t* __restrict__ vb,
                                               const uint16_t* __restrict__ wkh, float* __restrict__ dst,
                                               int tile0, int nt, int n, Rows rw) {
@@ -299,7 +303,7 @@ __device__ __forceinline__ void state_segment(const uint16_t* __restrict__ kb, c
         project<D>(x, sWA, lane, u);
         if (it + 2 < nt) load_k(x, tile + 2);
         uint32_t pk[C::NPK];
-        softmax_pair<D>(u, valid, pk);
+        softmax_pair<D, CENTRE>(u, valid, pk);
         // turn phi from "token per lane" to "feature slot per lane" with an MFMA against the 0/1
         // selection operands: the accumulator is then (after an exact repack to fp16) the A operand
         // of S = phi^T V with the tokens of a 16-token k-step in the order {4g..4g+3, 8+4g..8+4g+3};
@@ -346,6 +350,10 @@ __device__ __forceinline__ void state_segment(const uint16_t* __restrict__ kb, c
       pair32(zs[fb], lo, hi);
       if (g == 0) zred[pw * D + 32 * fb + lane] = lo + hi;
     }
+    if constexpr (CENTRE) {
+      __syncthreads();      // the two barriers of the accumulate branch's column-sum reduction
+      __syncthreads();
+    }
   } else {
     // ---- acc wavefronts ------------------------------------------------------------------
     const int mi = pw / 2, ni = pw % 2;
@@ -373,6 +381,9 @@ __device__ __forceinline__ void state_segment(const uint16_t* __restrict__ kb, c
         vr[i] = ld_nt(reinterpret_cast<const uint4*>(vb + (size_t)tv * rw.sn) + c);
       }
     };
+    float csum[WMN];                                 // CENTRE: column sums of V over the lane's tokens
+#pragma unroll
+    for (int j = 0; j < WMN; ++j) csum[j] = 0.f;
     // one step: park V tile `it` (held in vr, refilled with the tile two steps ahead), then
     // accumulate tile it-1 from the other buffer
     auto acc_step = [&](uint4 (&vr)[VPT], int it) {
@@ -413,6 +424,14 @@ __device__ __forceinline__ void state_segment(const uint16_t* __restrict__ kb, c
 #pragma unroll
             for (int j = 0; j < WMN; ++j)
               s[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[ks][i], b[ks][j], s[i][j], 0, 0, 0);
+          if constexpr (CENTRE) {
+#pragma unroll
+            for (int j = 0; j < WMN; ++j) {
+              const uint4 q = __builtin_bit_cast(uint4, b[ks][j]);
+              csum[j] = add_pair_f16(q.x, csum[j]); csum[j] = add_pair_f16(q.y, csum[j]);
+              csum[j] = add_pair_f16(q.z, csum[j]); csum[j] = add_pair_f16(q.w, csum[j]);
+            }
+          }
           __builtin_amdgcn_sched_barrier(0);
         }
       }
@@ -426,6 +445,36 @@ __device__ __forceinline__ void state_segment(const uint16_t* __restrict__ kb, c
       if (it + 1 <= nt) acc_step(vc, it + 1);
     }
     const int c = lane % 32;
+    float corr[WMN];
+#pragma unroll
+    for (int j = 0; j < WMN; ++j) corr[j] = 0.f;
+    if constexpr (CENTRE) {
+      // column sums of v: the two lane groups of the wavefronts mi = 0 (mi = 1 holds the same sums), in a
+      // fixed order; every step has ended with a barrier, so the tile buffers are free.  Rows past n
+      // were parked as copies of row n - 1: their share is taken out again.
+      float* svp = reinterpret_cast<float*>(sBuf);            // [D] sums, then [D] (2/D) x sums
+#pragma unroll
+      for (int j = 0; j < WMN; ++j) {
+        float lo, hi;
+        pair32(csum[j], lo, hi);
+        if (mi == 0 && g == 0) svp[32 * (ni * WMN + j) + c] = lo + hi;
+      }
+      __syncthreads();
+      float* svs = svp + D;
+      if (atid < D) {
+        const int t_hi = (tile0 + nt) * kTile;
+        const int dup = t_hi > n ? t_hi - n : 0;
+        float t = svp[atid];
+        if (dup > 0) {
+          const uint32_t last = bf16x2_to_f16x2((uint32_t)vb[(size_t)(n - 1) * rw.sn + atid]) & 0xffffu;
+          t -= (float)dup * (float)__builtin_bit_cast(_Float16, (uint16_t)last);
+        }
+        svs[atid] = t * (2.0f / D);
+      }
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < WMN; ++j) corr[j] = svs[32 * (ni * WMN + j) + c];
+    }
 #pragma unroll
     for (int i = 0; i < WMN; ++i)
 #pragma unroll
@@ -433,19 +482,25 @@ __device__ __forceinline__ void state_segment(const uint16_t* __restrict__ kb, c
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int f = turned_feature<D>(fblk(i), 8 * (r / 4) + 4 * g + (r % 4));
-          dst[f * D + 32 * (ni * WMN + j) + c] = s[i][j][r];
+          dst[f * D + 32 * (ni * WMN + j) + c] = CENTRE ? s[i][j][r] + corr[j] : s[i][j][r];
         }
   }
-  // z: the four phi wavefronts, in a fixed order
+  // z: the four phi wavefronts, in a fixed order (CENTRE: plus 2/D per token of the segment)
   __syncthreads();
-  if (tid < D)
-    dst[D * D + turned_feature<D>(tid / 32, tid % 32)] = (zred[tid] + zred[2 * D + tid]) + (zred[D + tid] + zred[3 * D + tid]);
+  if (tid < D) {
+    float zv = (zred[tid] + zred[2 * D + tid]) + (zred[D + tid] + zred[3 * D + tid]);
+    if constexpr (CENTRE) {
+      const int t_lo = tile0 * kTile, t_hi = (tile0 + nt) * kTile < n ? (tile0 + nt) * kTile : n;
+      zv += (2.0f / D) * (float)(t_hi - t_lo);
+    }
+    dst[D * D + turned_feature<D>(tid / 32, tid % 32)] = zv;
+  }
   __syncthreads();                               // the next segment reuses every LDS region
 }
 
 // Grid: Split::G workgroups; workgroup g takes the tiles [lo(g), lo(g+1)) of the call's (b,h)-major
 // tile sequence, one segment per head it touches (at most two).
-template <int D>
+template <int D, bool CENTRE>
 __global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                                                                 const uint16_t* __restrict__ wk, float* __restrict__ partials,
                                                                 int H, int n, Split sp, Rows rw) {
@@ -457,7 +512,7 @@ __global__ __launch_bounds__(NT1) void state_partials_ws_kernel(const uint16_t* 
     const long long head0 = (long long)bh * sp.ntile;
     const long long seg_hi = hi < head0 + sp.ntile ? hi : head0 + sp.ntile;
     const int slot = g - split_owner(sp, head0);
-    state_segment<D>(k + head_base(rw, bh, H), v + head_base(rw, bh, H), wk + (size_t)(bh % H) * D * (D / 2),
+    state_segment<D, CENTRE>(k + head_base(rw, bh, H), v + head_base(rw, bh, H), wk + (size_t)(bh % H) * D * (D / 2),
                      partials + ((size_t)bh * sp.PS + slot) * (size_t)(D + 1) * D,
                      (int)(lo - head0), (int)(seg_hi - lo), n, rw);
     lo = seg_hi;
@@ -476,20 +531,22 @@ constexpr size_t apply_smem() {
 
 }  // namespace
 
+namespace {
+template <int D, bool CENTRE>
+hipError_t run_state_ws(const void* k, const void* v, const void* wk, float* partials, const Plan& p, hipStream_t s) {
+  hipError_t e;
+  if ((e = set_smem_once<state_partials_ws_kernel<D, CENTRE>>(state_ws_smem<D>())) != hipSuccess) return e;
+  state_partials_ws_kernel<D, CENTRE><<<dim3(p.split.G), dim3(NT1), state_ws_smem<D>(), s>>>(
+      (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)wk, partials, p.H, p.n, p.split, p.rows);
+  return hipGetLastError();
+}
+}  // namespace
+
 hipError_t launch_state_partials_bf16(const void* k, const void* v, const void* wk, float* partials,
                                       const Plan& p, hipStream_t s) {
-  dim3 grid(p.split.G), block(NT1);
-  hipError_t e;
-  if (p.d == 128) {
-    if ((e = set_smem_once<state_partials_ws_kernel<128>>(state_ws_smem<128>())) != hipSuccess) return e;
-    state_partials_ws_kernel<128><<<grid, block, state_ws_smem<128>(), s>>>(
-        (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)wk, partials, p.H, p.n, p.split, p.rows);
-  } else {
-    if ((e = set_smem_once<state_partials_ws_kernel<64>>(state_ws_smem<64>())) != hipSuccess) return e;
-    state_partials_ws_kernel<64><<<grid, block, state_ws_smem<64>(), s>>>(
-        (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)wk, partials, p.H, p.n, p.split, p.rows);
-  }
-  return hipGetLastError();
+  if (p.d == 128)
+    return p.centred ? run_state_ws<128, true>(k, v, wk, partials, p, s) : run_state_ws<128, false>(k, v, wk, partials, p, s);
+  return p.centred ? run_state_ws<64, true>(k, v, wk, partials, p, s) : run_state_ws<64, false>(k, v, wk, partials, p, s);
 }
 
 namespace {

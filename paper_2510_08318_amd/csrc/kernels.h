@@ -58,6 +58,7 @@ struct Plan {
   int B, H, n, d;
   int kind;         // kPhiHedgehog or kPhiRelu (set by the dispatch, not by make_plan)
   bool bf16_storage; // the fp32-arithmetic kernels read and write bf16 tensors (LINATTN_BF16_F32MATH)
+  bool centred;      // LINATTN_FLAG_CENTRED (set by the dispatch): phi minus its mean in the sums over tokens, centred operand images
   int BH;
   Rows rows;        // memory layout of the token tensors
   Split split;      // bf16 forward state pass
@@ -80,6 +81,8 @@ struct Plan {
   size_t off_dgimg;       // fp16 [BH][d*d]       operand image of dS for dL/dphi(k)
   size_t off_wimg;        // [H][4][d*d bytes]    W~_q image, W~_q transposed image, then the same for W~_k
   size_t off_scales;      // fp32 [BH][2]         power-of-two scales of the S and dS images
+  size_t off_centre;      // centred backward: fp32 [BH][3][d] (mean value row vbar, constant row of dv, centred dz), then
+                          // [BH][P][d+8] per-workgroup column sums of dO/den (d) and the sum of -delta/den (1)
   size_t off_drpart;      // fp32 [BH][P] + [kDotParts]: per-workgroup parts of dL/dr (mixed attention, Eq. 6)
   size_t off_dwpart;      // fp32 [2][BH][P][d*d/2] partial dW~ of the two sides (weight gradients only)
   size_t du_bytes;        // bytes of one dL/du region
@@ -105,6 +108,7 @@ struct BwdArgs {
   void* gimg;
   void *simg, *dsimg, *dgimg, *wimg;
   float* scales;
+  float *vbar, *dv_row, *dzc, *cs_part;   // centred backward (Plan::off_centre)
   // mixed attention (Eq. 6): softmax-branch output, the layer's r, dL/dr; all null when off
   const void* blend_in;
   const float* blend_r;
@@ -155,6 +159,9 @@ hipError_t launch_bwd_f32(const BwdArgs& a, const Plan& p, hipStream_t s);
 hipError_t launch_relu_bwd_bf16(const BwdArgs& a, const Plan& p, hipStream_t s);
 // part[0 .. kDotParts-1] = partial sums of sum_i a[i] * b[i] over two contiguous bf16 arrays (elems % 8 == 0).
 hipError_t launch_dot_bf16(const void* a, const void* b, size_t elems, float* part, hipStream_t s);
+// part[0 .. kDotParts-1] = partial sums of sum_i a[i] * (b[i] - vbar[bh(i)][channel(i)]) over two bf16 token tensors in the
+// plan's layout; vbar fp32 [BH][d].
+hipError_t launch_dot_centred_bf16(const void* a, const void* b, const float* vbar, float* part, const Plan& p, hipStream_t s);
 // dr = sum of the count parts in a fixed order if 0 <= *r <= 1, else 0 (Eq. 6, clipped r).
 hipError_t launch_dr_reduce(const float* part, int count, const float* r, float* dr, hipStream_t s);
 

@@ -130,12 +130,21 @@ __device__ __forceinline__ void project(const uint4 (&xb)[Cfg<D>::UK], const uin
   }
 }
 
+// Sum of the two fp16 halves of a packed pair, added to an fp32 accumulator (v_dot2_f32_f16 against (1, 1):
+// exact products, fp32 sum).
+__device__ __forceinline__ float add_pair_f16(uint32_t p, float acc) {
+  const f16x2 one = {(_Float16)1.0f, (_Float16)1.0f};
+  return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, p), one, acc, false);
+}
+
 // Second half of Eq. 5: the two softmaxes over the d/2 features (in-lane, plus one exchange with
 // lane^32).  pk[] receives the lane's d/2 values of phi as fp16 pairs: first LOC values
 // softmax(+u) for features g*LOC .. g*LOC+LOC-1, then LOC values softmax(-u) for the same
 // features.  valid == false zeroes the token (tail masking happens after phi: phi(0) is the
 // uniform vector, not zero).
-template <int D>
+// CENTRE: the values are phi - 2/D (phi minus its mean over the features), so that the fp16 rounding
+// acts on the deviation from the uniform map; the caller adds (2/D) x the column sums back.
+template <int D, bool CENTRE = false>
 __device__ __forceinline__ void softmax_pair(const f32x16 (&u)[Cfg<D>::UM], bool valid, uint32_t (&pk)[Cfg<D>::NPK]) {
   using C = Cfg<D>;
   float mx = u[0][0], mn = u[0][0];
@@ -163,8 +172,15 @@ __device__ __forceinline__ void softmax_pair(const f32x16 (&u)[Cfg<D>::UM], bool
       }
     pair32(s, lo, hi); s = lo + hi;
     const float inv = valid ? __builtin_amdgcn_rcpf(s) : 0.f;
+    if constexpr (CENTRE) {
+      const float mc = valid ? -2.0f / D : 0.f;
+#pragma unroll
+      for (int j = 0; j < C::LOC / 2; ++j)
+        pk[half * (C::LOC / 2) + j] = pack_f16x2(fmaf(e[2 * j], inv, mc), fmaf(e[2 * j + 1], inv, mc));
+    } else {
 #pragma unroll
     for (int j = 0; j < C::LOC / 2; ++j) pk[half * (C::LOC / 2) + j] = pack_f16x2(e[2 * j] * inv, e[2 * j + 1] * inv);
+    }
   }
 }
 
@@ -476,7 +492,7 @@ __device__ __forceinline__ float wave_max_paired(float x) {
 // instruction writes two whole rows of d channels.
 template <int D>
 __device__ __forceinline__ void store_token_rows(uint16_t* base, size_t sn, int t0, int n, int lane,
-                                                 const f32x16 (&acc)[D / 32], float mul) {
+                                                 const f32x16 (&acc)[D / 32], float mul, const float (&add)[D / 32]) {
   constexpr int MB = D / 32;
   static_assert(MB == 2 || MB == 4, "head width 64 or 128");
   const int c = lane % 32, g = lane / 32;
@@ -487,11 +503,11 @@ __device__ __forceinline__ void store_token_rows(uint16_t* base, size_t sn, int 
     char* dst = ub + (size_t)row * sn * 2 + lo;
     if constexpr (MB == 4) {
       uint2 v;
-      v.x = pack_bf16x2(acc[0][r] * mul, acc[1][r] * mul);
-      v.y = pack_bf16x2(acc[2][r] * mul, acc[3][r] * mul);
+      v.x = pack_bf16x2(fmaf(acc[0][r], mul, add[0]), fmaf(acc[1][r], mul, add[1]));
+      v.y = pack_bf16x2(fmaf(acc[2][r], mul, add[2]), fmaf(acc[3][r], mul, add[3]));
       *reinterpret_cast<uint2*>(dst) = v;
     } else {
-      *reinterpret_cast<uint32_t*>(dst) = pack_bf16x2(acc[0][r] * mul, acc[1][r] * mul);
+      *reinterpret_cast<uint32_t*>(dst) = pack_bf16x2(fmaf(acc[0][r], mul, add[0]), fmaf(acc[1][r], mul, add[1]));
     }
   };
   if (t0 + 32 <= n) {
@@ -502,6 +518,15 @@ __device__ __forceinline__ void store_token_rows(uint16_t* base, size_t sn, int 
     for (int r = 0; r < 16; ++r)
       if (t0 + 8 * (r / 4) + (r % 4) + 4 * g < n) put(r);
   }
+}
+
+template <int D>
+__device__ __forceinline__ void store_token_rows(uint16_t* base, size_t sn, int t0, int n, int lane,
+                                                 const f32x16 (&acc)[D / 32], float mul) {
+  float zero[D / 32];
+#pragma unroll
+  for (int i = 0; i < D / 32; ++i) zero[i] = 0.f;
+  store_token_rows<D>(base, sn, t0, n, lane, acc, mul, zero);
 }
 
 // 32x32x16 MFMA on operands carried as f16x8 registers whose bits are fp16 or (BF16) bf16.
@@ -519,10 +544,13 @@ __device__ __forceinline__ f32x16 mfma16(f16x8 a, f16x8 b, f32x16 c) {
 // of the z sum for that k-step (per-token weights, the same in every column); z_hi picks which of
 // the wavefront's A blocks feeds it, do_z whether this wavefront owns a z block at all.
 // BF16: the tiles and wop's operands hold bf16 instead of fp16 (same bits per element, bf16 MFMA).
-template <int D, bool BF16 = false, typename WOp>
+// SUMS: also accumulate csum[j] += the sum over the tile's tokens of the B operand's column of this lane
+// (a lane holds 8 tokens of one channel per k-step) and *wsum += the sum of wop's operand (fp16 tiles only).
+template <int D, bool BF16 = false, bool SUMS = false, typename WOp>
 __device__ __forceinline__ void contract_tile(const char* sA, const char* sB, const int (&offA)[D / 64][2],
                                               const int (&offB)[D / 64][2], f32x16 (&s)[D / 64][D / 64],
-                                              f32x16& zacc, bool z_hi, bool do_z, WOp wop) {
+                                              f32x16& zacc, bool z_hi, bool do_z, WOp wop,
+                                              float* csum = nullptr, float* wsum = nullptr) {
   constexpr int RS = D * 2, WMN = D / 64, KSN = kTile / 16;
   f16x8 a[KSN][WMN], b[KSN][WMN], wv[KSN];
   auto request = [&](int kn) {
@@ -547,6 +575,18 @@ __device__ __forceinline__ void contract_tile(const char* sA, const char* sB, co
       zacc = mfma16<BF16>(az, wv[ks], zacc);
     } else if (do_z) {
       zacc = mfma16<BF16>(a[ks][0], wv[ks], zacc);
+    }
+    if constexpr (SUMS) {
+#pragma unroll
+      for (int j = 0; j < WMN; ++j) {
+        const uint4 q = __builtin_bit_cast(uint4, b[ks][j]);
+        csum[j] = add_pair_f16(q.x, csum[j]); csum[j] = add_pair_f16(q.y, csum[j]);
+        csum[j] = add_pair_f16(q.z, csum[j]); csum[j] = add_pair_f16(q.w, csum[j]);
+      }
+      const uint4 q = __builtin_bit_cast(uint4, wv[ks]);
+      float t = *wsum;
+      t = add_pair_f16(q.x, t); t = add_pair_f16(q.y, t); t = add_pair_f16(q.z, t); t = add_pair_f16(q.w, t);
+      *wsum = t;
     }
     __builtin_amdgcn_sched_barrier(0);
   }

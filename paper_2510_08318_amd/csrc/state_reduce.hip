@@ -226,7 +226,53 @@ __global__ __launch_bounds__(256) void dot_bf16_kernel(const uint4* __restrict__
   if (threadIdx.x == 0) part[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
+// The same with the head's mean value row taken off b: part = sum a[i] * (b[i] - vbar[bh(i)][ch(i)]), for a, b
+// in the layout `rw` of the token tensors (d a power of two).  The query-side backward works with the output
+// minus vbar; this is the matching form of the sum dout . s of the mixed attention's dL/dr.
+__global__ __launch_bounds__(256) void dot_centred_bf16_kernel(const uint4* __restrict__ a, const uint4* __restrict__ b,
+                                                               const float* __restrict__ vbar, size_t n16,
+                                                               float* __restrict__ part, int n, int H, int d, int bnhd) {
+  __shared__ float red[4];
+  float acc = 0.f;
+  const int dshift = d == 128 ? 7 : 6;
+  auto term = [&](uint4 x, uint4 y, size_t i) {
+    const size_t e0 = i * 8, row = e0 >> dshift;
+    const int ch = (int)(e0 & (size_t)(d - 1));
+    size_t bh;
+    if (bnhd) { const size_t bt = row / (size_t)H; bh = (bt / (size_t)n) * H + (row - bt * H); }
+    else bh = row / (size_t)n;
+    const float* vb = vbar + bh * d + ch;
+    const uint32_t xs[4] = {x.x, x.y, x.z, x.w}, ys[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      acc = fmaf(__builtin_bit_cast(float, xs[j] << 16), __builtin_bit_cast(float, ys[j] << 16) - vb[2 * j], acc);
+      acc = fmaf(__builtin_bit_cast(float, xs[j] & 0xffff0000u), __builtin_bit_cast(float, ys[j] & 0xffff0000u) - vb[2 * j + 1], acc);
+    }
+  };
+  const size_t stride = (size_t)gridDim.x * 256;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    uint4 x[4], y[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) { x[u] = ld_nt16(a + i + u * stride); y[u] = ld_nt16(b + i + u * stride); }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) term(x[u], y[u], i + u * stride);
+  }
+  for (; i < n16; i += stride) term(a[i], b[i], i);
+  for (int m = 32; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
+  if (threadIdx.x % 64 == 0) red[threadIdx.x / 64] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) part[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
 }  // namespace
+
+hipError_t launch_dot_centred_bf16(const void* a, const void* b, const float* vbar, float* part, const Plan& p, hipStream_t s) {
+  const size_t elems = (size_t)p.BH * p.n * p.d;
+  dot_centred_bf16_kernel<<<kDotParts, 256, 0, s>>>((const uint4*)a, (const uint4*)b, vbar, elems / 8, part, p.n, p.H, p.d,
+                                                    p.rows.sn != (size_t)p.d);
+  return hipGetLastError();
+}
 
 hipError_t launch_dot_bf16(const void* a, const void* b, size_t elems, float* part, hipStream_t s) {
   dot_bf16_kernel<<<kDotParts, 256, 0, s>>>((const uint4*)a, (const uint4*)b, elems / 8, part);

@@ -79,10 +79,11 @@ class Layer:
     """Buffers + descriptor of one linear-attention layer (Eq. 3 with the map of Eq. 5)."""
 
     def __init__(self, wq: torch.Tensor, wk: torch.Tensor, B: int, n: int, *, keep_state: bool = True,
-                 want_wgrads: bool = False, layout: str = "bhnd", f32_math: bool = False):
+                 want_wgrads: bool = False, layout: str = "bhnd", f32_math: bool = False, centred: bool = False):
         """layout "bhnd": q, k, v, out are [B, H, n, d]; "bnhd": [B, n, H, d] (heads interleaved per token).
         want_wgrads: False, True (both dW~_q and dW~_k), or "q" / "k" for one of them.
-        f32_math (bf16 tensors only): fp32 arithmetic on the bf16 tensors (LINATTN_BF16_F32MATH)."""
+        f32_math (bf16 tensors only): fp32 arithmetic on the bf16 tensors (LINATTN_BF16_F32MATH).
+        centred (bf16 matrix-core path only): LINATTN_FLAG_CENTRED."""
         assert layout in ("bhnd", "bnhd")
         self.layout = layout
         assert wq.is_cuda and wk.is_cuda and wq.dtype == wk.dtype and wq.shape == wk.shape
@@ -105,7 +106,8 @@ class Layer:
         assert self.workspace.data_ptr() % 256 == 0
         self.phi_id = B_.linattn_phi_create(B_.PHI_HEDGEHOG, self.dtype, self.H, self.d, self.wq, self.wk,
                                             self.dwq, self.dwk, self.state, self.workspace, self.workspace_bytes,
-                                            B_.LAYOUT_BNHD if layout == "bnhd" else B_.LAYOUT_BHND)
+                                            B_.LAYOUT_BNHD if layout == "bnhd" else B_.LAYOUT_BHND,
+                                            flags=B_.FLAG_CENTRED if centred else 0)
 
     def set_blend(self, s=None, r=None, dr=None):
         """Mixed attention (Eq. 6): s = softmax-branch output (dtype and layout of out), r = device fp32[1],

@@ -239,3 +239,16 @@ def test_bf16_storage_fp32_arithmetic_dtype_is_accepted_on_the_host():
     finally:
         L.linattn_phi_destroy(pid)
     assert L.linattn_phi_create(L.PHI_HEDGEHOG, 4, H, d, P, P + 65536, check=False) == L.E_DTYPE
+
+
+def test_descriptor_flags_are_checked_on_the_host():
+    """LINATTN_FLAG_CENTRED goes with the Eq. 5 map in LINATTN_BF16 only; unknown flag bits are refused."""
+    header = open(os.path.join(ROOT, "include", "linattn.h")).read()
+    assert re.search(r"#define\s+LINATTN_FLAG_CENTRED\s+1u\b", header) and L.FLAG_CENTRED == 1
+    H, d = 2, 128
+    pid = L.linattn_phi_create(L.PHI_HEDGEHOG, L.BF16, H, d, P, P + 65536, flags=L.FLAG_CENTRED)
+    assert pid >= 16 and L.linattn_phi_destroy(pid) == L.OK
+    assert L.linattn_phi_create(L.PHI_HEDGEHOG, L.F32, H, d, P, P + 65536, flags=L.FLAG_CENTRED, check=False) == L.E_PHI
+    assert L.linattn_phi_create(L.PHI_HEDGEHOG, L.BF16_F32MATH, H, d, P, P + 65536, flags=L.FLAG_CENTRED, check=False) == L.E_PHI
+    assert L.linattn_phi_create(L.PHI_RELU, L.BF16, H, d, None, None, flags=L.FLAG_CENTRED, check=False) == L.E_PHI
+    assert L.linattn_phi_create(L.PHI_HEDGEHOG, L.BF16, H, d, P, P + 65536, flags=2, check=False) == L.E_PHI

@@ -1,0 +1,139 @@
+"""LINATTN_FLAG_CENTRED: the matrix-core path with phi minus its mean in the two sums over tokens and centred
+operand images of S and dS.  Exact in real arithmetic, so every case of the default path must still hold; the
+case the default path documents as outside its contract -- phi within a few per cent of uniform -- must meet
+1e-2 on all five gradients."""
+import numpy as np
+import pytest
+
+from oracle import linattn_oracle as O
+from paper_2510_08318_amd import synth
+
+pytestmark = pytest.mark.gpu
+NAMES = ["dq", "dk", "dv", "dwq", "dwk"]
+TOL = 1e-2
+STATE_TOL = 2e-3      # exported fp32 state, normwise (as for the default path)
+
+
+def _run(x, layout="bhnd", blend=None, centred=True):
+    import torch
+    from paper_2510_08318_amd import torch_glue as G
+    q, k, v, wq, wk, do = [G.to_device(t) for t in (x.q, x.k, x.v, x.wq, x.wk, x.dout)]
+    perm = (lambda t: t.permute(0, 2, 1, 3).contiguous()) if layout == "bnhd" else (lambda t: t)
+    back = (lambda t: t.permute(0, 2, 1, 3)) if layout == "bnhd" else (lambda t: t)
+    q, k, v, do = [perm(t) for t in (q, k, v, do)]
+    lay = G.Layer(wq, wk, x.B, x.n, want_wgrads=True, layout=layout, centred=centred)
+    dr = None
+    if blend is not None:
+        s, r = blend
+        dr = torch.zeros(1, device="cuda")
+        lay.set_blend(perm(G.to_device(s)), torch.tensor([r], device="cuda"), dr)
+    out = lay.forward(q, k, v)
+    dq, dk, dv = lay.backward(q, k, v, do)
+    torch.cuda.synchronize()
+    res = {"out": G.to_host_f64(back(out)), "state": G.to_host_f64(lay.state),
+           "grads": [G.to_host_f64(back(t)) for t in (dq, dk, dv)] + [G.to_host_f64(lay.dwq), G.to_host_f64(lay.dwk)],
+           "dr": None if dr is None else float(dr.item())}
+    lay.close()
+    return res
+
+
+def _errors(x, label):
+    got = _run(x)
+    errs = {"out": O.err_metric(got["out"], O.fwd_bh(x.q, x.k, x.v, x.wq, x.wk))[0]}
+    st_ref = O.state_bh(x.k, x.v, x.wk)
+    errs["state"] = max(float(np.linalg.norm(got["state"][b, h] - st_ref[b, h]) / np.linalg.norm(st_ref[b, h]))
+                        for b in range(x.B) for h in range(x.H))
+    ref = O.bwd_bh(x.q, x.k, x.v, x.wq, x.wk, x.dout)
+    dv_scale = np.abs(ref[2]).max()
+    for name, g, r in zip(NAMES, got["grads"], ref):
+        assert np.isfinite(g).all(), name
+        if np.sqrt(np.mean(r ** 2)) < 1e-6 * dv_scale:        # identically zero in exact arithmetic (n = 1)
+            errs[name] = float(np.abs(g - r).max() / dv_scale)
+        else:
+            errs[name] = O.err_metric(g, r)[0]
+    print(f"[centred {label}] " + ", ".join(f"{k} {v:.2e}" for k, v in errs.items()))
+    return errs
+
+
+def _assert_contract(errs):
+    assert errs["state"] <= STATE_TOL, errs
+    assert all(errs[k] <= TOL for k in ["out"] + NAMES), errs
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_near_uniform_phi_meets_the_contract(d):
+    """q, k scaled by 0.01: the default path is pinned at 0.2 here (tests/test_range_gpu.py)."""
+    from tests.test_range_gpu import _scaled
+    _assert_contract(_errors(_scaled(d, sq=0.01, sk=0.01), f"near-uniform d={d}"))
+    _assert_contract(_errors(_scaled(d, sq=0.001, sk=0.05), f"nearer-uniform d={d}"))
+
+
+@pytest.mark.parametrize("n,H,d", [(1, 2, 128), (31, 2, 64), (129, 3, 128), (700, 2, 64), (4133, 3, 128), (2049, 20, 64)])
+def test_recipe_inputs_ragged_lengths(n, H, d):
+    """Several tiles, ragged tails (the copies of the last row that the state pass parks are taken out of the
+    column sums), one to several workgroups per head."""
+    _assert_contract(_errors(synth.generate("C5", n=n, H=H, d=d), f"C5 n={n} H={H} d={d}"))
+
+
+@pytest.mark.parametrize("scales", [dict(sq=8, sk=8), dict(sq=30, sk=30), dict(sv=1000), dict(sv=1e-3), dict(sdo=1e4), dict(sdo=1e-6)],
+                         ids=lambda s: ",".join(f"{k}={v}" for k, v in s.items()))
+def test_rescaled_inputs(scales):
+    from tests.test_range_gpu import _scaled
+    _assert_contract(_errors(_scaled(128, **scales), str(scales)))
+
+
+def test_nonzero_mean_values():
+    """v with a large common offset: S is then dominated by z vbar^T, which the centred images take out."""
+    x = synth.generate("C5", n=1500, H=2, d=128)
+    v = O.to_f64(x.v)
+    x.v = synth._pack((v + 3.0 * np.abs(v).max()).astype(np.float32), x.dtype)
+    _assert_contract(_errors(x, "offset v"))
+
+
+def test_stepped_gradients_and_outliers():
+    from tests.test_range_gpu import _stepped
+    for steps in (dict(dout=(0.0, 1e-6)), dict(dout=(1.0, 2.0 ** 13)), dict(v=(1.0, 2.0 ** 12))):
+        x = _stepped(128, H=16, n=6161, **steps)
+        errs = _errors(x, str(steps))
+        names = [k for k in errs if not (k == "dq" and "dout" in steps)]     # dq spans two magnitudes with a stepped dout
+        assert all(errs[k] <= TOL for k in names if k != "state"), errs
+    x = synth.generate("C3", n=3000, H=2, with_dout=True)
+    errs = _errors(x, "outliers")
+    assert all(errs[k] <= TOL for k in ("out", "dq", "dv", "dwq")) and errs["dk"] <= 0.25 and errs["dwk"] <= 5e-2, errs
+
+
+def test_layouts_agree_bitwise_and_runs_repeat():
+    x = synth.generate("C5", n=517, H=3, d=128)
+    a, b, c = _run(x), _run(x, layout="bnhd"), _run(x)
+    for u, w in ((a, b), (a, c)):
+        assert np.array_equal(u["out"], w["out"]) and np.array_equal(u["state"], w["state"])
+        for g, h in zip(u["grads"], w["grads"]):
+            assert np.array_equal(g, h)
+
+
+def test_mixed_attention():
+    x = synth.generate("C5", n=700, H=2, d=128)
+    rng = np.random.default_rng(5)
+    s = synth._pack((rng.standard_normal(x.q.shape) * 0.1).astype(np.float32), x.dtype)
+    for r in (0.37, 1.0, 0.0):
+        got = _run(x, blend=(s, r))
+        assert O.err_metric(got["out"], O.blend_fwd_bh(x.q, x.k, x.v, x.wq, x.wk, s, r))[0] <= TOL
+        ref = O.blend_bwd_bh(x.q, x.k, x.v, x.wq, x.wk, s, r, x.dout)
+        scale = max(np.sqrt(np.mean(t ** 2)) for t in ref[:3])
+        for name, g, rr in zip(NAMES, got["grads"], ref[:5]):
+            if np.sqrt(np.mean(rr ** 2)) < 1e-9 * max(scale, 1e-30):          # r' = 1: the linear branch gets no gradient
+                assert np.abs(g).max() <= 1e-6 * max(1.0, np.abs(O.to_f64(x.dout)).max()), name
+            else:
+                assert O.err_metric(g, rr)[0] <= TOL, (name, r)
+        assert abs(got["dr"] - ref[6]) <= 1e-3 * max(1.0, abs(ref[6])), (r, got["dr"], ref[6])
+
+
+def test_the_flag_changes_only_roundings():
+    """Default and centred runs of the same inputs agree to the contract's own resolution; the exported states agree
+    normwise to the fp16 resolution of phi."""
+    x = synth.generate("C2", n=3000, H=4, with_dout=True)
+    a, b = _run(x, centred=False), _run(x, centred=True)
+    assert O.err_metric(b["out"], a["out"])[0] <= TOL
+    assert np.linalg.norm(a["state"] - b["state"]) <= 1e-3 * np.linalg.norm(a["state"])
+    for g, h in zip(a["grads"], b["grads"]):
+        assert O.err_metric(h, g)[0] <= 2 * TOL

@@ -151,3 +151,18 @@ def test_values_up_to_the_documented_limit(d):
     assert 6.0e4 < np.abs(O.to_f64(x.v)).max() < 65504
     errs = _errors(x)
     assert max(errs.values()) <= 1e-2, errs
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("mult", [0.3, 1.0, 3.0])
+def test_values_with_a_common_offset(d, mult):
+    """v with a mean of 1.4, 4.7 and 14 standard deviations (activations are rarely mean-free).  S = z vbar^T + ...
+    and v_j dS^T + dz then carry a common part that cancels in dq and dk; the backward's operand images are built
+    with vbar taken out (S - z vbar^T on the query side, dz matched to the rounded dS image on the key side), so
+    the roundings do not see it."""
+    x = synth.generate("C5", n=1500, H=2, d=d)
+    v = O.to_f64(x.v)
+    x.v = synth._pack((v + mult * np.abs(v).max()).astype(np.float32), x.dtype)
+    errs = _errors(x)
+    print(f"[offset v x{mult} d={d}] " + ", ".join(f"{k} {e:.2e}" for k, e in errs.items()))
+    assert max(errs.values()) <= 1e-2, errs
