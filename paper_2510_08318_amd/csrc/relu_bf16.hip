@@ -182,9 +182,17 @@ __global__ __launch_bounds__(NT) void relu_state_kernel(const uint16_t* __restri
 //         entry (ks, mb, lane=(c,g)) holds M[channel_cols(mb,c)][16ks + 8g + e], e = 0..7
 // grid (BH, 8): slice blockIdx.y of the entries.
 constexpr int PT = 512;      // threads of the image builder (staging the state is latency-bound)
-template <int D>
+// The images are built with the head's mean value row taken out, as in the Eq. 5 path (exact in real
+// arithmetic; values with a common offset then cost the gradients nothing):
+//   pass over S (DS = false): S^c = S - z c^T with c = sum_f S[f] / sum_f z[f], the phi-weighted mean of v (any
+//     row c would do: the query side then works with o - c and delta - dO . c, dq is unchanged up to
+//     eps / den, and its dz comes out as dz + dS c); c is written to `mean_row`;
+//   pass over dS (DS = true): dzc[f] = dz[f] - c . r(dS[f]) with r the fp16 rounding of the image, so that
+//     v_j . r(dS[f]) + dzc[f] = (v_j - c) . r(dS[f]) + (dz + dS c)[f] holds exactly on the key side.
+template <int D, bool DS>
 __global__ __launch_bounds__(PT) void relu_prep_kernel(const float* __restrict__ state, uint4* __restrict__ cimg,
-                                                        uint4* __restrict__ timg, float* __restrict__ scale_out) {
+                                                        uint4* __restrict__ timg, float* __restrict__ scale_out,
+                                                        float* __restrict__ mean_row, float* __restrict__ dzc) {
   using L = ApplyLayout<D>;
   constexpr int CIMG = L::KS * L::MBZ * 64, TIMG = L::KS * L::MB * 64;
   extern __shared__ uint4 prep_stage[];
@@ -196,8 +204,32 @@ __global__ __launch_bounds__(PT) void relu_prep_kernel(const float* __restrict__
     for (int i = tid; i < (D + 1) * D / 4; i += PT) reinterpret_cast<uint4*>(S)[i] = gsrc[i];
   }
   __syncthreads();
+  __shared__ float cM[D];
+  if constexpr (!DS) {
+    if (tid < D) {
+      float sv = 0.f, zt = 0.f;
+      for (int f = 0; f < D; ++f) { sv += S[f * D + tid]; zt += S[D * D + f]; }
+      const float c = zt > 0.f ? sv / zt : 0.f;
+      cM[tid] = c;
+      if (blockIdx.y == 0) mean_row[(size_t)bh * D + tid] = c;
+    }
+    __syncthreads();
+    for (int i = tid; i < D * D; i += PT) S[i] -= S[D * D + i / D] * cM[i % D];
+    __syncthreads();
+  } else {
+    if (tid < D) cM[tid] = mean_row[(size_t)bh * D + tid];
+    __syncthreads();
+  }
   const float scale = head_scale<D, PT>(S, red, tid);      // every block of a head computes the same value
   if (blockIdx.y == 0 && tid == 0) scale_out[2 * bh] = scale;      // [BH][2]: S, dS
+  if constexpr (DS) {
+    if (blockIdx.y == 0 && tid < D) {
+      const float inv = __builtin_amdgcn_rcpf(scale);       // exact: a power of two
+      float dot = 0.f;
+      for (int ch = 0; ch < D; ++ch) dot = fmaf((float)(_Float16)(scale * S[tid * D + ch]), cM[ch], dot);
+      dzc[(size_t)bh * D + tid] = S[D * D + tid] - dot * inv;
+    }
+  }
   const int first = blockIdx.y * PT + tid, step = PT * gridDim.y;
   for (int idx = first; idx < CIMG; idx += step) cimg[(size_t)bh * CIMG + idx] = state_image_entry<D, true, kPhiRelu>(S, scale, idx);
   for (int idx = first; idx < TIMG; idx += step) {
@@ -500,7 +532,7 @@ __global__ __launch_bounds__(NTK) void relu_bwd_k_kernel(const uint16_t* __restr
                                                          const float* __restrict__ dstate, const uint4* __restrict__ cimg,
                                                          const uint4* __restrict__ timg, const float* __restrict__ scale_ptr,
                                                          uint16_t* __restrict__ dk, uint16_t* __restrict__ dv,
-                                                         int H, int n, Rows rw) {
+                                                         const float* __restrict__ dzc, int H, int n, Rows rw) {
   using C = Cfg<D>;
   using L = ApplyLayout<D>;
   using Piece = typename RowPieceT<L::MB>::type;
@@ -518,14 +550,12 @@ __global__ __launch_bounds__(NTK) void relu_bwd_k_kernel(const uint16_t* __restr
   const uint16_t* vb = v + head_base(rw, bh, H);
   uint16_t* dkb = dk + head_base(rw, bh, H);
   uint16_t* dvb = dv + head_base(rw, bh, H);
-  const float* ds = dstate + (size_t)bh * (D + 1) * D;
-
   copy_image<NTK>(cimg + (size_t)bh * CIMG, sC, CIMG, tid);
   copy_image<NTK>(timg + (size_t)bh * TIMG, sT, TIMG, tid);
   const float inv_scale = __builtin_amdgcn_rcpf(scale_ptr[2 * bh]);    // exact: power of two
   float dzl[L::MB];
 #pragma unroll
-  for (int mb = 0; mb < L::MB; ++mb) dzl[mb] = ds[D * D + L::channel_cols(mb, c)];
+  for (int mb = 0; mb < L::MB; ++mb) dzl[mb] = dzc[(size_t)bh * D + L::channel_cols(mb, c)];   // dz matched to the image (relu_prep_kernel)
   __syncthreads();
 
   const int nblk = (n + 31) / 32;
@@ -611,8 +641,9 @@ hipError_t run_state(const void* k, const void* v, float* partials, const Plan& 
 template <int D>
 hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   hipError_t e;
-  if ((e = set_smem_once<relu_prep_kernel<D>>(prep_smem<D>())) != hipSuccess) return e;
-  relu_prep_kernel<D><<<dim3(p.BH, 8), PT, prep_smem<D>(), s>>>(a.state, (uint4*)a.simg, (uint4*)a.gimg, a.scales);
+  if ((e = set_smem_once<relu_prep_kernel<D, false>>(prep_smem<D>())) != hipSuccess) return e;
+  if ((e = set_smem_once<relu_prep_kernel<D, true>>(prep_smem<D>())) != hipSuccess) return e;
+  relu_prep_kernel<D, false><<<dim3(p.BH, 8), PT, prep_smem<D>(), s>>>(a.state, (uint4*)a.simg, (uint4*)a.gimg, a.scales, a.vbar, nullptr);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if ((e = set_smem_once<relu_bwd_q_kernel<D>>(q_smem<D>())) != hipSuccess) return e;
   relu_bwd_q_kernel<D><<<dim3(p.P, p.BH), NT, q_smem<D>(), s>>>(
@@ -620,12 +651,12 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
       (uint16_t*)a.dq, a.partials, p.H, p.n, p.P, p.rows);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if ((e = launch_state_reduce(a.partials, a.dstate, p, s)) != hipSuccess) return e;
-  relu_prep_kernel<D><<<dim3(p.BH, 8), PT, prep_smem<D>(), s>>>(a.dstate, (uint4*)a.dsimg, (uint4*)a.dgimg, a.scales + 1);
+  relu_prep_kernel<D, true><<<dim3(p.BH, 8), PT, prep_smem<D>(), s>>>(a.dstate, (uint4*)a.dsimg, (uint4*)a.dgimg, a.scales + 1, a.vbar, a.dzc);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if ((e = set_smem_once<relu_bwd_k_kernel<D>>(k_smem<D>())) != hipSuccess) return e;
   relu_bwd_k_kernel<D><<<dim3(p.KP, p.BH), NTK, k_smem<D>(), s>>>(
       (const uint16_t*)a.k, (const uint16_t*)a.v, a.dstate, (const uint4*)a.dsimg, (const uint4*)a.dgimg, a.scales + 1,
-      (uint16_t*)a.dk, (uint16_t*)a.dv, p.H, p.n, p.rows);
+      (uint16_t*)a.dk, (uint16_t*)a.dv, a.dzc, p.H, p.n, p.rows);
   return hipGetLastError();
 }
 

@@ -166,3 +166,16 @@ def test_values_with_a_common_offset(d, mult):
     errs = _errors(x)
     print(f"[offset v x{mult} d={d}] " + ", ".join(f"{k} {e:.2e}" for k, e in errs.items()))
     assert max(errs.values()) <= 1e-2, errs
+
+
+@pytest.mark.parametrize("mult", [0.3, 3.0])
+def test_relu_map_values_with_a_common_offset(mult):
+    from oracle import relu_oracle as R
+    from tests.test_relu_gpu import _run
+    x = synth.generate("C5", n=1500, H=2, d=128)
+    v = O.to_f64(x.v)
+    x.v = synth._pack((v + mult * np.abs(v).max()).astype(np.float32), x.dtype)
+    got, _ = _run(x)
+    ref = [R.relu_fwd_bh(x.q, x.k, x.v)] + list(R.relu_bwd_bh(x.q, x.k, x.v, x.dout))
+    errs = {name: O.err_metric(g, r)[0] for name, g, r in zip(["out", "dq", "dk", "dv"], got, ref)}
+    assert max(errs.values()) <= 1e-2, errs
