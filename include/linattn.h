@@ -47,7 +47,8 @@
  *     tokens' carries |v_j| / rms|v| times the error of an ordinary row.  For the rows at 20x
  *     magnitude of the Wan-14B-shaped test recipe (0.1 % of the tokens) this reads up to 1e-1 of the
  *     slice RMS, and dW~_k, which weights those rows by |k_j| once more, up to 2e-2; all other rows of
- *     dk, and dq, dv, dW~_q everywhere, meet 1e-2.  Second exception: where phi is within a few per
+ *     dk, and dq, dv, dW~_q everywhere, meet 1e-2.  (A common offset of v, however large, is not an
+ *     exception: the backward's operand images are built with the head's mean value row taken out.)  Second exception: where phi is within a few per
  *     cent of uniform (the spread of x W~ over the features far below 1), dq, dk and dW~ are
  *     differences of nearly equal rows of S and dS and come out up to 0.2 off; out and dv keep 1e-2.
  *     LINATTN_FLAG_CENTRED removes this exception (not the first) at a cost of 3-4 %.

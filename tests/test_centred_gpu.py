@@ -137,3 +137,42 @@ def test_the_flag_changes_only_roundings():
     assert np.linalg.norm(a["state"] - b["state"]) <= 1e-3 * np.linalg.norm(a["state"])
     for g, h in zip(a["grads"], b["grads"]):
         assert O.err_metric(h, g)[0] <= 2 * TOL
+
+
+def _structured():
+    """Inputs with the structure activations have and the i.i.d. recipe lacks: offsets, unequal channel scales,
+    low-rank tokens.  Each case: (label, inputs, bound without the flag, bound with it)."""
+    rng = np.random.default_rng(11)
+
+    def base():
+        return synth.generate("C5", n=1500, H=2, d=128)
+
+    def mod(x, name, f):
+        setattr(x, name, synth._pack(f(O.to_f64(getattr(x, name))).astype(np.float32), x.dtype))
+        return x
+    yield "v channel offsets of 3 sigma", mod(base(), "v", lambda a: a + 3 * a.std() * rng.standard_normal(128)), TOL, TOL
+    for name in ("k", "v", "dout"):
+        sc = np.exp(rng.normal(0, 1.0, 128))
+        yield f"{name} channel scales lognormal(1)", mod(base(), name, lambda a: a * sc), TOL, TOL
+    yield "q offset 0.3 max|q|", mod(base(), "q", lambda a: a + 0.3 * np.abs(a).max()), TOL, TOL
+    yield "k offset 0.3 max|k|", mod(base(), "k", lambda a: a + 0.3 * np.abs(a).max()), TOL, TOL
+    # a common offset in the upstream gradient makes dS nearly constant over the features: the flag's domain
+    yield "dout offset 3 max|dout|", mod(base(), "dout", lambda a: a + 3.0 * np.abs(a).max()), 2e-2, TOL
+    x = base()
+    for name in ("q", "k", "v"):
+        a = O.to_f64(getattr(x, name))
+        low = rng.standard_normal((1, 2, 1500, 4)) @ rng.standard_normal((4, 128))
+        setattr(x, name, synth._pack((0.1 * a + low * a.std() / 2).astype(np.float32), x.dtype))
+    yield "rank-4 tokens + 10 % noise", x, TOL, TOL
+
+
+def test_structured_inputs_both_settings():
+    for label, x, bound_default, bound_centred in _structured():
+        ref = O.bwd_bh(x.q, x.k, x.v, x.wq, x.wk, x.dout)
+        oref = O.fwd_bh(x.q, x.k, x.v, x.wq, x.wk)
+        for centred, bound in ((False, bound_default), (True, bound_centred)):
+            got = _run(x, centred=centred)
+            errs = {"out": O.err_metric(got["out"], oref)[0]}
+            errs.update({n: O.err_metric(g, r)[0] for n, g, r in zip(NAMES, got["grads"], ref)})
+            print(f"[structured {label} centred={centred}] " + ", ".join(f"{k} {v:.2e}" for k, v in errs.items()))
+            assert max(errs.values()) <= bound, (label, centred, errs)
