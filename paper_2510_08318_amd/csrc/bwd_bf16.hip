@@ -199,15 +199,16 @@ __device__ __forceinline__ void phi_jacobian(const float (&gp)[Cfg<D>::LOC], con
 // (lane (t,g) holds features g*LOC + 8ks + e of token t); the B operands are the W~ image.
 // acc[mb][r] of lane (c,g) is its * dx[token 8*(r/4) + 4g + r%4][channel MB*c + mb].
 //
-// du_blk != nullptr: the scaled fp16 du of the block is also written out for the dW~ kernel, as the
-// B operands of a contraction over the tokens.  A second MFMA against 0/1 selection operands turns
-// it (exactly) so that a lane holds one feature and 16 tokens; entry (ks2, j, lane=(c,g)) of the
-// block's image holds feature 32j + c of tokens 16*ks2 + {4g .. 4g+3, 8+4g .. 8+4g+3}.  Rows of
-// tokens that do not exist are zero.  *du_its receives the inverse scale (0 for an all-zero block).
+// IMG: the scaled fp16 du of the block is also returned as the B operands of the contraction over the
+// tokens that gives dW~.  A second MFMA against 0/1 selection operands turns it (exactly) so that a
+// lane holds one feature and 16 tokens; entry (ks2, j) of lane (c,g) holds feature 32j + c of tokens
+// 16*ks2 + {4g .. 4g+3, 8+4g .. 8+4g+3}.  Rows of tokens that do not exist are zero.  img_its receives
+// the inverse scale (0 for an all-zero block).
 // AHEAD: lookahead of the W~ operand reads of dx (pipelined_operands).
-template <int D, int AHEAD>
+template <int D, int AHEAD, bool IMG>
 __device__ __forceinline__ void du_to_dx(const float (&du)[Cfg<D>::LOC], const uint4* sWB, int lane, bool valid,
-                                         uint4* du_blk, float* du_its, f32x16 (&acc)[D / 32], float& its) {
+                                         uint4 (&img)[2 * (Cfg<D>::HALF / 32)], float& img_its,
+                                         f32x16 (&acc)[D / 32], float& its, uint32_t (&dub)[Cfg<D>::LOC / 2]) {
   using C = Cfg<D>;
   using L = ApplyLayout<D>;
   constexpr int DK = C::LOC / 8;
@@ -219,11 +220,11 @@ __device__ __forceinline__ void du_to_dx(const float (&du)[Cfg<D>::LOC], const u
   pair32(m, lo, hi); m = fmaxf(lo, hi);
   m = wave_max_paired(m);
   const float ts = valid ? pow2_normaliser(m) : 0.f;
-  uint32_t dub[C::LOC / 2];
 #pragma unroll
   for (int j = 0; j < C::LOC / 2; ++j) dub[j] = pack_f16x2(du[2 * j] * ts, du[2 * j + 1] * ts);
   its = __builtin_amdgcn_rcpf(pow2_normaliser(m));     // exact: a power of two
-  if (du_blk) {
+  img_its = m > 0.f ? its : 0.f;
+  if constexpr (IMG) {
     constexpr int NB = C::HALF / 32;
     const int c = lane % 32, g = lane / 32;
     f32x16 ta[NB];
@@ -254,9 +255,9 @@ __device__ __forceinline__ void du_to_dx(const float (&du)[Cfg<D>::LOC], const u
         uint4 o;
         o.x = pack_f16x2(ta[j][8 * ks2], ta[j][8 * ks2 + 1]);     o.y = pack_f16x2(ta[j][8 * ks2 + 2], ta[j][8 * ks2 + 3]);
         o.z = pack_f16x2(ta[j][8 * ks2 + 4], ta[j][8 * ks2 + 5]); o.w = pack_f16x2(ta[j][8 * ks2 + 6], ta[j][8 * ks2 + 7]);
-        du_blk[(ks2 * NB + j) * 64 + lane] = o;
+        img[ks2 * NB + j] = o;
       }
-    if (lane == 0) *du_its = m > 0.f ? its : 0.f;
+    img_its = m > 0.f ? its : 0.f;
   }
 #pragma unroll
   for (int mb = 0; mb < L::MB; ++mb)
@@ -272,17 +273,132 @@ __device__ __forceinline__ void du_to_dx(const float (&du)[Cfg<D>::LOC], const u
       });
 }
 
+// ---- dW~ = sum_i x_i^T du_i, accumulated inside the kernels that make du ---------------------
+// The workgroup parks 128 tokens in LDS as two fp16 tiles, x [kTile][D] and du [kTile][D/2] (rows swizzled
+// like the phi tile; a 32-token block of du carries the power-of-two scale du_to_dx gave it, with the
+// inverse scales beside the tile).  Its NW wavefronts then contract over the tokens with transposing
+// reads of both tiles: wavefront w owns the feature block w % NB and RB 32-channel row blocks and brings
+// the blocks to one common power-of-two scale that follows the running maximum of the workgroup
+// (gamma_step; the accumulators are rescaled by the exact ratio when a tile raises it).  Partials per
+// workgroup are reduced in a fixed order afterwards.
+template <int D, int NW>
+struct DwTile {
+  static constexpr int HALF = D / 2;
+  static constexpr int LOC = D / 4;
+  static constexpr int RSX = D * 2;                        // bytes per row of the x tile
+  static constexpr int RSU = HALF * 2;                     // bytes per row of the du tile
+  static constexpr int NB = HALF / 32;                     // 32-column blocks of du
+  static constexpr int RB = (D / 32) * NB >= NW ? (D / 32) * NB / NW : 1;   // row blocks per wavefront
+  static constexpr int BPT = kTile / 32;                   // du blocks per parked tile
+  static constexpr int KSN = kTile / 16;
+  static constexpr int DU_BYTES = kTile * RSU;
+  f32x16 acc[RB];
+  float gamma;
+  int fb, row0;
+  bool active;
+
+  __device__ __forceinline__ void init(int w) {
+    fb = w % NB; row0 = (w / NB) * RB;
+    active = row0 < D / 32;
+    gamma = kGammaUnset;
+#pragma unroll
+    for (int i = 0; i < RB; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  }
+  // The x rows of block slot (0..3) as the projection holds them: lane (t,g) has the 16-byte chunks 2ks + g of token t.
+  static __device__ __forceinline__ void park_x(const uint4 (&xr)[D / 16], char* sX, int slot, int lane) {
+    const int row = 32 * slot + lane % 32, g = lane / 32;
+    char* rowp = sX + row * RSX;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) {
+      uint4 hv;
+      hv.x = bf16x2_to_f16x2(xr[ks].x); hv.y = bf16x2_to_f16x2(xr[ks].y);
+      hv.z = bf16x2_to_f16x2(xr[ks].z); hv.w = bf16x2_to_f16x2(xr[ks].w);
+      *reinterpret_cast<uint4*>(rowp + (((2 * ks + g) ^ swz<D>(row)) * 16)) = hv;
+    }
+  }
+  // The scaled fp16 du of block slot (0..3) of the parked tile, as du_to_dx packs it: lane (t,g) holds features
+  // g*LOC .. g*LOC + LOC-1 of token t.
+  static __device__ __forceinline__ void park_du(const uint32_t (&dub)[LOC / 2], float blk_its, char* sU, float* sIts, int slot, int lane) {
+    const int row = 32 * slot + lane % 32, g = lane / 32;
+    char* rowp = sU + row * RSU;
+#pragma unroll
+    for (int c = 0; c < LOC / 8; ++c) {
+      uint4 v; v.x = dub[4 * c]; v.y = dub[4 * c + 1]; v.z = dub[4 * c + 2]; v.w = dub[4 * c + 3];
+      *reinterpret_cast<uint4*>(rowp + (((g * (LOC / 8) + c) ^ swz<HALF>(row)) * 16)) = v;
+    }
+    if (lane == 0) sIts[slot] = blk_its;
+  }
+  // lane: pass lane + opaque_zero() from inside the tile loop: the read offsets are then worked out per tile (a few
+  // integer operations) instead of being held in registers, or spilled, across the whole loop
+  __device__ __forceinline__ void contract(const char* sX, const char* sU, const float* sIts, int lane) {
+    float its[BPT];
+    float m = 0.f;
+#pragma unroll
+    for (int i = 0; i < BPT; ++i) { its[i] = sIts[i]; m = fmaxf(m, its[i]); }
+    float gnext = gamma;
+    float ratio = gamma_step(gnext, gamma_for(m));
+    // the same in every lane: kept in scalar registers
+    gamma = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, gnext)));
+    ratio = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, ratio)));
+    if (ratio != 1.f) {
+#pragma unroll
+      for (int j = 0; j < RB; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[j][r] *= ratio;
+    }
+    if (!active) return;
+    int offA[RB][2], offB[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      offB[j] = tr_offset_g4<HALF>(32 * fb, lane, j);
+#pragma unroll
+      for (int i = 0; i < RB; ++i) offA[i][j] = tr_offset_g4<D>(32 * (row0 + i), lane, j);
+    }
+    // every operand is requested before the first MFMA: one LDS latency for the tile instead of one per k-step
+    f16x8 a[KSN][RB], b[KSN];
+#pragma unroll
+    for (int ks = 0; ks < KSN; ++ks) {
+      b[ks] = read_tr(sU + ks * 16 * RSU, offB[0], offB[1]);
+#pragma unroll
+      for (int i = 0; i < RB; ++i) a[ks][i] = read_tr(sX + ks * 16 * RSX, offA[i][0], offA[i][1]);
+    }
+#pragma unroll
+    for (int ks = 0; ks < KSN; ++ks) {
+      const _Float16 f = (_Float16)(gamma * its[ks / 2]);   // a power of two, or 0 for an all-zero block
+      const f16x8 bo = b[ks] * f;
+#pragma unroll
+      for (int i = 0; i < RB; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[ks][i], bo, acc[i], 0, 0, 0);
+    }
+  }
+  // part: this workgroup's [D][HALF] partial
+  __device__ __forceinline__ void store(float* part, int lane) const {
+    if (!active) return;
+    const float ig = __builtin_amdgcn_rcpf(gamma);
+    const int c = lane % 32, g = lane / 32;
+#pragma unroll
+    for (int i = 0; i < RB; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        part[(32 * (row0 + i) + 8 * (r / 4) + 4 * g + (r % 4)) * HALF + 32 * fb + c] = acc[i][r] * ig;
+  }
+};
+
 // ---- query side --------------------------------------------------------------------------
 // BLEND: dout is the gradient of the mixed output of Eq. 6; the linear branch receives
 // (1 - r') dout, and the workgroup's part of -sum dout . o goes to dr_part (dL/dr = sum dout . (s - o);
 // the sum dout . s is a separate streaming dot product, taken only when dL/dr is asked for).
-template <int D, bool BLEND, bool CENTRE>
+// DW: dW~_q is accumulated here as well (DwTile): after the tile's dS contraction the phi and dO tiles in LDS
+// are dead, and the tile's q rows (read again: the registers that held them are long reused) and du images
+// take their place.
+template <int D, bool BLEND, bool CENTRE, bool DW>
 __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ dout,
                                                    const uint16_t* __restrict__ wq, const float* __restrict__ state,
                                                    const uint4* __restrict__ gimg, const uint4* __restrict__ simg,
                                                    const uint4* __restrict__ wimg, const float* __restrict__ scales,
                                                    uint16_t* __restrict__ dq,
-                                                   float* __restrict__ partials, uint4* __restrict__ du_img, float* __restrict__ du_its,
+                                                   float* __restrict__ partials, float* __restrict__ dw_part,
                                                    const uint16_t* __restrict__ blend, const float* __restrict__ rptr,
                                                    float* __restrict__ dr_part,
                                                    float* __restrict__ cs_part,
@@ -294,8 +410,8 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
   constexpr int WMN = D / 64;
   constexpr int SA_IMG = L::KS * L::MBZ * 64;
   constexpr int WB_IMG = (C::LOC / 8) * L::MB * 64;
-  constexpr int DU_BLK = 2 * (C::HALF / 32) * 64;          // 16-byte entries of one block's du image
   constexpr float kMean = 2.0f / D;                        // mean of phi over its features
+  using DWT = DwTile<D, NT / 64>;
   extern __shared__ uint4 smem[];
   uint4* sWA = smem;
   uint4* sSA = sWA + C::W_IMG;
@@ -304,7 +420,8 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
   char* sDO = sPhi + kTile * RS;                           // [kTile][D] fp16: gamma * dO / den
   uint16_t* sW16 = reinterpret_cast<uint16_t*>(sDO + kTile * RS);   // [kTile] fp16: -gamma * delta / den
   float* sZ = reinterpret_cast<float*>(sW16 + kTile);      // [D] z, unscaled
-  float* sRed = sZ + D;                                    // [8]
+  float* sRed = sZ + D;                                    // [8]: 0..3 the tile's operand maxima, 4..7 the du blocks' inverse scales
+  char* sDU = reinterpret_cast<char*>(sRed + 8);           // DW: the tile's du, [kTile][D/2] fp16
 
   const int tid = threadIdx.x, lane = tid % 64;
   const int w = __builtin_amdgcn_readfirstlane(tid / 64);
@@ -342,29 +459,36 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
   }
   const int zmb = (WMN == 2) ? (2 * mi + ni) : mi;
   const bool do_z = (WMN == 2) || (ni == 0);
+  // read offsets of the dS contraction; DW: worked out again in every tile (registers are what is short there)
   int offA[WMN][2], offB[WMN][2];
+  auto set_offsets = [&](int ln) {
 #pragma unroll
-  for (int i = 0; i < WMN; ++i)
+    for (int i = 0; i < WMN; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      offA[i][j] = tr_offset<D>(32 * (mi * WMN + i), lane, j);
-      offB[i][j] = tr_offset<D>(32 * (ni * WMN + i), lane, j);
-    }
+      for (int j = 0; j < 2; ++j) {
+        offA[i][j] = tr_offset<D>(32 * (mi * WMN + i), ln, j);
+        offB[i][j] = tr_offset<D>(32 * (ni * WMN + i), ln, j);
+      }
+  };
+  if constexpr (!DW) set_offsets(lane);
   const int prow = 32 * w + (lane % 32);
   const int psw = swz<D>(prow);
   float gamma = kGammaUnset;
+  DWT dwt;
+  if constexpr (DW) dwt.init(w);
 
-  // the lane's q rows of a tile are requested for the next tile as soon as the projection has
-  // consumed this tile's copy (never behind a branch: after the last tile it is simply read again);
-  // its dO rows are requested at the top of the tile and first needed after the projection, the
-  // softmaxes and o
+  // the lane's q rows of the next tile are requested late in this tile, behind the softmax Jacobian: the
+  // middle of the chain is where registers are short (never behind a branch: after the last tile the rows
+  // are simply read again); its dO rows are requested at the top of the tile and first needed after the
+  // projection, the softmaxes and o
   uint4 xq[C::UK];
-  auto load_q = [&](int tile) {
+  auto load_rows = [&](uint4 (&x)[C::UK], int tile) {
     const int t = tile * kTile + prow;
     const uint4* row = reinterpret_cast<const uint4*>(qb + (size_t)(t < n ? t : n - 1) * rw.sn);
 #pragma unroll
-    for (int ks = 0; ks < C::UK; ++ks) xq[ks] = row[2 * ks + g];
+    for (int ks = 0; ks < C::UK; ++ks) x[ks] = row[2 * ks + g];
   };
+  auto load_q = [&](int tile) { load_rows(xq, tile); };
   load_q(p < ntile ? p : 0);
   for (int tile = p; tile < ntile; tile += P) {
     const int t = tile * kTile + prow;
@@ -381,7 +505,11 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
     // dout . s is taken here, while few registers are live.
     f32x16 u[C::UM];
     project<D, 3>(xq, sWA, lane, u);
-    load_q(tile + P < ntile ? tile + P : tile);
+    uint4 xr[C::UK];                              // this tile's rows once more, for dW~ (rows past n repeat row n - 1: their du is zero)
+    if constexpr (DW) {
+#pragma unroll
+      for (int ks = 0; ks < C::UK; ++ks) xr[ks] = xq[ks];
+    }
     float pp[C::LOC], pm[C::LOC];
     uint32_t pk[C::NPK];
     softmax_full<D>(u, pp, pm, pk);
@@ -443,7 +571,11 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
     __syncthreads();                             // previous tile's operand reads are done
     {
       const float m = fmaxf(fmaxf(sRed[0], sRed[1]), fmaxf(sRed[2], sRed[3]));
-      const float ratio = gamma_step(gamma, gamma_for(m));
+      float gnext = gamma;
+      float ratio = gamma_step(gnext, gamma_for(m));
+      // the same in every lane: kept in scalar registers
+      gamma = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, gnext)));
+      ratio = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, ratio)));
       if (ratio != 1.f) {                        // this tile is larger than every earlier one
         if constexpr (CENTRE) {
           wsum *= ratio;
@@ -503,8 +635,9 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
 #pragma unroll
         for (int r = 0; r < 16; ++r) ga[mb][r] = 0.f;
       // the S image of this product stays in global memory (LDS is full); its operands are
-      // requested GPF k-steps ahead, otherwise every MFMA waits for its own load
-      constexpr int GPF = 3;
+      // requested GPF k-steps ahead, otherwise every MFMA waits for its own load (0: 213 us for this kernel at the
+      // training shape, 3: 162 us; 2 measures like 3 and leaves 16 registers to the rest)
+      constexpr int GPF = 2;
       uint4 gop[G::KS][G::GM];
 #pragma unroll
       for (int ks = 0; ks < GPF; ++ks)
@@ -541,20 +674,37 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
     float du[C::LOC];
     phi_jacobian<D>(gp, gm, pp, pm, du);
 
+    // The next tile's q rows, and (DW) this tile's rows once more for dW~, wanted after the dS contraction.  Both go
+    // out before the dq stores: loads and stores retire in order, and a wait for a load issued behind the
+    // stores would wait for the stores as well.
+    load_q(tile + P < ntile ? tile + P : tile);
+
     {
       f32x16 xa[L::MB];
       float its;
       const int blk = tile * (kTile / 32) + w;
-      const bool keep = du_img != nullptr && blk * 32 < n;
-      du_to_dx<D, 3>(du, sWB, lane, valid, keep ? du_img + ((size_t)bh * nblk + blk) * DU_BLK : nullptr,
-                  du_its + (size_t)bh * nblk + blk, xa, its);
+      uint4 dimg[2 * DWT::NB];
+      uint32_t dub[C::LOC / 2];
+      float blk_its = 0.f;
+      du_to_dx<D, 3, false>(du, sWB, lane, valid, dimg, blk_its, xa, its, dub);
+      // the previous tile's dW~ contraction has read its du tile: every wavefront has passed this tile's first barrier since
+      if constexpr (DW) DWT::park_du(dub, blk_its, sDU, sRed + 4, w, lane);
       store_token_rows<D>(dqb, rw.sn, blk * 32, n, lane, xa, its);
     }
 
     __syncthreads();
+    if constexpr (DW) set_offsets(lane + opaque_zero());
     contract_tile<D, false, CENTRE>(sPhi, sDO, offA, offB, s, zacc, ni != 0, do_z,
                      [&](int ks) { return as_f16x8(*reinterpret_cast<const uint4*>(sW16 + 16 * ks + 8 * g)); }, csum, &wsum);
+    if constexpr (DW) {
+      __syncthreads();                           // every wavefront is done with the phi and dO tiles
+      DWT::park_x(xr, sPhi, w, lane);
+      __syncthreads();
+      dwt.contract(sPhi, sDU, sRed + 4, lane + opaque_zero());
+      // the next tile's barrier before it parks phi and dO covers these reads
+    }
   }
+  if constexpr (DW) dwt.store(dw_part + ((size_t)bh * P + p) * (size_t)D * C::HALF, lane);
 
   const float ig = __builtin_amdgcn_rcpf(gamma);    // exact: gamma is a power of two
   if constexpr (CENTRE) {
@@ -730,8 +880,18 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
     {
       f32x16 xa[L::MB];
       float its;
-      du_to_dx<D, KAHEAD>(du, sWB, lane, valid, du_img ? du_img + ((size_t)bh * nblk + b) * DU_BLK : nullptr,
-                  du_its + (size_t)bh * nblk + b, xa, its);
+      uint4 dimg[2 * (C::HALF / 32)];
+      uint32_t dub[C::LOC / 2];
+      float dimg_its = 0.f;
+      if (du_img) {
+        du_to_dx<D, KAHEAD, true>(du, sWB, lane, valid, dimg, dimg_its, xa, its, dub);
+        uint4* dst = du_img + ((size_t)bh * nblk + b) * DU_BLK;
+#pragma unroll
+        for (int e = 0; e < 2 * (C::HALF / 32); ++e) dst[e * 64 + lane] = dimg[e];
+        if (lane == 0) du_its[(size_t)bh * nblk + b] = dimg_its;
+      } else {
+        du_to_dx<D, KAHEAD, false>(du, sWB, lane, valid, dimg, dimg_its, xa, its, dub);
+      }
       store_token_rows<D>(dkb, rw.sn, b * 32, n, lane, xa, its);
     }
   }
@@ -870,24 +1030,26 @@ __global__ __launch_bounds__(NT) void dw_mfma_kernel(DwSides sides, int H, int n
   }
 }
 
-template <int D>
+template <int D, bool DW>
 constexpr size_t q_smem() {
   return sizeof(uint4) * (Cfg<D>::W_IMG + ApplyLayout<D>::KS * ApplyLayout<D>::MBZ * 64 + (Cfg<D>::LOC / 8) * ApplyLayout<D>::MB * 64)
-       + 2 * (size_t)kTile * D * 2 + kTile * 2 + (D + 8) * sizeof(float);
+       + 2 * (size_t)kTile * D * 2 + kTile * 2 + (D + 8) * sizeof(float) + (DW ? DwTile<D, NT / 64>::DU_BYTES : 0);
 }
 template <int D>
 constexpr size_t k_smem() {
   return sizeof(uint4) * (Cfg<D>::W_IMG + ApplyLayout<D>::KS * ApplyLayout<D>::MBZ * 64 + GradLayout<D>::IMG
                           + (Cfg<D>::LOC / 8) * ApplyLayout<D>::MB * 64) + (D + 8) * sizeof(float);
 }
+template <auto Kernel>
+struct KernelTag {
+  static constexpr auto value = Kernel;
+};
 template <int D, bool CENTRE>
 hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   hipError_t e;
   // a dL/du region: the blocks' operand images, then (256-byte aligned) one inverse scale per block
   const size_t du_img_bytes = ((size_t)p.BH * ((p.n + 31) / 32) * 32 * (D / 2) * 2 + 255) & ~(size_t)255;
-  uint4* duq = reinterpret_cast<uint4*>(a.du_q);
   uint4* duk = reinterpret_cast<uint4*>(a.du_k);
-  float* duq_its = reinterpret_cast<float*>(reinterpret_cast<char*>(a.du_q) + du_img_bytes);
   float* duk_its = reinterpret_cast<float*>(reinterpret_cast<char*>(a.du_k) + du_img_bytes);
   if ((e = set_smem_once<bwd_prep_kernel<D, true, CENTRE>>(prep_smem_bytes<D>())) != hipSuccess) return e;
   if ((e = set_smem_once<bwd_prep_kernel<D, false, CENTRE>>(prep_smem_bytes<D>())) != hipSuccess) return e;
@@ -895,25 +1057,28 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
                                                        (const uint16_t*)a.wq, (const uint16_t*)a.wk, (uint4*)a.wimg, p.H,
                                                        a.vbar, nullptr, nullptr, nullptr, p.P);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  if (a.blend_in) {
-    if ((e = set_smem_once<bwd_q_kernel<D, true, CENTRE>>(q_smem<D>())) != hipSuccess) return e;
-    bwd_q_kernel<D, true, CENTRE><<<dim3(p.P, p.BH), NT, q_smem<D>(), s>>>(
+  const size_t side_elems = (size_t)p.BH * p.P * D * (D / 2);      // the two sides' dW~ partials sit one behind the other
+  auto launch_q = [&](auto kernel) -> hipError_t {
+    const size_t smem = a.dwq ? q_smem<D, true>() : q_smem<D, false>();
+    hipError_t e2 = set_smem_once<decltype(kernel)::value>(smem);
+    if (e2 != hipSuccess) return e2;
+    decltype(kernel)::value<<<dim3(p.P, p.BH), NT, smem, s>>>(
         (const uint16_t*)a.q, (const uint16_t*)a.dout, (const uint16_t*)a.wq, a.state, (const uint4*)a.gimg,
         (const uint4*)a.simg, (const uint4*)a.wimg, a.scales,
-        (uint16_t*)a.dq, a.partials, a.dwq ? duq : nullptr, duq_its,
-        (const uint16_t*)a.blend_in, a.blend_r, a.dr_part, a.cs_part, p.H, p.n, p.P, p.rows);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+        (uint16_t*)a.dq, a.partials, a.dw_part,
+        (const uint16_t*)a.blend_in, a.blend_r, a.blend_in ? a.dr_part : nullptr, a.cs_part, p.H, p.n, p.P, p.rows);
+    return hipGetLastError();
+  };
+  if (a.blend_in) {
+    e = a.dwq ? launch_q(KernelTag<bwd_q_kernel<D, true, CENTRE, true>>{}) : launch_q(KernelTag<bwd_q_kernel<D, true, CENTRE, false>>{});
+    if (e != hipSuccess) return e;
     if (a.blend_dr) {
       if ((e = launch_dot_centred_bf16(a.dout, a.blend_in, a.vbar, a.dr_part + (size_t)p.BH * p.P, p, s)) != hipSuccess) return e;
       if ((e = launch_dr_reduce(a.dr_part, p.BH * p.P + kDotParts, a.blend_r, a.blend_dr, s)) != hipSuccess) return e;
     }
   } else {
-    if ((e = set_smem_once<bwd_q_kernel<D, false, CENTRE>>(q_smem<D>())) != hipSuccess) return e;
-    bwd_q_kernel<D, false, CENTRE><<<dim3(p.P, p.BH), NT, q_smem<D>(), s>>>(
-        (const uint16_t*)a.q, (const uint16_t*)a.dout, (const uint16_t*)a.wq, a.state, (const uint4*)a.gimg,
-        (const uint4*)a.simg, (const uint4*)a.wimg, a.scales,
-        (uint16_t*)a.dq, a.partials, a.dwq ? duq : nullptr, duq_its, nullptr, nullptr, nullptr, a.cs_part, p.H, p.n, p.P, p.rows);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    e = a.dwq ? launch_q(KernelTag<bwd_q_kernel<D, false, CENTRE, true>>{}) : launch_q(KernelTag<bwd_q_kernel<D, false, CENTRE, false>>{});
+    if (e != hipSuccess) return e;
   }
   if ((e = launch_state_reduce(a.partials, a.dstate, p, s)) != hipSuccess) return e;
   // images of dS: the second half of the scales array, no W~ images
@@ -927,16 +1092,19 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
       (uint16_t*)a.dk, (uint16_t*)a.dv, a.dwk ? duk : nullptr, duk_its, a.dzc, a.dv_row, p.H, p.n, p.rows);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (a.dwq || a.dwk) {
-    // partial sums of the two sides sit one behind the other in the dW~ partial region
-    const size_t side_elems = (size_t)p.BH * p.P * D * (D / 2);
-    DwSides sides{};
+    // the query side's partials are complete (bwd_q_kernel); the key side's come from its dL/du images
+    if (a.dwk) {
+      DwSides sides{};
+      sides.s[0] = DwSide{(const uint16_t*)a.k, duk, duk_its, a.dw_part + side_elems};
+      dw_mfma_kernel<D><<<dim3(p.P, p.BH, 1), NT, 0, s>>>(sides, p.H, p.n, p.P, p.rows);
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    const float* parts[2];
     float* outs[2];
     int ns = 0;
-    if (a.dwq) { sides.s[ns] = DwSide{(const uint16_t*)a.q, duq, duq_its, a.dw_part + ns * side_elems}; outs[ns++] = a.dwq; }
-    if (a.dwk) { sides.s[ns] = DwSide{(const uint16_t*)a.k, duk, duk_its, a.dw_part + ns * side_elems}; outs[ns++] = a.dwk; }
-    dw_mfma_kernel<D><<<dim3(p.P, p.BH, ns), NT, 0, s>>>(sides, p.H, p.n, p.P, p.rows);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    if ((e = launch_dw_reduce2(sides.s[0].part, outs[0], ns > 1 ? sides.s[1].part : nullptr, ns > 1 ? outs[1] : nullptr, p, s)) != hipSuccess) return e;
+    if (a.dwq) { parts[ns] = a.dw_part; outs[ns++] = a.dwq; }
+    if (a.dwk) { parts[ns] = a.dw_part + side_elems; outs[ns++] = a.dwk; }
+    if ((e = launch_dw_reduce2(parts[0], outs[0], ns > 1 ? parts[1] : nullptr, ns > 1 ? outs[1] : nullptr, p, s)) != hipSuccess) return e;
   }
   return hipSuccess;
 }

@@ -204,16 +204,14 @@ __global__ __launch_bounds__(NT3) void apply_bf16_kernel(const uint16_t* __restr
       // stores the tail of out stays dirty in the last-level cache and is written back under
       // whatever kernel runs next (measured: the next call's state pass loses 30 us, this pass
       // gains 20 us)
+      // No branch around any of them: rows past n go to a sink instead (a select), see store_token_rows.
       char* ub = reinterpret_cast<char*>(ob + (size_t)(b * 32) * rw.sn) + lane_off;
-      if (full) {
+      char* sink = reinterpret_cast<char*>(g_store_sink) + lane * 8;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) st_nt(reinterpret_cast<Piece*>(ub + (size_t)(8 * (r / 4) + (r % 4)) * rw.sn * 2), word[r]);
-      } else {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = 8 * (r / 4) + (r % 4);
-          if (b * 32 + row + 4 * g < n) st_nt(reinterpret_cast<Piece*>(ub + (size_t)row * rw.sn * 2), word[r]);
-        }
+      for (int r = 0; r < 16; ++r) {
+        const int row = 8 * (r / 4) + (r % 4);
+        const bool there = full || b * 32 + row + 4 * g < n;
+        st_nt(reinterpret_cast<Piece*>(there ? ub + (size_t)row * rw.sn * 2 : sink), word[r]);
       }
     }
   }

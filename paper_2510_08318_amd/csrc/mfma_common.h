@@ -487,6 +487,9 @@ __device__ __forceinline__ float wave_max_paired(float x) {
   return fmaxf(a, b);
 }
 
+// Where the stores of token rows past the end of a head go (8 bytes per lane; the contents mean nothing).
+static __device__ __attribute__((aligned(256))) unsigned char g_store_sink[64 * 8];
+
 // Accumulators with tokens on the rows (lane (c,g), register r: token t0 + 8*(r/4) + 4g + r%4,
 // channels MB*c .. MB*c + MB-1 in acc[0..MB-1]) -> mul * acc as bf16 rows of base.  Every store
 // instruction writes two whole rows of d channels.
@@ -498,9 +501,16 @@ __device__ __forceinline__ void store_token_rows(uint16_t* base, size_t sn, int 
   const int c = lane % 32, g = lane / 32;
   char* ub = reinterpret_cast<char*>(base + (size_t)t0 * sn);
   const uint32_t lo = ((uint32_t)(4 * g) * (uint32_t)sn + (uint32_t)(MB * c)) * 2u;
-  auto put = [&](int r) {
+  // No branch around any of the stores: rows past n go to a sink instead (a select).  Behind branches the
+  // compiler cannot count the stores in flight, and a later wait for a load that was requested before them
+  // (the next block's rows) turns into a wait for the stores as well.
+  const bool full = t0 + 32 <= n;
+  char* sink = reinterpret_cast<char*>(g_store_sink) + lane * 8;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
     const int row = 8 * (r / 4) + (r % 4);
-    char* dst = ub + (size_t)row * sn * 2 + lo;
+    const bool there = full || t0 + row + 4 * g < n;
+    char* dst = there ? ub + (size_t)row * sn * 2 + lo : sink;
     if constexpr (MB == 4) {
       uint2 v;
       v.x = pack_bf16x2(fmaf(acc[0][r], mul, add[0]), fmaf(acc[1][r], mul, add[1]));
@@ -509,14 +519,6 @@ __device__ __forceinline__ void store_token_rows(uint16_t* base, size_t sn, int 
     } else {
       *reinterpret_cast<uint32_t*>(dst) = pack_bf16x2(fmaf(acc[0][r], mul, add[0]), fmaf(acc[1][r], mul, add[1]));
     }
-  };
-  if (t0 + 32 <= n) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) put(r);
-  } else {
-#pragma unroll
-    for (int r = 0; r < 16; ++r)
-      if (t0 + 8 * (r / 4) + (r % 4) + 4 * g < n) put(r);
   }
 }
 
