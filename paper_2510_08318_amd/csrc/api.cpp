@@ -77,14 +77,9 @@ bool make_plan(int B, int H, int n, int d, int dtype, int layout, Plan* p) {
   r.off_centre = off;   off = up(off + ((size_t)BH * 3 * d + (size_t)BH * r.P * (d + 8)) * sizeof(float));
   r.off_drpart = off;   off = up(off + ((size_t)BH * r.P + kDotParts) * sizeof(float));
   r.bytes_no_wgrads = off;
-  r.off_dwpart = off;   off = up(off + 2 * (size_t)BH * r.P * d * (d / 2) * sizeof(float));
-  {
-    // fp32 mode keeps dL/du as fp32 rows; bf16 mode keeps fp16 operand images of 32-token blocks,
-    // followed by one fp32 scale per block
-    const size_t nblk = ((size_t)n + 31) / 32;
-    r.du_bytes = dtype == LINATTN_BF16 ? up((size_t)BH * nblk * 32 * (d / 2) * 2) + (size_t)BH * nblk * sizeof(float)
-                                       : (size_t)BH * n * (d / 2) * sizeof(float);
-  }
+  r.off_dwpart = off;   off = up(off + (size_t)BH * (r.P + (r.P > r.KP ? r.P : r.KP)) * d * (d / 2) * sizeof(float));
+  // the fp32-arithmetic modes keep dL/du as fp32 rows for a separate dW~ pass; the bf16 kernels accumulate dW~ where du is made
+  r.du_bytes = dtype == LINATTN_BF16 ? 0 : (size_t)BH * n * (d / 2) * sizeof(float);
   r.off_du_q = off;     off = up(off + r.du_bytes);
   r.off_du_k = off;     off = up(off + r.du_bytes);
   r.total_bytes = off;

@@ -8,9 +8,9 @@
 //   through phi  du = p+ (g+ - <g+,p+>) - p- (g- - <g-,p->),   dx = du W~^T,   dW~ = sum x^T du
 //
 // bwd_prep_kernel : fp16 operand image of S for g (rows = features, contraction over channels)
-// bwd_q_kernel    : per 128-token tile: phi(Q), o, delta, g, du, dq; dS, dz partials (split-n)
-// bwd_k_kernel    : per 32-token block: phi(K), g, du, dk, dv
-// dw_mfma_kernel  : dW~ partials = x^T du per token split (reduced in state_reduce.hip)
+// bwd_q_kernel    : per 128-token tile: phi(Q), o, delta, g, du, dq; dS, dz partials (split-n); dW~_q partials
+// bwd_k_kernel    : per 32-token block: phi(K), g, du, dk, dv; dW~_k partials
+// (the partials are reduced in state_reduce.hip)
 //
 // Precision: every 16-bit MFMA operand except the stored bf16 q, k (projection) is fp16.
 // Operands that belong to one token only (dO_i for g_i, du_i for dx_i) are scaled by a per-token
@@ -199,16 +199,12 @@ __device__ __forceinline__ void phi_jacobian(const float (&gp)[Cfg<D>::LOC], con
 // (lane (t,g) holds features g*LOC + 8ks + e of token t); the B operands are the W~ image.
 // acc[mb][r] of lane (c,g) is its * dx[token 8*(r/4) + 4g + r%4][channel MB*c + mb].
 //
-// IMG: the scaled fp16 du of the block is also returned as the B operands of the contraction over the
-// tokens that gives dW~.  A second MFMA against 0/1 selection operands turns it (exactly) so that a
-// lane holds one feature and 16 tokens; entry (ks2, j) of lane (c,g) holds feature 32j + c of tokens
-// 16*ks2 + {4g .. 4g+3, 8+4g .. 8+4g+3}.  Rows of tokens that do not exist are zero.  img_its receives
-// the inverse scale (0 for an all-zero block).
+// dub receives the scaled fp16 du as packed (lane (t,g): features g*LOC .. g*LOC + LOC-1 of token t; zero for tokens
+// that do not exist), blk_its the inverse scale (0 for an all-zero block): what the dW~ contraction parks.
 // AHEAD: lookahead of the W~ operand reads of dx (pipelined_operands).
-template <int D, int AHEAD, bool IMG>
+template <int D, int AHEAD>
 __device__ __forceinline__ void du_to_dx(const float (&du)[Cfg<D>::LOC], const uint4* sWB, int lane, bool valid,
-                                         uint4 (&img)[2 * (Cfg<D>::HALF / 32)], float& img_its,
-                                         f32x16 (&acc)[D / 32], float& its, uint32_t (&dub)[Cfg<D>::LOC / 2]) {
+                                         f32x16 (&acc)[D / 32], float& its, uint32_t (&dub)[Cfg<D>::LOC / 2], float& blk_its) {
   using C = Cfg<D>;
   using L = ApplyLayout<D>;
   constexpr int DK = C::LOC / 8;
@@ -223,42 +219,7 @@ __device__ __forceinline__ void du_to_dx(const float (&du)[Cfg<D>::LOC], const u
 #pragma unroll
   for (int j = 0; j < C::LOC / 2; ++j) dub[j] = pack_f16x2(du[2 * j] * ts, du[2 * j + 1] * ts);
   its = __builtin_amdgcn_rcpf(pow2_normaliser(m));     // exact: a power of two
-  img_its = m > 0.f ? its : 0.f;
-  if constexpr (IMG) {
-    constexpr int NB = C::HALF / 32;
-    const int c = lane % 32, g = lane / 32;
-    f32x16 ta[NB];
-#pragma unroll
-    for (int j = 0; j < NB; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) ta[j][r] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < DK; ++ks) {
-      uint4 aq; aq.x = dub[4 * ks]; aq.y = dub[4 * ks + 1]; aq.z = dub[4 * ks + 2]; aq.w = dub[4 * ks + 3];
-      const f16x8 aop = as_f16x8(aq);
-#pragma unroll
-      for (int j = 0; j < NB; ++j) {
-        // B[k = 8g + e][column c] = 1 where the feature behind row k, g*LOC + 8ks + e, is 32j + c
-        const int f = 32 * j + c, rem = f % C::LOC;
-        const uint32_t one = (g == f / C::LOC) ? ((rem & 1) ? 0x3C000000u : 0x00003C00u) : 0u;
-        const int slot = (rem >> 1) - 4 * ks;
-        uint4 sq;
-        sq.x = slot == 0 ? one : 0u; sq.y = slot == 1 ? one : 0u;
-        sq.z = slot == 2 ? one : 0u; sq.w = slot == 3 ? one : 0u;
-        ta[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop, as_f16x8(sq), ta[j], 0, 0, 0);
-      }
-    }
-#pragma unroll
-    for (int ks2 = 0; ks2 < 2; ++ks2)
-#pragma unroll
-      for (int j = 0; j < NB; ++j) {
-        uint4 o;
-        o.x = pack_f16x2(ta[j][8 * ks2], ta[j][8 * ks2 + 1]);     o.y = pack_f16x2(ta[j][8 * ks2 + 2], ta[j][8 * ks2 + 3]);
-        o.z = pack_f16x2(ta[j][8 * ks2 + 4], ta[j][8 * ks2 + 5]); o.w = pack_f16x2(ta[j][8 * ks2 + 6], ta[j][8 * ks2 + 7]);
-        img[ks2 * NB + j] = o;
-      }
-    img_its = m > 0.f ? its : 0.f;
-  }
+  blk_its = m > 0.f ? its : 0.f;
 #pragma unroll
   for (int mb = 0; mb < L::MB; ++mb)
 #pragma unroll
@@ -291,6 +252,7 @@ struct DwTile {
   static constexpr int RB = (D / 32) * NB >= NW ? (D / 32) * NB / NW : 1;   // row blocks per wavefront
   static constexpr int BPT = kTile / 32;                   // du blocks per parked tile
   static constexpr int KSN = kTile / 16;
+  static constexpr int KBATCH = NW > 4 ? KSN / 2 : KSN;     // k-steps whose operands are in flight together
   static constexpr int DU_BYTES = kTile * RSU;
   f32x16 acc[RB];
   float gamma;
@@ -356,20 +318,24 @@ struct DwTile {
 #pragma unroll
       for (int i = 0; i < RB; ++i) offA[i][j] = tr_offset_g4<D>(32 * (row0 + i), lane, j);
     }
-    // every operand is requested before the first MFMA: one LDS latency for the tile instead of one per k-step
-    f16x8 a[KSN][RB], b[KSN];
+    // the operands of KBATCH k-steps are requested before their first MFMA: one LDS latency per batch instead of one
+    // per k-step (the whole tile at once where the wavefront has 512 registers, half of it where it has 256)
 #pragma unroll
-    for (int ks = 0; ks < KSN; ++ks) {
-      b[ks] = read_tr(sU + ks * 16 * RSU, offB[0], offB[1]);
+    for (int k0 = 0; k0 < KSN; k0 += KBATCH) {
+      f16x8 a[KBATCH][RB], b[KBATCH];
 #pragma unroll
-      for (int i = 0; i < RB; ++i) a[ks][i] = read_tr(sX + ks * 16 * RSX, offA[i][0], offA[i][1]);
-    }
+      for (int ks = 0; ks < KBATCH; ++ks) {
+        b[ks] = read_tr(sU + (k0 + ks) * 16 * RSU, offB[0], offB[1]);
 #pragma unroll
-    for (int ks = 0; ks < KSN; ++ks) {
-      const _Float16 f = (_Float16)(gamma * its[ks / 2]);   // a power of two, or 0 for an all-zero block
-      const f16x8 bo = b[ks] * f;
+        for (int i = 0; i < RB; ++i) a[ks][i] = read_tr(sX + (k0 + ks) * 16 * RSX, offA[i][0], offA[i][1]);
+      }
 #pragma unroll
-      for (int i = 0; i < RB; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[ks][i], bo, acc[i], 0, 0, 0);
+      for (int ks = 0; ks < KBATCH; ++ks) {
+        const _Float16 f = (_Float16)(gamma * its[(k0 + ks) / 2]);   // a power of two, or 0 for an all-zero block
+        const f16x8 bo = b[ks] * f;
+#pragma unroll
+        for (int i = 0; i < RB; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[ks][i], bo, acc[i], 0, 0, 0);
+      }
     }
   }
   // part: this workgroup's [D][HALF] partial
@@ -683,10 +649,9 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
       f32x16 xa[L::MB];
       float its;
       const int blk = tile * (kTile / 32) + w;
-      uint4 dimg[2 * DWT::NB];
       uint32_t dub[C::LOC / 2];
       float blk_its = 0.f;
-      du_to_dx<D, 3, false>(du, sWB, lane, valid, dimg, blk_its, xa, its, dub);
+      du_to_dx<D, 3>(du, sWB, lane, valid, xa, its, dub, blk_its);
       // the previous tile's dW~ contraction has read its du tile: every wavefront has passed this tile's first barrier since
       if constexpr (DW) DWT::park_du(dub, blk_its, sDU, sRed + 4, w, lane);
       store_token_rows<D>(dqb, rw.sn, blk * 32, n, lane, xa, its);
@@ -751,13 +716,16 @@ constexpr int NTK = 512;     // 8 wavefronts, one workgroup per compute unit
 // MFMA (0) measured 101.5 us, one ahead 102.9, three ahead 106.7, the compiler's own order 105.
 constexpr int KAHEAD = 0;
 
-template <int D>
+// DW: dW~_k is accumulated here as well (DwTile).  The eight wavefronts then walk their blocks in step: after each
+// round of eight blocks the wavefronts 0-3 park their k rows (read again) and du, all eight contract over those
+// 128 tokens (one 32 x 32 block of dW~_k each), then the same for the blocks of the wavefronts 4-7.
+template <int D, bool DW>
 __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                                                     const uint16_t* __restrict__ wk, const float* __restrict__ dstate,
                                                     const uint4* __restrict__ dsimg, const uint4* __restrict__ dgimg,
                                                     const uint4* __restrict__ wimg, const float* __restrict__ scales,
                                                     uint16_t* __restrict__ dk, uint16_t* __restrict__ dv,
-                                                    uint4* __restrict__ du_img, float* __restrict__ du_its,
+                                                    float* __restrict__ dw_part,
                                                     const float* __restrict__ dzc, const float* __restrict__ dv_row,
                                                     int H, int n, Rows rw) {
   using C = Cfg<D>;
@@ -766,14 +734,16 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
   constexpr int NW = NTK / 64;
   constexpr int SA_IMG = L::KS * L::MBZ * 64;
   constexpr int WB_IMG = (C::LOC / 8) * L::MB * 64;
-  constexpr int DU_BLK = 2 * (C::HALF / 32) * 64;          // 16-byte entries of one block's du image
+  using DWT = DwTile<D, NW>;
   extern __shared__ uint4 smem[];
   uint4* sWA = smem;
   uint4* sVA = sWA + C::W_IMG;             // image of dS^T for dv (contraction over features)
   uint4* sGA = sVA + SA_IMG;               // image of dS for g (contraction over channels)
   uint4* sWB = sGA + G::IMG;
   float* sZ = reinterpret_cast<float*>(sWB + WB_IMG);   // [D] dz, unscaled
-  float* sRed = sZ + D;
+  float* sRed = sZ + D;                                 // [8]: DW: 0..3 the parked du blocks' inverse scales
+  char* sX = reinterpret_cast<char*>(sRed + 8);         // DW: [kTile][D] fp16, k rows of four blocks
+  char* sU = sX + kTile * D * 2;                        // DW: [kTile][D/2] fp16, their du
 
   const int tid = threadIdx.x, lane = tid % 64;
   const int w = __builtin_amdgcn_readfirstlane(tid / 64);
@@ -802,13 +772,14 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
   const int nblk = (n + 31) / 32;
   const int stride = gridDim.x * NW;
   uint4 xk[C::UK], vr[D / 16];
-  auto load_k = [&](int b) {
+  auto load_rows = [&](uint4 (&x)[C::UK], int b) {
     const int t = b * 32 + (lane % 32);
     const int tc = t < n ? t : (n - 1);
     const uint4* row = reinterpret_cast<const uint4*>(kb + (size_t)tc * rw.sn);
 #pragma unroll
-    for (int ks = 0; ks < C::UK; ++ks) xk[ks] = row[2 * ks + g];
+    for (int ks = 0; ks < C::UK; ++ks) x[ks] = row[2 * ks + g];
   };
+  auto load_k = [&](int b) { load_rows(xk, b); };
   auto load_v = [&](int b) {
     const int t = b * 32 + (lane % 32);
     const int tc = t < n ? t : (n - 1);
@@ -816,15 +787,22 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
 #pragma unroll
     for (int i = 0; i < D / 16; ++i) vr[i] = vrow[i];
   };
+  DWT dwt;
+  if constexpr (DW) dwt.init(w);
+  // DW: every wavefront of the workgroup makes the same number of rounds (there are barriers inside); a wavefront
+  // whose block does not exist works on tokens past n: its loads repeat row n - 1, its du is zero, its stores go
+  // to the sink
   int b = blockIdx.x * NW + w;
-  if (b < nblk) load_k(b);
-  for (; b < nblk; b += stride) {
+  if (DW || b < nblk) load_k(b);
+  for (int b0 = blockIdx.x * NW; DW ? b0 < nblk : b < nblk; b0 += stride, b += stride) {
     const int t = b * 32 + (lane % 32);
     const bool valid = t < n;
     load_v(b);                                        // wanted after the projection, the softmax and dv
     f32x16 u[C::UM];
     project<D>(xk, sWA, lane, u);
-    if (b + stride < nblk) load_k(b + stride);        // next block's k flies during this one
+    if constexpr (!DW) {
+      if (b + stride < nblk) load_k(b + stride);      // next block's k flies during this one
+    }
     float pp[C::LOC], pm[C::LOC];
     uint32_t pk[C::NPK];
     softmax_full<D>(u, pp, pm, pk);
@@ -880,154 +858,35 @@ __global__ __launch_bounds__(NTK) void bwd_k_kernel(const uint16_t* __restrict__
     {
       f32x16 xa[L::MB];
       float its;
-      uint4 dimg[2 * (C::HALF / 32)];
       uint32_t dub[C::LOC / 2];
-      float dimg_its = 0.f;
-      if (du_img) {
-        du_to_dx<D, KAHEAD, true>(du, sWB, lane, valid, dimg, dimg_its, xa, its, dub);
-        uint4* dst = du_img + ((size_t)bh * nblk + b) * DU_BLK;
-#pragma unroll
-        for (int e = 0; e < 2 * (C::HALF / 32); ++e) dst[e * 64 + lane] = dimg[e];
-        if (lane == 0) du_its[(size_t)bh * nblk + b] = dimg_its;
-      } else {
-        du_to_dx<D, KAHEAD, false>(du, sWB, lane, valid, dimg, dimg_its, xa, its, dub);
+      float blk_its = 0.f;
+      du_to_dx<D, KAHEAD>(du, sWB, lane, valid, xa, its, dub, blk_its);
+      uint4 xr[C::UK];
+      if constexpr (DW) {
+        // the next block's k rows (with the dW~ accumulator resident they do not fit beside the middle of the chain) and
+        // this block's rows once more; both before the dk stores: a wait for them must not wait for the stores
+        load_k(b + stride);
+        load_rows(xr, b);
       }
       store_token_rows<D>(dkb, rw.sn, b * 32, n, lane, xa, its);
-    }
-  }
-}
-
-// ---- dW~ = sum_{b, i} x_i^T du_i on MFMA -----------------------------------------------------
-// x [BH][n][D] bf16; du as written by du_to_dx: per 32-token block the fp16 B operands of the
-// contraction over the tokens, scaled by a power of two per block, with the inverse scales in
-// du_its.  Per 128-token tile x is parked in LDS as fp16 and read with transposing reads in the
-// token order of the du operands, which come straight from global memory and are brought to one
-// common power-of-two scale per workgroup (taken from its first tile).  Wavefront w owns the
-// feature block w % NB and RB 32-channel row blocks.  Partials per (b,h) and split are reduced in
-// a fixed order afterwards.
-// Both sides (W~_q from q and its du, W~_k from k and its du) run in one launch, side = blockIdx.z:
-// twice the workgroups per compute unit hide each other's waits.
-struct DwSide {
-  const uint16_t* x;
-  const uint4* du_img;
-  const float* du_its;
-  float* part;
-};
-struct DwSides {
-  DwSide s[2];
-};
-template <int D>
-__global__ __launch_bounds__(NT) void dw_mfma_kernel(DwSides sides, int H, int n, int P, Rows rw) {
-  const uint16_t* __restrict__ x = sides.s[blockIdx.z].x;
-  const uint4* __restrict__ du_img = sides.s[blockIdx.z].du_img;
-  const float* __restrict__ du_its = sides.s[blockIdx.z].du_its;
-  float* __restrict__ part = sides.s[blockIdx.z].part;
-  constexpr int HALF = D / 2;
-  constexpr int RSX = D * 2;
-  constexpr int NB = HALF / 32;                 // 32-column blocks of du
-  constexpr int RB = D / 64;                    // row blocks per wavefront
-  constexpr int XPT = (kTile * (D / 8)) / NT;   // 16-byte chunks of the x tile per thread
-  constexpr int BPT = kTile / 32;               // du blocks per tile
-  constexpr int DU_BLK = 2 * NB * 64;
-  __shared__ __attribute__((aligned(16))) char sX[kTile * RSX];
-  const int tid = threadIdx.x, lane = tid % 64;
-  const int w = __builtin_amdgcn_readfirstlane(tid / 64);
-  const int g = lane / 32;
-  const int bh = blockIdx.y, p = blockIdx.x;
-  const uint16_t* xb = x + head_base(rw, bh, H);
-  const int ntile = (n + kTile - 1) / kTile;
-  const int nblk = (n + 31) / 32;
-  const uint4* ub = du_img + (size_t)bh * nblk * DU_BLK + lane;
-  const float* sb = du_its + (size_t)bh * nblk;
-  const int fb = w % NB, row0 = (w / NB) * RB;
-  const bool active = row0 < D / 32;
-
-  f32x16 acc[RB];
+      if constexpr (DW) {
 #pragma unroll
-  for (int j = 0; j < RB; ++j)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
-  int offA[RB][2];
-#pragma unroll
-  for (int i = 0; i < RB; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j) offA[i][j] = tr_offset_g4<D>(32 * (active ? row0 + i : 0), lane, j);
-  float gamma = kGammaUnset;
-  uint4 xr[XPT], ur[2 * BPT];
-  float its[BPT];
-  // the next tile's rows are requested while the current one is contracted
-  auto load_tile = [&](int tile) {
-    const int t0 = tile * kTile;
-#pragma unroll
-    for (int i = 0; i < XPT; ++i) {
-      const int idx = tid + NT * i, r = idx / (D / 8), c = idx % (D / 8);
-      const int t = t0 + r;
-      xr[i] = t < n ? ld_nt(reinterpret_cast<const uint4*>(xb + (size_t)t * rw.sn) + c) : make_uint4(0, 0, 0, 0);
-    }
-#pragma unroll
-    for (int i = 0; i < BPT; ++i) {
-      const int blk = tile * BPT + i;
-      const bool there = blk < nblk;
-      its[i] = there ? sb[blk] : 0.f;
-#pragma unroll
-      for (int ks2 = 0; ks2 < 2; ++ks2)
-        ur[2 * i + ks2] = there ? ub[((size_t)blk * 2 * NB + ks2 * NB + fb) * 64] : make_uint4(0, 0, 0, 0);
-    }
-  };
-  if (p < ntile) load_tile(p);
-  for (int tile = p; tile < ntile; tile += P) {
-    {
-      // the tile's largest block scale (a power of two, the same in every thread)
-      float m = 0.f;
-#pragma unroll
-      for (int i = 0; i < BPT; ++i) m = fmaxf(m, its[i]);
-      const float ratio = gamma_step(gamma, gamma_for(m));
-      if (ratio != 1.f) {
-#pragma unroll
-        for (int j = 0; j < RB; ++j)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) acc[j][r] *= ratio;
-      }
-    }
-    __syncthreads();                              // previous tile's operand reads are done
-#pragma unroll
-    for (int i = 0; i < XPT; ++i) {
-      const int idx = tid + NT * i, r = idx / (D / 8), c = idx % (D / 8);
-      uint4 hv;
-      hv.x = bf16x2_to_f16x2(xr[i].x); hv.y = bf16x2_to_f16x2(xr[i].y);
-      hv.z = bf16x2_to_f16x2(xr[i].z); hv.w = bf16x2_to_f16x2(xr[i].w);
-      *reinterpret_cast<uint4*>(sX + r * RSX + ((c ^ swz<D>(r)) * 16)) = hv;
-    }
-    f16x8 bo[2 * BPT];
-#pragma unroll
-    for (int i = 0; i < BPT; ++i) {
-      const _Float16 f = (_Float16)(gamma * its[i]);        // a power of two, or 0 for an all-zero block
-#pragma unroll
-      for (int ks2 = 0; ks2 < 2; ++ks2) bo[2 * i + ks2] = as_f16x8(ur[2 * i + ks2]) * f;
-    }
-    if (tile + P < ntile) load_tile(tile + P);
-    __syncthreads();
-    if (active) {
-#pragma unroll
-      for (int ks = 0; ks < kTile / 16; ++ks) {
-#pragma unroll
-        for (int i = 0; i < RB; ++i) {
-          const f16x8 a = read_tr(sX + ks * 16 * RSX, offA[i][0], offA[i][1]);
-          acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bo[ks], acc[i], 0, 0, 0);
+        for (int half = 0; half < 2; ++half) {
+          __syncthreads();                             // the tiles' previous readers are done
+          if (w / 4 == half) {
+            // (addresses worked out here, from a lane index the optimiser cannot hoist: held across the loop they end up
+            // in scratch memory, and a wait for a scratch load also waits for the dk stores just issued)
+            const int lz = lane + opaque_zero();
+            DWT::park_x(xr, sX, w % 4, lz);
+            DWT::park_du(dub, blk_its, sU, sRed, w % 4, lz);
+          }
+          __syncthreads();
+          dwt.contract(sX, sU, sRed, lane + opaque_zero());
         }
       }
     }
   }
-  if (active) {
-    const float ig = __builtin_amdgcn_rcpf(gamma);
-    float* dst = part + ((size_t)bh * P + p) * (size_t)D * HALF;
-    const int c = lane % 32;
-#pragma unroll
-    for (int i = 0; i < RB; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r)
-        dst[(32 * (row0 + i) + 8 * (r / 4) + 4 * g + (r % 4)) * HALF + 32 * fb + c] = acc[i][r] * ig;
-  }
+  if constexpr (DW) dwt.store(dw_part + ((size_t)bh * gridDim.x + blockIdx.x) * (size_t)D * C::HALF, lane);
 }
 
 template <int D, bool DW>
@@ -1035,10 +894,11 @@ constexpr size_t q_smem() {
   return sizeof(uint4) * (Cfg<D>::W_IMG + ApplyLayout<D>::KS * ApplyLayout<D>::MBZ * 64 + (Cfg<D>::LOC / 8) * ApplyLayout<D>::MB * 64)
        + 2 * (size_t)kTile * D * 2 + kTile * 2 + (D + 8) * sizeof(float) + (DW ? DwTile<D, NT / 64>::DU_BYTES : 0);
 }
-template <int D>
+template <int D, bool DW>
 constexpr size_t k_smem() {
   return sizeof(uint4) * (Cfg<D>::W_IMG + ApplyLayout<D>::KS * ApplyLayout<D>::MBZ * 64 + GradLayout<D>::IMG
-                          + (Cfg<D>::LOC / 8) * ApplyLayout<D>::MB * 64) + (D + 8) * sizeof(float);
+                          + (Cfg<D>::LOC / 8) * ApplyLayout<D>::MB * 64) + (D + 8) * sizeof(float)
+       + (DW ? (size_t)kTile * D * 2 + DwTile<D, NTK / 64>::DU_BYTES : 0);
 }
 template <auto Kernel>
 struct KernelTag {
@@ -1047,17 +907,14 @@ struct KernelTag {
 template <int D, bool CENTRE>
 hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   hipError_t e;
-  // a dL/du region: the blocks' operand images, then (256-byte aligned) one inverse scale per block
-  const size_t du_img_bytes = ((size_t)p.BH * ((p.n + 31) / 32) * 32 * (D / 2) * 2 + 255) & ~(size_t)255;
-  uint4* duk = reinterpret_cast<uint4*>(a.du_k);
-  float* duk_its = reinterpret_cast<float*>(reinterpret_cast<char*>(a.du_k) + du_img_bytes);
   if ((e = set_smem_once<bwd_prep_kernel<D, true, CENTRE>>(prep_smem_bytes<D>())) != hipSuccess) return e;
   if ((e = set_smem_once<bwd_prep_kernel<D, false, CENTRE>>(prep_smem_bytes<D>())) != hipSuccess) return e;
   bwd_prep_kernel<D, true, CENTRE><<<dim3(p.BH, PREP_Y), PT, prep_smem_bytes<D>(), s>>>(a.state, (uint4*)a.gimg, (uint4*)a.simg, a.scales,
                                                        (const uint16_t*)a.wq, (const uint16_t*)a.wk, (uint4*)a.wimg, p.H,
                                                        a.vbar, nullptr, nullptr, nullptr, p.P);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  const size_t side_elems = (size_t)p.BH * p.P * D * (D / 2);      // the two sides' dW~ partials sit one behind the other
+  // dW~ partials: [BH][P] blocks of the query side, then [BH][KP] of the key side
+  const size_t side_elems = (size_t)p.BH * p.P * D * (D / 2);
   auto launch_q = [&](auto kernel) -> hipError_t {
     const size_t smem = a.dwq ? q_smem<D, true>() : q_smem<D, false>();
     hipError_t e2 = set_smem_once<decltype(kernel)::value>(smem);
@@ -1085,26 +942,19 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   bwd_prep_kernel<D, false, CENTRE><<<dim3(p.BH, PREP_Y), PT, prep_smem_bytes<D>(), s>>>(a.dstate, (uint4*)a.dgimg, (uint4*)a.dsimg, a.scales + 1,
                                                         nullptr, nullptr, nullptr, p.H, a.vbar, a.dv_row, a.dzc, a.cs_part, p.P);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  if ((e = set_smem_once<bwd_k_kernel<D>>(k_smem<D>())) != hipSuccess) return e;
-  bwd_k_kernel<D><<<dim3(p.KP, p.BH), NTK, k_smem<D>(), s>>>(
-      (const uint16_t*)a.k, (const uint16_t*)a.v, (const uint16_t*)a.wk, a.dstate,
-      (const uint4*)a.dsimg, (const uint4*)a.dgimg, (const uint4*)a.wimg, a.scales,
-      (uint16_t*)a.dk, (uint16_t*)a.dv, a.dwk ? duk : nullptr, duk_its, a.dzc, a.dv_row, p.H, p.n, p.rows);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
+  auto launch_k = [&](auto kernel, size_t smem) -> hipError_t {
+    hipError_t e2 = set_smem_once<decltype(kernel)::value>(smem);
+    if (e2 != hipSuccess) return e2;
+    decltype(kernel)::value<<<dim3(p.KP, p.BH), NTK, smem, s>>>(
+        (const uint16_t*)a.k, (const uint16_t*)a.v, (const uint16_t*)a.wk, a.dstate,
+        (const uint4*)a.dsimg, (const uint4*)a.dgimg, (const uint4*)a.wimg, a.scales,
+        (uint16_t*)a.dk, (uint16_t*)a.dv, a.dw_part + side_elems, a.dzc, a.dv_row, p.H, p.n, p.rows);
+    return hipGetLastError();
+  };
+  e = a.dwk ? launch_k(KernelTag<bwd_k_kernel<D, true>>{}, k_smem<D, true>()) : launch_k(KernelTag<bwd_k_kernel<D, false>>{}, k_smem<D, false>());
+  if (e != hipSuccess) return e;
   if (a.dwq || a.dwk) {
-    // the query side's partials are complete (bwd_q_kernel); the key side's come from its dL/du images
-    if (a.dwk) {
-      DwSides sides{};
-      sides.s[0] = DwSide{(const uint16_t*)a.k, duk, duk_its, a.dw_part + side_elems};
-      dw_mfma_kernel<D><<<dim3(p.P, p.BH, 1), NT, 0, s>>>(sides, p.H, p.n, p.P, p.rows);
-      if ((e = hipGetLastError()) != hipSuccess) return e;
-    }
-    const float* parts[2];
-    float* outs[2];
-    int ns = 0;
-    if (a.dwq) { parts[ns] = a.dw_part; outs[ns++] = a.dwq; }
-    if (a.dwk) { parts[ns] = a.dw_part + side_elems; outs[ns++] = a.dwk; }
-    if ((e = launch_dw_reduce2(parts[0], outs[0], ns > 1 ? parts[1] : nullptr, ns > 1 ? outs[1] : nullptr, p, s)) != hipSuccess) return e;
+    if ((e = launch_dw_reduce2(a.dwq ? a.dw_part : nullptr, a.dwq, p.P, a.dwk ? a.dw_part + side_elems : nullptr, a.dwk, p.KP, p, s)) != hipSuccess) return e;
   }
   return hipSuccess;
 }

@@ -84,11 +84,9 @@ struct Plan {
   size_t off_centre;      // centred backward: fp32 [BH][3][d] (mean value row vbar, constant row of dv, centred dz), then
                           // [BH][P][d+8] per-workgroup column sums of dO/den (d) and the sum of -delta/den (1)
   size_t off_drpart;      // fp32 [BH][P] + [kDotParts]: per-workgroup parts of dL/dr (mixed attention, Eq. 6)
-  size_t off_dwpart;      // fp32 [2][BH][P][d*d/2] partial dW~ of the two sides (weight gradients only)
-  size_t du_bytes;        // bytes of one dL/du region
-  size_t off_du_q;        // dL/du of the query side (weight gradients only): fp32 [BH][n][d/2] in fp32 mode;
-                          // in bf16 mode fp16 [BH][ceil(n/32)][32*d/2] operand images of 32-token blocks, each
-                          // scaled by a power of two, then (256-byte aligned) fp32 [BH][ceil(n/32)] inverse scales
+  size_t off_dwpart;      // fp32 [BH][P][d*d/2] partial dW~_q, then [BH][max(P, KP)][d*d/2] partial dW~_k (weight gradients only)
+  size_t du_bytes;        // bytes of one dL/du region (0 in bf16 mode: dW~ is accumulated where du is made)
+  size_t off_du_q;        // dL/du of the query side (weight gradients, fp32 arithmetic only): fp32 [BH][n][d/2]
   size_t off_du_k;        // the same for the key side
   size_t bytes_no_wgrads; // workspace needed by forward and by backward without dW~
   size_t total_bytes;
@@ -151,8 +149,8 @@ hipError_t launch_apply_bf16(const void* q, const void* wq, const float* state, 
 // dw[H][d][d/2] = sum over batch and tokens of x^T du; x is [B,H,n,d] bf16 or fp32, du fp32 [B,H,n,d/2].
 // dw[h][e] = sum over b, then over the P splits, of part[(b*H+h)][p][e].
 hipError_t launch_dw_reduce(const float* part, float* dw, const Plan& p, hipStream_t s);
-// The same for two (partials, output) pairs in one launch; the second pair may be null.
-hipError_t launch_dw_reduce2(const float* part0, float* dw0, const float* part1, float* dw1, const Plan& p, hipStream_t s);
+// The same for two (partials, output, partials per (b,h)) triples in one launch; a triple whose output is null is skipped.
+hipError_t launch_dw_reduce2(const float* part0, float* dw0, int P0, const float* part1, float* dw1, int P1, const Plan& p, hipStream_t s);
 hipError_t launch_dw(const void* x, bool x_is_bf16, const float* du, float* part, float* dw, const Plan& p, hipStream_t s);
 hipError_t launch_bwd_bf16(const BwdArgs& a, const Plan& p, hipStream_t s);
 hipError_t launch_bwd_f32(const BwdArgs& a, const Plan& p, hipStream_t s);

@@ -155,14 +155,15 @@ __global__ __launch_bounds__(256) void dw_partial_kernel(const XT* __restrict__ 
 }
 
 // dw[h][e] = sum_b sum_p part[(b*H + h)][p][e], b then p ascending.
-// blockIdx.z picks one of up to two (partials, output) pairs.
-__global__ __launch_bounds__(256) void dw_reduce_kernel(const float* __restrict__ part0, float* __restrict__ dw0,
-                                                        const float* __restrict__ part1, float* __restrict__ dw1,
-                                                        int B, int H, int P, int elems) {
+// blockIdx.z picks one of up to two (partials, output, partials per (b,h)) triples; a triple without output is skipped.
+__global__ __launch_bounds__(256) void dw_reduce_kernel(const float* __restrict__ part0, float* __restrict__ dw0, int P0,
+                                                        const float* __restrict__ part1, float* __restrict__ dw1, int P1,
+                                                        int B, int H, int elems) {
   const float* part = blockIdx.z ? part1 : part0;
   float* dw = blockIdx.z ? dw1 : dw0;
+  const int P = blockIdx.z ? P1 : P0;
   const int e = blockIdx.x * 256 + threadIdx.x, h = blockIdx.y;
-  if (e >= elems) return;
+  if (e >= elems || dw == nullptr) return;
   float acc = 0.f;
   for (int b = 0; b < B; ++b) {
     const float* src = part + ((size_t)(b * H + h) * P) * elems + e;
@@ -319,13 +320,13 @@ hipError_t launch_dw(const void* x, bool x_is_bf16, const float* du, float* part
 
 hipError_t launch_dw_reduce(const float* part, float* dw, const Plan& p, hipStream_t s) {
   const int elems = p.d * (p.d / 2);
-  dw_reduce_kernel<<<dim3((elems + 255) / 256, p.H), 256, 0, s>>>(part, dw, nullptr, nullptr, p.B, p.H, p.P, elems);
+  dw_reduce_kernel<<<dim3((elems + 255) / 256, p.H), 256, 0, s>>>(part, dw, p.P, nullptr, nullptr, 0, p.B, p.H, elems);
   return hipGetLastError();
 }
 
-hipError_t launch_dw_reduce2(const float* part0, float* dw0, const float* part1, float* dw1, const Plan& p, hipStream_t s) {
+hipError_t launch_dw_reduce2(const float* part0, float* dw0, int P0, const float* part1, float* dw1, int P1, const Plan& p, hipStream_t s) {
   const int elems = p.d * (p.d / 2);
-  dw_reduce_kernel<<<dim3((elems + 255) / 256, p.H, part1 ? 2 : 1), 256, 0, s>>>(part0, dw0, part1, dw1, p.B, p.H, p.P, elems);
+  dw_reduce_kernel<<<dim3((elems + 255) / 256, p.H, 2), 256, 0, s>>>(part0, dw0, P0, part1, dw1, P1, p.B, p.H, elems);
   return hipGetLastError();
 }
 
