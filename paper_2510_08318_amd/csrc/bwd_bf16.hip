@@ -158,8 +158,16 @@ __global__ __launch_bounds__(PT) void bwd_prep_kernel(const float* __restrict__ 
     }
   }
   const int first = blockIdx.y * PT + tid, step = PT * gridDim.y;
-  for (int idx = first; idx < G::IMG; idx += step) gimg[(size_t)bh * G::IMG + idx] = grad_image_entry<D>(S, scale, idx);
-  for (int idx = first; idx < SIMG; idx += step) simg[(size_t)bh * SIMG + idx] = state_image_entry<D, !WQK>(S, scale, idx);
+  if constexpr (WQK) {
+    // one tile for both products of the query side, then the z block (together as large as an image of S)
+    constexpr int TILE = D * D / 8;
+    static_assert(TILE + L::KS * 64 == SIMG, "tile + z block fill the image region");
+    for (int idx = first; idx < TILE; idx += step) simg[(size_t)bh * SIMG + idx] = state_tile_entry<D>(S, scale, idx);
+    for (int idx = first; idx < L::KS * 64; idx += step) simg[(size_t)bh * SIMG + TILE + idx] = state_z_entry<D>(S, scale, idx);
+  } else {
+    for (int idx = first; idx < G::IMG; idx += step) gimg[(size_t)bh * G::IMG + idx] = grad_image_entry<D>(S, scale, idx);
+    for (int idx = first; idx < SIMG; idx += step) simg[(size_t)bh * SIMG + idx] = state_image_entry<D, true>(S, scale, idx);
+  }
   if constexpr (WQK) {
     if (bh < H) {
       static_assert(C::W_IMG == WB_IMG, "the four W~ images have one size");
@@ -361,7 +369,7 @@ struct DwTile {
 template <int D, bool BLEND, bool CENTRE, bool DW>
 __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ dout,
                                                    const uint16_t* __restrict__ wq, const float* __restrict__ state,
-                                                   const uint4* __restrict__ gimg, const uint4* __restrict__ simg,
+                                                   const uint4* __restrict__ simg,
                                                    const uint4* __restrict__ wimg, const float* __restrict__ scales,
                                                    uint16_t* __restrict__ dq,
                                                    float* __restrict__ partials, float* __restrict__ dw_part,
@@ -380,7 +388,8 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
   using DWT = DwTile<D, NT / 64>;
   extern __shared__ uint4 smem[];
   uint4* sWA = smem;
-  uint4* sSA = sWA + C::W_IMG;
+  uint4* sSA = sWA + C::W_IMG;                             // the state tile (state_tile_entry), then its z block
+  const char* sT = reinterpret_cast<const char*>(sSA);
   uint4* sWB = sSA + SA_IMG;
   char* sPhi = reinterpret_cast<char*>(sWB + WB_IMG);      // [kTile][D] fp16: phi(q) (CENTRE: phi(q) - 2/D)
   char* sDO = sPhi + kTile * RS;                           // [kTile][D] fp16: gamma * dO / den
@@ -400,7 +409,6 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
   const float om = BLEND ? 1.f - fminf(fmaxf(*rptr, 0.f), 1.f) : 1.f;      // 1 - r'
   float dr_acc = 0.f;
   const float* sb = state + (size_t)bh * (D + 1) * D;
-  const uint4* gim = gimg + (size_t)bh * G::IMG;
   const int ntile = (n + kTile - 1) / kTile;
   const int nblk = (n + 31) / 32;
 
@@ -491,9 +499,19 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
 #pragma unroll
         for (int mb = 0; mb < L::MB; ++mb) oa[mb][r] = 0.f;
       }
-      const uint4* ssa = sSA + lane + opaque_zero();
+      const int lz = lane + opaque_zero();
+      const uint4* szi = sSA + D * D / 8 + lz;     // the z block behind the tile
+      int offT[L::MB][2];
+#pragma unroll
+      for (int mb = 0; mb < L::MB; ++mb)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) offT[mb][j] = tr_offset<D>(32 * mb, lz, j);
       pipelined_operands<L::KS * L::MBZ, 3>(
-          [&](int i) { return ssa[i * 64]; },
+          [&](int i) {
+            const int ks = i / L::MBZ, mb = i % L::MBZ;
+            if (mb == L::MB) return szi[ks * 64];
+            return __builtin_bit_cast(uint4, read_tr(sT + ks * 16 * RS, offT[mb < L::MB ? mb : 0][0], offT[mb < L::MB ? mb : 0][1]));
+          },
           [&](int i, uint4 a) {
             const int ks = i / L::MBZ, mb = i % L::MBZ;
             uint4 bq; bq.x = pk[4 * ks]; bq.y = pk[4 * ks + 1]; bq.z = pk[4 * ks + 2]; bq.w = pk[4 * ks + 3];
@@ -600,31 +618,26 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
       for (int mb = 0; mb < G::GM; ++mb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) ga[mb][r] = 0.f;
-      // the S image of this product stays in global memory (LDS is full); its operands are
-      // requested GPF k-steps ahead, otherwise every MFMA waits for its own load (0: 213 us for this kernel at the
-      // training shape, 3: 162 us; 2 measures like 3 and leaves 16 registers to the rest)
-      constexpr int GPF = 2;
-      uint4 gop[G::KS][G::GM];
-#pragma unroll
-      for (int ks = 0; ks < GPF; ++ks)
-#pragma unroll
-        for (int mb = 0; mb < G::GM; ++mb) gop[ks][mb] = gim[(ks * G::GM + mb) * 64 + lane];
-#pragma unroll
-      for (int ks = 0; ks < G::KS; ++ks) {
-        if (ks + GPF < G::KS) {
-#pragma unroll
-          for (int mb = 0; mb < G::GM; ++mb) gop[ks + GPF][mb] = gim[((ks + GPF) * G::GM + mb) * 64 + lane];
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        uint4 bq;
-        bq.x = pack_f16x2(dof[8 * ks] * stok, dof[8 * ks + 1] * stok);     bq.y = pack_f16x2(dof[8 * ks + 2] * stok, dof[8 * ks + 3] * stok);
-        bq.z = pack_f16x2(dof[8 * ks + 4] * stok, dof[8 * ks + 5] * stok); bq.w = pack_f16x2(dof[8 * ks + 6] * stok, dof[8 * ks + 7] * stok);
-        const f16x8 bop = as_f16x8(bq);
-#pragma unroll
-        for (int mb = 0; mb < G::GM; ++mb)
-          ga[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(gop[ks][mb]), bop, ga[mb], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-      }
+      // A operand (ks, mb): the lane's feature row of block mb, channels g*D/2 + 8ks .. +7 = chunks 2ks and 2ks+1
+      // of that row, the lane group's 8 bytes of each (state_tile_entry)
+      const int lz = lane + opaque_zero();
+      const char* grow = sT + state_tile_grad_row<D>(lz);
+      const int sw16 = swz<D>((state_tile_grad_row<D>(lz) / RS) % 16) * 16;
+      pipelined_operands<G::KS * G::GM, 4>(
+          [&](int i) {
+            const int ks = i / G::GM, mb = i % G::GM;
+            const char* rowp = grow + 32 * mb * RS;
+            const uint2 lo = *reinterpret_cast<const uint2*>(rowp + ((32 * ks) ^ sw16));
+            const uint2 hi = *reinterpret_cast<const uint2*>(rowp + ((32 * ks + 16) ^ sw16));
+            return make_uint4(lo.x, lo.y, hi.x, hi.y);
+          },
+          [&](int i, uint4 a) {
+            const int ks = i / G::GM, mb = i % G::GM;
+            uint4 bq;
+            bq.x = pack_f16x2(dof[8 * ks] * stok, dof[8 * ks + 1] * stok);     bq.y = pack_f16x2(dof[8 * ks + 2] * stok, dof[8 * ks + 3] * stok);
+            bq.z = pack_f16x2(dof[8 * ks + 4] * stok, dof[8 * ks + 5] * stok); bq.w = pack_f16x2(dof[8 * ks + 6] * stok, dof[8 * ks + 7] * stok);
+            ga[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a), as_f16x8(bq), ga[mb], 0, 0, 0);
+          });
       const float r1 = om * __builtin_amdgcn_rcpf(den_s * stok);     // (1 - r') / (scale * stok * den)
       const float r2 = om * delta * inv_den;
 #pragma unroll
@@ -909,7 +922,7 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
   hipError_t e;
   if ((e = set_smem_once<bwd_prep_kernel<D, true, CENTRE>>(prep_smem_bytes<D>())) != hipSuccess) return e;
   if ((e = set_smem_once<bwd_prep_kernel<D, false, CENTRE>>(prep_smem_bytes<D>())) != hipSuccess) return e;
-  bwd_prep_kernel<D, true, CENTRE><<<dim3(p.BH, PREP_Y), PT, prep_smem_bytes<D>(), s>>>(a.state, (uint4*)a.gimg, (uint4*)a.simg, a.scales,
+  bwd_prep_kernel<D, true, CENTRE><<<dim3(p.BH, PREP_Y), PT, prep_smem_bytes<D>(), s>>>(a.state, nullptr, (uint4*)a.simg, a.scales,
                                                        (const uint16_t*)a.wq, (const uint16_t*)a.wk, (uint4*)a.wimg, p.H,
                                                        a.vbar, nullptr, nullptr, nullptr, p.P);
   if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -920,7 +933,7 @@ hipError_t run_bwd(const BwdArgs& a, const Plan& p, hipStream_t s) {
     hipError_t e2 = set_smem_once<decltype(kernel)::value>(smem);
     if (e2 != hipSuccess) return e2;
     decltype(kernel)::value<<<dim3(p.P, p.BH), NT, smem, s>>>(
-        (const uint16_t*)a.q, (const uint16_t*)a.dout, (const uint16_t*)a.wq, a.state, (const uint4*)a.gimg,
+        (const uint16_t*)a.q, (const uint16_t*)a.dout, (const uint16_t*)a.wq, a.state,
         (const uint4*)a.simg, (const uint4*)a.wimg, a.scales,
         (uint16_t*)a.dq, a.partials, a.dw_part,
         (const uint16_t*)a.blend_in, a.blend_r, a.blend_in ? a.dr_part : nullptr, a.cs_part, p.H, p.n, p.P, p.rows);

@@ -357,6 +357,45 @@ __device__ __forceinline__ uint4 grad_image_entry(const float* __restrict__ S, f
   return r;
 }
 
+// One fp16 tile of the state that serves both products of the query-side backward, o = phi S (contraction over
+// the features) and g = dO S^T (contraction over the channels).  Row rho = 16ks + 8g + e holds the feature
+// that lane group g feeds as element e of k-step ks of phi (ApplyLayout::feature), column position
+// p = 32mb + i holds the channel behind accumulator row i of row block mb (ApplyLayout::channel): a
+// transposing read of rows 16ks .. 16ks+15, columns 32mb .. 32mb+31 is then the A operand (ks, mb) of o, and
+// the 8 channels g*D/2 + 8ks' .. +7 that a lane group feeds to g in k-step ks' sit in one row as two runs of
+// four positions, 16*ks' + 4g .. +3 and 8 further on: two 8-byte reads.  The 16-byte chunks of a row are
+// XOR-swizzled with swz<D>(rho), like every tile that is read with transposing reads.
+// idx = rho * (D/8) + (chunk as stored).
+template <int D>
+__device__ __forceinline__ uint4 state_tile_entry(const float* __restrict__ S, float scale, int idx) {
+  using L = ApplyLayout<D>;
+  const int rho = idx / (D / 8), c = (idx % (D / 8)) ^ swz<D>(rho);
+  const int f = L::feature(rho / 16, (rho / 8) % 2, rho % 8);
+  float x[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int pos = 8 * c + e;
+    x[e] = scale * S[f * D + L::channel(pos / 32, pos % 32)];
+  }
+  uint4 r;
+  r.x = pack_f16x2(x[0], x[1]); r.y = pack_f16x2(x[2], x[3]);
+  r.z = pack_f16x2(x[4], x[5]); r.w = pack_f16x2(x[6], x[7]);
+  return r;
+}
+// The z block of the image built by state_image_entry alone: entry (ks, lane).
+template <int D>
+__device__ __forceinline__ uint4 state_z_entry(const float* __restrict__ S, float scale, int idx) {
+  using L = ApplyLayout<D>;
+  return state_image_entry<D>(S, scale, ((idx / 64) * L::MBZ + L::MB) * 64 + idx % 64);
+}
+// Byte offset, inside the tile, of the row that holds feature GradLayout::feature(0, m) for this lane
+// (m = lane % 32), plus the lane group's 8 bytes inside a chunk; row block mb of g is 32*mb rows further on.
+template <int D>
+__device__ __forceinline__ int state_tile_grad_row(int lane) {
+  const int m = lane % 32, gg = (m / 4) % 2, r = 4 * (m / 8) + (m % 4);
+  return (16 * (r / 8) + 8 * gg + (r % 8)) * (D * 2) + 8 * (lane / 32);
+}
+
 // W~ [D][D/2] bf16 (one head) -> LDS image (fp16, exact) of the B operands of dX = dU W~^T
 // (contraction over the d/2 pre-softmax features, tokens on the accumulator rows): entry
 // (ks, mb, lane=(c,g)) holds W~[channel_cols(mb,c)][g*LOC + 8ks + e], e = 0..7; ks < LOC/8, mb < D/32.

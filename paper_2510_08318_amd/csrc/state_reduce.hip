@@ -164,10 +164,18 @@ __global__ __launch_bounds__(256) void dw_reduce_kernel(const float* __restrict_
   const int P = blockIdx.z ? P1 : P0;
   const int e = blockIdx.x * 256 + threadIdx.x, h = blockIdx.y;
   if (e >= elems || dw == nullptr) return;
+  // eight partials are requested together and then added in ascending order (a missing one adds 0): one memory
+  // latency per eight terms instead of one per term, the order of the sum unchanged
   float acc = 0.f;
   for (int b = 0; b < B; ++b) {
     const float* src = part + ((size_t)(b * H + h) * P) * elems + e;
-    for (int p = 0; p < P; ++p) acc += src[(size_t)p * elems];
+    for (int p0 = 0; p0 < P; p0 += 8) {
+      float v[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = p0 + j < P ? src[(size_t)(p0 + j) * elems] : 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc += v[j];
+    }
   }
   dw[(size_t)h * elems + e] = acc;
 }
