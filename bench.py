@@ -33,7 +33,7 @@ PREWARM_SECONDS = 0.25         # forward calls before --warmup, so that short ru
 # profiles/fwd_wan14b_720p_pmc.md.  None for workloads that have not been measured.
 MEASURED_TRAFFIC = {("C3", 0): 1_553_370_522 + 19_021_824, ("C3", 2): 794_324_787 + 774_176_666}
 # The same for one linattn_bwd call (all its kernels), weight gradients on: profiles/bwd_wan1p3b_480p_pmc.md.
-MEASURED_TRAFFIC_BWD = {"C5": 816_400_000 + 446_700_000}
+MEASURED_TRAFFIC_BWD = {"C5": 560_400_000 + 338_100_000}
 
 
 def _hip():

@@ -170,9 +170,9 @@ int linattn_phi_set_blend(int phi_id, const void* blend_in, const float* blend_r
 size_t linattn_workspace_bytes(int B, int H, int n, int d, int kind, int dtype);
 
 /* Scratch bytes linattn_bwd needs when the descriptor asks for dwq or dwk (W~ is learnable, Eq. 5):
- * the above plus two buffers for dL/du (fp32 mode: fp32 [B,H,n,d/2]; bf16 mode: half that, fp16 in
- * 32-token blocks) and the partial sums of dW~.  For LINATTN_PHI_RELU (no weights) it equals
- * linattn_workspace_bytes. */
+ * the above plus the partial sums of dW~ (one [d][d/2] fp32 block per workgroup of the two main kernels) and, in
+ * the fp32-arithmetic modes only, two fp32 buffers [B,H,n,d/2] for dL/du (the bf16 kernels accumulate dW~ where
+ * du is made).  For LINATTN_PHI_RELU (no weights) it equals linattn_workspace_bytes. */
 size_t linattn_workspace_bytes_wgrads(int B, int H, int n, int d, int kind, int dtype);
 
 /*
