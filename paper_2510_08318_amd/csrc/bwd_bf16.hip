@@ -92,10 +92,21 @@ __global__ __launch_bounds__(PT) void bwd_prep_kernel(const float* __restrict__ 
   __syncthreads();
   __shared__ float cA[D], cB[D], cC[D];
   constexpr int HF = D / 2;
+  constexpr int PARTS = PT / D;                    // threads per channel (or feature) in the sums below
+  __shared__ float part[PT];
   if constexpr (WQK) {
+    {
+      // column sums of the + half of S, PARTS threads per channel over HF / PARTS rows each; the + half of z sums to n
+      const int ch = tid % D, q = tid / D;
+      float sv = 0.f;
+      for (int f = q * (HF / PARTS); f < (q + 1) * (HF / PARTS); ++f) sv += S[f * D + ch];
+      part[tid] = sv;
+    }
+    __syncthreads();
     if (tid < D) {
       float sv = 0.f, nt = 0.f;
-      for (int f = 0; f < HF; ++f) { sv += S[f * D + tid]; nt += S[D * D + f]; }
+      for (int q = 0; q < PARTS; ++q) sv += part[q * D + tid];
+      for (int f = 0; f < HF; ++f) nt += S[D * D + f];
       const float vb = sv / nt;
       cA[tid] = vb;
       if (blockIdx.y == 0) vbar[(size_t)bh * D + tid] = vb;
@@ -150,11 +161,15 @@ __global__ __launch_bounds__(PT) void bwd_prep_kernel(const float* __restrict__ 
   const float scale = head_scale<D, PT>(S, red, tid);      // every block of a head computes the same value
   if (blockIdx.y == 0 && tid == 0) scale_out[2 * bh] = scale;
   if constexpr (!WQK) {
-    if (blockIdx.y == 0 && tid < D) {
+    if (blockIdx.y == 0) {
+      // PARTS adjacent threads per feature, D / PARTS channels each, combined inside the wavefront
+      const int f = tid / PARTS, q = tid % PARTS;
       const float inv = __builtin_amdgcn_rcpf(scale);       // exact: a power of two
       float dot = 0.f;
-      for (int ch = 0; ch < D; ++ch) dot = fmaf((float)(_Float16)(scale * S[tid * D + ch]), cC[ch], dot);
-      dzc[(size_t)bh * D + tid] = cB[tid] - dot * inv;
+      for (int ch = q * (D / PARTS); ch < (q + 1) * (D / PARTS); ++ch)
+        dot = fmaf((float)(_Float16)(scale * S[f * D + ch]), cC[ch], dot);
+      for (int m = 1; m < PARTS; m <<= 1) dot += __shfl_xor(dot, m, 64);
+      if (q == 0) dzc[(size_t)bh * D + f] = cB[f] - dot * inv;
     }
   }
   const int first = blockIdx.y * PT + tid, step = PT * gridDim.y;
@@ -360,6 +375,10 @@ struct DwTile {
 };
 
 // ---- query side --------------------------------------------------------------------------
+// LDS operands of the query-side kernel's MFMA phases are requested QAHEAD MFMAs before their use (one more for g):
+// with one wavefront per SIMD nothing else hides an LDS latency.  3 (4 for g) against 5 (6): 296 -> 293 us per
+// backward call at the training shape; 8 measures between the two.
+constexpr int QAHEAD = 5;
 // BLEND: dout is the gradient of the mixed output of Eq. 6; the linear branch receives
 // (1 - r') dout, and the workgroup's part of -sum dout . o goes to dr_part (dL/dr = sum dout . (s - o);
 // the sum dout . s is a separate streaming dot product, taken only when dL/dr is asked for).
@@ -478,7 +497,7 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
     // linear in dout, so the factor 1 - r' is applied to the scalars that carry it (om below).
     // dout . s is taken here, while few registers are live.
     f32x16 u[C::UM];
-    project<D, 3>(xq, sWA, lane, u);
+    project<D, QAHEAD>(xq, sWA, lane, u);
     uint4 xr[C::UK];                              // this tile's rows once more, for dW~ (rows past n repeat row n - 1: their du is zero)
     if constexpr (DW) {
 #pragma unroll
@@ -506,7 +525,7 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
       for (int mb = 0; mb < L::MB; ++mb)
 #pragma unroll
         for (int j = 0; j < 2; ++j) offT[mb][j] = tr_offset<D>(32 * mb, lz, j);
-      pipelined_operands<L::KS * L::MBZ, 3>(
+      pipelined_operands<L::KS * L::MBZ, QAHEAD>(
           [&](int i) {
             const int ks = i / L::MBZ, mb = i % L::MBZ;
             if (mb == L::MB) return szi[ks * 64];
@@ -623,7 +642,7 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
       const int lz = lane + opaque_zero();
       const char* grow = sT + state_tile_grad_row<D>(lz);
       const int sw16 = swz<D>((state_tile_grad_row<D>(lz) / RS) % 16) * 16;
-      pipelined_operands<G::KS * G::GM, 4>(
+      pipelined_operands<G::KS * G::GM, QAHEAD + 1>(
           [&](int i) {
             const int ks = i / G::GM, mb = i % G::GM;
             const char* rowp = grow + 32 * mb * RS;
@@ -664,7 +683,7 @@ __global__ __launch_bounds__(NT) void bwd_q_kernel(const uint16_t* __restrict__ 
       const int blk = tile * (kTile / 32) + w;
       uint32_t dub[C::LOC / 2];
       float blk_its = 0.f;
-      du_to_dx<D, 3>(du, sWB, lane, valid, xa, its, dub, blk_its);
+      du_to_dx<D, QAHEAD>(du, sWB, lane, valid, xa, its, dub, blk_its);
       // the previous tile's dW~ contraction has read its du tile: every wavefront has passed this tile's first barrier since
       if constexpr (DW) DWT::park_du(dub, blk_its, sDU, sRed + 4, w, lane);
       store_token_rows<D>(dqb, rw.sn, blk * 32, n, lane, xa, its);
