@@ -354,20 +354,27 @@ __global__ __launch_bounds__(NT) void relu_bwd_q_kernel(const uint16_t* __restri
   float* myRow = sRow + w * 64;
   float gamma = kGammaUnset;
 
+  // The rows of a tile are requested inside the tile before it, each set as soon as its registers are free (the
+  // accumulator-layout q rows before the dq stores, the operand-layout q and dO rows behind the parking of phi
+  // and dO): with one wavefront per SIMD nothing else hides the latency of a load at the top of a tile.  Never
+  // behind a branch: after the last tile its rows are simply read again.
+  uint4 xq[C::UK], dor[C::UK];
+  Piece qrow[16];
+  auto load_operand_rows = [&](int tile) {
+    const int t = tile * kTile + prow;
+    const int tc = t < n ? t : (n - 1);
+    const uint4* row = reinterpret_cast<const uint4*>(qb + (size_t)tc * rw.sn);
+    const uint4* drow = reinterpret_cast<const uint4*>(dob + (size_t)tc * rw.sn);
+#pragma unroll
+    for (int ks = 0; ks < C::UK; ++ks) { xq[ks] = row[2 * ks + g]; dor[ks] = drow[2 * ks + g]; }
+  };
+  load_operand_rows(p < ntile ? p : 0);
+  load_row_pieces<D>(qb, rw.sn, (p < ntile ? p : 0) * kTile + 32 * w, n, lane, qrow);
   for (int tile = p; tile < ntile; tile += P) {
     const int t0 = tile * kTile + 32 * w;
     const int t = tile * kTile + prow;
     const bool valid = t < n;
-    const int tc = valid ? t : (n - 1);
-    uint4 xq[C::UK], dor[C::UK];
-    {
-      const uint4* row = reinterpret_cast<const uint4*>(qb + (size_t)tc * rw.sn);
-      const uint4* drow = reinterpret_cast<const uint4*>(dob + (size_t)tc * rw.sn);
-#pragma unroll
-      for (int ks = 0; ks < C::UK; ++ks) { xq[ks] = row[2 * ks + g]; dor[ks] = drow[2 * ks + g]; }
-    }
-    Piece qrow[16];
-    load_row_pieces<D>(qb, rw.sn, t0, n, lane, qrow);
+    const int next = tile + P < ntile ? tile + P : tile;
 
     // block scale of dO
     float dmax = 0.f;
@@ -430,6 +437,7 @@ __global__ __launch_bounds__(NT) void relu_bwd_q_kernel(const uint16_t* __restri
         dqa[mb][r] = piece_elem(qrow[r], mb) > 0.f ? val : 0.f;
       }
     }
+    load_row_pieces<D>(qb, rw.sn, next * kTile + 32 * w, n, lane, qrow);
     store_token_rows<D>(dqb, rw.sn, t0, n, lane, dqa, 1.f);
 
     // the per-token scalars back onto the lanes that own the tokens
@@ -500,6 +508,7 @@ __global__ __launch_bounds__(NT) void relu_bwd_q_kernel(const uint16_t* __restri
       }
       if (g == 0) sW16[prow] = (uint16_t)(pack_f16x2(live ? -delta_t * sc : 0.f, 0.f) & 0xffffu);
     }
+    load_operand_rows(next);
     __syncthreads();
     contract_tile<D>(sPhi, sDO, offA, offB, s, zacc, ni != 0, do_z,
                      [&](int ks) { return as_f16x8(*reinterpret_cast<const uint4*>(sW16 + 16 * ks + 8 * g)); });
