@@ -51,7 +51,7 @@
  *     exception: the backward's operand images are built with the head's mean value row taken out.)  Second exception: where phi is within a few per
  *     cent of uniform (the spread of x W~ over the features far below 1), dq, dk and dW~ are
  *     differences of nearly equal rows of S and dS and come out up to 0.2 off; out and dv keep 1e-2.
- *     LINATTN_FLAG_CENTRED removes this exception (not the first) at a cost of 3-4 %.
+ *     LINATTN_FLAG_CENTRED removes this exception (not the first) at a cost of 3-5 %.
  *   - LINATTN_BF16_F32MATH reads and writes the same bf16 tensors but does all arithmetic in fp32
  *     (the kernels of the fp32 mode, no matrix cores, no fp16 operands): none of the limits above
  *     applies, |v| may be any finite bf16 value, and the only rounding that matters is the bf16
